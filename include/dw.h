@@ -1,0 +1,172 @@
+/*
+ * dw.h -- C ABI of the dynamic-weighted elastic AdaHessian hot path for AMD MI355X (gfx950).
+ *
+ * The library simulates one master ("centre") and k worker replicas of a ReLU MLP classifier on a
+ * single GPU, as in the paper's single-device experiments (Xu & Carr, "A Dynamic Weighting Strategy
+ * to Mitigate Worker Node Failure in Distributed Deep Learning", Section VI).  Its three hot calls
+ * follow the paper's problem statement:
+ *
+ *   dw_init          master model + k workers, each starting as a copy of it   (Section II, assumptions)
+ *   dw_worker_step   one local AdaHessian step per worker on its own minibatch  (Section II eq.(2),(4);
+ *                    Section IV-B: Hutchinson estimate z*(Hz), spatial averaging, Adam-like moments)
+ *   dw_elastic_sync  one communication round every tau steps: log-distance u, raw score a,
+ *                    weights h1(a), h2(a), elastic pull of worker and master    (Section V-B eq.(10)-(13);
+ *                    Section IV-A eq.(8)-(9) for the fixed-rate case; tau: Section VI footnote)
+ *
+ * Conventions
+ *   - Every function returns DW_OK (0) or a negative dw_status; dw_elastic_sync returns 1 when a round
+ *     was enqueued and 0 when the step count is not a multiple of tau.  On error nothing is enqueued.
+ *   - Pointers named d_* are device pointers, h_* are host pointers.  The caller owns all memory,
+ *     including the workspace handed to dw_init, and the stream.  The library allocates no device
+ *     memory and never synchronises the stream, except dw_get_state/dw_set_state/dw_init (see there).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls on one handle must be
+ *     issued from one host thread at a time and on one stream.
+ *   - Canonical parameter layout (index space of theta, m, v, g, Hz and of the Rademacher vector z):
+ *     for l = 1..L the weight W_l row-major [d_l][d_{l-1}] followed by the bias b_l[d_l], no padding.
+ *   - Rademacher bits: element j of z is +1 when bit (j mod 32) of 32-bit word floor(j/32) is set, else -1.
+ */
+#ifndef DW_H_
+#define DW_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DW_MAX_LAYERS 8      /* linear layers L                                  */
+#define DW_MAX_K 64          /* worker replicas k                                */
+#define DW_MAX_P 8           /* length p of the raw-score history weights c_j    */
+#define DW_MAX_CLASSES 16    /* width d_L of the output layer                    */
+
+typedef enum {
+  DW_OK = 0,
+  DW_ERR_NULL = -1,          /* a required pointer is NULL                                   */
+  DW_ERR_CONFIG = -2,        /* dims / k / batch / dtype out of range or misaligned          */
+  DW_ERR_HYPER = -3,         /* lr, beta, eps, alpha, kappa, p, c_j or avg_block invalid      */
+  DW_ERR_WORKSPACE = -4,     /* workspace too small or not 256-byte aligned                  */
+  DW_ERR_ARG = -5,           /* bad call argument (mode, worker index, range, alignment)     */
+  DW_ERR_HIP = -6,           /* a HIP runtime call failed (see dw_last_hip_error)            */
+  DW_ERR_MODE = -7           /* call not valid for this handle (MLP call on a flat problem ...) */
+} dw_status;
+
+/* arithmetic type of the network part (optimizer state is always fp32) */
+#define DW_F32 0             /* fp32 weights, activations, MFMA accumulation                            */
+#define DW_BF16 1            /* bf16 weights/activations (round-to-nearest-even), fp32 accumulation     */
+
+/* how dw_elastic_sync chooses the per-worker weights (h1_i, h2_i) */
+#define DW_FIXED 0           /* h1 = h2 = alpha: plain elastic averaging (Section IV-A)                 */
+#define DW_MANUAL 1          /* caller-supplied, "as if we know when a node will fail" (Section VI)     */
+#define DW_DYNAMIC 2         /* h1(a), h2(a) from the raw score (Section V-B)                           */
+
+/* selectors for dw_get_state / dw_set_state */
+#define DW_S_THETA 0         /* float[P]   worker parameters                                            */
+#define DW_S_M 1             /* float[P]   first moment                                                 */
+#define DW_S_V 2             /* float[P]   second moment                                                */
+#define DW_S_G 3             /* float[P]   last gradient                                                */
+#define DW_S_HZ 4            /* float[P]   last Hessian-vector product                                  */
+#define DW_S_CENTRE 5        /* float[P]   master parameters (worker index ignored)                     */
+#define DW_S_ZBITS 6         /* uint32[ceil(P/32)] bits of the last z drawn by the library              */
+#define DW_S_SCORE 7         /* double[4]  {u, a, h1, h2} of the last round (get only)                  */
+#define DW_S_U_HIST 8        /* double[1+DW_MAX_P+1]: count n, then the n most recent u, oldest first   */
+#define DW_S_STEPS 9         /* int64[1]   local steps t_i taken by the worker                          */
+
+typedef struct dw_handle dw_handle;
+
+typedef struct {
+  int32_t n_layers;                 /* L >= 1 linear layers; 0 = flat parameter vector (update/sync only)   */
+  int32_t dims[DW_MAX_LAYERS + 1];  /* d_0..d_L; d_0..d_{L-1} multiples of 4 (8 for DW_BF16), d_L <= DW_MAX_CLASSES */
+  int64_t n_params;                 /* flat problem: P (multiple of 4); MLP: 0 or the P implied by dims     */
+  int32_t k;                        /* workers, 1..DW_MAX_K                                                 */
+  int32_t batch;                    /* minibatch size B per worker (m of eq.(2)); ignored when n_layers = 0 */
+  int32_t dtype;                    /* DW_F32 | DW_BF16                                                     */
+  float lr, beta1, beta2, eps;      /* eta and beta of Section VII; eps added to the denominator            */
+  float hpow;                       /* Hessian power: denominator (sqrt(v_hat))^hpow + eps                  */
+  int32_t avg_block;                /* spatial-averaging block b along fan-in: power of two <= 256 dividing
+                                       d_0..d_{L-1} (flat problem: dividing P); 1 = no averaging             */
+  float alpha;                      /* fixed moving rate, 0 < alpha <= 1 (Section IV-A)                     */
+  float kappa;                      /* the negative constant of the piecewise maps h1, h2 (Section V-B)      */
+  int32_t p;                        /* number of history differences, 1..DW_MAX_P                           */
+  float c[DW_MAX_P];                /* c_0 (most recent) .. c_{p-1}; must sum to 1 within 1e-5 (eq.(10)-(11)) */
+  uint64_t seed;                    /* seed of the library's Rademacher stream                              */
+} dw_config;
+
+/* Human-readable text for a status code (never NULL). */
+const char* dw_strerror(int status);
+/* hipError_t (as int) of the last HIP failure seen by this thread's calls, 0 if none. */
+int dw_last_hip_error(void);
+
+/* Validate a configuration and return the parameter count P per replica through *n_params. */
+int dw_param_count(const dw_config* cfg, int64_t* n_params);
+
+/* Device bytes dw_init needs for this configuration; 0 if the configuration is invalid. */
+size_t dw_workspace_bytes(const dw_config* cfg);
+
+/*
+ * Create a handle over a caller-allocated workspace (256-byte aligned device memory of at least
+ * dw_workspace_bytes(cfg) bytes, which must outlive the handle).  The centre is set to theta0 and all
+ * k workers to copies of it (Section II: each worker starts with a copy of the master's model);
+ * moments, step counts and the u history start empty.  theta0 holds P floats in canonical layout and may
+ * live on the host (theta0_on_device = 0; copied synchronously) or on the device.
+ */
+int dw_init(dw_handle** out, const dw_config* cfg, void* d_workspace, size_t workspace_bytes,
+            const float* theta0, int theta0_on_device, void* stream);
+
+/* Free the host-side handle (device memory stays with the caller). */
+int dw_destroy(dw_handle* h);
+
+/*
+ * One local AdaHessian step for every active worker (Section IV-B; update rule eq.(4)):
+ *   forward and backward pass on the worker's minibatch -> mean loss and gradient g   (eq.(2), eq.(6))
+ *   Rademacher z, Hessian-vector product Hz of the same minibatch loss, D = z*Hz       (Hutchinson, n = 1)
+ *   block mean of D over avg_block neighbours along fan-in (biases excluded)
+ *   m = b1 m + (1-b1) g;  v = b2 v + (1-b2) D^2;  theta -= lr * (m/(1-b1^t)) / ((sqrt(v/(1-b2^t)))^hpow + eps)
+ * and the squared distance of the new theta to the centre, kept for the next dw_elastic_sync.
+ *
+ *   d_x       [k][B][d_0] inputs: float (DW_F32) or bfloat16 (DW_BF16), 16-byte aligned
+ *   d_y       [k][B] int32 class labels in [0, d_L)
+ *   d_zbits   [k][zwords] uint32 sign bits of z per worker, zwords = 2*ceil(P/64); NULL = drawn by the
+ *             library from its counter-based stream at (seed, worker, t_i)
+ *   h_active  [k] bytes, 0 = the worker is frozen this step (no update, t_i unchanged); NULL = all active
+ *   d_loss    [k] floats receiving the mean minibatch loss per worker (untouched for frozen ones); may be NULL
+ */
+int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* d_zbits,
+                   const uint8_t* h_active, float* d_loss, void* stream);
+
+/*
+ * The optimizer part of dw_worker_step alone, on caller-supplied gradients and Hessian-vector products
+ * d_g, d_hz ([k][P] floats each, 16-byte aligned; worker i at offset i*P).  Other arguments as above.
+ * Valid for flat problems and for MLP problems.
+ */
+int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint32_t* d_zbits,
+                   const uint8_t* h_active, void* stream);
+
+/*
+ * One communication round (Section V-B), taken only when the number of dw_worker_step/dw_update_only calls
+ * so far is a multiple of tau (tau >= 1).  Every worker records u_i = log||theta_i - centre|| (centre as at
+ * the start of the round) in its history and its raw score a_i (eq.(10)-(11)); then for each participating
+ * worker  theta_i -= h1_i (theta_i - centre)  (eq.(12))  and the centre moves by the sum over participating
+ * workers of  h2_i (theta_i - centre)  (eq.(13)), all differences taken against the centre before the round.
+ *
+ *   mode            DW_FIXED | DW_MANUAL | DW_DYNAMIC
+ *   h_h1, h_h2      [k] floats, required for DW_MANUAL, ignored otherwise
+ *   h_participate   [k] bytes, 0 = this worker's communication is suppressed in this round (it still
+ *                   records u); NULL = all participate
+ * Returns 1 if a round was enqueued, 0 if skipped, negative on error.
+ */
+int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2,
+                    const uint8_t* h_participate, int tau, void* stream);
+
+/*
+ * Copy `count` elements starting at element `offset` of a state array to / from host memory.  Both calls
+ * synchronise the stream before returning.  dw_set_state accepts DW_S_THETA, DW_S_M, DW_S_V, DW_S_CENTRE and
+ * DW_S_STEPS (for DW_BF16 the bf16 weight copy is refreshed after THETA is set).
+ */
+int dw_get_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, void* h_buf, void* stream);
+int dw_set_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, const void* h_buf, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DW_H_ */

@@ -1,0 +1,208 @@
+"""Thin ctypes binding over libdw.so (declared in include/dw.h).
+
+Argument marshalling only: every step of the method runs in the library's HIP kernels.  PyTorch is used
+for device memory (the workspace and the caller's tensors) and for the current stream.  There is no CPU
+fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdw.so")
+
+DW_MAX_LAYERS, DW_MAX_K, DW_MAX_P, DW_MAX_CLASSES = 8, 64, 8, 16
+DW_F32, DW_BF16 = 0, 1
+DW_FIXED, DW_MANUAL, DW_DYNAMIC = 0, 1, 2
+(DW_S_THETA, DW_S_M, DW_S_V, DW_S_G, DW_S_HZ, DW_S_CENTRE, DW_S_ZBITS, DW_S_SCORE, DW_S_U_HIST,
+ DW_S_STEPS) = range(10)
+
+EXPORTS = ("dw_strerror", "dw_last_hip_error", "dw_param_count", "dw_workspace_bytes", "dw_init", "dw_destroy",
+           "dw_worker_step", "dw_update_only", "dw_elastic_sync", "dw_get_state", "dw_set_state")
+
+
+class dw_config(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("dims", C.c_int32 * (DW_MAX_LAYERS + 1)), ("n_params", C.c_int64),
+        ("k", C.c_int32), ("batch", C.c_int32), ("dtype", C.c_int32),
+        ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+        ("hpow", C.c_float), ("avg_block", C.c_int32),
+        ("alpha", C.c_float), ("kappa", C.c_float), ("p", C.c_int32), ("c", C.c_float * DW_MAX_P),
+        ("seed", C.c_uint64),
+    ]
+
+
+class DwError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d, hip error %d)" % (
+            where, lib().dw_strerror(status).decode(), status, lib().dw_last_hip_error()))
+
+
+_LIB = None
+
+
+def lib() -> C.CDLL:
+    """Load libdw.so once and declare the prototypes of include/dw.h."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libdw.so is missing: build it with `python -m paper_2409_09242_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
+    L.dw_strerror.restype = C.c_char_p; L.dw_strerror.argtypes = [i32]
+    L.dw_last_hip_error.restype = i32; L.dw_last_hip_error.argtypes = []
+    L.dw_param_count.restype = i32; L.dw_param_count.argtypes = [C.POINTER(dw_config), C.POINTER(i64)]
+    L.dw_workspace_bytes.restype = C.c_size_t; L.dw_workspace_bytes.argtypes = [C.POINTER(dw_config)]
+    L.dw_init.restype = i32
+    L.dw_init.argtypes = [C.POINTER(vp), C.POINTER(dw_config), vp, C.c_size_t, vp, i32, vp]
+    L.dw_destroy.restype = i32; L.dw_destroy.argtypes = [vp]
+    L.dw_worker_step.restype = i32; L.dw_worker_step.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    L.dw_update_only.restype = i32; L.dw_update_only.argtypes = [vp, vp, vp, vp, vp, vp]
+    L.dw_elastic_sync.restype = i32; L.dw_elastic_sync.argtypes = [vp, i32, vp, vp, vp, i32, vp]
+    L.dw_get_state.restype = i32; L.dw_get_state.argtypes = [vp, i32, i32, i64, i64, vp, vp]
+    L.dw_set_state.restype = i32; L.dw_set_state.argtypes = [vp, i32, i32, i64, i64, vp, vp]
+    _LIB = L
+    return L
+
+
+def make_config(*, dims: Optional[Sequence[int]], k: int, batch: int = 0, bf16: bool = False, n_params: int = 0,
+                lr=0.01, beta1=0.9, beta2=0.999, eps=1e-4, hpow=1.0, avg_block=1, alpha=0.1, kappa=-0.1,
+                c: Sequence[float] = (0.4, 0.3, 0.2, 0.1), seed: int = 0) -> dw_config:
+    cfg = dw_config()
+    if dims is None:
+        cfg.n_layers = 0
+        cfg.n_params = n_params
+    else:
+        cfg.n_layers = len(dims) - 1
+        for i, d in enumerate(dims):
+            cfg.dims[i] = d
+        cfg.n_params = 0
+    cfg.k, cfg.batch, cfg.dtype = k, batch, (DW_BF16 if bf16 else DW_F32)
+    cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.hpow, cfg.avg_block = lr, beta1, beta2, eps, hpow, avg_block
+    cfg.alpha, cfg.kappa, cfg.p = alpha, kappa, len(c)
+    for j, cj in enumerate(c):
+        cfg.c[j] = cj
+    cfg.seed = seed
+    return cfg
+
+
+def config_from_workload(w, **overrides) -> dw_config:
+    kw = dict(dims=w.dims, k=w.k, batch=w.batch, bf16=w.bf16, n_params=w.n_params if w.dims is None else 0,
+              lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, hpow=w.hpow, avg_block=w.avg_block,
+              alpha=w.alpha, kappa=w.kappa, c=w.c, seed=w.seed)
+    kw.update(overrides)
+    return make_config(**kw)
+
+
+def param_count(cfg: dw_config) -> int:
+    n = C.c_int64(0)
+    st = lib().dw_param_count(C.byref(cfg), C.byref(n))
+    if st != 0:
+        raise DwError(st, "dw_param_count")
+    return n.value
+
+
+def _u8(a) -> Optional[np.ndarray]:
+    return None if a is None else np.ascontiguousarray(np.asarray(a, dtype=np.uint8))
+
+
+def _ptr(a):
+    if a is None:
+        return None
+    if isinstance(a, np.ndarray):
+        return a.ctypes.data_as(C.c_void_p)
+    return C.c_void_p(a.data_ptr())        # torch tensor
+
+
+class Handle:
+    """One master + k workers on the current CUDA device; owns the workspace tensor."""
+
+    def __init__(self, cfg: dw_config, theta0, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.cfg = cfg
+        self.k = cfg.k
+        self.P = param_count(cfg)
+        self.zwords = 2 * ((self.P + 63) // 64)
+        nbytes = lib().dw_workspace_bytes(C.byref(cfg))
+        if nbytes == 0:
+            raise DwError(-2, "dw_workspace_bytes")
+        self.device = torch.device(device)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = self.workspace.data_ptr()
+        self._ws_ptr = (base + 255) // 256 * 256
+        self._h = C.c_void_p()
+        if isinstance(theta0, np.ndarray):
+            t0 = np.ascontiguousarray(theta0, dtype=np.float32)
+            assert t0.shape == (self.P,)
+            st = lib().dw_init(C.byref(self._h), C.byref(cfg), self._ws_ptr, nbytes, _ptr(t0), 0, self._stream())
+        else:
+            assert theta0.is_cuda and theta0.dtype == torch.float32 and theta0.numel() == self.P
+            st = lib().dw_init(C.byref(self._h), C.byref(cfg), self._ws_ptr, nbytes, _ptr(theta0), 1, self._stream())
+        if st != 0:
+            raise DwError(st, "dw_init")
+
+    def _stream(self):
+        return C.c_void_p(self.torch.cuda.current_stream(self.device).cuda_stream)
+
+    def close(self):
+        if self._h:
+            lib().dw_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the three hot calls -------------------------------------------------------------------------
+    def worker_step(self, x, y, zbits=None, active=None, loss=None):
+        act = _u8(active)
+        st = lib().dw_worker_step(self._h, _ptr(x), _ptr(y), _ptr(zbits), _ptr(act), _ptr(loss), self._stream())
+        if st != 0:
+            raise DwError(st, "dw_worker_step")
+
+    def update_only(self, g, hz, zbits=None, active=None):
+        act = _u8(active)
+        st = lib().dw_update_only(self._h, _ptr(g), _ptr(hz), _ptr(zbits), _ptr(act), self._stream())
+        if st != 0:
+            raise DwError(st, "dw_update_only")
+
+    def elastic_sync(self, mode=DW_DYNAMIC, tau=1, h1=None, h2=None, participate=None) -> bool:
+        a1 = None if h1 is None else np.ascontiguousarray(h1, dtype=np.float32)
+        a2 = None if h2 is None else np.ascontiguousarray(h2, dtype=np.float32)
+        part = _u8(participate)
+        st = lib().dw_elastic_sync(self._h, mode, _ptr(a1), _ptr(a2), _ptr(part), tau, self._stream())
+        if st < 0:
+            raise DwError(st, "dw_elastic_sync")
+        return st == 1
+
+    # ---- state access --------------------------------------------------------------------------------
+    _DT = {DW_S_ZBITS: np.uint32, DW_S_SCORE: np.float64, DW_S_U_HIST: np.float64, DW_S_STEPS: np.int64}
+
+    def get_state(self, what: int, worker: int = 0, offset: int = 0, count: Optional[int] = None) -> np.ndarray:
+        if count is None:
+            count = {DW_S_ZBITS: self.zwords, DW_S_SCORE: 4, DW_S_U_HIST: 2 + DW_MAX_P, DW_S_STEPS: 1}.get(
+                what, self.P) - offset
+        out = np.empty(count, dtype=self._DT.get(what, np.float32))
+        st = lib().dw_get_state(self._h, what, worker, offset, count, _ptr(out), self._stream())
+        if st != 0:
+            raise DwError(st, "dw_get_state")
+        return out
+
+    def set_state(self, what: int, worker: int, values, offset: int = 0):
+        arr = np.ascontiguousarray(values, dtype=self._DT.get(what, np.float32))
+        st = lib().dw_set_state(self._h, what, worker, offset, arr.size, _ptr(arr), self._stream())
+        if st != 0:
+            raise DwError(st, "dw_set_state")
+
+    def all_state(self, what: int) -> np.ndarray:
+        return np.stack([self.get_state(what, i) for i in range(self.k)])

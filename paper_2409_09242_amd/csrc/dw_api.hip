@@ -1,0 +1,448 @@
+// Host side of libdw: configuration checks, workspace carving, per-call bookkeeping and the order in
+// which the kernels of one worker step / one communication round are enqueued.  Nothing here computes
+// any part of the method on the host except the scalars 1 - beta^t (Section IV-B bias correction) and
+// the keys of the Rademacher stream.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "dw_internal.h"
+
+using namespace dw;
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+inline int hip_fail(hipError_t e) {
+  g_last_hip = (int)e;
+  return DW_ERR_HIP;
+}
+#define DW_HIP(expr)                                   \
+  do {                                                 \
+    hipError_t e__ = (expr);                           \
+    if (e__ != hipSuccess) return hip_fail(e__);       \
+  } while (0)
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
+
+
+int validate(const dw_config* c, Layout* lay) {
+  if (!c) return DW_ERR_NULL;
+  if (c->k < 1 || c->k > DW_MAX_K) return DW_ERR_CONFIG;
+  if (c->dtype != DW_F32 && c->dtype != DW_BF16) return DW_ERR_CONFIG;
+  if (c->n_layers < 0 || c->n_layers > DW_MAX_LAYERS) return DW_ERR_CONFIG;
+  const int L = c->n_layers;
+  const int align = c->dtype == DW_BF16 ? 8 : 4;
+  int64_t P = 0;
+  if (L == 0) {
+    if (c->n_params < 4 || c->n_params % 4 != 0) return DW_ERR_CONFIG;
+    P = c->n_params;
+  } else {
+    if (c->batch < 1 || c->batch > (1 << 20)) return DW_ERR_CONFIG;
+    for (int l = 0; l <= L; ++l)
+      if (c->dims[l] < 1 || c->dims[l] > (1 << 20)) return DW_ERR_CONFIG;
+    for (int l = 0; l < L; ++l)
+      if (c->dims[l] % align != 0) return DW_ERR_CONFIG;
+    if (c->dims[L] > DW_MAX_CLASSES) return DW_ERR_CONFIG;
+    for (int l = 1; l <= L; ++l) {
+      lay->woff[l - 1] = P;
+      P += (int64_t)c->dims[l] * c->dims[l - 1];
+      lay->boff[l - 1] = P;
+      P += c->dims[l];
+    }
+    if (c->n_params != 0 && c->n_params != P) return DW_ERR_CONFIG;
+  }
+  // hyper-parameters
+  if (!(c->lr > 0.f) || !(c->beta1 >= 0.f && c->beta1 < 1.f) || !(c->beta2 >= 0.f && c->beta2 < 1.f) ||
+      !(c->eps > 0.f) || !(c->hpow >= 0.f && c->hpow <= 2.f))
+    return DW_ERR_HYPER;
+  if (!is_pow2(c->avg_block) || c->avg_block > 256) return DW_ERR_HYPER;
+  if (L == 0) {
+    if (P % c->avg_block != 0) return DW_ERR_HYPER;
+  } else {
+    for (int l = 0; l < L; ++l)
+      if (c->dims[l] % c->avg_block != 0) return DW_ERR_HYPER;
+  }
+  if (!(c->alpha > 0.f && c->alpha <= 1.f) || !(c->kappa < 0.f)) return DW_ERR_HYPER;
+  if (c->p < 1 || c->p > DW_MAX_P) return DW_ERR_HYPER;
+  double csum = 0.0;
+  for (int j = 0; j < c->p; ++j) {
+    if (!(c->c[j] >= 0.f)) return DW_ERR_HYPER;
+    csum += c->c[j];
+  }
+  if (std::fabs(csum - 1.0) > 1e-5) return DW_ERR_HYPER;
+
+  // workspace
+  const int k = c->k;
+  lay->P = P;
+  lay->Pp = round_up(P, 64);
+  lay->z_stride = round_up(2 * ((P + 63) / 64), 64);
+  lay->n_upd_blocks = (lay->Pp + kUpdChunk - 1) / kUpdChunk;
+  size_t pos = 0;
+  auto take = [&](size_t bytes) { size_t at = pos; pos += (size_t)round_up((int64_t)bytes, 256); return at; };
+  const size_t vec = (size_t)k * lay->Pp * sizeof(float);
+  lay->theta = take(vec); lay->m = take(vec); lay->v = take(vec);
+  lay->centre = take((size_t)lay->Pp * sizeof(float));
+  if (L > 0) { lay->g = take(vec); lay->hz = take(vec); }
+  if (c->dtype == DW_BF16) lay->wb16 = take((size_t)k * lay->Pp * 2);
+  lay->zbits = take((size_t)k * lay->z_stride * 4);
+  if (L > 0) {
+    const size_t es = c->dtype == DW_BF16 ? 2 : 4;
+    const int64_t B = c->batch;
+    int dmax = 4;
+    for (int l = 1; l < L; ++l) {
+      lay->act[l] = take((size_t)k * B * c->dims[l] * es);
+      lay->ract[l] = take((size_t)k * B * c->dims[l] * es);
+      if (c->dims[l] > dmax) dmax = c->dims[l];
+    }
+    for (int b = 0; b < 2; ++b) {
+      lay->delta[b] = take((size_t)k * B * dmax * es);
+      lay->rdelta[b] = take((size_t)k * B * dmax * es);
+    }
+    const size_t head = (size_t)k * B * DW_MAX_CLASSES * sizeof(float);
+    lay->sL = take(head); lay->rsL = take(head); lay->dL = take(head); lay->rdL = take(head);
+    if (c->dtype == DW_BF16) { lay->dL16 = take(head / 2); lay->rdL16 = take(head / 2); }
+  }
+  lay->partials = take((size_t)k * lay->n_upd_blocks * sizeof(double));
+  lay->u_ring = take((size_t)k * (DW_MAX_P + 1) * sizeof(double));
+  lay->score = take((size_t)k * 4 * sizeof(double));
+  lay->omh1 = take((size_t)k * sizeof(float));
+  lay->h2 = take((size_t)k * sizeof(float));
+  lay->loss = take((size_t)k * sizeof(float));
+  lay->total = pos;
+  return DW_OK;
+}
+
+uint64_t mix64_host(uint64_t x) {
+  x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+  x ^= x >> 27; x *= 0x94D049BB133111EBull;
+  x ^= x >> 31;
+  return x;
+}
+
+uint64_t mask_from(const uint8_t* h, int k) {
+  uint64_t mk = 0;
+  for (int i = 0; i < k; ++i)
+    if (!h || h[i]) mk |= 1ull << i;
+  return mk;
+}
+
+}  // namespace
+
+struct dw_handle {
+  dw_config cfg;
+  Layout lay;
+  char* ws;
+  int64_t t[DW_MAX_K];      // local steps per worker
+  int64_t calls;            // dw_worker_step / dw_update_only calls so far
+  int64_t rounds;           // communication rounds so far
+  bool norms_valid;         // the squared distances in `partials` match the current theta and centre
+
+  template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+};
+
+namespace {
+
+void fill_update_args(dw_handle* h, UpdateArgs& a, const float* g, const float* hz, int64_t g_stride,
+                      const uint32_t* zbits, int64_t z_stride, uint64_t active) {
+  const dw_config& c = h->cfg;
+  const Layout& L = h->lay;
+  a.theta = h->at<float>(L.theta); a.m = h->at<float>(L.m); a.v = h->at<float>(L.v);
+  a.g = g; a.hz = hz; a.centre = h->at<float>(L.centre);
+  a.zbits = zbits;
+  a.wb16 = c.dtype == DW_BF16 ? h->at<uint16_t>(L.wb16) : nullptr;
+  a.partials = h->at<double>(L.partials);
+  a.P = L.P; a.Pp = L.Pp; a.g_stride = g_stride; a.z_stride = z_stride;
+  a.k = c.k; a.avg_block = c.avg_block;
+  a.lr = c.lr; a.beta1 = c.beta1; a.beta2 = c.beta2; a.eps = c.eps; a.hpow = c.hpow;
+  a.active_mask = active;
+  a.bias.n = c.n_layers;
+  for (int l = 0; l < c.n_layers; ++l) {
+    a.bias.begin[l] = L.boff[l];
+    a.bias.end[l] = L.boff[l] + c.dims[l + 1];
+  }
+  for (int i = 0; i < DW_MAX_K; ++i) {
+    a.sc.inv_bc1[i] = 1.f; a.sc.inv_bc2[i] = 1.f;
+    if (i < c.k && ((active >> i) & 1ull)) {
+      const double t = (double)h->t[i];      // already incremented for this step
+      a.sc.inv_bc1[i] = (float)(1.0 / (1.0 - std::pow((double)c.beta1, t)));
+      a.sc.inv_bc2[i] = (float)(1.0 / (1.0 - std::pow((double)c.beta2, t)));
+    }
+  }
+}
+
+// draw z for the active workers at their current step counts (before the increment)
+int draw_z(dw_handle* h, uint64_t active, hipStream_t s) {
+  uint64_t keys[DW_MAX_K];
+  const uint64_t G = 0x9E3779B97F4A7C15ull;
+  for (int i = 0; i < h->cfg.k; ++i) {
+    const uint64_t k1 = mix64_host(h->cfg.seed + G * (uint64_t)(i + 1));
+    keys[i] = mix64_host(k1 + G * (uint64_t)(h->t[i] + 1));
+  }
+  DW_HIP(launch_rademacher(h->at<uint32_t>(h->lay.zbits), h->lay.z_stride, (h->lay.P + 63) / 64, keys,
+                           h->cfg.k, active, s));
+  return DW_OK;
+}
+
+int run_update(dw_handle* h, const float* g, const float* hz, int64_t g_stride, const uint32_t* d_zbits,
+               uint64_t active, hipStream_t s) {
+  const uint32_t* zb = d_zbits ? d_zbits : h->at<uint32_t>(h->lay.zbits);
+  const int64_t zs = d_zbits ? 2 * ((h->lay.P + 63) / 64) : h->lay.z_stride;
+  for (int i = 0; i < h->cfg.k; ++i)
+    if ((active >> i) & 1ull) h->t[i] += 1;
+  UpdateArgs a;
+  fill_update_args(h, a, g, hz, g_stride, zb, zs, active);
+  DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
+  h->norms_valid = true;
+  h->calls += 1;
+  return DW_OK;
+}
+
+}  // namespace
+
+
+extern "C" {
+
+const char* dw_strerror(int status) {
+  switch (status) {
+    case DW_OK: return "ok";
+    case DW_ERR_NULL: return "required pointer is NULL";
+    case DW_ERR_CONFIG: return "invalid configuration (dims, k, batch, dtype or alignment)";
+    case DW_ERR_HYPER: return "invalid hyper-parameter (lr, beta, eps, hpow, avg_block, alpha, kappa, p or c)";
+    case DW_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case DW_ERR_ARG: return "invalid call argument";
+    case DW_ERR_HIP: return "HIP runtime error";
+    case DW_ERR_MODE: return "call not valid for this handle";
+    default: return status > 0 ? "ok (positive result)" : "unknown status";
+  }
+}
+
+int dw_last_hip_error(void) { return g_last_hip; }
+
+int dw_param_count(const dw_config* cfg, int64_t* n_params) {
+  if (!cfg || !n_params) return DW_ERR_NULL;
+  Layout lay;
+  const int st = validate(cfg, &lay);
+  if (st != DW_OK) return st;
+  *n_params = lay.P;
+  return DW_OK;
+}
+
+size_t dw_workspace_bytes(const dw_config* cfg) {
+  Layout lay;
+  if (validate(cfg, &lay) != DW_OK) return 0;
+  return lay.total;
+}
+
+int dw_init(dw_handle** out, const dw_config* cfg, void* d_workspace, size_t workspace_bytes,
+            const float* theta0, int theta0_on_device, void* stream) {
+  if (!out || !cfg || !d_workspace || !theta0) return DW_ERR_NULL;
+  Layout lay;
+  const int st = validate(cfg, &lay);
+  if (st != DW_OK) return st;
+  if (workspace_bytes < lay.total || (reinterpret_cast<uintptr_t>(d_workspace) & 255u)) return DW_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  dw_handle* h = new (std::nothrow) dw_handle();
+  if (!h) return DW_ERR_ARG;
+  h->cfg = *cfg;
+  h->lay = lay;
+  h->ws = reinterpret_cast<char*>(d_workspace);
+  std::memset(h->t, 0, sizeof(h->t));
+  h->calls = 0; h->rounds = 0; h->norms_valid = false;
+  int rc = DW_OK;
+  do {
+    hipError_t e = launch_fill_zero(h->ws, lay.total, s);            // moments, padding, history: all zero
+    if (e != hipSuccess) { rc = hip_fail(e); break; }
+    e = hipMemcpyAsync(h->at<float>(lay.centre), theta0, (size_t)lay.P * sizeof(float),
+                       theta0_on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) { rc = hip_fail(e); break; }
+    e = launch_broadcast(h->at<float>(lay.theta), h->at<float>(lay.centre),
+                         cfg->dtype == DW_BF16 ? h->at<uint16_t>(lay.wb16) : nullptr, lay.Pp, cfg->k, s);
+    if (e != hipSuccess) { rc = hip_fail(e); break; }
+    if (!theta0_on_device) {
+      e = hipStreamSynchronize(s);                                    // the host buffer may go away
+      if (e != hipSuccess) { rc = hip_fail(e); break; }
+    }
+  } while (0);
+  if (rc != DW_OK) { delete h; return rc; }
+  *out = h;
+  return DW_OK;
+}
+
+int dw_destroy(dw_handle* h) {
+  if (!h) return DW_ERR_NULL;
+  delete h;
+  return DW_OK;
+}
+
+int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* d_zbits,
+                   const uint8_t* h_active, float* d_loss, void* stream) {
+  if (!h || !d_x || !d_y) return DW_ERR_NULL;
+  if (h->cfg.n_layers == 0) return DW_ERR_MODE;
+  if ((reinterpret_cast<uintptr_t>(d_x) & 15u) || (reinterpret_cast<uintptr_t>(d_zbits) & 7u)) return DW_ERR_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const uint64_t active = mask_from(h_active, h->cfg.k);
+  if (active == 0) { h->calls += 1; return DW_OK; }
+  if (!d_zbits) {
+    const int st = draw_z(h, active, s);
+    if (st != DW_OK) return st;
+  }
+  const uint32_t* zb = d_zbits ? d_zbits : h->at<uint32_t>(h->lay.zbits);
+  const int64_t zs = d_zbits ? 2 * ((h->lay.P + 63) / 64) : h->lay.z_stride;
+  float* loss = d_loss ? d_loss : h->at<float>(h->lay.loss);
+  const int st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, s);
+  if (st != DW_OK) return st;
+  return run_update(h, h->at<float>(h->lay.g), h->at<float>(h->lay.hz), h->lay.Pp, d_zbits, active, s);
+}
+
+int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint32_t* d_zbits,
+                   const uint8_t* h_active, void* stream) {
+  if (!h || !d_g || !d_hz) return DW_ERR_NULL;
+  if (h->lay.P % 4 != 0) return DW_ERR_MODE;          // worker i sits at offset i*P: needs 16-byte rows
+  if ((reinterpret_cast<uintptr_t>(d_g) & 15u) || (reinterpret_cast<uintptr_t>(d_hz) & 15u) ||
+      (reinterpret_cast<uintptr_t>(d_zbits) & 7u))
+    return DW_ERR_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const uint64_t active = mask_from(h_active, h->cfg.k);
+  if (active == 0) { h->calls += 1; return DW_OK; }
+  if (!d_zbits) {
+    const int st = draw_z(h, active, s);
+    if (st != DW_OK) return st;
+  }
+  return run_update(h, d_g, d_hz, h->lay.P, d_zbits, active, s);
+}
+
+int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2,
+                    const uint8_t* h_participate, int tau, void* stream) {
+  if (!h) return DW_ERR_NULL;
+  if (mode != DW_FIXED && mode != DW_MANUAL && mode != DW_DYNAMIC) return DW_ERR_ARG;
+  if (mode == DW_MANUAL && (!h_h1 || !h_h2)) return DW_ERR_NULL;
+  if (tau < 1) return DW_ERR_ARG;
+  if (h->calls % tau != 0) return 0;
+  hipStream_t s = (hipStream_t)stream;
+  const dw_config& c = h->cfg;
+  const Layout& L = h->lay;
+  if (!h->norms_valid) {
+    // distances only: no worker is marked active, so the update kernel just measures theta_i - centre
+    UpdateArgs a;
+    fill_update_args(h, a, nullptr, nullptr, 0, h->at<uint32_t>(L.zbits), L.z_stride, 0ull);
+    DW_HIP(launch_update(a, (int)L.n_upd_blocks, s));
+  }
+  WeightArgs w;
+  w.partials = h->at<double>(L.partials);
+  w.n_blocks = (int)L.n_upd_blocks;
+  w.u_ring = h->at<double>(L.u_ring);
+  w.score = h->at<double>(L.score);
+  w.omh1 = h->at<float>(L.omh1);
+  w.h2 = h->at<float>(L.h2);
+  w.k = c.k; w.p = c.p; w.mode = mode;
+  const int ring = c.p + 1;
+  w.slot = (int)(h->rounds % ring);
+  w.n_valid = (int)(h->rounds + 1 < ring ? h->rounds + 1 : ring);
+  w.alpha = c.alpha; w.kappa = c.kappa;
+  for (int j = 0; j < DW_MAX_P; ++j) w.c[j] = j < c.p ? c.c[j] : 0.f;
+  for (int i = 0; i < DW_MAX_K; ++i) {
+    w.man_h1[i] = (mode == DW_MANUAL && i < c.k) ? h_h1[i] : 0.f;
+    w.man_h2[i] = (mode == DW_MANUAL && i < c.k) ? h_h2[i] : 0.f;
+  }
+  DW_HIP(launch_weights(w, s));
+  PullArgs p;
+  p.theta = h->at<float>(L.theta); p.centre = h->at<float>(L.centre);
+  p.wb16 = c.dtype == DW_BF16 ? h->at<uint16_t>(L.wb16) : nullptr;
+  p.omh1 = w.omh1; p.h2 = w.h2;
+  p.Pp = L.Pp; p.k = c.k;
+  p.part_mask = mask_from(h_participate, c.k);
+  DW_HIP(launch_pull(p, s));
+  h->rounds += 1;
+  h->norms_valid = false;
+  return 1;
+}
+
+static int state_ptr(dw_handle* h, int what, int worker, int64_t offset, int64_t count, char** ptr, size_t* bytes) {
+  const Layout& L = h->lay;
+  const int k = h->cfg.k;
+  if (offset < 0 || count < 0) return DW_ERR_ARG;
+  if (what != DW_S_CENTRE && (worker < 0 || worker >= k)) return DW_ERR_ARG;
+  size_t base = 0, es = 4;
+  int64_t n = L.P, stride = L.Pp;
+  switch (what) {
+    case DW_S_THETA: base = L.theta; break;
+    case DW_S_M: base = L.m; break;
+    case DW_S_V: base = L.v; break;
+    case DW_S_G: if (h->cfg.n_layers == 0) return DW_ERR_MODE; base = L.g; break;
+    case DW_S_HZ: if (h->cfg.n_layers == 0) return DW_ERR_MODE; base = L.hz; break;
+    case DW_S_CENTRE: base = L.centre; worker = 0; break;
+    case DW_S_ZBITS: base = L.zbits; n = 2 * ((L.P + 63) / 64); stride = L.z_stride; break;
+    case DW_S_SCORE: base = L.score; es = 8; n = 4; stride = 4; break;
+    default: return DW_ERR_ARG;
+  }
+  if (offset + count > n) return DW_ERR_ARG;
+  *ptr = h->ws + base + ((size_t)worker * stride + offset) * es;
+  *bytes = (size_t)count * es;
+  return DW_OK;
+}
+
+int dw_get_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, void* h_buf, void* stream) {
+  if (!h || !h_buf) return DW_ERR_NULL;
+  hipStream_t s = (hipStream_t)stream;
+  if (what == DW_S_STEPS) {
+    if (worker < 0 || worker >= h->cfg.k || offset != 0 || count != 1) return DW_ERR_ARG;
+    *reinterpret_cast<int64_t*>(h_buf) = h->t[worker];
+    return DW_OK;
+  }
+  if (what == DW_S_U_HIST) {
+    if (worker < 0 || worker >= h->cfg.k || offset != 0 || count != 2 + DW_MAX_P) return DW_ERR_ARG;
+    double ring[DW_MAX_P + 1];
+    DW_HIP(hipMemcpyAsync(ring, h->at<double>(h->lay.u_ring) + (size_t)worker * (DW_MAX_P + 1), sizeof(ring),
+                          hipMemcpyDeviceToHost, s));
+    DW_HIP(hipStreamSynchronize(s));
+    double* out = reinterpret_cast<double*>(h_buf);
+    const int R = h->cfg.p + 1;
+    const int n = (int)(h->rounds < R ? h->rounds : R);
+    out[0] = (double)n;
+    for (int j = 0; j < DW_MAX_P + 1; ++j) out[1 + j] = 0.0;
+    for (int j = 0; j < n; ++j) {                      // oldest first
+      const int64_t round = h->rounds - n + j;
+      out[1 + j] = ring[round % R];
+    }
+    return DW_OK;
+  }
+  char* p; size_t bytes;
+  const int st = state_ptr(h, what, worker, offset, count, &p, &bytes);
+  if (st != DW_OK) return st;
+  if (bytes == 0) return DW_OK;
+  DW_HIP(hipMemcpyAsync(h_buf, p, bytes, hipMemcpyDeviceToHost, s));
+  DW_HIP(hipStreamSynchronize(s));
+  return DW_OK;
+}
+
+int dw_set_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, const void* h_buf, void* stream) {
+  if (!h || !h_buf) return DW_ERR_NULL;
+  hipStream_t s = (hipStream_t)stream;
+  if (what == DW_S_STEPS) {
+    if (worker < 0 || worker >= h->cfg.k || offset != 0 || count != 1) return DW_ERR_ARG;
+    const int64_t t = *reinterpret_cast<const int64_t*>(h_buf);
+    if (t < 0) return DW_ERR_ARG;
+    h->t[worker] = t;
+    return DW_OK;
+  }
+  if (what != DW_S_THETA && what != DW_S_M && what != DW_S_V && what != DW_S_CENTRE) return DW_ERR_ARG;
+  char* p; size_t bytes;
+  const int st = state_ptr(h, what, worker, offset, count, &p, &bytes);
+  if (st != DW_OK) return st;
+  if (bytes == 0) return DW_OK;
+  DW_HIP(hipMemcpyAsync(p, h_buf, bytes, hipMemcpyHostToDevice, s));
+  if (what == DW_S_THETA && h->cfg.dtype == DW_BF16) {
+    float* th = h->at<float>(h->lay.theta) + (size_t)worker * h->lay.Pp;
+    uint16_t* wb = h->at<uint16_t>(h->lay.wb16) + (size_t)worker * h->lay.Pp;
+    DW_HIP(launch_refresh_bf16(th, wb, h->lay.Pp, s));
+  }
+  DW_HIP(hipStreamSynchronize(s));
+  if (what == DW_S_THETA || what == DW_S_CENTRE) h->norms_valid = false;
+  return DW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,386 @@
+// Streaming kernels of the optimizer and of the communication round (gfx950, wave64).
+//
+//   update_kernel   Section IV-B: D = z*Hz (Hutchinson, one sample), block mean of D along fan-in,
+//                   Adam-like moments with D in the second moment, bias correction, parameter update
+//                   (the preconditioned step of eq.(4)); also the squared distance of the new parameters
+//                   to the centre, which the next communication round turns into u (Section V-B).
+//   weight_kernel   Section V-B: u = log||theta_i - centre||, history, raw score a (eq.(10)-(11)),
+//                   piecewise-linear weights h1(a), h2(a).
+//   pull_kernel     Section V-B eq.(12)-(13): elastic pull of every participating worker and of the centre.
+//
+// All three are bound by HBM bandwidth.  One thread owns the same four consecutive parameters of every
+// worker: the centre values stay in registers while the block walks over the k replicas, so the centre is
+// read once per launch, and the reduction over workers into the centre needs no atomics.
+#include "dw_internal.h"
+
+namespace dw {
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float sign_from_bit(uint32_t bits, int b) {
+  // bit set -> +1, clear -> -1
+  return ((bits >> b) & 1u) ? 1.0f : -1.0f;
+}
+
+__device__ __forceinline__ bool in_bias(const BiasRanges& br, int64_t j) {
+  bool r = false;
+#pragma unroll
+  for (int l = 0; l < DW_MAX_LAYERS; ++l)
+    if (l < br.n) r = r || (j >= br.begin[l] && j < br.end[l]);
+  return r;
+}
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+  return x;
+}
+
+__device__ __forceinline__ float denom_pow(float vhat, float hpow) {
+  // (sqrt(v_hat))^hpow
+  if (hpow == 1.0f) return sqrtf(vhat);
+  if (hpow == 0.0f) return 1.0f;
+  if (hpow == 2.0f) return vhat;
+  return powf(vhat, 0.5f * hpow);
+}
+
+template <bool HAS_B16>
+__global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int64_t nq = (a.P + 3) >> 2;      // caller-supplied g / Hz rows end at P
+  const int64_t qbase = (int64_t)blockIdx.x * (kUpdThreads * kUpdQuads) + tid;
+  __shared__ double wave_part[DW_MAX_K][kUpdThreads / 64];
+
+  float4 cen[kUpdQuads];
+  bool valid[kUpdQuads], avg[kUpdQuads];
+  uint32_t zshift[kUpdQuads];
+#pragma unroll
+  for (int u = 0; u < kUpdQuads; ++u) {
+    const int64_t q = qbase + (int64_t)u * kUpdThreads;
+    valid[u] = q < nq;
+    cen[u] = valid[u] ? reinterpret_cast<const float4*>(a.centre)[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    avg[u] = a.avg_block > 1 && !in_bias(a.bias, q << 2);
+    zshift[u] = (uint32_t)((q << 2) & 31);
+  }
+  const float inv_b = 1.0f / (float)a.avg_block;
+  const int group_lanes = a.avg_block >> 2;           // lanes that share one averaging block (when b > 4)
+
+  for (int i = 0; i < a.k; ++i) {
+    const bool active = (a.active_mask >> i) & 1ull;
+    float nsum = 0.f;
+    float4* th4 = reinterpret_cast<float4*>(a.theta + (int64_t)i * a.Pp);
+    if (active) {
+      float4* m4 = reinterpret_cast<float4*>(a.m + (int64_t)i * a.Pp);
+      float4* v4 = reinterpret_cast<float4*>(a.v + (int64_t)i * a.Pp);
+      const float4* g4 = reinterpret_cast<const float4*>(a.g + (int64_t)i * a.g_stride);
+      const float4* h4 = reinterpret_cast<const float4*>(a.hz + (int64_t)i * a.g_stride);
+      const uint32_t* zb = a.zbits + (int64_t)i * a.z_stride;
+      const float ib1 = a.sc.inv_bc1[i], ib2 = a.sc.inv_bc2[i];
+      float4 G[kUpdQuads], H[kUpdQuads], T[kUpdQuads], M[kUpdQuads], V[kUpdQuads];
+      uint32_t Z[kUpdQuads];
+#pragma unroll
+      for (int u = 0; u < kUpdQuads; ++u) {
+        const int64_t q = qbase + (int64_t)u * kUpdThreads;
+        if (valid[u]) {
+          G[u] = g4[q]; H[u] = h4[q]; T[u] = th4[q]; M[u] = m4[q]; V[u] = v4[q];
+          Z[u] = zb[q >> 3] >> zshift[u];
+        } else {
+          G[u] = H[u] = T[u] = M[u] = V[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+          Z[u] = 0;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kUpdQuads; ++u) {
+        const int64_t q = qbase + (int64_t)u * kUpdThreads;
+        float g[4] = {G[u].x, G[u].y, G[u].z, G[u].w};
+        float hz[4] = {H[u].x, H[u].y, H[u].z, H[u].w};
+        float th[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
+        float mm[4] = {M[u].x, M[u].y, M[u].z, M[u].w};
+        float vv[4] = {V[u].x, V[u].y, V[u].z, V[u].w};
+        const float cc[4] = {cen[u].x, cen[u].y, cen[u].z, cen[u].w};
+        float D[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) D[e] = sign_from_bit(Z[u], e) * hz[e];       // Hutchinson: z * Hz
+        // spatial average over avg_block consecutive parameters (all lanes take part in the shuffles)
+        float Ds[4] = {D[0], D[1], D[2], D[3]};
+        if (a.avg_block == 2) {
+          const float p0 = 0.5f * (D[0] + D[1]), p1 = 0.5f * (D[2] + D[3]);
+          if (avg[u]) { Ds[0] = Ds[1] = p0; Ds[2] = Ds[3] = p1; }
+        } else if (a.avg_block >= 4) {
+          float s = (D[0] + D[1]) + (D[2] + D[3]);
+          for (int off = 1; off < group_lanes; off <<= 1) s += __shfl_xor(s, off);
+          s *= inv_b;
+          if (avg[u]) { Ds[0] = Ds[1] = Ds[2] = Ds[3] = s; }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          mm[e] = a.beta1 * mm[e] + (1.0f - a.beta1) * g[e];
+          vv[e] = a.beta2 * vv[e] + (1.0f - a.beta2) * (Ds[e] * Ds[e]);
+          const float mhat = mm[e] * ib1;
+          const float vhat = vv[e] * ib2;
+          th[e] = th[e] - a.lr * (mhat / (denom_pow(vhat, a.hpow) + a.eps));
+          const float d = th[e] - cc[e];
+          nsum += d * d;
+        }
+        if (valid[u]) {
+          th4[q] = make_float4(th[0], th[1], th[2], th[3]);
+          m4[q] = make_float4(mm[0], mm[1], mm[2], mm[3]);
+          v4[q] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+          if (HAS_B16) {
+            ushort4 w;
+            w.x = f32_to_bf16_rne(th[0]); w.y = f32_to_bf16_rne(th[1]);
+            w.z = f32_to_bf16_rne(th[2]); w.w = f32_to_bf16_rne(th[3]);
+            reinterpret_cast<ushort4*>(a.wb16 + (int64_t)i * a.Pp)[q] = w;
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kUpdQuads; ++u) {
+        const int64_t q = qbase + (int64_t)u * kUpdThreads;
+        if (valid[u]) {
+          const float4 t = th4[q];
+          const float d0 = t.x - cen[u].x, d1 = t.y - cen[u].y, d2 = t.z - cen[u].z, d3 = t.w - cen[u].w;
+          nsum += (d0 * d0 + d1 * d1) + (d2 * d2 + d3 * d3);
+        }
+      }
+    }
+    const double ws = wave_sum((double)nsum);
+    if (lane == 0) wave_part[i][wave] = ws;
+  }
+  __syncthreads();
+  if (tid < a.k) {
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < kUpdThreads / 64; ++w) s += wave_part[tid][w];
+    a.partials[(int64_t)tid * gridDim.x + blockIdx.x] = s;
+  }
+}
+
+hipError_t launch_update(const UpdateArgs& a, int n_blocks, hipStream_t s) {
+  if (a.wb16)
+    hipLaunchKernelGGL(update_kernel<true>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(update_kernel<false>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Dynamic-weight scalars: one block per worker.
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void weight_kernel(WeightArgs a) {
+  const int i = blockIdx.x;
+  const int tid = threadIdx.x;
+  __shared__ double red[256 / 64];
+  double s = 0.0;
+  for (int b = tid; b < a.n_blocks; b += 256) s += a.partials[(int64_t)i * a.n_blocks + b];
+  s = wave_sum(s);
+  if ((tid & 63) == 0) red[tid >> 6] = s;
+  __syncthreads();
+  if (tid != 0) return;
+  double S = 0.0;
+  for (int w = 0; w < 256 / 64; ++w) S += red[w];
+  // u = log ||theta_i - centre||_2 (natural log; squared norm floored so identical vectors stay finite)
+  const double u = 0.5 * log(S > 1e-30 ? S : 1e-30);
+  const int ring = a.p + 1;
+  double* R = a.u_ring + (int64_t)i * (DW_MAX_P + 1);
+  R[a.slot] = u;
+  // raw score: c_0 weighs the newest difference u_t - u_{t-1}, c_1 the one before, ...; differences the
+  // history cannot supply yet contribute nothing
+  double sc = 0.0;
+  for (int j = 0; j < a.p; ++j) {
+    if (j + 1 >= a.n_valid) break;
+    const int hi = (a.slot - j + 2 * ring) % ring;
+    const int lo = (a.slot - j - 1 + 2 * ring) % ring;
+    sc += (double)a.c[j] * (R[hi] - R[lo]);
+  }
+  double h1, h2;
+  const double alpha = a.alpha, kappa = a.kappa;
+  if (a.mode == DW_FIXED) {
+    h1 = alpha; h2 = alpha;
+  } else if (a.mode == DW_MANUAL) {
+    h1 = a.man_h1[i]; h2 = a.man_h2[i];
+  } else if (sc < kappa) {
+    h1 = 1.0; h2 = 0.0;
+  } else if (sc <= 0.0) {
+    h1 = 1.0 + (1.0 - alpha) / kappa * (sc - kappa);
+    h2 = -alpha / kappa * sc + alpha;
+  } else {
+    h1 = alpha; h2 = alpha;
+  }
+  double* out = a.score + (int64_t)i * 4;
+  out[0] = u; out[1] = sc; out[2] = h1; out[3] = h2;
+  a.omh1[i] = (float)(1.0 - h1);
+  a.h2[i] = (float)h2;
+}
+
+hipError_t launch_weights(const WeightArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(weight_kernel, dim3(a.k), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Elastic pull.  theta_i <- centre + (1-h1_i)(theta_i - centre)  (the same value as eq.(12), written so
+// that h1 = 1 returns the centre exactly);  centre <- centre + sum_i h2_i (theta_i - centre)  (eq.(13)).
+// ---------------------------------------------------------------------------------------------------
+template <bool HAS_B16>
+__global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a) {
+  const int64_t nq = a.Pp >> 2;
+  const int64_t qbase = (int64_t)blockIdx.x * (kUpdThreads * kUpdQuads) + threadIdx.x;
+  float4 cen[kUpdQuads], acc[kUpdQuads];
+  bool valid[kUpdQuads];
+#pragma unroll
+  for (int u = 0; u < kUpdQuads; ++u) {
+    const int64_t q = qbase + (int64_t)u * kUpdThreads;
+    valid[u] = q < nq;
+    cen[u] = valid[u] ? reinterpret_cast<const float4*>(a.centre)[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  for (int i = 0; i < a.k; ++i) {
+    if (!((a.part_mask >> i) & 1ull)) continue;
+    const float o = a.omh1[i], w = a.h2[i];
+    float4* th4 = reinterpret_cast<float4*>(a.theta + (int64_t)i * a.Pp);
+    float4 T[kUpdQuads];
+#pragma unroll
+    for (int u = 0; u < kUpdQuads; ++u) {
+      const int64_t q = qbase + (int64_t)u * kUpdThreads;
+      T[u] = valid[u] ? th4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+#pragma unroll
+    for (int u = 0; u < kUpdQuads; ++u) {
+      const int64_t q = qbase + (int64_t)u * kUpdThreads;
+      const float d0 = T[u].x - cen[u].x, d1 = T[u].y - cen[u].y, d2 = T[u].z - cen[u].z, d3 = T[u].w - cen[u].w;
+      float4 r;
+      r.x = fmaf(o, d0, cen[u].x); r.y = fmaf(o, d1, cen[u].y);
+      r.z = fmaf(o, d2, cen[u].z); r.w = fmaf(o, d3, cen[u].w);
+      acc[u].x = fmaf(w, d0, acc[u].x); acc[u].y = fmaf(w, d1, acc[u].y);
+      acc[u].z = fmaf(w, d2, acc[u].z); acc[u].w = fmaf(w, d3, acc[u].w);
+      if (valid[u]) {
+        th4[q] = r;
+        if (HAS_B16) {
+          ushort4 b;
+          b.x = f32_to_bf16_rne(r.x); b.y = f32_to_bf16_rne(r.y);
+          b.z = f32_to_bf16_rne(r.z); b.w = f32_to_bf16_rne(r.w);
+          reinterpret_cast<ushort4*>(a.wb16 + (int64_t)i * a.Pp)[q] = b;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kUpdQuads; ++u) {
+    const int64_t q = qbase + (int64_t)u * kUpdThreads;
+    if (valid[u]) {
+      float4 c = cen[u];
+      c.x += acc[u].x; c.y += acc[u].y; c.z += acc[u].z; c.w += acc[u].w;
+      reinterpret_cast<float4*>(a.centre)[q] = c;
+    }
+  }
+}
+
+hipError_t launch_pull(const PullArgs& a, hipStream_t s) {
+  const int64_t nq = a.Pp >> 2;
+  const int n_blocks = (int)((nq + kUpdThreads * kUpdQuads - 1) / (kUpdThreads * kUpdQuads));
+  if (a.wb16)
+    hipLaunchKernelGGL(pull_kernel<true>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
+  else
+    hipLaunchKernelGGL(pull_kernel<false>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Rademacher bits: a stateless counter-based stream on the SplitMix64 output function (Steele, Lea &
+// Flood 2014).  64-bit word w of a worker is mix(key + GAMMA*(w+1)); element j of z is +1 when bit
+// (j mod 64) of word j/64 is set.  The paper only asks for a Rademacher vector (Section IV-B).
+// ---------------------------------------------------------------------------------------------------
+struct RadKeys { uint64_t key[DW_MAX_K]; };
+
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+  x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+  x ^= x >> 27; x *= 0x94D049BB133111EBull;
+  x ^= x >> 31;
+  return x;
+}
+
+__global__ __launch_bounds__(256) void rademacher_kernel(uint32_t* zbits, int64_t z_stride, int64_t n_words64,
+                                                         RadKeys keys, uint64_t active_mask) {
+  const int i = blockIdx.y;
+  if (!((active_mask >> i) & 1ull)) return;
+  const int64_t w = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (w >= n_words64) return;
+  const uint64_t x = mix64(keys.key[i] + 0x9E3779B97F4A7C15ull * (uint64_t)(w + 1));
+  uint2 o; o.x = (uint32_t)x; o.y = (uint32_t)(x >> 32);
+  reinterpret_cast<uint2*>(zbits + (int64_t)i * z_stride)[w] = o;
+}
+
+hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words64, const uint64_t* keys_host,
+                             int k, uint64_t active_mask, hipStream_t s) {
+  RadKeys keys;
+  for (int i = 0; i < DW_MAX_K; ++i) keys.key[i] = i < k ? keys_host[i] : 0;
+  dim3 grid((unsigned)((n_words64 + 255) / 256), (unsigned)k);
+  hipLaunchKernelGGL(rademacher_kernel, grid, dim3(256), 0, s, zbits, z_stride, n_words64, keys, active_mask);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Small utilities: replicate the centre into all workers, zero fill, refresh the bf16 weight copy.
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void broadcast_kernel(float* theta, const float* centre, uint16_t* wb16,
+                                                        int64_t Pp, int k) {
+  const int64_t nq = Pp >> 2;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256) {
+    const float4 c = reinterpret_cast<const float4*>(centre)[q];
+    ushort4 b;
+    b.x = f32_to_bf16_rne(c.x); b.y = f32_to_bf16_rne(c.y); b.z = f32_to_bf16_rne(c.z); b.w = f32_to_bf16_rne(c.w);
+    for (int i = 0; i < k; ++i) {
+      reinterpret_cast<float4*>(theta + (int64_t)i * Pp)[q] = c;
+      if (wb16) reinterpret_cast<ushort4*>(wb16 + (int64_t)i * Pp)[q] = b;
+    }
+  }
+}
+
+hipError_t launch_broadcast(float* theta, const float* centre, uint16_t* wb16, int64_t Pp, int k, hipStream_t s) {
+  const int64_t nq = Pp >> 2;
+  int64_t nb = (nq + 255) / 256;
+  if (nb > 65536) nb = 65536;
+  hipLaunchKernelGGL(broadcast_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta, centre, wb16, Pp, k);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* p, int64_t n16) {
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < n16; q += (int64_t)gridDim.x * 256)
+    p[q] = make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {   // bytes must be a multiple of 16
+  const int64_t n16 = (int64_t)(bytes / 16);
+  if (n16 == 0) return hipSuccess;
+  int64_t nb = (n16 + 255) / 256;
+  if (nb > 65536) nb = 65536;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)nb), dim3(256), 0, s, reinterpret_cast<uint4*>(p), n16);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void refresh_bf16_kernel(const float* theta, uint16_t* wb16, int64_t nq) {
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256) {
+    const float4 c = reinterpret_cast<const float4*>(theta)[q];
+    ushort4 b;
+    b.x = f32_to_bf16_rne(c.x); b.y = f32_to_bf16_rne(c.y); b.z = f32_to_bf16_rne(c.z); b.w = f32_to_bf16_rne(c.w);
+    reinterpret_cast<ushort4*>(wb16)[q] = b;
+  }
+}
+
+hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hipStream_t s) {
+  const int64_t nq = n >> 2;
+  int64_t nb = (nq + 255) / 256;
+  if (nb > 65536) nb = 65536;
+  if (nb == 0) return hipSuccess;
+  hipLaunchKernelGGL(refresh_bf16_kernel, dim3((unsigned)nb), dim3(256), 0, s, theta, wb16, nq);
+  return hipGetLastError();
+}
+
+}  // namespace dw

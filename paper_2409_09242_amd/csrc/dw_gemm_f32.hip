@@ -1,0 +1,277 @@
+// fp32 "dual-number" GEMM for gfx950: C = X*Y and RC = RX*Y + X*RY in one pass over the tiles.
+//
+// Forward and backward propagation of the MLP (Section II eq.(2)) and the propagation of their
+// directional derivatives along z, which yields the Hessian-vector product Hz of the Hutchinson estimate
+// (Section IV-B), all have this product-rule shape:
+//   forward      s  = a W^T,            Rs  = Ra W^T + a V^T            (V = z reshaped like W)
+//   data grad    d' = d W,              Rd' = Rd W + d V
+//   weight grad  gW = d^T a,            HzW = Rd^T a + d^T Ra
+// so one kernel template serves the three, sharing every tile load between the plain product and its
+// R-companion.  The +-1 operand V is never stored as a matrix: its tile is expanded from the sign bits of
+// z while the W tile is staged.
+//
+// Tiling: 256 threads = 4 waves; block tile BM x BN x 16; tiles are staged k-major in LDS so that each
+// lane's MFMA operand (v_mfma_f32_32x32x2_f32: lane l supplies A[l%32][l/32] and B[l/32][l%32]) is one
+// conflict-free 32-bit LDS read; global loads are 16-byte and prefetched into registers one tile ahead.
+#include "dw_internal.h"
+
+namespace dw {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 16;
+constexpr int PAD = 4;
+constexpr int NT = 256;
+
+enum RyMode { RY_NONE = 0, RY_MEM = 1, RY_BITS = 2 };
+
+template <int ROWS>                      // ROWS = extent of the non-contraction index in the tile (BM or BN)
+struct TileLoader {
+  static constexpr int CNT = ROWS * BK / 4;            // float4 per tile
+  static constexpr int NL = (CNT + NT - 1) / NT;       // float4 per thread
+
+  // position of float4 number idx inside the tile: (r = non-contraction index, kk = contraction index)
+  template <bool KC>
+  __device__ static __forceinline__ void pos(int idx, int& r, int& kk) {
+    if (KC) { r = idx / (BK / 4); kk = (idx % (BK / 4)) * 4; }      // 4 consecutive kk at one r
+    else    { kk = idx / (ROWS / 4); r = (idx % (ROWS / 4)) * 4; }  // 4 consecutive r at one kk
+  }
+
+  template <bool KC>
+  __device__ static __forceinline__ void load(const float* __restrict__ src, int ld, int r0, int k0, int R, int K,
+                                              float4 (&reg)[NL]) {
+#pragma unroll
+    for (int it = 0; it < NL; ++it) {
+      const int idx = it * NT + (int)threadIdx.x;
+      int r, kk; pos<KC>(idx, r, kk);
+      const bool ok = idx < CNT && (r0 + r) < R && (k0 + kk) < K;
+      const int64_t off = KC ? (int64_t)(r0 + r) * ld + (k0 + kk) : (int64_t)(k0 + kk) * ld + (r0 + r);
+      reg[it] = ok ? *reinterpret_cast<const float4*>(src + off) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+
+  // sign bits of the four elements that load<KC> would read (0 when out of range)
+  template <bool KC>
+  __device__ static __forceinline__ void load_bits(const uint32_t* __restrict__ zb, int64_t z_off, int ld, int r0,
+                                                   int k0, int R, int K, uint32_t (&reg)[NL]) {
+#pragma unroll
+    for (int it = 0; it < NL; ++it) {
+      const int idx = it * NT + (int)threadIdx.x;
+      int r, kk; pos<KC>(idx, r, kk);
+      const bool ok = idx < CNT && (r0 + r) < R && (k0 + kk) < K;
+      const int64_t off = z_off + (KC ? (int64_t)(r0 + r) * ld + (k0 + kk) : (int64_t)(k0 + kk) * ld + (r0 + r));
+      reg[it] = ok ? (zb[off >> 5] >> (off & 31)) & 0xFu : 0u;
+    }
+  }
+
+  template <bool KC>
+  __device__ static __forceinline__ void store(float (*lds)[ROWS + PAD], const float4 (&reg)[NL]) {
+#pragma unroll
+    for (int it = 0; it < NL; ++it) {
+      const int idx = it * NT + (int)threadIdx.x;
+      if (idx < CNT) {
+        int r, kk; pos<KC>(idx, r, kk);
+        if (KC) {
+          lds[kk + 0][r] = reg[it].x; lds[kk + 1][r] = reg[it].y;
+          lds[kk + 2][r] = reg[it].z; lds[kk + 3][r] = reg[it].w;
+        } else {
+          *reinterpret_cast<float4*>(&lds[kk][r]) = reg[it];
+        }
+      }
+    }
+  }
+
+  template <bool KC>
+  __device__ static __forceinline__ void store_bits(float (*lds)[ROWS + PAD], const uint32_t (&reg)[NL]) {
+#pragma unroll
+    for (int it = 0; it < NL; ++it) {
+      const int idx = it * NT + (int)threadIdx.x;
+      if (idx < CNT) {
+        int r, kk; pos<KC>(idx, r, kk);
+        float4 v;
+        v.x = (reg[it] & 1u) ? 1.f : -1.f; v.y = (reg[it] & 2u) ? 1.f : -1.f;
+        v.z = (reg[it] & 4u) ? 1.f : -1.f; v.w = (reg[it] & 8u) ? 1.f : -1.f;
+        if (KC) {
+          lds[kk + 0][r] = v.x; lds[kk + 1][r] = v.y; lds[kk + 2][r] = v.z; lds[kk + 3][r] = v.w;
+        } else {
+          *reinterpret_cast<float4*>(&lds[kk][r]) = v;
+        }
+      }
+    }
+  }
+};
+
+template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI>
+__global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
+  static_assert(WM * WN == 4, "four waves per block");
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
+  const int worker = blockIdx.y;
+  if (!((a.active_mask >> worker) & 1ull)) return;
+
+  const int tiles_m = (a.M + BM - 1) / BM;
+  const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm0 = (wave % WM) * (BM / WM), wn0 = (wave / WM) * (BN / WN);
+  const int l32 = lane & 31, lhalf = lane >> 5;
+
+  __shared__ __attribute__((aligned(16))) float Xs[BK][BM + PAD];
+  __shared__ __attribute__((aligned(16))) float RXs[HAS_RX ? BK : 1][BM + PAD];
+  __shared__ __attribute__((aligned(16))) float Ys[BK][BN + PAD];
+  __shared__ __attribute__((aligned(16))) float RYs[RYM != RY_NONE ? BK : 1][BN + PAD];
+
+  const float* X = reinterpret_cast<const float*>(a.X) + (int64_t)worker * a.x_wstride;
+  const float* RX = HAS_RX ? reinterpret_cast<const float*>(a.RX) + (int64_t)worker * a.x_wstride : nullptr;
+  const float* Y = reinterpret_cast<const float*>(a.Y) + (int64_t)worker * a.y_wstride;
+  const float* RY = RYM == RY_MEM ? reinterpret_cast<const float*>(a.RY) + (int64_t)worker * a.y_wstride : nullptr;
+  const uint32_t* zb = a.zbits + (int64_t)worker * a.z_stride;
+
+  using LX = TileLoader<BM>;
+  using LY = TileLoader<BN>;
+  float4 xr[LX::NL], rxr[LX::NL], yr[LY::NL], ryr[LY::NL];
+  uint32_t zr[LY::NL];
+
+  floatx16 acc[TM][TN], racc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; racc[i][j][r] = 0.f; }
+
+  float gb_acc = 0.f, hzb_acc = 0.f;     // EPI_WGRAD: column sums of X and RX (bias gradients)
+
+  const int nkt = (a.K + BK - 1) / BK;
+  auto fetch = [&](int kt) {
+    const int k0 = kt * BK;
+    LX::template load<X_KC>(X, a.ldx, row0, k0, a.M, a.K, xr);
+    if (HAS_RX) LX::template load<X_KC>(RX, a.ldx, row0, k0, a.M, a.K, rxr);
+    LY::template load<Y_KC>(Y, a.ldy, col0, k0, a.N, a.K, yr);
+    if (RYM == RY_MEM) LY::template load<Y_KC>(RY, a.ldy, col0, k0, a.N, a.K, ryr);
+    if (RYM == RY_BITS) LY::template load_bits<Y_KC>(zb, a.z_off, a.ldy, col0, k0, a.N, a.K, zr);
+  };
+
+  fetch(0);
+  for (int kt = 0; kt < nkt; ++kt) {
+    LX::template store<X_KC>(Xs, xr);
+    if (HAS_RX) LX::template store<X_KC>(RXs, rxr);
+    LY::template store<Y_KC>(Ys, yr);
+    if (RYM == RY_MEM) LY::template store<Y_KC>(RYs, ryr);
+    if (RYM == RY_BITS) LY::template store_bits<Y_KC>(RYs, zr);
+    __syncthreads();
+    if (kt + 1 < nkt) fetch(kt + 1);
+
+    if (EPI == EPI_WGRAD && tn == 0 && (int)threadIdx.x < BM) {
+#pragma unroll
+      for (int kk = 0; kk < BK; ++kk) {
+        gb_acc += Xs[kk][threadIdx.x];
+        if (HAS_RX) hzb_acc += RXs[kk][threadIdx.x];
+      }
+    }
+
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      const int ks = kk + lhalf;
+      float xa[TM], rxa[TM], yb[TN], ryb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        xa[i] = Xs[ks][wm0 + i * 32 + l32];
+        if (HAS_RX) rxa[i] = RXs[ks][wm0 + i * 32 + l32];
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        yb[j] = Ys[ks][wn0 + j * 32 + l32];
+        if (RYM != RY_NONE) ryb[j] = RYs[ks][wn0 + j * 32 + l32];
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[i], yb[j], acc[i][j], 0, 0, 0);
+          if (HAS_RX) racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(rxa[i], yb[j], racc[i][j], 0, 0, 0);
+          if (RYM != RY_NONE) racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[i], ryb[j], racc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+  }
+
+  // epilogue: lane holds column n = l32 of each 32x32 tile, rows (r/4)*8 + lhalf*4 + r%4
+  float* C = reinterpret_cast<float*>(a.C) + (int64_t)worker * a.c_wstride;
+  float* RC = reinterpret_cast<float*>(a.RC) + (int64_t)worker * a.c_wstride;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = col0 + wn0 + j * 32 + l32;
+    const bool n_ok = n < a.N;
+    float bias = 0.f, cz = 0.f;
+    if ((EPI == EPI_RELU || EPI == EPI_LINEAR) && n_ok) {
+      bias = a.bias[(int64_t)worker * a.bias_wstride + n];
+      const int64_t bi = a.zb_off + n;
+      cz = ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = row0 + wm0 + i * 32 + (r >> 2) * 8 + lhalf * 4 + (r & 3);
+        if (!n_ok || m >= a.M) continue;
+        float c = acc[i][j][r], rc = racc[i][j][r];
+        const int64_t o = (int64_t)m * a.ldc + n;
+        if (EPI == EPI_RELU) {
+          c += bias; rc += cz;
+          const bool on = c > 0.f;
+          C[o] = on ? c : 0.f;
+          RC[o] = on ? rc : 0.f;
+        } else if (EPI == EPI_LINEAR) {
+          C[o] = c + bias;
+          RC[o] = rc + cz;
+        } else if (EPI == EPI_MASK) {
+          const float* msk = reinterpret_cast<const float*>(a.mask_src) + (int64_t)worker * a.mask_wstride;
+          const bool on = msk[(int64_t)m * a.ld_mask + n] > 0.f;
+          C[o] = on ? c : 0.f;
+          RC[o] = on ? rc : 0.f;
+        } else {
+          C[o] = c;
+          RC[o] = rc;
+        }
+      }
+    }
+  }
+  if (EPI == EPI_WGRAD && tn == 0 && (int)threadIdx.x < BM) {
+    const int m = row0 + threadIdx.x;
+    if (m < a.M) {
+      a.gb[(int64_t)worker * a.c_wstride + m] = gb_acc;
+      a.hzb[(int64_t)worker * a.c_wstride + m] = hzb_acc;
+    }
+  }
+}
+
+template <int BM, int BN, int WM, int WN>
+static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
+  const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+  const dim3 grid((unsigned)tiles, (unsigned)a.k), block(NT);
+#define DW_LAUNCH(XKC, YKC, RX, RYM, EPI) \
+  hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>), grid, block, 0, s, a)
+  const bool rx = a.RX != nullptr;
+  if (a.epi == EPI_RELU) {                     // forward, hidden layer
+    if (rx) DW_LAUNCH(true, true, true, RY_BITS, EPI_RELU); else DW_LAUNCH(true, true, false, RY_BITS, EPI_RELU);
+  } else if (a.epi == EPI_LINEAR) {            // forward, output layer
+    if (rx) DW_LAUNCH(true, true, true, RY_BITS, EPI_LINEAR); else DW_LAUNCH(true, true, false, RY_BITS, EPI_LINEAR);
+  } else if (a.epi == EPI_MASK) {              // data gradient
+    DW_LAUNCH(true, false, true, RY_BITS, EPI_MASK);
+  } else {                                     // weight gradient
+    if (a.RY) DW_LAUNCH(false, false, true, RY_MEM, EPI_WGRAD); else DW_LAUNCH(false, false, true, RY_NONE, EPI_WGRAD);
+  }
+#undef DW_LAUNCH
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
+  if (a.N <= 32) return launch_shape<128, 32, 4, 1>(a, s);
+  if (a.M <= 32) return launch_shape<32, 128, 1, 4>(a, s);
+  const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.k;
+  if (big_tiles >= 512) return launch_shape<128, 128, 2, 2>(a, s);
+  return launch_shape<64, 64, 2, 2>(a, s);
+}
+
+}  // namespace dw

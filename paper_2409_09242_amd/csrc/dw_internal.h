@@ -1,0 +1,135 @@
+// Internal declarations shared by the host API and the kernel translation units of libdw.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dw.h"
+
+namespace dw {
+
+constexpr int kUpdThreads = 256;      // threads per block of the streaming update / pull kernels
+constexpr int kUpdQuads = 4;          // float4 groups per thread and worker
+constexpr int64_t kUpdChunk = (int64_t)kUpdThreads * kUpdQuads * 4;   // parameters per block
+
+// per-launch scalars of the fused AdaHessian update (Section IV-B), one entry per worker
+struct UpdateScalars {
+  float inv_bc1[DW_MAX_K];            // 1 / (1 - beta1^t_i)
+  float inv_bc2[DW_MAX_K];            // 1 / (1 - beta2^t_i)
+};
+
+// where biases sit in the canonical layout (they are excluded from spatial averaging)
+struct BiasRanges {
+  int n;
+  int64_t begin[DW_MAX_LAYERS];
+  int64_t end[DW_MAX_LAYERS];
+};
+
+struct UpdateArgs {
+  float* theta; float* m; float* v;   // [k][Pp]
+  const float* g; const float* hz;    // [k][g_stride]
+  const float* centre;                // [Pp]
+  const uint32_t* zbits;              // [k][z_stride] sign bits of z
+  uint16_t* wb16;                     // [k][Pp] bf16 copy of theta or nullptr
+  double* partials;                   // [k][n_blocks] squared-distance partial sums
+  int64_t P;                          // parameters per worker; only groups of four below P are touched
+  int64_t Pp;                         // padded parameter count (multiple of 64), row stride of theta, m, v
+  int64_t g_stride, z_stride;
+  int k;
+  int avg_block;                      // power of two, 1..256
+  float lr, beta1, beta2, eps, hpow;
+  uint64_t active_mask;               // bit i: worker i takes the step (others only report their distance)
+  BiasRanges bias;
+  UpdateScalars sc;
+};
+
+struct WeightArgs {                   // dynamic-weight scalars of one communication round (Section V-B)
+  const double* partials;             // [k][n_blocks]
+  int n_blocks;
+  double* u_ring;                     // [k][DW_MAX_P+1]
+  double* score;                      // [k][4] = u, a, h1, h2
+  float* omh1;                        // [k] 1 - h1_i   (0 pull for absent workers is handled by the mask)
+  float* h2;                          // [k]
+  int k, p, mode;
+  int slot;                           // ring slot receiving this round's u
+  int n_valid;                        // values of u in the ring after the push (<= p+1)
+  float alpha, kappa;
+  float c[DW_MAX_P];
+  float man_h1[DW_MAX_K], man_h2[DW_MAX_K];
+};
+
+struct PullArgs {
+  float* theta; float* centre;        // [k][Pp], [Pp]
+  uint16_t* wb16;                     // bf16 copy of theta or nullptr
+  const float* omh1; const float* h2; // [k] device scalars written by the weight kernel
+  int64_t Pp;
+  int k;
+  uint64_t part_mask;                 // bit i: worker i communicates in this round
+};
+
+hipError_t launch_update(const UpdateArgs& a, int n_blocks, hipStream_t s);
+hipError_t launch_weights(const WeightArgs& a, hipStream_t s);
+hipError_t launch_pull(const PullArgs& a, hipStream_t s);
+hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words64, const uint64_t* keys_host,
+                             int k, uint64_t active_mask, hipStream_t s);
+hipError_t launch_broadcast(float* theta, const float* centre, uint16_t* wb16, int64_t Pp, int k, hipStream_t s);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hipStream_t s);
+
+// ---- network part ------------------------------------------------------------------------------------
+
+enum GemmKind { GEMM_FWD = 0, GEMM_DGRAD = 1, GEMM_WGRAD = 2 };
+enum Epilogue { EPI_RELU = 0, EPI_LINEAR = 1, EPI_MASK = 2, EPI_WGRAD = 3 };
+
+// One "dual-number" GEMM: C = X*Y and RC = RX*Y + X*RY for all workers (grid y = worker).
+// Element strides describe how the logical operands X[M][K], Y[K][N] sit in memory.
+struct GemmArgs {
+  const void* X; const void* RX;      // RX == nullptr: that term is absent
+  const void* Y; const void* RY;      // RY == nullptr and ry_bits == 0: absent
+  int ry_bits;                        // RY is the +-1 direction z, read from zbits at z_off + element offset in Y
+  const uint32_t* zbits; int64_t z_stride; int64_t z_off;
+  int64_t x_wstride, y_wstride;       // per-worker element strides of X/RX and Y/RY
+  int x_kcontig, y_kcontig;           // 1: contraction index is the contiguous one
+  int ldx, ldy;
+  int M, N, K;
+  void* C; void* RC; int ldc; int64_t c_wstride;      // outputs [M][ldc]
+  const void* mask_src; int ld_mask; int64_t mask_wstride;   // EPI_MASK: keep where mask_src > 0
+  const float* bias; int64_t bias_wstride;            // EPI_RELU / EPI_LINEAR: theta + b_off
+  int64_t zb_off;                                     // bit offset of the bias part of z
+  float* gb; float* hzb;                              // EPI_WGRAD: bias-gradient outputs (g + b_off, hz + b_off)
+  int epi;
+  int k;
+  uint64_t active_mask;
+};
+
+hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
+hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
+
+struct HeadArgs {                     // softmax cross-entropy on the output layer and its R-derivative
+  const float* s; const float* Rs;    // [k][B][ld] logits and their directional derivative
+  float* delta; float* Rdelta;        // [k][B][ld] outputs (padding columns zeroed)
+  uint16_t* delta_b16; uint16_t* Rdelta_b16;   // optional bf16 copies
+  const int32_t* y;                   // [k][B]
+  float* loss;                        // [k] or nullptr
+  int B, C, ld, k;
+  uint64_t active_mask;
+};
+hipError_t launch_head(const HeadArgs& a, hipStream_t s);
+
+struct Layout {            // byte offsets into the workspace, all multiples of 256
+  int64_t P = 0, Pp = 0, z_stride = 0, n_upd_blocks = 0;
+  int64_t woff[DW_MAX_LAYERS] = {0}, boff[DW_MAX_LAYERS] = {0};
+  size_t theta = 0, m = 0, v = 0, g = 0, hz = 0, centre = 0, wb16 = 0, zbits = 0;
+  size_t act[DW_MAX_LAYERS] = {0}, ract[DW_MAX_LAYERS] = {0};   // a_l, Ra_l for l = 1..L-1 (index l)
+  size_t delta[2] = {0, 0}, rdelta[2] = {0, 0};                  // ping-pong hidden-layer errors
+  size_t sL = 0, rsL = 0, dL = 0, rdL = 0, dL16 = 0, rdL16 = 0;  // output layer, fp32 [k][B][16] (+ bf16 copies)
+  size_t partials = 0, u_ring = 0, score = 0, omh1 = 0, h2 = 0, loss = 0;
+  size_t total = 0;
+};
+
+// Enqueue forward, R-forward, backward and R-backward of all layers for the active workers; leaves the mean
+// gradient in the g buffer and the Hessian-vector product in the hz buffer (returns a dw_status).
+int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
+                const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s);
+
+}  // namespace dw

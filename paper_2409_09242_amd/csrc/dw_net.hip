@@ -1,0 +1,170 @@
+// Forward / backward pass of the MLP classifier and of its directional derivative along z.
+//
+// Per worker and minibatch (Section II eq.(2), Section III-B eq.(6)): a_0 = x, s_l = a_{l-1} W_l^T + b_l,
+// a_l = ReLU(s_l), p = softmax(s_L), loss = -mean log p[y]; backward d_L = (p - onehot)/B,
+// gW_l = d_l^T a_{l-1}, gb_l = sum_n d_l, d_{l-1} = (d_l W_l) * [s_{l-1} > 0].
+// The Hessian-vector product of the Hutchinson estimate (Section IV-B) is the derivative of that gradient
+// along z = (V_l, c_l): Ra_0 = 0, Rs_l = Ra_{l-1} W_l^T + a_{l-1} V_l^T + c_l, Ra_l = [s_l > 0] Rs_l,
+// Rd_L = p * (Rs_L - <p, Rs_L>)/B, HzW_l = Rd_l^T a_{l-1} + d_l^T Ra_{l-1}, Hzb_l = sum_n Rd_l,
+// Rd_{l-1} = (Rd_l W_l + d_l V_l) * [s_{l-1} > 0].
+// Every matrix product above runs in the dual GEMM kernels; this file holds the softmax head and the
+// order of the launches.
+#include "dw_internal.h"
+
+namespace dw {
+
+__device__ __forceinline__ uint16_t bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// one block per worker; thread n handles sample n (looping when B > blockDim)
+__global__ __launch_bounds__(256) void head_kernel(HeadArgs a) {
+  const int i = blockIdx.x;
+  if (!((a.active_mask >> i) & 1ull)) return;
+  const float* S = a.s + (int64_t)i * a.B * a.ld;
+  const float* RS = a.Rs + (int64_t)i * a.B * a.ld;
+  float* D = a.delta + (int64_t)i * a.B * a.ld;
+  float* RD = a.Rdelta + (int64_t)i * a.B * a.ld;
+  const int32_t* Y = a.y + (int64_t)i * a.B;
+  const float invB = 1.0f / (float)a.B;
+  float loss = 0.f;
+  for (int n = threadIdx.x; n < a.B; n += blockDim.x) {
+    float s[DW_MAX_CLASSES], rs[DW_MAX_CLASSES];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < DW_MAX_CLASSES; ++c) {
+      s[c] = c < a.C ? S[(int64_t)n * a.ld + c] : -INFINITY;
+      rs[c] = c < a.C ? RS[(int64_t)n * a.ld + c] : 0.f;
+      mx = fmaxf(mx, s[c]);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int c = 0; c < DW_MAX_CLASSES; ++c) {
+      s[c] = c < a.C ? expf(s[c] - mx) : 0.f;
+      sum += s[c];
+    }
+    const float inv = 1.0f / sum;
+    const int y = Y[n];
+    float dot = 0.f, py = 1.f;
+#pragma unroll
+    for (int c = 0; c < DW_MAX_CLASSES; ++c) {
+      s[c] *= inv;                                   // p_c
+      dot += s[c] * rs[c];
+      if (c == y) py = s[c];
+    }
+    loss -= logf(py);
+#pragma unroll
+    for (int c = 0; c < DW_MAX_CLASSES; ++c) {
+      float d = 0.f, rd = 0.f;
+      if (c < a.C) {
+        d = (s[c] - (c == y ? 1.f : 0.f)) * invB;    // d(mean loss)/d s_L
+        rd = s[c] * (rs[c] - dot) * invB;            // its derivative along Rs_L
+      }
+      if (c < a.ld) {
+        D[(int64_t)n * a.ld + c] = d;
+        RD[(int64_t)n * a.ld + c] = rd;
+        if (a.delta_b16) {
+          a.delta_b16[((int64_t)i * a.B + n) * a.ld + c] = bf16_rne(d);
+          a.Rdelta_b16[((int64_t)i * a.B + n) * a.ld + c] = bf16_rne(rd);
+        }
+      }
+    }
+  }
+  __shared__ float red[256];
+  red[threadIdx.x] = loss;
+  __syncthreads();
+  for (int st = 128; st >= 1; st >>= 1) {
+    if ((int)threadIdx.x < st) red[threadIdx.x] += red[threadIdx.x + st];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0 && a.loss) a.loss[i] = red[0] * invB;
+}
+
+hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(head_kernel, dim3(a.k), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
+                const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s) {
+  if (cfg.dtype != DW_F32) return DW_ERR_MODE;       // bf16 network kernels are not wired in yet
+  const int L = cfg.n_layers, k = cfg.k, B = cfg.batch;
+  const int HL = DW_MAX_CLASSES;                     // row stride of the output-layer buffers
+  float* theta = reinterpret_cast<float*>(ws + lay.theta);
+  float* g = reinterpret_cast<float*>(ws + lay.g);
+  float* hz = reinterpret_cast<float*>(ws + lay.hz);
+  auto act = [&](int l) -> const void* { return l == 0 ? d_x : (const void*)(ws + lay.act[l]); };
+  auto ract = [&](int l) -> const void* { return l == 0 ? nullptr : (const void*)(ws + lay.ract[l]); };
+  auto act_stride = [&](int l) -> int64_t { return (int64_t)B * cfg.dims[l]; };
+  hipError_t e;
+
+  // forward with R-forward
+  for (int l = 1; l <= L; ++l) {
+    GemmArgs a{};
+    a.X = act(l - 1); a.RX = ract(l - 1); a.x_wstride = act_stride(l - 1); a.x_kcontig = 1; a.ldx = cfg.dims[l - 1];
+    a.Y = theta + lay.woff[l - 1]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 1;
+    a.ldy = cfg.dims[l - 1];
+    a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1]; a.zb_off = lay.boff[l - 1];
+    a.M = B; a.N = cfg.dims[l]; a.K = cfg.dims[l - 1];
+    a.bias = theta + lay.boff[l - 1]; a.bias_wstride = lay.Pp;
+    if (l < L) {
+      a.C = ws + lay.act[l]; a.RC = ws + lay.ract[l]; a.ldc = cfg.dims[l]; a.c_wstride = act_stride(l);
+      a.epi = EPI_RELU;
+    } else {
+      a.C = ws + lay.sL; a.RC = ws + lay.rsL; a.ldc = HL; a.c_wstride = (int64_t)B * HL;
+      a.epi = EPI_LINEAR;
+    }
+    a.k = k; a.active_mask = active;
+    if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+  }
+
+  // softmax cross-entropy head
+  {
+    HeadArgs hd{};
+    hd.s = reinterpret_cast<const float*>(ws + lay.sL); hd.Rs = reinterpret_cast<const float*>(ws + lay.rsL);
+    hd.delta = reinterpret_cast<float*>(ws + lay.dL); hd.Rdelta = reinterpret_cast<float*>(ws + lay.rdL);
+    hd.delta_b16 = nullptr; hd.Rdelta_b16 = nullptr;
+    hd.y = d_y; hd.loss = d_loss; hd.B = B; hd.C = cfg.dims[L]; hd.ld = HL; hd.k = k; hd.active_mask = active;
+    if ((e = launch_head(hd, s)) != hipSuccess) return DW_ERR_HIP;
+  }
+
+  // backward with R-backward, output layer first
+  for (int l = L; l >= 1; --l) {
+    const void* dl; const void* rdl; int ldd; int64_t dstride;
+    if (l == L) {
+      dl = ws + lay.dL; rdl = ws + lay.rdL; ldd = HL; dstride = (int64_t)B * HL;
+    } else {
+      dl = ws + lay.delta[l & 1]; rdl = ws + lay.rdelta[l & 1]; ldd = cfg.dims[l]; dstride = act_stride(l);
+    }
+    {   // weight gradient and its R-companion: contraction over the minibatch
+      GemmArgs a{};
+      a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 0; a.ldx = ldd;
+      a.Y = act(l - 1); a.RY = ract(l - 1); a.ry_bits = 0; a.y_wstride = act_stride(l - 1); a.y_kcontig = 0;
+      a.ldy = cfg.dims[l - 1];
+      a.zbits = zbits; a.z_stride = z_stride;
+      a.M = cfg.dims[l]; a.N = cfg.dims[l - 1]; a.K = B;
+      a.C = g + lay.woff[l - 1]; a.RC = hz + lay.woff[l - 1]; a.ldc = cfg.dims[l - 1]; a.c_wstride = lay.Pp;
+      a.gb = g + lay.boff[l - 1]; a.hzb = hz + lay.boff[l - 1];
+      a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
+      if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+    }
+    if (l > 1) {   // data gradient through W_l, masked by the ReLU of layer l-1
+      GemmArgs a{};
+      a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 1; a.ldx = ldd;
+      a.Y = theta + lay.woff[l - 1]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0;
+      a.ldy = cfg.dims[l - 1];
+      a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1];
+      a.M = B; a.N = cfg.dims[l - 1]; a.K = cfg.dims[l];
+      a.C = ws + lay.delta[(l - 1) & 1]; a.RC = ws + lay.rdelta[(l - 1) & 1]; a.ldc = cfg.dims[l - 1];
+      a.c_wstride = act_stride(l - 1);
+      a.mask_src = act(l - 1); a.ld_mask = cfg.dims[l - 1]; a.mask_wstride = act_stride(l - 1);
+      a.epi = EPI_MASK; a.k = k; a.active_mask = active;
+      if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+    }
+  }
+  return DW_OK;
+}
+
+}  // namespace dw

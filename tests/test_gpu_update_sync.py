@@ -1,0 +1,138 @@
+"""GPU parity of the optimizer and communication kernels against the oracle (Section IV-B, Section V-B)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dw_oracle as O
+from paper_2409_09242_amd import binding as B
+from paper_2409_09242_amd import workloads as W
+from parity import RTOL_UPDATE, close, oracle_config
+
+pytestmark = pytest.mark.gpu
+
+
+def _flat_case(P, k, seed, **kw):
+    rng = W.rng_for(seed, 23)
+    theta0 = rng.uniform(-0.01, 0.01, size=P).astype(np.float32)
+    w = W.scaled(W.C5, k=k, n_params=P, seed=seed, **kw)
+    return w, theta0, rng
+
+
+def _compare_state(h, tr, what_list=("theta", "m", "v", "centre"), rtol=RTOL_UPDATE, tag=""):
+    for i in range(tr.cfg.k):
+        if "theta" in what_list:
+            close(h.get_state(B.DW_S_THETA, i), tr.theta[i], rtol, "%s theta[%d]" % (tag, i))
+        if "m" in what_list:
+            close(h.get_state(B.DW_S_M, i), tr.m[i], rtol, "%s m[%d]" % (tag, i))
+        if "v" in what_list:
+            close(h.get_state(B.DW_S_V, i), tr.v[i], rtol, "%s v[%d]" % (tag, i))
+    if "centre" in what_list:
+        close(h.get_state(B.DW_S_CENTRE), tr.centre, rtol, "%s centre" % tag)
+
+
+def test_rademacher_bits_are_bit_exact():
+    P, k = 4 * 1000 + 4, 3
+    w, theta0, rng = _flat_case(P, k, 77)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    g = torch.zeros(k, P, device="cuda"); hz = torch.zeros(k, P, device="cuda")
+    for step in range(3):
+        active = [1, step != 1, 1]
+        h.update_only(g, hz, active=active)
+        for i in range(k):
+            t_i = step if i != 1 else (step if step < 1 else step - 1)
+            if not active[i]:
+                continue
+            want = O.words_to_u32(O.rademacher_words(w.seed, i, t_i, P))
+            got = h.get_state(B.DW_S_ZBITS, i)
+            np.testing.assert_array_equal(got, want)
+    assert [int(h.get_state(B.DW_S_STEPS, i)[0]) for i in range(k)] == [3, 2, 3]
+
+
+@pytest.mark.parametrize("P,k,avg_block,hpow", [
+    (4096 * 3 + 64, 4, 1, 1.0),        # several blocks plus a ragged tail
+    (4096 * 2 + 512, 3, 32, 1.0),      # block mean across lanes
+    (1024, 2, 4, 0.5), (8, 1, 2, 1.0), (4096 + 256, 5, 256, 2.0), (2048, 2, 8, 0.0),
+])
+def test_update_and_dynamic_sync_follow_the_oracle(P, k, avg_block, hpow):
+    w, theta0, rng = _flat_case(P, k, 100 + avg_block, avg_block=avg_block, hpow=hpow)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    tr = O.OracleTrainer(oracle_config(w, dims=None), theta0.astype(np.float64))
+    for step in range(7):
+        g = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+        hz = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+        active = None if step != 3 else [i % 2 == 0 for i in range(k)]
+        part = None if step != 4 else [i != 0 for i in range(k)]
+        h.update_only(torch.from_numpy(g).cuda(), torch.from_numpy(hz).cuda(), active=active)
+        tr.update_only(g, hz, active=active)
+        _compare_state(h, tr, ("theta", "m", "v"), tag="step %d" % step)
+        did = h.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part)
+        assert did and tr.elastic_sync(O.MODE_DYNAMIC, tau=1, participate=part)
+        for i in range(k):
+            sc = h.get_state(B.DW_S_SCORE, i)
+            assert abs(sc[0] - tr.last_u[i]) < 1e-5, (step, i, sc, tr.last_u[i])
+            assert abs(sc[1] - tr.last_a[i]) < 2e-5
+            assert abs(sc[2] - tr.last_h1[i]) < 5e-4 and abs(sc[3] - tr.last_h2[i]) < 5e-4
+        _compare_state(h, tr, ("theta", "centre"), tag="sync %d" % step)
+    hist = h.get_state(B.DW_S_U_HIST, 0)
+    assert int(hist[0]) == 5
+    np.testing.assert_allclose(hist[1:6], tr.u_hist[0], atol=1e-5)
+
+
+def test_fixed_manual_modes_tau_gating_and_exact_reset():
+    P, k = 4096 + 128, 4
+    w, theta0, rng = _flat_case(P, k, 5)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    tr = O.OracleTrainer(oracle_config(w, dims=None), theta0.astype(np.float64))
+    g = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+    hz = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+    gd, hd = torch.from_numpy(g).cuda(), torch.from_numpy(hz).cuda()
+    for step in range(1, 5):
+        h.update_only(gd, hd); tr.update_only(g, hz)
+        did = h.elastic_sync(B.DW_FIXED, tau=2)
+        assert did == (step % 2 == 0) == tr.elastic_sync(O.MODE_FIXED, tau=2)
+    _compare_state(h, tr, tag="fixed")
+    # manual weights: worker 2 is reset (h1 = 1) and ignored by the centre (h2 = 0)
+    h1 = [0.1, 0.3, 1.0, 0.1]; h2 = [0.1, 0.05, 0.0, 0.1]
+    h.update_only(gd, hd); tr.update_only(g, hz)
+    c_before = h.get_state(B.DW_S_CENTRE)
+    h.elastic_sync(B.DW_MANUAL, tau=1, h1=h1, h2=h2); tr.elastic_sync(O.MODE_MANUAL, 1, h1, h2)
+    _compare_state(h, tr, tag="manual")
+    np.testing.assert_array_equal(h.get_state(B.DW_S_THETA, 2), c_before)     # exact copy of the old centre
+    # a worker with h2 = 0 cannot move the centre: perturb it and repeat the same round
+    h.update_only(gd, hd)
+    snap = [h.get_state(B.DW_S_THETA, i) for i in range(k)]
+    c0 = h.get_state(B.DW_S_CENTRE)
+    h.elastic_sync(B.DW_MANUAL, tau=1, h1=h1, h2=h2)
+    c1 = h.get_state(B.DW_S_CENTRE)
+    for i in range(k):
+        h.set_state(B.DW_S_THETA, i, snap[i] + (50.0 if i == 2 else 0.0))
+    h.set_state(B.DW_S_CENTRE, 0, c0)
+    h.elastic_sync(B.DW_MANUAL, tau=1, h1=h1, h2=h2)
+    np.testing.assert_array_equal(h.get_state(B.DW_S_CENTRE), c1)
+
+
+def test_sync_right_after_init_is_a_fixed_point():
+    P, k = 1024, 3
+    w, theta0, _ = _flat_case(P, k, 9)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    assert h.elastic_sync(B.DW_DYNAMIC, tau=1)
+    for i in range(k):
+        np.testing.assert_array_equal(h.get_state(B.DW_S_THETA, i), theta0)
+        assert h.get_state(B.DW_S_SCORE, i)[0] == pytest.approx(0.5 * np.log(1e-30))
+    np.testing.assert_array_equal(h.get_state(B.DW_S_CENTRE), theta0)
+
+
+def test_call_errors():
+    w, theta0, _ = _flat_case(1024, 2, 3)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    x = torch.zeros(8, device="cuda")
+    with pytest.raises(B.DwError):
+        h.worker_step(x, x)                       # flat problem has no network
+    with pytest.raises(B.DwError):
+        h.elastic_sync(5)
+    with pytest.raises(B.DwError):
+        h.elastic_sync(B.DW_MANUAL)               # weights missing
+    with pytest.raises(B.DwError):
+        h.get_state(B.DW_S_THETA, 7)
+    with pytest.raises(B.DwError):
+        h.get_state(B.DW_S_THETA, 0, offset=1000, count=100)

@@ -1,0 +1,78 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what include/dw.h declares, and validates
+configurations on the host (no kernel is launched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2409_09242_amd import binding as B
+from paper_2409_09242_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "dw.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dw_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _declared()
+    assert set(names) == set(B.EXPORTS), names
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_strerror_and_param_count():
+    lib = B.lib()
+    assert lib.dw_strerror(0) == b"ok"
+    assert b"workspace" in lib.dw_strerror(-4)
+    for w in (W.C1, W.C2, W.C3, W.C4, W.C5):
+        cfg = B.config_from_workload(w)
+        assert B.param_count(cfg) == w.P
+        assert lib.dw_workspace_bytes(C.byref(cfg)) > 4 * w.P * w.k * 3
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("k", 0, -2), ("k", 65, -2), ("batch", 0, -2), ("dtype", 7, -2),
+    ("lr", 0.0, -3), ("beta1", 1.0, -3), ("eps", 0.0, -3), ("avg_block", 3, -3), ("avg_block", 512, -3),
+    ("alpha", 0.0, -3), ("alpha", 1.5, -3), ("kappa", 0.0, -3), ("kappa", 0.2, -3), ("p", 0, -3), ("p", 9, -3),
+])
+def test_bad_config_is_rejected(field, value, status):
+    cfg = B.config_from_workload(W.C1)
+    setattr(cfg, field, value)
+    n = C.c_int64()
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == status
+    assert B.lib().dw_workspace_bytes(C.byref(cfg)) == 0
+
+
+def test_bad_dims_and_weights():
+    n = C.c_int64()
+    cfg = B.make_config(dims=(30, 64, 10), k=2, batch=4)            # d_0 not a multiple of 4
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == -2
+    cfg = B.make_config(dims=(32, 64, 17), k=2, batch=4)            # too many classes
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == -2
+    cfg = B.make_config(dims=(32, 64, 10), k=2, batch=4, bf16=True)
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == 0
+    cfg = B.make_config(dims=(36, 64, 10), k=2, batch=4, bf16=True)  # bf16 needs multiples of 8
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == -2
+    cfg = B.make_config(dims=(32, 64, 10), k=2, batch=4, c=(0.5, 0.4))   # weights must sum to one
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == -3
+    cfg = B.make_config(dims=(32, 48, 10), k=2, batch=4, avg_block=32)   # block must divide fan-in 48
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == -3
+    cfg = B.make_config(dims=None, k=2, n_params=1002)                    # flat P must be a multiple of 4
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == -2
+    assert B.lib().dw_param_count(None, C.byref(n)) == -1
+
+
+def test_null_handles_are_rejected_without_a_gpu():
+    lib = B.lib()
+    assert lib.dw_destroy(None) == -1
+    assert lib.dw_worker_step(None, None, None, None, None, None, None) == -1
+    assert lib.dw_elastic_sync(None, 0, None, None, None, 1, None) == -1
+    h = C.c_void_p()
+    cfg = B.config_from_workload(W.C1)
+    assert lib.dw_init(C.byref(h), C.byref(cfg), None, 0, None, 0, None) == -1

@@ -166,6 +166,7 @@ class StepTrace:
     z: Optional[np.ndarray] = None
     pre_acts: List[np.ndarray] = field(default_factory=list)   # s_l, l = 1..L
     min_abs_preact: float = math.inf                           # distance of the closest hidden unit to a ReLU kink
+    ties: List[np.ndarray] = field(default_factory=list)       # per hidden layer: bool [B,d_l], |s_l| within the tie band
 
 
 def forward(theta, x, dims, q: Callable = _identity):
@@ -197,13 +198,20 @@ def loss_only(theta, x, y, dims) -> float:
     return float(np.mean(lse - sL[np.arange(len(y)), y]))
 
 
-def grad_and_hvp(theta, x, y, dims, z=None, q: Callable = _identity, trace: Optional[StepTrace] = None):
+def grad_and_hvp(theta, x, y, dims, z=None, q: Callable = _identity, trace: Optional[StepTrace] = None,
+                 tie_band: float = 0.0, tie_choice: Optional[Sequence[np.ndarray]] = None):
     """Mean minibatch gradient g (Section II eq.(2)) and, when z is given, the Hessian-vector
     product Hz of the same minibatch loss (the H z of the Hutchinson display, Section IV-B).
 
     Hz is the derivative of g along the direction z: every quantity X of the forward and
     backward pass gets a companion RX = d/dr X(theta + r z) at r = 0, propagated by the product
     and chain rules.  ReLU contributes its 0/1 slope (slope 0 at exactly 0, curvature 0).
+
+    Ties at the ReLU kink: the gradient of a ReLU network jumps where a pre-activation crosses 0, so
+    for a hidden unit with |s| < tie_band * rms(s_l) an implementation in lower precision may
+    legitimately land on either side.  Such units are reported in trace.ties, and for them only
+    (never for any other unit) the 0/1 slope may be dictated through tie_choice (one bool [B,d_l]
+    array per hidden layer).  With tie_band = 0 there are no ties and the slope is [s > 0].
     """
     theta = np.asarray(theta, dtype=F64)
     x = np.asarray(x, dtype=F64)
@@ -217,10 +225,21 @@ def grad_and_hvp(theta, x, y, dims, z=None, q: Callable = _identity, trace: Opti
 
     a, s = forward(theta, x, dims, q)
     Wq = [q(W) for (W, _) in layers]
+    slope = []                                                 # ReLU slope of hidden layer l = 1..L-1
+    ties = []
+    for l in range(1, L):
+        s_l = s[l - 1]
+        on = s_l > 0.0
+        tie = np.abs(s_l) < tie_band * math.sqrt(float(np.mean(s_l * s_l))) if tie_band > 0.0 else np.zeros_like(on)
+        if tie_choice is not None:
+            on = np.where(tie, np.asarray(tie_choice[l - 1], dtype=bool), on)
+        slope.append(on)
+        ties.append(tie)
     if trace is not None:
         trace.pre_acts = s
         hidden = [np.abs(v).min() for v in s[:-1]]
         trace.min_abs_preact = float(min(hidden)) if hidden else math.inf
+        trace.ties = ties
 
     # R-forward: Ra_0 = 0 (the input does not depend on theta)
     if want_h:
@@ -231,7 +250,7 @@ def grad_and_hvp(theta, x, y, dims, z=None, q: Callable = _identity, trace: Opti
             Rs_l = Ra[l - 1] @ Wq[l - 1].T + a[l - 1] @ V.T + c
             Rs.append(Rs_l)
             if l < L:
-                Ra.append(q((s[l - 1] > 0.0) * Rs_l))
+                Ra.append(q(slope[l - 1] * Rs_l))
 
     # loss and output error
     p = softmax_rows(s[-1])
@@ -257,7 +276,7 @@ def grad_and_hvp(theta, x, y, dims, z=None, q: Callable = _identity, trace: Opti
             hz[w_off:b_off] = (Rdq.T @ a[l - 1] + dq.T @ Ra[l - 1]).reshape(-1)
             hz[b_off:b_off + d_out] = Rdq.sum(axis=0)
         if l > 1:
-            mask = (s[l - 2] > 0.0)
+            mask = slope[l - 2]
             if want_h:
                 V, _ = zl[l - 1]
                 Rdelta = (Rdq @ Wq[l - 1] + dq @ V) * mask
@@ -432,9 +451,10 @@ class OracleTrainer:
         words = rademacher_words(self.cfg.seed, worker, int(self.t[worker]), self.P)
         return words_to_signs(words, self.P)
 
-    def worker_step(self, x, y, z_signs=None, active=None):
+    def worker_step(self, x, y, z_signs=None, active=None, tie_band=0.0, tie_choice=None):
         """One local AdaHessian step per active worker.  x: [k,B,d0], y: [k,B] ints.
         z_signs: optional [k,P] of +-1 (else drawn from the counter-based stream at (seed, i, t_i)).
+        tie_band / tie_choice[i]: see grad_and_hvp.
         Returns the per-worker mean losses (nan for inactive workers)."""
         cfg = self.cfg
         losses = np.full(cfg.k, np.nan)
@@ -443,7 +463,8 @@ class OracleTrainer:
                 continue
             z = self.draw_z(i) if z_signs is None else np.asarray(z_signs[i], dtype=F64)
             tr = StepTrace()
-            loss, g, hz = grad_and_hvp(self.theta[i], x[i], y[i], cfg.dims, z, self.q, tr)
+            loss, g, hz = grad_and_hvp(self.theta[i], x[i], y[i], cfg.dims, z, self.q, tr, tie_band,
+                                       None if tie_choice is None else tie_choice[i])
             self.traces[i] = tr
             self.t[i] += 1
             self.theta[i], self.m[i], self.v[i] = adahessian_update(

@@ -368,6 +368,15 @@ static int state_ptr(dw_handle* h, int what, int worker, int64_t offset, int64_t
   if (what != DW_S_CENTRE && (worker < 0 || worker >= k)) return DW_ERR_ARG;
   size_t base = 0, es = 4;
   int64_t n = L.P, stride = L.Pp;
+  if (what > DW_S_ACT && what < DW_S_ACT + h->cfg.n_layers) {
+    const int l = what - DW_S_ACT;
+    es = h->cfg.dtype == DW_BF16 ? 2 : 4;
+    n = (int64_t)h->cfg.batch * h->cfg.dims[l];
+    if (offset + count > n) return DW_ERR_ARG;
+    *ptr = h->ws + L.act[l] + ((size_t)worker * n + offset) * es;
+    *bytes = (size_t)count * es;
+    return DW_OK;
+  }
   switch (what) {
     case DW_S_THETA: base = L.theta; break;
     case DW_S_M: base = L.m; break;

@@ -33,34 +33,42 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a) {
   for (int n = threadIdx.x; n < a.B; n += blockDim.x) {
     float s[DW_MAX_CLASSES], rs[DW_MAX_CLASSES];
     float mx = -INFINITY;
+    int amax = 0;
 #pragma unroll
     for (int c = 0; c < DW_MAX_CLASSES; ++c) {
       s[c] = c < a.C ? S[(int64_t)n * a.ld + c] : -INFINITY;
       rs[c] = c < a.C ? RS[(int64_t)n * a.ld + c] : 0.f;
-      mx = fmaxf(mx, s[c]);
+      if (s[c] > mx) { mx = s[c]; amax = c; }
     }
-    float sum = 0.f;
-#pragma unroll
-    for (int c = 0; c < DW_MAX_CLASSES; ++c) {
-      s[c] = c < a.C ? expf(s[c] - mx) : 0.f;
-      sum += s[c];
-    }
-    const float inv = 1.0f / sum;
     const int y = Y[n];
-    float dot = 0.f, py = 1.f;
+    // e_c = exp(s_c - max); the largest term is exactly 1, so sums that leave it (or the label's term)
+    // out keep full relative precision when the prediction is confident
+    float rest_max = 0.f, rest_y = 0.f, sy = 0.f;
 #pragma unroll
     for (int c = 0; c < DW_MAX_CLASSES; ++c) {
-      s[c] *= inv;                                   // p_c
-      dot += s[c] * rs[c];
-      if (c == y) py = s[c];
+      const float e = c < a.C ? expf(s[c] - mx) : 0.f;
+      if (c == y) sy = s[c] - mx;
+      if (c != amax) rest_max += e;
+      if (c != y) rest_y += e;
+      s[c] = e;
     }
-    loss -= logf(py);
+    const float sum = 1.0f + rest_max;
+    const float inv = 1.0f / sum;
+#pragma unroll
+    for (int c = 0; c < DW_MAX_CLASSES; ++c) s[c] *= inv;   // p_c
+    loss += log1pf(rest_max) - sy;                   // -log p_y = log(sum_c e_c) - (s_y - max)
+    const float one_minus_py = rest_y * inv;         // 1 - p_y without cancellation
 #pragma unroll
     for (int c = 0; c < DW_MAX_CLASSES; ++c) {
       float d = 0.f, rd = 0.f;
       if (c < a.C) {
-        d = (s[c] - (c == y ? 1.f : 0.f)) * invB;    // d(mean loss)/d s_L
-        rd = s[c] * (rs[c] - dot) * invB;            // its derivative along Rs_L
+        d = (c == y ? -one_minus_py : s[c]) * invB;  // d(mean loss)/d s_L = (p - onehot)/B
+        // its derivative along Rs_L: p_c (Rs_c - <p, Rs>) / B, with Rs_c - <p, Rs> written as
+        // sum_c' p_c' (Rs_c - Rs_c') so that a confident prediction does not cancel
+        float ctr = 0.f;
+#pragma unroll
+        for (int c2 = 0; c2 < DW_MAX_CLASSES; ++c2) ctr += s[c2] * (rs[c] - rs[c2]);
+        rd = s[c] * ctr * invB;
       }
       if (c < a.ld) {
         D[(int64_t)n * a.ld + c] = d;

@@ -6,7 +6,8 @@ import torch
 from oracle import dw_oracle as O
 from paper_2409_09242_amd import binding as B
 from paper_2409_09242_amd import workloads as W
-from parity import RTOL_GRAD, RTOL_HV, RTOL_UPDATE, close, close_layers, oracle_config
+import parity
+from parity import RTOL_GRAD, RTOL_HV, RTOL_UPDATE, close, close_layers, close_update, oracle_config
 
 pytestmark = pytest.mark.gpu
 
@@ -46,7 +47,8 @@ def test_gradient_and_hvp_match_the_oracle(dims, batch, k):
         close_layers(h.get_state(B.DW_S_G, i), tr.traces[i].g, dims, RTOL_GRAD, "g[%d]" % i)
         close_layers(h.get_state(B.DW_S_HZ, i), tr.traces[i].hz, dims, RTOL_HV, "hz[%d]" % i)
         upd = h.get_state(B.DW_S_THETA, i) - theta0
-        close_layers(upd, tr.theta[i] - theta0.astype(np.float64), dims, RTOL_UPDATE, "update[%d]" % i)
+        close_update(upd, tr.theta[i] - theta0.astype(np.float64), tr, i, dims, RTOL_UPDATE, "update[%d]" % i)
+    print("worst err/bound:", parity.OBSERVED)
 
 
 def test_caller_supplied_z_and_frozen_worker():
@@ -63,46 +65,99 @@ def test_caller_supplied_z_and_frozen_worker():
     tr.worker_step(x[0], y[0], z_signs=zs, active=active)
     for i in (0, 2):
         close_layers(h.get_state(B.DW_S_HZ, i), tr.traces[i].hz, w.dims, RTOL_HV, "hz[%d]" % i)
-        close_layers(h.get_state(B.DW_S_THETA, i) - theta0, tr.theta[i] - theta0, w.dims, RTOL_UPDATE, "upd")
+        close_update(h.get_state(B.DW_S_THETA, i) - theta0, tr.theta[i] - theta0, tr, i, w.dims, RTOL_UPDATE, "upd")
     np.testing.assert_array_equal(h.get_state(B.DW_S_THETA, 1), theta0)
     assert int(h.get_state(B.DW_S_STEPS, 1)[0]) == 0
 
 
-def _run_trajectory(w, steps, rtol_scale=1.0):
+TIE_BAND = 2e-5     # hidden units with |s| below this fraction of the layer's rms count as ReLU ties
+
+
+def _gpu_slopes(h, w):
+    """The GPU's ReLU on/off pattern, used by the oracle for tie units only."""
+    L = len(w.dims) - 1
+    return [[h.get_state(B.DW_S_ACT + l, i) > 0 for l in range(1, L)] for i in range(w.k)]
+
+
+def _run_trajectory(w, steps, forced, n_pool=4, check_every=1):
+    """Run `steps` worker steps with the configuration's communication schedule on both sides.
+
+    forced=True: before every step the GPU's state (theta, m, v, centre) is overwritten with the oracle's,
+    so each step and each round is compared on its own to the strict tolerances.  forced=False: both sides
+    run freely; the division by sqrt(v_hat)+eps amplifies fp32 rounding from step to step, so only a loose
+    agreement is asserted there.
+    """
     h, tr, theta0 = _setup(w)
-    n_pool = 4
     x, y = W.minibatch_pool(w, n_pool)
     xd, yd = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
     sched = W.participation_schedule(w, steps // w.tau + 1)
     rounds = 0
+    n_ties = 0
+    loss = torch.zeros(w.k, device="cuda")
     for step in range(1, steps + 1):
         b = (step - 1) % n_pool
+        if forced and step > 1:
+            for i in range(w.k):
+                h.set_state(B.DW_S_THETA, i, tr.theta[i]); h.set_state(B.DW_S_M, i, tr.m[i])
+                h.set_state(B.DW_S_V, i, tr.v[i])
+            h.set_state(B.DW_S_CENTRE, 0, tr.centre)
         prev = tr.theta.copy()
         prev_gpu = h.all_state(B.DW_S_THETA)
-        h.worker_step(xd[b], yd[b])
-        tr.worker_step(x[b], y[b])
-        margin = min(t.min_abs_preact for t in tr.traces)
-        now_gpu = h.all_state(B.DW_S_THETA)
-        for i in range(w.k):
-            close_layers(now_gpu[i] - prev_gpu[i], tr.theta[i] - prev[i], w.dims, RTOL_UPDATE * rtol_scale,
-                         "step %d update[%d] (kink margin %.2e)" % (step, i, margin))
+        h.worker_step(xd[b], yd[b], loss=loss)
+        ref_loss = tr.worker_step(x[b], y[b], tie_band=TIE_BAND, tie_choice=_gpu_slopes(h, w))
+        n_ties += sum(int(t.sum()) for trc in tr.traces for t in trc.ties)
+        if forced and (step % check_every == 0 or step == 1):
+            close(loss.cpu().numpy(), ref_loss, 1e-5, "step %d loss" % step)
+            now_gpu = h.all_state(B.DW_S_THETA)
+            for i in range(w.k):
+                close_layers(h.get_state(B.DW_S_G, i), tr.traces[i].g, w.dims, RTOL_GRAD, "step %d g[%d]" % (step, i))
+                close_layers(h.get_state(B.DW_S_HZ, i), tr.traces[i].hz, w.dims, RTOL_HV, "step %d hz[%d]" % (step, i))
+                close_update(now_gpu[i] - prev_gpu[i], tr.theta[i] - prev[i], tr, i, w.dims, RTOL_UPDATE,
+                             "step %d update[%d]" % (step, i))
+                close(h.get_state(B.DW_S_M, i), tr.m[i], RTOL_UPDATE, "step %d m[%d]" % (step, i))
+                close(h.get_state(B.DW_S_V, i), tr.v[i], RTOL_HV, "step %d v[%d]" % (step, i))
         part = sched[rounds]
+        pre_t, pre_c = tr.theta.copy(), tr.centre.copy()
+        if forced:
+            pre_gpu_t, pre_gpu_c = h.all_state(B.DW_S_THETA), h.get_state(B.DW_S_CENTRE)
         did = h.elastic_sync(B.DW_DYNAMIC, tau=w.tau, participate=part)
         assert did == tr.elastic_sync(O.MODE_DYNAMIC, tau=w.tau, participate=part)
         if did:
             rounds += 1
-            for i in range(w.k):
-                sc = h.get_state(B.DW_S_SCORE, i)
-                assert abs(sc[2] - tr.last_h1[i]) < 1e-3 and abs(sc[3] - tr.last_h2[i]) < 1e-3, (step, i, sc)
-            close(h.get_state(B.DW_S_CENTRE), tr.centre, RTOL_UPDATE * rtol_scale * 10, "centre after round %d" % rounds)
-    for i in range(w.k):
-        close(h.get_state(B.DW_S_THETA, i), tr.theta[i], 1e-3, "final theta[%d]" % i)
-    return h, tr
+            if forced:
+                # The weights are a 9x-amplified ((1-alpha)/|kappa|) function of differences of u, and u is the
+                # log of a norm dominated by the few worst-conditioned updates, so fp32 noise in Hz reaches
+                # h1, h2 at the 1e-3 level; the pull is then checked with that uncertainty times |theta_i - centre|.
+                H_TOL = 5e-3
+                extra_c = np.zeros(w.P)
+                for i in range(w.k):
+                    sc = h.get_state(B.DW_S_SCORE, i)
+                    assert abs(sc[0] - tr.last_u[i]) < 5e-4, (step, i, sc, tr.last_u[i])
+                    assert abs(sc[2] - tr.last_h1[i]) < H_TOL and abs(sc[3] - tr.last_h2[i]) < H_TOL, (step, i, sc)
+                    dist = np.abs(pre_t[i] - pre_c) * (1.0 if part[i] else 0.0)
+                    extra_c += H_TOL * dist
+                    close(h.get_state(B.DW_S_THETA, i) - pre_gpu_t[i], tr.theta[i] - pre_t[i], RTOL_UPDATE,
+                          "round %d pull[%d]" % (rounds, i), extra=H_TOL * dist)
+                close(h.get_state(B.DW_S_CENTRE) - pre_gpu_c, tr.centre - pre_c, RTOL_UPDATE,
+                      "round %d centre" % rounds, extra=extra_c)
+    rel = max(np.linalg.norm(h.get_state(B.DW_S_THETA, i) - tr.theta[i]) / np.linalg.norm(tr.theta[i] - theta0)
+              for i in range(w.k))
+    print("forced" if forced else "free", w.name, "steps", steps, "rounds", rounds, "tie units", n_ties,
+          "final |theta_gpu-theta_ref|/|theta_ref-theta0| = %.3g" % rel, "worst err/bound:", parity.OBSERVED)
+    return rel
 
 
-def test_trajectory_c1_tiny():
-    _run_trajectory(W.C1, W.C1.steps)
+def test_trajectory_c1_tiny_forced():
+    _run_trajectory(W.C1, W.C1.steps, forced=True)
 
 
-def test_trajectory_c2():
-    _run_trajectory(W.C2, W.C2.steps)
+def test_trajectory_c1_tiny_free_running():
+    assert _run_trajectory(W.C1, W.C1.steps, forced=False) < 0.05
+
+
+def test_trajectory_c2_forced():
+    _run_trajectory(W.C2, W.C2.steps, forced=True)
+
+
+def test_trajectory_c2_free_running():
+    assert _run_trajectory(W.C2, W.C2.steps, forced=False) < 0.05

@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark of the elastic AdaHessian hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch of synthetic input: dw_worker_step for all k workers
+(forward, backward, Hessian-vector product, fused AdaHessian update) followed by dw_elastic_sync, which
+takes a communication round every tau steps.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: metric/value (worker-steps/s over the whole job), a `roofline` object for the kernel
+class that takes the most time (HIP-event timing of every launch in a second pass over the same steps), a
+`kernels` breakdown, the update-only HBM stress (`update_stress`) and the CPU oracle timed on this host
+(`cpu_baseline`).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA
+
+
+def class_flops(w):
+    """Multiply-add work (flop) per all-worker step for each GEMM class."""
+    d, B, k = w.dims, w.batch, w.k
+    L = len(d) - 1
+    fwd = sum(2.0 * B * d[l] * d[l - 1] * (3 if l > 1 else 2) for l in range(1, L + 1))
+    wgrad = fwd
+    dgrad = sum(2.0 * B * d[l] * d[l - 1] * 3 for l in range(2, L + 1))
+    return {"gemm_fwd": fwd * k, "gemm_wgrad": wgrad * k, "gemm_dgrad": dgrad * k}
+
+
+def class_bytes(w, P, k):
+    """Algorithmic HBM bytes per launch for the streaming classes: the update reads g, Hz, theta, m, v and
+    writes theta, m, v (32 B per parameter and worker, +2 B for the bf16 weight copy); the pull reads and
+    writes theta (8 B per parameter and worker) and the centre (8 B per parameter)."""
+    upd = (32.0 + (2.0 if w.bf16 else 0.0)) * P * k
+    pull = (8.0 + (2.0 if w.bf16 else 0.0)) * P * k + 8.0 * P
+    return {"update": upd, "pull": pull}
+
+
+def run_mlp(w, steps, warmup, n_pool):
+    import torch
+    from paper_2409_09242_amd import binding as B
+    from paper_2409_09242_amd import workloads as W
+
+    theta0 = W.init_theta(w.dims, w.seed)
+    x, y = W.minibatch_pool(w, n_pool, bf16_round=W.to_bf16_f32 if w.bf16 else None)
+    xd = torch.from_numpy(x).cuda()
+    if w.bf16:
+        xd = xd.to(torch.bfloat16)
+    yd = torch.from_numpy(y).cuda()
+    h = B.Handle(B.config_from_workload(w), theta0)
+    sched = W.participation_schedule(w, (2 * steps + warmup) // w.tau + 2)
+    state = {"round": 0, "step": 0}
+
+    def one_step():
+        b = state["step"] % n_pool
+        h.worker_step(xd[b], yd[b])
+        if h.elastic_sync(B.DW_DYNAMIC, tau=w.tau, participate=sched[state["round"]]):
+            state["round"] += 1
+        state["step"] += 1
+
+    for _ in range(warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # second pass over the same number of steps with every launch bracketed by HIP events
+    h.profile(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        one_step()
+    prof = h.profile_read()
+    elapsed_prof = time.perf_counter() - t1
+    h.profile(False)
+    return h, elapsed, prof, elapsed_prof
+
+
+def run_update_stress(iters=20, warmup=3):
+    """Configuration 5: flat P = 1e8 per replica, k = 16; one fused AdaHessian update + one dynamic-weighted
+    elastic round per iteration.  Returns GB/s figures against the HBM peak."""
+    import torch
+    from paper_2409_09242_amd import binding as B
+    from paper_2409_09242_amd import workloads as W
+
+    w = W.C5
+    P, k = w.n_params, w.k
+    gen = torch.Generator(device="cuda").manual_seed(w.seed)
+    theta0 = (torch.rand(P, device="cuda", generator=gen) - 0.5) * 0.02
+    g = torch.randn(k, P, device="cuda", generator=gen) * 0.1
+    hz = torch.randn(k, P, device="cuda", generator=gen) * 0.1
+    h = B.Handle(B.config_from_workload(w), theta0)
+    for _ in range(warmup):
+        h.update_only(g, hz)
+        h.elastic_sync(B.DW_DYNAMIC, tau=1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(iters):
+        h.update_only(g, hz)
+        h.elastic_sync(B.DW_DYNAMIC, tau=1)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    h.profile(True)
+    for _ in range(iters):
+        h.update_only(g, hz)
+        h.elastic_sync(B.DW_DYNAMIC, tau=1)
+    prof = h.profile_read()
+    h.profile(False)
+    by = class_bytes(w, P, k)
+    total_bytes = by["update"] + by["pull"] + 4.0 * P          # + the centre read by the update
+    upd_ms = prof["update"][1] / max(prof["update"][0], 1)
+    pull_ms = prof["pull"][1] / max(prof["pull"][0], 1)
+    out = {
+        "workload": w.name, "P": P, "k": k, "iters": iters,
+        "ms_per_iter": 1e3 * el / iters,
+        "bytes_per_iter": total_bytes,
+        "GB/s": total_bytes / (el / iters) / 1e9,
+        "frac_of_hbm_peak": total_bytes / (el / iters) / 1e9 / PEAK_HBM_GBS,
+        "update_kernel": {"ms": upd_ms, "GB/s": by["update"] / (upd_ms * 1e-3) / 1e9,
+                          "frac": by["update"] / (upd_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+        "pull_kernel": {"ms": pull_ms, "GB/s": by["pull"] / (pull_ms * 1e-3) / 1e9,
+                        "frac": by["pull"] / (pull_ms * 1e-3) / 1e9 / PEAK_HBM_GBS},
+    }
+    del h, g, hz, theta0
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(w, budget_s=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import dw_oracle as O
+    from paper_2409_09242_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    est_rate = 2.0e10 * max(cores, 1) / 8.0                    # rough fp64 flop/s, only used to size the sample
+    per_worker = w.flops_per_worker_step()
+    k_s = int(max(1, min(w.k, budget_s * est_rate / per_worker)))
+    ws = W.scaled(w, k=k_s)
+    theta0 = W.init_theta(ws.dims, ws.seed)
+    x, y = W.minibatch_pool(ws, 1, bf16_round=W.to_bf16_f32 if w.bf16 else None)
+    tr = O.OracleTrainer(O.OracleConfig(dims=ws.dims, k=k_s, lr=ws.lr, beta1=ws.beta1, beta2=ws.beta2, eps=ws.eps,
+                                        hpow=ws.hpow, avg_block=ws.avg_block, alpha=ws.alpha, kappa=ws.kappa,
+                                        c=ws.c, seed=ws.seed, bf16=ws.bf16), theta0.astype(np.float64))
+    t0 = time.perf_counter()
+    n = 0
+    while True:
+        tr.worker_step(x[0], y[0])
+        tr.elastic_sync(O.MODE_DYNAMIC, tau=ws.tau)
+        n += 1
+        if time.perf_counter() - t0 > budget_s * 0.6 or n >= 50:
+            break
+    el = time.perf_counter() - t0
+    return {"value": k_s * n / el, "unit": "worker-steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d of %d workers, %d steps of %s (numpy float64)" % (k_s, w.k, n, w.name)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the simulated workers are batched on a single device and this build "
+              "has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2409_09242_amd import workloads as W
+    if not torch.cuda.is_available():
+        print("no GPU visible", file=sys.stderr)
+        return 3
+    w = W.WORKLOADS[args.workload]
+    n_pool = 4 if w.bf16 else 8
+    h, elapsed, prof, elapsed_prof = run_mlp(w, args.steps, args.warmup, n_pool)
+    dtype = "bf16" if w.bf16 else "f32"
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = w.k * args.steps / elapsed
+
+    fl = class_flops(w)
+    by = class_bytes(w, w.P, w.k)
+    kernels = {}
+    for name in ("gemm_fwd", "gemm_wgrad", "gemm_dgrad", "head", "update", "weights", "pull", "rademacher"):
+        n, ms = prof[name]
+        if n == 0:
+            continue
+        entry = {"launches": n, "avg_ms": ms / n, "ms_per_step": ms / args.steps}
+        if name in fl:
+            entry["TFLOP/s"] = fl[name] / (ms / args.steps * 1e-3) / 1e12
+        if name in by:
+            entry["GB/s"] = by[name] / (ms / n * 1e-3) / 1e9
+        kernels[name] = entry
+    gemm_ms = sum(kernels[c]["ms_per_step"] for c in fl if c in kernels)
+    dominant = max(kernels, key=lambda c: kernels[c]["ms_per_step"])
+    if dominant in fl:
+        # one roofline entry for the GEMM family (one kernel template): all its launches of a step together
+        ach = sum(fl.values()) / (gemm_ms * 1e-3) / 1e12
+        roof = {"kernel": "dual_gemm (%s)" % dtype, "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS[dtype],
+                "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[dtype], "traffic": None,
+                "avg_ms_per_step": gemm_ms, "dominant_class": dominant}
+    else:
+        ach = kernels[dominant]["GB/s"]
+        roof = {"kernel": dominant, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_ms": kernels[dominant]["avg_ms"]}
+    del h
+    torch.cuda.empty_cache()
+
+    out = {
+        "metric": "AdaHessian worker-steps/s (incl. Hv)", "value": value, "unit": "worker-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": w.name, "k": w.k, "dims": list(w.dims), "batch": w.batch, "tau": w.tau,
+                   "stale": w.stale, "sync": "dynamic"},
+        "flop_per_step": w.flops_per_worker_step() * w.k,
+        "step_TFLOP/s": w.flops_per_worker_step() * w.k / (ms_per_step * 1e-3) / 1e12,
+        "ms_per_step_profiled": 1e3 * elapsed_prof / args.steps,
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    if not args.no_stress:
+        out["update_stress"] = run_update_stress()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -168,6 +168,25 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
 int dw_get_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, void* h_buf, void* stream);
 int dw_set_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, const void* h_buf, void* stream);
 
+/*
+ * Per-kernel timing for benchmarks (not part of the method).  While enabled, every kernel the handle launches
+ * is bracketed by two HIP events on the caller's stream.  dw_profile_read synchronises the stream and returns,
+ * per kernel class, the number of launches and their summed duration in milliseconds since the last read
+ * (arrays of DW_N_KERNEL_CLASSES entries), then clears the record.  At most 8192 launches are kept between
+ * reads; *n_dropped receives how many were not recorded (may be NULL).
+ */
+#define DW_N_KERNEL_CLASSES 8
+#define DW_K_RADEMACHER 0    /* Rademacher bit generator                         */
+#define DW_K_GEMM_FWD 1      /* forward + R-forward GEMMs                        */
+#define DW_K_HEAD 2          /* softmax cross-entropy head                       */
+#define DW_K_GEMM_WGRAD 3    /* weight-gradient + Hz GEMMs                       */
+#define DW_K_GEMM_DGRAD 4    /* data-gradient + R-data-gradient GEMMs            */
+#define DW_K_UPDATE 5        /* fused AdaHessian update (+ distance partials)    */
+#define DW_K_WEIGHTS 6       /* dynamic-weight scalars                           */
+#define DW_K_PULL 7          /* elastic pull + centre reduction                  */
+int dw_profile(dw_handle* h, int enable);
+int dw_profile_read(dw_handle* h, int64_t* n_launches, double* total_ms, int64_t* n_dropped, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,9 @@ DW_FIXED, DW_MANUAL, DW_DYNAMIC = 0, 1, 2
 DW_S_ACT = 16
 
 EXPORTS = ("dw_strerror", "dw_last_hip_error", "dw_param_count", "dw_workspace_bytes", "dw_init", "dw_destroy",
-           "dw_worker_step", "dw_update_only", "dw_elastic_sync", "dw_get_state", "dw_set_state")
+           "dw_worker_step", "dw_update_only", "dw_elastic_sync", "dw_get_state", "dw_set_state",
+           "dw_profile", "dw_profile_read")
+KERNEL_CLASSES = ("rademacher", "gemm_fwd", "head", "gemm_wgrad", "gemm_dgrad", "update", "weights", "pull")
 
 
 class dw_config(C.Structure):
@@ -69,6 +71,8 @@ def lib() -> C.CDLL:
     L.dw_elastic_sync.restype = i32; L.dw_elastic_sync.argtypes = [vp, i32, vp, vp, vp, i32, vp]
     L.dw_get_state.restype = i32; L.dw_get_state.argtypes = [vp, i32, i32, i64, i64, vp, vp]
     L.dw_set_state.restype = i32; L.dw_set_state.argtypes = [vp, i32, i32, i64, i64, vp, vp]
+    L.dw_profile.restype = i32; L.dw_profile.argtypes = [vp, i32]
+    L.dw_profile_read.restype = i32; L.dw_profile_read.argtypes = [vp, vp, vp, vp, vp]
     _LIB = L
     return L
 
@@ -212,6 +216,24 @@ class Handle:
         st = lib().dw_set_state(self._h, what, worker, offset, arr.size, _ptr(arr), self._stream())
         if st != 0:
             raise DwError(st, "dw_set_state")
+
+    # ---- per-kernel timing -----------------------------------------------------------------------------
+    def profile(self, enable: bool):
+        st = lib().dw_profile(self._h, 1 if enable else 0)
+        if st != 0:
+            raise DwError(st, "dw_profile")
+
+    def profile_read(self) -> dict:
+        """{class name: (launches, total ms)} since the last read; synchronises the stream."""
+        n = np.zeros(len(KERNEL_CLASSES), dtype=np.int64)
+        ms = np.zeros(len(KERNEL_CLASSES), dtype=np.float64)
+        dropped = np.zeros(1, dtype=np.int64)
+        st = lib().dw_profile_read(self._h, _ptr(n), _ptr(ms), _ptr(dropped), self._stream())
+        if st != 0:
+            raise DwError(st, "dw_profile_read")
+        out = {name: (int(n[i]), float(ms[i])) for i, name in enumerate(KERNEL_CLASSES)}
+        out["dropped"] = int(dropped[0])
+        return out
 
     def all_state(self, what: int) -> np.ndarray:
         return np.stack([self.get_state(what, i) for i in range(self.k)])

@@ -140,6 +140,7 @@ struct dw_handle {
   int64_t calls;            // dw_worker_step / dw_update_only calls so far
   int64_t rounds;           // communication rounds so far
   bool norms_valid;         // the squared distances in `partials` match the current theta and centre
+  Profiler* prof;           // non-null while per-kernel timing is enabled
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
@@ -251,7 +252,7 @@ int dw_init(dw_handle** out, const dw_config* cfg, void* d_workspace, size_t wor
   h->lay = lay;
   h->ws = reinterpret_cast<char*>(d_workspace);
   std::memset(h->t, 0, sizeof(h->t));
-  h->calls = 0; h->rounds = 0; h->norms_valid = false;
+  h->calls = 0; h->rounds = 0; h->norms_valid = false; h->prof = nullptr;
   int rc = DW_OK;
   do {
     hipError_t e = launch_fill_zero(h->ws, lay.total, s);            // moments, padding, history: all zero
@@ -272,8 +273,53 @@ int dw_init(dw_handle** out, const dw_config* cfg, void* d_workspace, size_t wor
   return DW_OK;
 }
 
+static void free_profiler(dw_handle* h) {
+  if (!h->prof) return;
+  for (int i = 0; i < h->prof->created; ++i) {
+    (void)hipEventDestroy(h->prof->start[i]);
+    (void)hipEventDestroy(h->prof->stop[i]);
+  }
+  delete h->prof;
+  h->prof = nullptr;
+}
+
+// makes the handle's profiler current for the launches of one API call
+struct ProfilerGuard {
+  explicit ProfilerGuard(dw_handle* h) { tl_profiler = h->prof; }
+  ~ProfilerGuard() { tl_profiler = nullptr; }
+};
+
+int dw_profile(dw_handle* h, int enable) {
+  if (!h) return DW_ERR_NULL;
+  if (enable && !h->prof) {
+    h->prof = new (std::nothrow) Profiler();
+    if (!h->prof) return DW_ERR_ARG;
+  } else if (!enable) {
+    free_profiler(h);
+  }
+  return DW_OK;
+}
+
+int dw_profile_read(dw_handle* h, int64_t* n_launches, double* total_ms, int64_t* n_dropped, void* stream) {
+  if (!h || !n_launches || !total_ms) return DW_ERR_NULL;
+  if (!h->prof) return DW_ERR_MODE;
+  DW_HIP(hipStreamSynchronize((hipStream_t)stream));
+  for (int c = 0; c < KC_COUNT; ++c) { n_launches[c] = 0; total_ms[c] = 0.0; }
+  Profiler* p = h->prof;
+  for (int i = 0; i < p->used; ++i) {
+    float ms = 0.f;
+    DW_HIP(hipEventElapsedTime(&ms, p->start[i], p->stop[i]));
+    n_launches[p->cls[i]] += 1;
+    total_ms[p->cls[i]] += (double)ms;
+  }
+  if (n_dropped) *n_dropped = p->dropped;
+  p->used = 0; p->dropped = 0;
+  return DW_OK;
+}
+
 int dw_destroy(dw_handle* h) {
   if (!h) return DW_ERR_NULL;
+  free_profiler(h);
   delete h;
   return DW_OK;
 }
@@ -282,6 +328,7 @@ int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint
                    const uint8_t* h_active, float* d_loss, void* stream) {
   if (!h || !d_x || !d_y) return DW_ERR_NULL;
   if (h->cfg.n_layers == 0) return DW_ERR_MODE;
+  ProfilerGuard pg(h);
   if ((reinterpret_cast<uintptr_t>(d_x) & 15u) || (reinterpret_cast<uintptr_t>(d_zbits) & 7u)) return DW_ERR_ARG;
   hipStream_t s = (hipStream_t)stream;
   const uint64_t active = mask_from(h_active, h->cfg.k);
@@ -302,6 +349,7 @@ int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint
                    const uint8_t* h_active, void* stream) {
   if (!h || !d_g || !d_hz) return DW_ERR_NULL;
   if (h->lay.P % 4 != 0) return DW_ERR_MODE;          // worker i sits at offset i*P: needs 16-byte rows
+  ProfilerGuard pg(h);
   if ((reinterpret_cast<uintptr_t>(d_g) & 15u) || (reinterpret_cast<uintptr_t>(d_hz) & 15u) ||
       (reinterpret_cast<uintptr_t>(d_zbits) & 7u))
     return DW_ERR_ARG;
@@ -322,6 +370,7 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
   if (mode == DW_MANUAL && (!h_h1 || !h_h2)) return DW_ERR_NULL;
   if (tau < 1) return DW_ERR_ARG;
   if (h->calls % tau != 0) return 0;
+  ProfilerGuard pg(h);
   hipStream_t s = (hipStream_t)stream;
   const dw_config& c = h->cfg;
   const Layout& L = h->lay;

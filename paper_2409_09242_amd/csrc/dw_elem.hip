@@ -163,6 +163,7 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
 }
 
 hipError_t launch_update(const UpdateArgs& a, int n_blocks, hipStream_t s) {
+  KernelScope ks(KC_UPDATE, s);
   if (a.wb16)
     hipLaunchKernelGGL(update_kernel<true>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
   else
@@ -220,6 +221,7 @@ __global__ __launch_bounds__(256) void weight_kernel(WeightArgs a) {
 }
 
 hipError_t launch_weights(const WeightArgs& a, hipStream_t s) {
+  KernelScope ks(KC_WEIGHTS, s);
   hipLaunchKernelGGL(weight_kernel, dim3(a.k), dim3(256), 0, s, a);
   return hipGetLastError();
 }
@@ -283,6 +285,7 @@ __global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a) {
 }
 
 hipError_t launch_pull(const PullArgs& a, hipStream_t s) {
+  KernelScope ks(KC_PULL, s);
   const int64_t nq = a.Pp >> 2;
   const int n_blocks = (int)((nq + kUpdThreads * kUpdQuads - 1) / (kUpdThreads * kUpdQuads));
   if (a.wb16)
@@ -319,6 +322,7 @@ __global__ __launch_bounds__(256) void rademacher_kernel(uint32_t* zbits, int64_
 
 hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words64, const uint64_t* keys_host,
                              int k, uint64_t active_mask, hipStream_t s) {
+  KernelScope ks(KC_RADEMACHER, s);
   RadKeys keys;
   for (int i = 0; i < DW_MAX_K; ++i) keys.key[i] = i < k ? keys_host[i] : 0;
   dim3 grid((unsigned)((n_words64 + 255) / 256), (unsigned)k);

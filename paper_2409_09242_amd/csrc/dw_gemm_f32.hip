@@ -267,6 +267,7 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
+  KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : a.epi == EPI_MASK ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);
   if (a.N <= 32) return launch_shape<128, 32, 4, 1>(a, s);
   if (a.M <= 32) return launch_shape<32, 128, 1, 4>(a, s);
   const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.k;

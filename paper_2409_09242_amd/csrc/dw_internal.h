@@ -133,3 +133,31 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s);
 
 }  // namespace dw
+
+// ---- optional per-kernel timing (HIP events on the caller's stream) ------------------------------------
+namespace dw {
+
+enum KernelClass {
+  KC_RADEMACHER = 0, KC_GEMM_FWD = 1, KC_HEAD = 2, KC_GEMM_WGRAD = 3, KC_GEMM_DGRAD = 4,
+  KC_UPDATE = 5, KC_WEIGHTS = 6, KC_PULL = 7, KC_COUNT = 8
+};
+
+struct Profiler {
+  static constexpr int kMaxLaunches = 8192;
+  hipEvent_t start[kMaxLaunches];
+  hipEvent_t stop[kMaxLaunches];
+  int cls[kMaxLaunches];
+  int created = 0;        // event pairs created so far
+  int used = 0;           // pairs recorded since the last read
+  int dropped = 0;
+};
+
+extern thread_local Profiler* tl_profiler;     // set by the API entry points while profiling is enabled
+
+struct KernelScope {                            // records an event before and after one kernel launch
+  Profiler* p; int slot; hipStream_t s;
+  KernelScope(int kclass, hipStream_t stream);
+  ~KernelScope();
+};
+
+}  // namespace dw

@@ -91,6 +91,7 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a) {
 }
 
 hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
+  KernelScope ks(KC_HEAD, s);
   hipLaunchKernelGGL(head_kernel, dim3(a.k), dim3(256), 0, s, a);
   return hipGetLastError();
 }

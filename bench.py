@@ -178,6 +178,8 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stress-only", action="store_true",
+                    help="run only the update-only HBM stress and print its figures (for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the simulated workers are batched on a single device and this build "
@@ -189,6 +191,9 @@ def main():
     if not torch.cuda.is_available():
         print("no GPU visible", file=sys.stderr)
         return 3
+    if args.stress_only:
+        print(json.dumps({"update_stress": run_update_stress()}))
+        return 0
     w = W.WORKLOADS[args.workload]
     n_pool = 4 if w.bf16 else 8
     h, elapsed, prof, elapsed_prof = run_mlp(w, args.steps, args.warmup, n_pool)

@@ -268,11 +268,11 @@ def grad_and_hvp(theta, x, y, dims, z=None, q: Callable = _identity, trace: Opti
     for l in range(L, 0, -1):
         w_off, b_off = offs[l - 1]
         d_out, d_in = dims[l], dims[l - 1]
-        dq = q(delta) if l < L else delta                      # hidden-layer errors are stored rounded
+        dq = q(delta)                                          # back-propagated errors are stored rounded
         g[w_off:b_off] = (dq.T @ a[l - 1]).reshape(-1)
         g[b_off:b_off + d_out] = dq.sum(axis=0)
         if want_h:
-            Rdq = q(Rdelta) if l < L else Rdelta
+            Rdq = q(Rdelta)
             hz[w_off:b_off] = (Rdq.T @ a[l - 1] + dq.T @ Ra[l - 1]).reshape(-1)
             hz[b_off:b_off + d_out] = Rdq.sum(axis=0)
         if l > 1:

@@ -98,7 +98,7 @@ hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s) {
-  if (cfg.dtype != DW_F32) return DW_ERR_MODE;       // bf16 network kernels are not wired in yet
+  const bool b16 = cfg.dtype == DW_BF16;
   const int L = cfg.n_layers, k = cfg.k, B = cfg.batch;
   const int HL = DW_MAX_CLASSES;                     // row stride of the output-layer buffers
   float* theta = reinterpret_cast<float*>(ws + lay.theta);
@@ -107,13 +107,19 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
   auto act = [&](int l) -> const void* { return l == 0 ? d_x : (const void*)(ws + lay.act[l]); };
   auto ract = [&](int l) -> const void* { return l == 0 ? nullptr : (const void*)(ws + lay.ract[l]); };
   auto act_stride = [&](int l) -> int64_t { return (int64_t)B * cfg.dims[l]; };
+  // weights as the GEMMs read them: fp32 master copy, or its bf16 rounding kept by the update and the pull
+  auto weights = [&](int l) -> const void* {
+    return b16 ? (const void*)(reinterpret_cast<uint16_t*>(ws + lay.wb16) + lay.woff[l - 1])
+               : (const void*)(theta + lay.woff[l - 1]);
+  };
+  auto gemm = [&](const GemmArgs& a) { return b16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s); };
   hipError_t e;
 
   // forward with R-forward
   for (int l = 1; l <= L; ++l) {
     GemmArgs a{};
     a.X = act(l - 1); a.RX = ract(l - 1); a.x_wstride = act_stride(l - 1); a.x_kcontig = 1; a.ldx = cfg.dims[l - 1];
-    a.Y = theta + lay.woff[l - 1]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 1;
+    a.Y = weights(l); a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 1;
     a.ldy = cfg.dims[l - 1];
     a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1]; a.zb_off = lay.boff[l - 1];
     a.M = B; a.N = cfg.dims[l]; a.K = cfg.dims[l - 1];
@@ -126,7 +132,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.epi = EPI_LINEAR;
     }
     a.k = k; a.active_mask = active;
-    if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+    if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
   }
 
   // softmax cross-entropy head
@@ -134,7 +140,8 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     HeadArgs hd{};
     hd.s = reinterpret_cast<const float*>(ws + lay.sL); hd.Rs = reinterpret_cast<const float*>(ws + lay.rsL);
     hd.delta = reinterpret_cast<float*>(ws + lay.dL); hd.Rdelta = reinterpret_cast<float*>(ws + lay.rdL);
-    hd.delta_b16 = nullptr; hd.Rdelta_b16 = nullptr;
+    hd.delta_b16 = b16 ? reinterpret_cast<uint16_t*>(ws + lay.dL16) : nullptr;
+    hd.Rdelta_b16 = b16 ? reinterpret_cast<uint16_t*>(ws + lay.rdL16) : nullptr;
     hd.y = d_y; hd.loss = d_loss; hd.B = B; hd.C = cfg.dims[L]; hd.ld = HL; hd.k = k; hd.active_mask = active;
     if ((e = launch_head(hd, s)) != hipSuccess) return DW_ERR_HIP;
   }
@@ -143,7 +150,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
   for (int l = L; l >= 1; --l) {
     const void* dl; const void* rdl; int ldd; int64_t dstride;
     if (l == L) {
-      dl = ws + lay.dL; rdl = ws + lay.rdL; ldd = HL; dstride = (int64_t)B * HL;
+      dl = ws + (b16 ? lay.dL16 : lay.dL); rdl = ws + (b16 ? lay.rdL16 : lay.rdL); ldd = HL; dstride = (int64_t)B * HL;
     } else {
       dl = ws + lay.delta[l & 1]; rdl = ws + lay.rdelta[l & 1]; ldd = cfg.dims[l]; dstride = act_stride(l);
     }
@@ -157,12 +164,12 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.C = g + lay.woff[l - 1]; a.RC = hz + lay.woff[l - 1]; a.ldc = cfg.dims[l - 1]; a.c_wstride = lay.Pp;
       a.gb = g + lay.boff[l - 1]; a.hzb = hz + lay.boff[l - 1];
       a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
-      if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+      if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
     }
     if (l > 1) {   // data gradient through W_l, masked by the ReLU of layer l-1
       GemmArgs a{};
       a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 1; a.ldx = ldd;
-      a.Y = theta + lay.woff[l - 1]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0;
+      a.Y = weights(l); a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0;
       a.ldy = cfg.dims[l - 1];
       a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1];
       a.M = B; a.N = cfg.dims[l - 1]; a.K = cfg.dims[l];
@@ -170,7 +177,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.c_wstride = act_stride(l - 1);
       a.mask_src = act(l - 1); a.ld_mask = cfg.dims[l - 1]; a.mask_wstride = act_stride(l - 1);
       a.epi = EPI_MASK; a.k = k; a.active_mask = active;
-      if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+      if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
     }
   }
   return DW_OK;

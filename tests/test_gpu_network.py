@@ -161,3 +161,68 @@ def test_trajectory_c2_forced():
 
 def test_trajectory_c2_free_running():
     assert _run_trajectory(W.C2, W.C2.steps, forced=False) < 0.05
+
+
+# ---------------------------------------------------------------------------------------------------------
+# bf16 network (bf16 weights / activations, fp32 accumulation and state).  A value that lands next to a bf16
+# rounding boundary may round differently on the two sides (2^-8 relative on that one entry), so tensors are
+# compared in norm: ||gpu - ref||_2 <= rtol ||ref||_2 per layer, plus a loose per-entry cap.
+# ---------------------------------------------------------------------------------------------------------
+def _to_bf16_bits(x32):
+    return (torch.from_numpy(x32).to(torch.bfloat16)).cuda()
+
+
+def close_norm(gpu, ref, rtol, what, cap=30.0):
+    gpu = np.asarray(gpu, dtype=np.float64); ref = np.asarray(ref, dtype=np.float64)
+    assert np.all(np.isfinite(gpu)), what
+    nr = np.linalg.norm(ref)
+    rel = np.linalg.norm(gpu - ref) / max(nr, 1e-300)
+    parity.OBSERVED["norm " + what.split("[")[0]] = max(parity.OBSERVED.get("norm " + what.split("[")[0], 0.0), rel / rtol)
+    assert rel <= rtol, "%s: relative L2 error %.3g > %.3g" % (what, rel, rtol)
+    rms = nr / np.sqrt(max(ref.size, 1))
+    worst = np.max(np.abs(gpu - ref) / np.maximum(np.abs(ref), rms)) if ref.size else 0.0
+    assert worst <= cap * rtol, "%s: worst entry off by %.3g of max(|ref|, rms)" % (what, worst)
+
+
+# an upstream bf16 rounding flip moves a pre-activation by about 1e-4 of the layer's rms, so the band of
+# ReLU ties is wider than in fp32
+TIE_BAND_BF16 = 1e-3
+
+BF16_SHAPES = [
+    ((32, 64, 10), 16, 4),
+    ((40, 8), 9, 2),
+    ((200, 136, 72, 10), 150, 2),
+    ((64, 264, 136, 12), 70, 3),
+    ((256, 1024, 512, 10), 384, 8),
+    ((512, 2048, 1024, 10), 512, 8),       # large tiles (128 x 256)
+]
+
+
+@pytest.mark.parametrize("dims,batch,k", BF16_SHAPES)
+def test_bf16_gradient_and_hvp_match_the_oracle(dims, batch, k):
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=2000 + batch, bf16=True)
+    h, tr, theta0 = _setup(w)
+    x, y = W.minibatch_pool(w, 1, bf16_round=W.to_bf16_f32)
+    loss = torch.zeros(k, device="cuda")
+    h.worker_step(_to_bf16_bits(x[0]), torch.from_numpy(y[0]).cuda(), loss=loss)
+    ref_loss = tr.worker_step(x[0], y[0], tie_band=TIE_BAND_BF16, tie_choice=_gpu_slopes_b16(h, w))
+    print("tie units", sum(int(t.sum()) for trc in tr.traces for t in trc.ties))
+    close(loss.cpu().numpy(), ref_loss, 1e-4, "loss")
+    for i in range(k):
+        g, hz = h.get_state(B.DW_S_G, i), h.get_state(B.DW_S_HZ, i)
+        for name, sl in parity.per_layer(dims):
+            close_norm(g[sl], tr.traces[i].g[sl], 3e-4, "g[%d]/%s" % (i, name))
+            close_norm(hz[sl], tr.traces[i].hz[sl], RTOL_HV, "hz[%d]/%s" % (i, name))
+    print("worst err/bound:", {k_: v for k_, v in parity.OBSERVED.items() if k_.startswith("norm")})
+
+
+def _gpu_slopes_b16(h, w):
+    L = len(w.dims) - 1
+    out = []
+    for i in range(w.k):
+        per = []
+        for l in range(1, L):
+            bits = h.get_state(B.DW_S_ACT + l, i)
+            per.append((bits != 0) & ((bits & 0x8000) == 0))
+        out.append(per)
+    return out

@@ -5,11 +5,15 @@
 // Hutchinson estimate, Section IV-B), on the bf16 matrix cores: v_mfma_f32_32x32x16_bf16, where lane l
 // supplies 8 consecutive k of row l%32, k-chunk l/32, for both operands.
 //
-// Tiling: 256 threads = 4 waves; block tile BM x BN x 32, LDS tiles stored [row][k] with 8 k per 16 bytes
-// (row stride 40 bf16 = 80 B, which makes the 16-byte operand reads conflict-free) and double-buffered, so
-// one barrier per k-tile.  Operands whose contraction index is the slow one in memory (W in the data
-// gradient, both operands of the weight gradient) are transposed in registers on their way into LDS:
-// a thread loads a 4(row) x 8(k) patch as eight 8-byte loads and writes four 16-byte LDS rows.
+// Tiling: 512 threads = 8 waves (two per SIMD, so one wave's LDS reads hide behind the other's MFMAs);
+// block tile BM x BN x 32, double-buffered in LDS with one barrier per k-tile.  Every global load and LDS
+// store is a plain 16-byte copy along the axis that is contiguous in memory:
+//   - an operand whose contraction index k is contiguous is staged [row][k] (row stride 40 bf16 = 80 B, so
+//     the 16-byte operand reads are conflict-free);
+//   - an operand stored k-major (W in the data gradient, both operands of the weight gradient) is staged
+//     [k][row] as it lies in memory and transposed by the LDS itself on the way out (ds_read_b64_tr_b16:
+//     within 16 lanes, lane i receives element i%4 of the 8-byte rows addressed by lanes i/4, 4+i/4, 8+i/4,
+//     12+i/4), which hands each lane its 4 consecutive k for one row.
 // The +-1 operand V (z reshaped like W) is expanded from the sign bits of z in the loader.
 #include "dw_internal.h"
 
@@ -17,12 +21,14 @@ namespace dw {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short v4i16 __attribute__((ext_vector_type(4)));
 
 namespace b16 {
 
 constexpr int BK = 32;          // k per tile (two MFMA k-steps of 16)
-constexpr int LDK = 40;         // LDS row stride in bf16 elements
-constexpr int NT = 256;
+constexpr int LDK = 40;         // row stride (elements) of a [row][k] tile
+constexpr int KPAD = 32;        // row padding (elements) of a [k][row] tile
+constexpr int NT = 512;
 
 enum RyMode { RY_NONE = 0, RY_MEM = 1, RY_BITS = 2 };
 
@@ -37,139 +43,97 @@ __device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float((uint
 __device__ __forceinline__ uint32_t pm1_pair(uint32_t b_lo, uint32_t b_hi) {
   return 0xBF80BF80u ^ (b_lo << 15) ^ (b_hi << 31);
 }
+__device__ __forceinline__ uint4 pm1_x8(uint32_t b) {
+  uint4 o;
+  o.x = pm1_pair(b & 1u, (b >> 1) & 1u); o.y = pm1_pair((b >> 2) & 1u, (b >> 3) & 1u);
+  o.z = pm1_pair((b >> 4) & 1u, (b >> 5) & 1u); o.w = pm1_pair((b >> 6) & 1u, (b >> 7) & 1u);
+  return o;
+}
 
-// One operand tile of R rows x BK k, loaded by NTH threads (thread index tl in [0, NTH)).
-//   KC = true : source rows are k-contiguous; unit = 8 k of one row (one 16-byte load, one 16-byte LDS store)
-//   KC = false: source is k-major ([k][row]); unit = patch of 4 rows x 8 k (eight 8-byte loads, register
-//               transpose, four 16-byte LDS stores)
+// One operand tile: R rows (the non-contraction index) x BK, moved by NTH threads in 16-byte units.
+//   KC = true : memory is [row][k]; unit u = 8 k of row u/4; LDS [R][LDK]
+//   KC = false: memory is [k][row]; unit u = 8 rows at k = u/(R/8); LDS [BK][R+KPAD]
 template <int R, int NTH, bool KC>
-struct Loader {
-  static constexpr int UNITS = KC ? R * (BK / 8) : (R / 4) * (BK / 8);
+struct Tile {
+  static constexpr int UNITS = R * BK / 8;
   static constexpr int UPT = (UNITS + NTH - 1) / NTH;
-  static constexpr int REGS = KC ? UPT : UPT * 4;          // uint4 registers per thread
+  static constexpr int LDS_ELEMS = KC ? R * LDK : BK * (R + KPAD);
+  static constexpr int LDR = R + KPAD;
 
-  __device__ static __forceinline__ void load(const uint16_t* __restrict__ src, int ld, int r0, int k0, int Rmax,
-                                              int K, int tl, uint4 (&reg)[REGS]) {
+  int64_t goff[UPT];      // element offset of the unit in the source at k0 = 0
+  int loff[UPT];          // element offset of the unit in the LDS tile
+  int kk[UPT];            // k index of the unit inside the tile
+  bool ok[UPT];           // row (KC) or column group (!KC) is inside the operand
+
+  __device__ __forceinline__ void init(int tl, int ld, int r0, int Rmax) {
 #pragma unroll
     for (int u = 0; u < UPT; ++u) {
       const int unit = u * NTH + tl;
       if (KC) {
         const int row = unit / (BK / 8), kc = (unit % (BK / 8)) * 8;
-        const bool ok = unit < UNITS && (r0 + row) < Rmax && (k0 + kc) < K;
-        reg[u] = ok ? *reinterpret_cast<const uint4*>(src + (int64_t)(r0 + row) * ld + (k0 + kc))
-                    : make_uint4(0, 0, 0, 0);
+        ok[u] = unit < UNITS && (r0 + row) < Rmax;
+        goff[u] = (int64_t)(r0 + row) * ld + kc;
+        loff[u] = row * LDK + kc;
+        kk[u] = kc;
       } else {
-        const int rq = (unit % (R / 4)) * 4, kq = (unit / (R / 4)) * 8;
-        const bool okr = unit < UNITS && (r0 + rq) < Rmax;
-        uint2 v[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const bool ok = okr && (k0 + kq + i) < K;
-          v[i] = ok ? *reinterpret_cast<const uint2*>(src + (int64_t)(k0 + kq + i) * ld + (r0 + rq)) : make_uint2(0, 0);
-        }
-        reg[u * 4 + 0] = make_uint4(v[0].x, v[0].y, v[1].x, v[1].y);
-        reg[u * 4 + 1] = make_uint4(v[2].x, v[2].y, v[3].x, v[3].y);
-        reg[u * 4 + 2] = make_uint4(v[4].x, v[4].y, v[5].x, v[5].y);
-        reg[u * 4 + 3] = make_uint4(v[6].x, v[6].y, v[7].x, v[7].y);
+        const int krow = unit / (R / 8), c = (unit % (R / 8)) * 8;
+        ok[u] = unit < UNITS && (r0 + c) < Rmax;
+        goff[u] = (int64_t)krow * ld + (r0 + c);
+        loff[u] = krow * LDR + c;
+        kk[u] = krow;
       }
     }
   }
-
-  // sign bits of the elements load() would read: KC: 8 bits per unit; !KC: 8 nibbles (k rows) per unit
-  __device__ static __forceinline__ void load_bits(const uint32_t* __restrict__ zb, int64_t z_off, int ld, int r0,
-                                                   int k0, int Rmax, int K, int tl, uint32_t (&reg)[UPT]) {
+  __device__ __forceinline__ int64_t at(int u, int k0, int ld) const {
+    return goff[u] + (KC ? (int64_t)k0 : (int64_t)k0 * ld);
+  }
+  __device__ __forceinline__ void load(const uint16_t* __restrict__ src, int ld, int k0, int K, uint4 (&reg)[UPT]) const {
+#pragma unroll
+    for (int u = 0; u < UPT; ++u)
+      reg[u] = (ok[u] && (k0 + kk[u]) < K) ? *reinterpret_cast<const uint4*>(src + at(u, k0, ld))
+                                           : make_uint4(0, 0, 0, 0);
+  }
+  __device__ __forceinline__ void load_bits(const uint32_t* __restrict__ zb, int64_t z_off, int ld, int k0, int K,
+                                            uint32_t (&reg)[UPT]) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u) {
-      const int unit = u * NTH + tl;
-      if (KC) {
-        const int row = unit / (BK / 8), kc = (unit % (BK / 8)) * 8;
-        const bool ok = unit < UNITS && (r0 + row) < Rmax && (k0 + kc) < K;
-        const int64_t off = z_off + (int64_t)(r0 + row) * ld + (k0 + kc);
-        reg[u] = ok ? (zb[off >> 5] >> (off & 31)) & 0xFFu : 0u;
-      } else {
-        const int rq = (unit % (R / 4)) * 4, kq = (unit / (R / 4)) * 8;
-        const bool okr = unit < UNITS && (r0 + rq) < Rmax;
-        uint32_t packed = 0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const bool ok = okr && (k0 + kq + i) < K;
-          const int64_t off = z_off + (int64_t)(k0 + kq + i) * ld + (r0 + rq);
-          const uint32_t nib = ok ? (zb[off >> 5] >> (off & 31)) & 0xFu : 0u;
-          packed |= nib << (4 * i);
-        }
-        reg[u] = packed;
-      }
+      const int64_t off = z_off + at(u, k0, ld);
+      reg[u] = (ok[u] && (k0 + kk[u]) < K) ? (zb[off >> 5] >> (off & 31)) & 0xFFu : 0u;
     }
   }
-
-  // v[i] = (elements of rows rq..rq+3 at k = kq+i) as two dwords; writes rows rq+j, j = 0..3
-  __device__ static __forceinline__ void store_patch(uint16_t (*lds)[LDK], int rq, int kq, const uint32_t (&lo)[8],
-                                                     const uint32_t (&hi)[8]) {
-    // lo[i] holds rows (rq, rq+1) at k_i, hi[i] rows (rq+2, rq+3)
-    uint4 o0, o1, o2, o3;
-    o0.x = __builtin_amdgcn_perm(lo[1], lo[0], 0x05040100u); o1.x = __builtin_amdgcn_perm(lo[1], lo[0], 0x07060302u);
-    o0.y = __builtin_amdgcn_perm(lo[3], lo[2], 0x05040100u); o1.y = __builtin_amdgcn_perm(lo[3], lo[2], 0x07060302u);
-    o0.z = __builtin_amdgcn_perm(lo[5], lo[4], 0x05040100u); o1.z = __builtin_amdgcn_perm(lo[5], lo[4], 0x07060302u);
-    o0.w = __builtin_amdgcn_perm(lo[7], lo[6], 0x05040100u); o1.w = __builtin_amdgcn_perm(lo[7], lo[6], 0x07060302u);
-    o2.x = __builtin_amdgcn_perm(hi[1], hi[0], 0x05040100u); o3.x = __builtin_amdgcn_perm(hi[1], hi[0], 0x07060302u);
-    o2.y = __builtin_amdgcn_perm(hi[3], hi[2], 0x05040100u); o3.y = __builtin_amdgcn_perm(hi[3], hi[2], 0x07060302u);
-    o2.z = __builtin_amdgcn_perm(hi[5], hi[4], 0x05040100u); o3.z = __builtin_amdgcn_perm(hi[5], hi[4], 0x07060302u);
-    o2.w = __builtin_amdgcn_perm(hi[7], hi[6], 0x05040100u); o3.w = __builtin_amdgcn_perm(hi[7], hi[6], 0x07060302u);
-    *reinterpret_cast<uint4*>(&lds[rq + 0][kq]) = o0;
-    *reinterpret_cast<uint4*>(&lds[rq + 1][kq]) = o1;
-    *reinterpret_cast<uint4*>(&lds[rq + 2][kq]) = o2;
-    *reinterpret_cast<uint4*>(&lds[rq + 3][kq]) = o3;
+  __device__ __forceinline__ void store(uint16_t* lds, const uint4 (&reg)[UPT], int tl) const {
+#pragma unroll
+    for (int u = 0; u < UPT; ++u)
+      if (u * NTH + tl < UNITS) *reinterpret_cast<uint4*>(lds + loff[u]) = reg[u];
   }
-
-  __device__ static __forceinline__ void store(uint16_t (*lds)[LDK], int tl, const uint4 (&reg)[REGS]) {
+  __device__ __forceinline__ void store_bits(uint16_t* lds, const uint32_t (&reg)[UPT], int tl) const {
 #pragma unroll
-    for (int u = 0; u < UPT; ++u) {
-      const int unit = u * NTH + tl;
-      if (unit >= UNITS) continue;
-      if (KC) {
-        const int row = unit / (BK / 8), kc = (unit % (BK / 8)) * 8;
-        *reinterpret_cast<uint4*>(&lds[row][kc]) = reg[u];
-      } else {
-        const int rq = (unit % (R / 4)) * 4, kq = (unit / (R / 4)) * 8;
-        const uint32_t lo[8] = {reg[u * 4 + 0].x, reg[u * 4 + 0].z, reg[u * 4 + 1].x, reg[u * 4 + 1].z,
-                                reg[u * 4 + 2].x, reg[u * 4 + 2].z, reg[u * 4 + 3].x, reg[u * 4 + 3].z};
-        const uint32_t hi[8] = {reg[u * 4 + 0].y, reg[u * 4 + 0].w, reg[u * 4 + 1].y, reg[u * 4 + 1].w,
-                                reg[u * 4 + 2].y, reg[u * 4 + 2].w, reg[u * 4 + 3].y, reg[u * 4 + 3].w};
-        store_patch(lds, rq, kq, lo, hi);
-      }
-    }
-  }
-
-  __device__ static __forceinline__ void store_bits(uint16_t (*lds)[LDK], int tl, const uint32_t (&reg)[UPT]) {
-#pragma unroll
-    for (int u = 0; u < UPT; ++u) {
-      const int unit = u * NTH + tl;
-      if (unit >= UNITS) continue;
-      if (KC) {
-        const int row = unit / (BK / 8), kc = (unit % (BK / 8)) * 8;
-        const uint32_t b = reg[u];
-        uint4 o;
-        o.x = pm1_pair(b & 1u, (b >> 1) & 1u); o.y = pm1_pair((b >> 2) & 1u, (b >> 3) & 1u);
-        o.z = pm1_pair((b >> 4) & 1u, (b >> 5) & 1u); o.w = pm1_pair((b >> 6) & 1u, (b >> 7) & 1u);
-        *reinterpret_cast<uint4*>(&lds[row][kc]) = o;
-      } else {
-        const int rq = (unit % (R / 4)) * 4, kq = (unit / (R / 4)) * 8;
-        uint32_t lo[8], hi[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const uint32_t nib = (reg[u] >> (4 * i)) & 0xFu;
-          lo[i] = pm1_pair(nib & 1u, (nib >> 1) & 1u);
-          hi[i] = pm1_pair((nib >> 2) & 1u, (nib >> 3) & 1u);
-        }
-        store_patch(lds, rq, kq, lo, hi);
-      }
-    }
+    for (int u = 0; u < UPT; ++u)
+      if (u * NTH + tl < UNITS) *reinterpret_cast<uint4*>(lds + loff[u]) = pm1_x8(reg[u]);
   }
 };
 
+// MFMA operand of one lane: 8 consecutive k (k-step ks, chunk lane/32) of tile row `row0 + lane%32`
+template <int R, bool KC>
+__device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int row0, int ks, int lane) {
+  if (KC) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(
+        lds + (row0 + (lane & 31)) * LDK + ks * 16 + (lane >> 5) * 8));
+  } else {
+    constexpr int LDR = R + KPAD;
+    const int s = lane & 15;
+    const uint16_t* p = lds + (ks * 16 + (lane >> 5) * 8 + (s >> 2)) * LDR + row0 + ((lane >> 4) & 1) * 16 + (s & 3) * 4;
+    typedef __attribute__((address_space(3))) v4i16 lds_v4;
+    struct { v4i16 a, b; } r;
+    r.a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4*)(p));
+    r.b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4*)(p + 4 * LDR));
+    return __builtin_bit_cast(bf16x8, r);
+  }
+}
+
 template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI>
 __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
-  static_assert(WM * WN == 4, "four waves per block");
+  static_assert(WM * WN == NT / 64, "eight waves per block");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
   const int worker = blockIdx.y;
@@ -183,31 +147,30 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   const int wm0 = (wave % WM) * (BM / WM), wn0 = (wave / WM) * (BN / WN);
   const int l32 = lane & 31, lhalf = lane >> 5;
 
+  // X and RX are each moved by one half of the block (whole waves); Y and RY by all threads
+  constexpr int XTH = HAS_RX ? NT / 2 : NT;
+  using TX = Tile<BM, XTH, X_KC>;
+  using TY = Tile<BN, NT, Y_KC>;
+  constexpr int X_ELEMS = TX::LDS_ELEMS, Y_ELEMS = TY::LDS_ELEMS;
+  constexpr int STAGE = X_ELEMS * (HAS_RX ? 2 : 1) + Y_ELEMS * (RYM != RY_NONE ? 2 : 1);
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-  // per stage: Xs[BM], RXs[BM] (if HAS_RX), Ys[BN], RYs[BN] (if RYM), each [rows][LDK]
-  constexpr int X_ROWS = BM * (HAS_RX ? 2 : 1);
-  constexpr int Y_ROWS = BN * (RYM != RY_NONE ? 2 : 1);
-  constexpr int STAGE = (X_ROWS + Y_ROWS) * LDK;
-  auto Xs = [&](int st) { return reinterpret_cast<uint16_t(*)[LDK]>(smem + st * STAGE); };
-  auto RXs = [&](int st) { return reinterpret_cast<uint16_t(*)[LDK]>(smem + st * STAGE + BM * LDK); };
-  auto Ys = [&](int st) { return reinterpret_cast<uint16_t(*)[LDK]>(smem + st * STAGE + X_ROWS * LDK); };
-  auto RYs = [&](int st) { return reinterpret_cast<uint16_t(*)[LDK]>(smem + st * STAGE + (X_ROWS + BN) * LDK); };
+  auto Xs = [&](int st) { return smem + st * STAGE; };
+  auto RXs = [&](int st) { return smem + st * STAGE + X_ELEMS; };
+  auto Ys = [&](int st) { return smem + st * STAGE + X_ELEMS * (HAS_RX ? 2 : 1); };
+  auto RYs = [&](int st) { return smem + st * STAGE + X_ELEMS * (HAS_RX ? 2 : 1) + Y_ELEMS; };
 
-  const uint16_t* X = reinterpret_cast<const uint16_t*>(a.X) + (int64_t)worker * a.x_wstride;
-  const uint16_t* RX = HAS_RX ? reinterpret_cast<const uint16_t*>(a.RX) + (int64_t)worker * a.x_wstride : nullptr;
+  const bool second_half = HAS_RX && tid >= XTH;
+  const int xtl = second_half ? tid - XTH : tid;
+  const uint16_t* xsrc = reinterpret_cast<const uint16_t*>(second_half ? a.RX : a.X) + (int64_t)worker * a.x_wstride;
   const uint16_t* Y = reinterpret_cast<const uint16_t*>(a.Y) + (int64_t)worker * a.y_wstride;
   const uint16_t* RY = RYM == RY_MEM ? reinterpret_cast<const uint16_t*>(a.RY) + (int64_t)worker * a.y_wstride : nullptr;
   const uint32_t* zb = a.zbits + (int64_t)worker * a.z_stride;
 
-  // X and RX are loaded by one half of the block each (the halves are whole waves); Y and RY by all threads
-  constexpr int XTH = HAS_RX ? NT / 2 : NT;
-  using LX = Loader<BM, XTH, X_KC>;
-  using LY = Loader<BN, NT, Y_KC>;
-  const bool second_half = HAS_RX && tid >= XTH;
-  const int xtl = second_half ? tid - XTH : tid;
-  const uint16_t* xsrc = second_half ? RX : X;
-  uint4 xr[LX::REGS], yr[LY::REGS], ryr[LY::REGS];
-  uint32_t zr[LY::UPT];
+  TX tx; TY ty;
+  tx.init(xtl, a.ldx, row0, a.M);
+  ty.init(tid, a.ldy, col0, a.N);
+  uint4 xr[TX::UPT], yr[TY::UPT], ryr[TY::UPT];
+  uint32_t zr[TY::UPT];
 
   floatx16 acc[TM][TN], racc[TM][TN];
 #pragma unroll
@@ -221,16 +184,16 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   const int nkt = (a.K + BK - 1) / BK;
   auto fetch = [&](int kt) {
     const int k0 = kt * BK;
-    LX::load(xsrc, a.ldx, row0, k0, a.M, a.K, xtl, xr);
-    LY::load(Y, a.ldy, col0, k0, a.N, a.K, tid, yr);
-    if (RYM == RY_MEM) LY::load(RY, a.ldy, col0, k0, a.N, a.K, tid, ryr);
-    if (RYM == RY_BITS) LY::load_bits(zb, a.z_off, a.ldy, col0, k0, a.N, a.K, tid, zr);
+    tx.load(xsrc, a.ldx, k0, a.K, xr);
+    ty.load(Y, a.ldy, k0, a.K, yr);
+    if (RYM == RY_MEM) ty.load(RY, a.ldy, k0, a.K, ryr);
+    if (RYM == RY_BITS) ty.load_bits(zb, a.z_off, a.ldy, k0, a.K, zr);
   };
   auto stash = [&](int st) {
-    LX::store(second_half ? RXs(st) : Xs(st), xtl, xr);
-    LY::store(Ys(st), tid, yr);
-    if (RYM == RY_MEM) LY::store(RYs(st), tid, ryr);
-    if (RYM == RY_BITS) LY::store_bits(RYs(st), tid, zr);
+    tx.store(second_half ? RXs(st) : Xs(st), xr, xtl);
+    ty.store(Ys(st), yr, tid);
+    if (RYM == RY_MEM) ty.store(RYs(st), ryr, tid);
+    if (RYM == RY_BITS) ty.store_bits(RYs(st), zr, tid);
   };
 
   fetch(0);
@@ -242,41 +205,51 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     const int cur = kt & 1;
     if (kt + 1 < nkt) stash(cur ^ 1);
     if (kt + 2 < nkt) fetch(kt + 2);
+    const uint16_t* xs = Xs(cur);
+    const uint16_t* rxs = RXs(cur);
+    const uint16_t* ys = Ys(cur);
+    const uint16_t* rys = RYs(cur);
 
-    if (EPI == EPI_WGRAD && tn == 0 && tid < BM) {
-      const uint16_t(*xs)[LDK] = Xs(cur);
-      const uint16_t(*rxs)[LDK] = RXs(cur);
+    if (EPI == EPI_WGRAD && tn == 0 && tid < BM) {      // bias gradients: sums over the minibatch (X is [k][m])
 #pragma unroll
-      for (int kk = 0; kk < BK; ++kk) {
-        gb_acc += bf2f(xs[tid][kk]);
-        if (HAS_RX) hzb_acc += bf2f(rxs[tid][kk]);
+      for (int kq = 0; kq < BK; ++kq) {
+        gb_acc += bf2f(xs[kq * TX::LDR + tid]);
+        if (HAS_RX) hzb_acc += bf2f(rxs[kq * TX::LDR + tid]);
       }
     }
 
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      const int kc = ks * 16 + lhalf * 8;
       bf16x8 xa[TM], rxa[TM], yb[TN], ryb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        xa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Xs(cur)[wm0 + i * 32 + l32][kc]));
-        if (HAS_RX)
-          rxa[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&RXs(cur)[wm0 + i * 32 + l32][kc]));
+        xa[i] = frag<BM, X_KC>(xs, wm0 + i * 32, ks, lane);
+        if (HAS_RX) rxa[i] = frag<BM, X_KC>(rxs, wm0 + i * 32, ks, lane);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        yb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Ys(cur)[wn0 + j * 32 + l32][kc]));
-        if (RYM != RY_NONE)
-          ryb[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&RYs(cur)[wn0 + j * 32 + l32][kc]));
+        yb[j] = frag<BN, Y_KC>(ys, wn0 + j * 32, ks, lane);
+        if (RYM != RY_NONE) ryb[j] = frag<BN, Y_KC>(rys, wn0 + j * 32, ks, lane);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+        for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], yb[j], acc[i][j], 0, 0, 0);
-          if (HAS_RX) racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rxa[i], yb[j], racc[i][j], 0, 0, 0);
-          if (RYM != RY_NONE) racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], ryb[j], racc[i][j], 0, 0, 0);
-        }
+      if (HAS_RX) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rxa[i], yb[j], racc[i][j], 0, 0, 0);
+      }
+      if (RYM != RY_NONE) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], ryb[j], racc[i][j], 0, 0, 0);
+      }
     }
     __syncthreads();
   }
@@ -330,16 +303,13 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   }
 }
 
-template <int BM, int BN, bool HAS_RX, int RYM>
-constexpr int smem_bytes() {
-  return 2 * (BM * (HAS_RX ? 2 : 1) + BN * (RYM != RY_NONE ? 2 : 1)) * LDK * 2;
-}
-
 template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   const dim3 grid((unsigned)tiles, (unsigned)a.k), block(NT);
-  constexpr int smem = smem_bytes<BM, BN, RX, RYM>();
+  constexpr int XTH = RX ? NT / 2 : NT;
+  constexpr int smem = 2 * 2 * (Tile<BM, XTH, XKC>::LDS_ELEMS * (RX ? 2 : 1) +
+                                Tile<BN, NT, YKC>::LDS_ELEMS * (RYM != RY_NONE ? 2 : 1));
   auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>;
   static bool configured = false;        // raise the dynamic LDS limit once per instantiation
   if (!configured) {
@@ -371,11 +341,11 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : a.epi == EPI_MASK ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);
-  if (a.N <= 32) return b16::launch_shape<128, 32, 4, 1>(a, s);
-  if (a.M <= 32) return b16::launch_shape<32, 128, 1, 4>(a, s);
+  if (a.N <= 32) return b16::launch_shape<256, 32, 8, 1>(a, s);
+  if (a.M <= 32) return b16::launch_shape<32, 256, 1, 8>(a, s);
   const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 255) / 256) * a.k;
-  if (big_tiles >= 256) return b16::launch_shape<128, 256, 2, 2>(a, s);
-  return b16::launch_shape<64, 64, 2, 2>(a, s);
+  if (big_tiles >= 256) return b16::launch_shape<128, 256, 2, 4>(a, s);
+  return b16::launch_shape<64, 128, 2, 4>(a, s);
 }
 
 }  // namespace dw

@@ -93,23 +93,30 @@ struct Tile {
       reg[u] = (ok[u] && (k0 + kk[u]) < K) ? *reinterpret_cast<const uint4*>(src + at(u, k0, ld))
                                            : make_uint4(0, 0, 0, 0);
   }
+  // the raw 32-bit word holding the unit's 8 sign bits; the shift is applied when the tile is stored, so
+  // that nothing waits on this load inside the prefetch
   __device__ __forceinline__ void load_bits(const uint32_t* __restrict__ zb, int64_t z_off, int ld, int k0, int K,
                                             uint32_t (&reg)[UPT]) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u) {
       const int64_t off = z_off + at(u, k0, ld);
-      reg[u] = (ok[u] && (k0 + kk[u]) < K) ? (zb[off >> 5] >> (off & 31)) & 0xFFu : 0u;
+      reg[u] = (ok[u] && (k0 + kk[u]) < K) ? zb[off >> 5] : 0u;
     }
+  }
+  __device__ __forceinline__ int bit_shift(int u, int64_t z_off, int k0, int ld) const {
+    return (int)((z_off + at(u, k0, ld)) & 31);
   }
   __device__ __forceinline__ void store(uint16_t* lds, const uint4 (&reg)[UPT], int tl) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u)
       if (u * NTH + tl < UNITS) *reinterpret_cast<uint4*>(lds + loff[u]) = reg[u];
   }
-  __device__ __forceinline__ void store_bits(uint16_t* lds, const uint32_t (&reg)[UPT], int tl) const {
+  __device__ __forceinline__ void store_bits(uint16_t* lds, const uint32_t (&reg)[UPT], int tl, int64_t z_off,
+                                             int k0, int ld) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u)
-      if (u * NTH + tl < UNITS) *reinterpret_cast<uint4*>(lds + loff[u]) = pm1_x8(reg[u]);
+      if (u * NTH + tl < UNITS)
+        *reinterpret_cast<uint4*>(lds + loff[u]) = pm1_x8((reg[u] >> bit_shift(u, z_off, k0, ld)) & 0xFFu);
   }
 };
 
@@ -136,11 +143,18 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   static_assert(WM * WN == NT / 64, "eight waves per block");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
-  const int worker = blockIdx.y;
-  if (!((a.active_mask >> worker) & 1ull)) return;
-
+  // Workgroups are handed to the 8 XCDs round-robin by their index.  The index is remapped so that each XCD
+  // works through a contiguous range of (worker, tile) pairs: the blocks that share a W tile or a worker's
+  // activations then run on the same XCD at about the same time and meet in its L2.
   const int tiles_m = (a.M + BM - 1) / BM;
-  const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+  const int tiles = tiles_m * ((a.N + BN - 1) / BN);
+  const int per_xcd = gridDim.x >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= tiles * a.k) return;
+  const int worker = logical / tiles;
+  if (!((a.active_mask >> worker) & 1ull)) return;
+  const int tile = logical - worker * tiles;
+  const int tm = tile % tiles_m, tn = tile / tiles_m;
   const int row0 = tm * BM, col0 = tn * BN;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -189,21 +203,21 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     if (RYM == RY_MEM) ty.load(RY, a.ldy, k0, a.K, ryr);
     if (RYM == RY_BITS) ty.load_bits(zb, a.z_off, a.ldy, k0, a.K, zr);
   };
-  auto stash = [&](int st) {
+  auto stash = [&](int st, int kt) {       // kt: the k-tile held in the registers
     tx.store(second_half ? RXs(st) : Xs(st), xr, xtl);
     ty.store(Ys(st), yr, tid);
     if (RYM == RY_MEM) ty.store(RYs(st), ryr, tid);
-    if (RYM == RY_BITS) ty.store_bits(RYs(st), zr, tid);
+    if (RYM == RY_BITS) ty.store_bits(RYs(st), zr, tid, a.z_off, kt * BK, a.ldy);
   };
 
   fetch(0);
-  stash(0);
+  stash(0, 0);
   if (nkt > 1) fetch(1);
   __syncthreads();
 
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nkt) stash(cur ^ 1);
+    if (kt + 1 < nkt) stash(cur ^ 1, kt + 1);
     if (kt + 2 < nkt) fetch(kt + 2);
     const uint16_t* xs = Xs(cur);
     const uint16_t* rxs = RXs(cur);
@@ -306,7 +320,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
 template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  const dim3 grid((unsigned)tiles, (unsigned)a.k), block(NT);
+  const dim3 grid((unsigned)((tiles * a.k + 7) / 8 * 8)), block(NT);
   constexpr int XTH = RX ? NT / 2 : NT;
   constexpr int smem = 2 * 2 * (Tile<BM, XTH, XKC>::LDS_ELEMS * (RX ? 2 : 1) +
                                 Tile<BN, NT, YKC>::LDS_ELEMS * (RYM != RY_NONE ? 2 : 1));

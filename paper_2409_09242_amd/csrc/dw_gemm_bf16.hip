@@ -60,63 +60,73 @@ struct Tile {
   static constexpr int LDS_ELEMS = KC ? R * LDK : BK * (R + KPAD);
   static constexpr int LDR = R + KPAD;
 
-  int64_t goff[UPT];      // element offset of the unit in the source at k0 = 0
-  int loff[UPT];          // element offset of the unit in the LDS tile
-  int kk[UPT];            // k index of the unit inside the tile
-  bool ok[UPT];           // row (KC) or column group (!KC) is inside the operand
+  // Unit u of this thread is unit number u*NTH + tl of the tile; a thread's units differ by constants, so
+  // only the first one's offsets are kept.
+  static constexpr bool FULL = UNITS % NTH == 0;                          // every thread owns UPT units
+  static constexpr int ROWS_PER_PASS = KC ? NTH / (BK / 8) : 0;           // KC: rows between a thread's units
+  static constexpr int K_PER_PASS = KC ? 0 : (NTH >= R / 8 ? NTH / (R / 8) : 0);   // !KC: k rows between them
+  int goff0;              // element offset of unit 0 in the source at k0 = 0 (an operand has < 2^31 elements)
+  int loff0;              // element offset of unit 0 in the LDS tile
+  int kk0;                // k index of unit 0 inside the tile
+  unsigned okmask;        // bit u: unit u exists and its row (KC) / column group (!KC) is inside the operand
 
   __device__ __forceinline__ void init(int tl, int ld, int r0, int Rmax) {
+    okmask = 0;
+    if (KC) {
+      const int row = tl / (BK / 8), kc = (tl % (BK / 8)) * 8;
+      goff0 = (r0 + row) * ld + kc; loff0 = row * LDK + kc; kk0 = kc;
 #pragma unroll
-    for (int u = 0; u < UPT; ++u) {
-      const int unit = u * NTH + tl;
-      if (KC) {
-        const int row = unit / (BK / 8), kc = (unit % (BK / 8)) * 8;
-        ok[u] = unit < UNITS && (r0 + row) < Rmax;
-        goff[u] = (int64_t)(r0 + row) * ld + kc;
-        loff[u] = row * LDK + kc;
-        kk[u] = kc;
-      } else {
-        const int krow = unit / (R / 8), c = (unit % (R / 8)) * 8;
-        ok[u] = unit < UNITS && (r0 + c) < Rmax;
-        goff[u] = (int64_t)krow * ld + (r0 + c);
-        loff[u] = krow * LDR + c;
-        kk[u] = krow;
-      }
+      for (int u = 0; u < UPT; ++u)
+        if ((FULL || u * NTH + tl < UNITS) && (r0 + row + u * ROWS_PER_PASS) < Rmax) okmask |= 1u << u;
+    } else {
+      const int krow = tl / (R / 8), c = (tl % (R / 8)) * 8;
+      goff0 = krow * ld + (r0 + c); loff0 = krow * LDR + c; kk0 = krow;
+#pragma unroll
+      for (int u = 0; u < UPT; ++u)
+        if ((FULL || u * NTH + tl < UNITS) && (r0 + c) < Rmax) okmask |= 1u << u;
     }
   }
-  __device__ __forceinline__ int64_t at(int u, int k0, int ld) const {
-    return goff[u] + (KC ? (int64_t)k0 : (int64_t)k0 * ld);
+  __device__ __forceinline__ int kk(int u) const { return KC ? kk0 : kk0 + u * K_PER_PASS; }
+  __device__ __forceinline__ int loff(int u) const {
+    return KC ? loff0 + u * ROWS_PER_PASS * LDK : loff0 + u * K_PER_PASS * LDR;
   }
+  __device__ __forceinline__ bool ok(int u, int k0, int K) const { return ((okmask >> u) & 1u) && (k0 + kk(u)) < K; }
+  __device__ __forceinline__ int64_t at(int u, int k0, int ld) const {
+    return KC ? (int64_t)goff0 + (int64_t)u * ROWS_PER_PASS * ld + k0
+              : (int64_t)goff0 + (int64_t)(u * K_PER_PASS + k0) * ld;
+  }
+  // Loads are unconditional (a unit outside the operand reads the operand's first elements instead), so the
+  // prefetch is free of branches and of waits; such a unit is zeroed when it is copied into LDS.
   __device__ __forceinline__ void load(const uint16_t* __restrict__ src, int ld, int k0, int K, uint4 (&reg)[UPT]) const {
 #pragma unroll
-    for (int u = 0; u < UPT; ++u)
-      reg[u] = (ok[u] && (k0 + kk[u]) < K) ? *reinterpret_cast<const uint4*>(src + at(u, k0, ld))
-                                           : make_uint4(0, 0, 0, 0);
+    for (int u = 0; u < UPT; ++u) {
+      const int64_t o = ok(u, k0, K) ? at(u, k0, ld) : 0;
+      reg[u] = *reinterpret_cast<const uint4*>(src + o);
+    }
   }
-  // the raw 32-bit word holding the unit's 8 sign bits; the shift is applied when the tile is stored, so
-  // that nothing waits on this load inside the prefetch
+  // the raw 32-bit word holding the unit's 8 sign bits; the bits are extracted when the tile is stored
   __device__ __forceinline__ void load_bits(const uint32_t* __restrict__ zb, int64_t z_off, int ld, int k0, int K,
                                             uint32_t (&reg)[UPT]) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u) {
-      const int64_t off = z_off + at(u, k0, ld);
-      reg[u] = (ok[u] && (k0 + kk[u]) < K) ? zb[off >> 5] : 0u;
+      const int64_t off = z_off + (ok(u, k0, K) ? at(u, k0, ld) : 0);
+      reg[u] = zb[off >> 5];
     }
   }
-  __device__ __forceinline__ int bit_shift(int u, int64_t z_off, int k0, int ld) const {
-    return (int)((z_off + at(u, k0, ld)) & 31);
-  }
-  __device__ __forceinline__ void store(uint16_t* lds, const uint4 (&reg)[UPT], int tl) const {
+  __device__ __forceinline__ void store(uint16_t* lds, const uint4 (&reg)[UPT], int tl, int k0, int K) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u)
-      if (u * NTH + tl < UNITS) *reinterpret_cast<uint4*>(lds + loff[u]) = reg[u];
+      if (FULL || u * NTH + tl < UNITS)
+        *reinterpret_cast<uint4*>(lds + loff(u)) = ok(u, k0, K) ? reg[u] : make_uint4(0, 0, 0, 0);
   }
   __device__ __forceinline__ void store_bits(uint16_t* lds, const uint32_t (&reg)[UPT], int tl, int64_t z_off,
                                              int k0, int ld) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u)
-      if (u * NTH + tl < UNITS)
-        *reinterpret_cast<uint4*>(lds + loff[u]) = pm1_x8((reg[u] >> bit_shift(u, z_off, k0, ld)) & 0xFFu);
+      if (FULL || u * NTH + tl < UNITS) {
+        const int sh = (int)((z_off + at(u, k0, ld)) & 31);
+        *reinterpret_cast<uint4*>(lds + loff(u)) = pm1_x8((reg[u] >> sh) & 0xFFu);
+      }
   }
 };
 
@@ -204,10 +214,71 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     if (RYM == RY_BITS) ty.load_bits(zb, a.z_off, a.ldy, k0, a.K, zr);
   };
   auto stash = [&](int st, int kt) {       // kt: the k-tile held in the registers
-    tx.store(second_half ? RXs(st) : Xs(st), xr, xtl);
-    ty.store(Ys(st), yr, tid);
-    if (RYM == RY_MEM) ty.store(RYs(st), ryr, tid);
+    tx.store(second_half ? RXs(st) : Xs(st), xr, xtl, kt * BK, a.K);
+    ty.store(Ys(st), yr, tid, kt * BK, a.K);
+    if (RYM == RY_MEM) ty.store(RYs(st), ryr, tid, kt * BK, a.K);
     if (RYM == RY_BITS) ty.store_bits(RYs(st), zr, tid, a.z_off, kt * BK, a.ldy);
+  };
+
+  // operand registers of one k-step; two sets alternate so that the LDS reads of the next k-step are in
+  // flight while the matrix cores work on the current one
+  struct Frags { bf16x8 xa[TM], rxa[TM], yb[TN], ryb[TN]; };
+  auto read_frags = [&](Frags& f, int st, int ks) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      f.xa[i] = frag<BM, X_KC>(Xs(st), wm0 + i * 32, ks, lane);
+      if (HAS_RX) f.rxa[i] = frag<BM, X_KC>(RXs(st), wm0 + i * 32, ks, lane);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      f.yb[j] = frag<BN, Y_KC>(Ys(st), wn0 + j * 32, ks, lane);
+      if (RYM != RY_NONE) f.ryb[j] = frag<BN, Y_KC>(RYs(st), wn0 + j * 32, ks, lane);
+    }
+  };
+  auto mfma_step = [&](const Frags& f) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.yb[j], acc[i][j], 0, 0, 0);
+    if (HAS_RX) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.rxa[i], f.yb[j], racc[i][j], 0, 0, 0);
+    }
+    if (RYM != RY_NONE) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.ryb[j], racc[i][j], 0, 0, 0);
+    }
+  };
+  static_assert(BK == 32, "the loop below is written for two k-steps per tile");
+
+  auto compute_tile = [&](int cur) {
+    if (EPI == EPI_WGRAD && tn == 0 && tid < BM) {       // bias gradients: sums over the minibatch (X is [k][m])
+      const uint16_t* xs = Xs(cur);
+      const uint16_t* rxs = RXs(cur);
+#pragma unroll
+      for (int kq = 0; kq < BK; ++kq) {
+        gb_acc += bf2f(xs[kq * TX::LDR + tid]);
+        if (HAS_RX) hzb_acc += bf2f(rxs[kq * TX::LDR + tid]);
+      }
+    }
+    Frags f0, f1;
+    read_frags(f0, cur, 0);
+    read_frags(f1, cur, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(f0);
+    mfma_step(f1);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto move_tiles = [&](int kt, int cur) {
+    if (kt + 1 < nkt) stash(cur ^ 1, kt + 1);            // registers -> the other LDS stage
+    if (kt + 2 < nkt) fetch(kt + 2);                     // global -> registers, for the iteration after next
   };
 
   fetch(0);
@@ -215,55 +286,18 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   if (nkt > 1) fetch(1);
   __syncthreads();
 
+  // The two waves that share a SIMD (w and w+4) run the two halves of an iteration in opposite order: one
+  // feeds the matrix cores while the other waits for its global loads and copies them into LDS, then they
+  // swap.  Both read LDS stage `cur` and write stage `cur^1`, so one barrier per k-tile is enough.
+  const bool compute_first = wave < (NT / 64) / 2;
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nkt) stash(cur ^ 1, kt + 1);
-    if (kt + 2 < nkt) fetch(kt + 2);
-    const uint16_t* xs = Xs(cur);
-    const uint16_t* rxs = RXs(cur);
-    const uint16_t* ys = Ys(cur);
-    const uint16_t* rys = RYs(cur);
-
-    if (EPI == EPI_WGRAD && tn == 0 && tid < BM) {      // bias gradients: sums over the minibatch (X is [k][m])
-#pragma unroll
-      for (int kq = 0; kq < BK; ++kq) {
-        gb_acc += bf2f(xs[kq * TX::LDR + tid]);
-        if (HAS_RX) hzb_acc += bf2f(rxs[kq * TX::LDR + tid]);
-      }
-    }
-
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 xa[TM], rxa[TM], yb[TN], ryb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        xa[i] = frag<BM, X_KC>(xs, wm0 + i * 32, ks, lane);
-        if (HAS_RX) rxa[i] = frag<BM, X_KC>(rxs, wm0 + i * 32, ks, lane);
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        yb[j] = frag<BN, Y_KC>(ys, wn0 + j * 32, ks, lane);
-        if (RYM != RY_NONE) ryb[j] = frag<BN, Y_KC>(rys, wn0 + j * 32, ks, lane);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], yb[j], acc[i][j], 0, 0, 0);
-      if (HAS_RX) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rxa[i], yb[j], racc[i][j], 0, 0, 0);
-      }
-      if (RYM != RY_NONE) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[i], ryb[j], racc[i][j], 0, 0, 0);
-      }
+    if (compute_first) {
+      compute_tile(cur);
+      move_tiles(kt, cur);
+    } else {
+      move_tiles(kt, cur);
+      compute_tile(cur);
     }
     __syncthreads();
   }

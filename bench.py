@@ -175,7 +175,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stress-only", action="store_true",

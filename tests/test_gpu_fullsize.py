@@ -1,0 +1,143 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+C3 runs the whole configured schedule (stragglers absent for three rounds, back in the fourth) step by step
+against the oracle.  C4 (bf16, 16 x 50M parameters) and C5 (16 x 1e8 parameters) are too large for the
+oracle to follow every worker, so the GPU runs all workers while the oracle follows a few of them in full
+(each worker's step is independent of the others) and samples the rest.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import dw_oracle as O
+from paper_2409_09242_amd import binding as B
+from paper_2409_09242_amd import workloads as W
+import parity
+from parity import RTOL_HV, RTOL_UPDATE, close, close_update, oracle_config
+import test_gpu_network as T
+
+pytestmark = pytest.mark.gpu
+
+
+def test_c3_full_schedule_forced():
+    """k=8, 3072-1024-1024-1024-10, B=256, tau=8: 32 steps = 4 rounds, so both stragglers rejoin once."""
+    T._run_trajectory(W.C3, 32, forced=True, n_pool=4, check_every=4)
+
+
+def test_c4_full_size_step_and_round():
+    """k=16, 4096^4-10 in bf16, B=512: one step of all 16 workers and one round; the oracle follows 3 workers."""
+    w = W.C4
+    follow = [0, 7, 15]
+    theta0 = W.init_theta(w.dims, w.seed)
+    x, y = W.minibatch_pool(w, 1, bf16_round=W.to_bf16_f32)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    loss = torch.zeros(w.k, device="cuda")
+    print("gpu step", flush=True)
+    h.worker_step(torch.from_numpy(x[0]).to(torch.bfloat16).cuda(), torch.from_numpy(y[0]).cuda(), loss=loss)
+    loss = loss.cpu().numpy()
+    assert np.all(np.isfinite(loss))
+    # the oracle only steps the followed workers; a worker's step does not depend on the others
+    tr = O.OracleTrainer(oracle_config(w, k=len(follow)), theta0.astype(np.float64))
+    tr.cfg.seed = w.seed
+    L = len(w.dims) - 1
+    for slot, i in enumerate(follow):
+        print("oracle worker", i, flush=True)
+        bits = [h.get_state(B.DW_S_ACT + l, i) for l in range(1, L)]
+        choice = [(b != 0) & ((b & 0x8000) == 0) for b in bits]
+        z = O.words_to_signs(O.rademacher_words(w.seed, i, 0, w.P), w.P)
+        np.testing.assert_array_equal(h.get_state(B.DW_S_ZBITS, i), O.words_to_u32(O.rademacher_words(w.seed, i, 0, w.P)))
+        trc = O.StepTrace()
+        ref_loss, g, hz = O.grad_and_hvp(theta0.astype(np.float64), x[0][i], y[0][i], w.dims, z, O.round_bf16, trc,
+                                         T.TIE_BAND_BF16, choice)
+        assert abs(loss[i] - ref_loss) <= 1e-4 * abs(ref_loss)
+        gg, hh = h.get_state(B.DW_S_G, i), h.get_state(B.DW_S_HZ, i)
+        for name, sl in parity.per_layer(w.dims):
+            T.close_norm(gg[sl], g[sl], T.RTOL_BF16_G, "c4 g[%d]/%s" % (i, name), cap=100.0)
+            T.close_norm(hh[sl], hz[sl], T.RTOL_BF16_HZ, "c4 hz[%d]/%s" % (i, name), cap=100.0)
+        # the update itself is checked from the GPU's own g and Hz (fp32 inputs on both sides): tight tolerance
+        th, m, v = O.adahessian_update(theta0.astype(np.float64), np.zeros(w.P), np.zeros(w.P), gg.astype(np.float64),
+                                       hh.astype(np.float64), z, 1, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps,
+                                       hpow=w.hpow, dims=w.dims, avg_block=w.avg_block)
+        close(h.get_state(B.DW_S_THETA, i) - theta0, th - theta0, RTOL_UPDATE, "c4 update[%d]" % i,
+              extra=2.0 ** -23 * np.abs(th))
+        close(h.get_state(B.DW_S_M, i), m, RTOL_UPDATE, "c4 m[%d]" % i)
+        close(h.get_state(B.DW_S_V, i), v, RTOL_UPDATE, "c4 v[%d]" % i)
+        tr.theta[slot] = h.get_state(B.DW_S_THETA, i).astype(np.float64)
+    # one round in which only the followed workers communicate (the others' communication is suppressed)
+    part = np.zeros(w.k, dtype=np.uint8); part[follow] = 1
+    pre = {i: h.get_state(B.DW_S_THETA, i) for i in follow}
+    untouched = h.get_state(B.DW_S_THETA, 3, 0, 100000)
+    assert h.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part)
+    assert tr.elastic_sync(O.MODE_DYNAMIC, tau=1)
+    for slot, i in enumerate(follow):
+        sc = h.get_state(B.DW_S_SCORE, i)
+        assert abs(sc[0] - tr.last_u[slot]) < 1e-5 and sc[1] == 0.0 and abs(sc[2] - w.alpha) < 1e-7
+        close(h.get_state(B.DW_S_THETA, i) - pre[i], tr.theta[slot] - pre[i], RTOL_UPDATE, "c4 pull[%d]" % i,
+              extra=2.0 ** -23 * np.abs(tr.theta[slot]))
+    close(h.get_state(B.DW_S_CENTRE) - theta0, tr.centre - theta0, RTOL_UPDATE, "c4 centre", extra=2.0 ** -23 * np.abs(tr.centre))
+    np.testing.assert_array_equal(h.get_state(B.DW_S_THETA, 3, 0, 100000), untouched)
+    print("worst err/bound:", {k_: v_ for k_, v_ in parity.OBSERVED.items() if "c4" in k_ or k_.startswith("norm")})
+
+
+def test_c5_full_size_update_and_rounds():
+    """k=16, flat P=1e8: two update + round iterations; the oracle follows workers 0 and 15 and the centre in
+    full, and checks sampled slices of every other worker."""
+    w = W.C5
+    P, k = w.n_params, w.k
+    follow = [0, 15]
+    gen = torch.Generator(device="cuda").manual_seed(w.seed)
+    theta0_d = (torch.rand(P, device="cuda", generator=gen) - 0.5) * 0.02
+    g_d = torch.randn(k, P, device="cuda", generator=gen) * 0.1
+    hz_d = torch.randn(k, P, device="cuda", generator=gen) * 0.1
+    h = B.Handle(B.config_from_workload(w), theta0_d)
+    theta0 = theta0_d.cpu().numpy().astype(np.float64)
+    rng = W.rng_for(w.seed, 31)
+    starts = np.sort(rng.integers(0, P // 4096 - 1, size=24)) * 4096
+    starts[0], starts[-1] = 0, P - 4096                         # first and last block of the vector
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, hpow=w.hpow, avg_block=1)
+    full = {i: dict(th=theta0.copy(), m=np.zeros(P), v=np.zeros(P), g=g_d[i].cpu().numpy().astype(np.float64),
+                    hz=hz_d[i].cpu().numpy().astype(np.float64), u=[]) for i in follow}
+    centre = theta0.copy()
+    samp = {i: dict(th=[theta0[s:s + 4096].copy() for s in starts], m=[np.zeros(4096) for _ in starts],
+                    v=[np.zeros(4096) for _ in starts]) for i in range(k)}
+    part = np.zeros(k, dtype=np.uint8); part[follow] = 1
+    for it in (1, 2):
+        print("iteration", it, flush=True)
+        h.update_only(g_d, hz_d)
+        for i in range(k):
+            z = O.words_to_signs(O.rademacher_words(w.seed, i, it - 1, P), P)
+            if i in full:
+                f = full[i]
+                f["th"], f["m"], f["v"] = O.adahessian_update(f["th"], f["m"], f["v"], f["g"], f["hz"], z, it, **hp)
+            for j, s in enumerate(starts):
+                sl = slice(int(s), int(s) + 4096)
+                gi = g_d[i, sl].cpu().numpy().astype(np.float64); hi = hz_d[i, sl].cpu().numpy().astype(np.float64)
+                sm = samp[i]
+                sm["th"][j], sm["m"][j], sm["v"][j] = O.adahessian_update(sm["th"][j], sm["m"][j], sm["v"][j], gi, hi,
+                                                                          z[sl], it, **hp)
+                close(h.get_state(B.DW_S_THETA, i, int(s), 4096), sm["th"][j], RTOL_UPDATE, "c5 theta")
+                close(h.get_state(B.DW_S_M, i, int(s), 4096), sm["m"][j], RTOL_UPDATE, "c5 m")
+                close(h.get_state(B.DW_S_V, i, int(s), 4096), sm["v"][j], RTOL_UPDATE, "c5 v")
+        assert h.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part)
+        new_centre = centre.copy()
+        for i in follow:
+            f = full[i]
+            f["u"].append(O.log_distance(f["th"], centre))
+            a = O.raw_score(f["u"], w.c)
+            h1, h2 = O.h1(a, w.alpha, w.kappa), O.h2(a, w.alpha, w.kappa)
+            sc = h.get_state(B.DW_S_SCORE, i)
+            assert abs(sc[0] - f["u"][-1]) < 1e-6 and abs(sc[1] - a) < 2e-6, (it, i, sc, f["u"], a)
+            assert abs(sc[2] - h1) < 1e-4 and abs(sc[3] - h2) < 1e-4
+            d = f["th"] - centre
+            f["th"] = f["th"] - h1 * d                                   # eq.(12)
+            new_centre += h2 * d                                        # eq.(13)
+        centre = new_centre
+        for j, s in enumerate(starts):
+            sl = slice(int(s), int(s) + 4096)
+            close(h.get_state(B.DW_S_CENTRE, 0, int(s), 4096), centre[sl], RTOL_UPDATE, "c5 centre")
+            for i in follow:
+                close(h.get_state(B.DW_S_THETA, i, int(s), 4096), full[i]["th"][sl], RTOL_UPDATE, "c5 pulled theta")
+                samp[i]["th"][j] = full[i]["th"][sl].copy()
+    # a suppressed worker was not pulled
+    close(h.get_state(B.DW_S_THETA, 5, int(starts[3]), 4096), samp[5]["th"][3], RTOL_UPDATE, "c5 suppressed worker")
+    print("worst err/bound:", {k_: v_ for k_, v_ in parity.OBSERVED.items() if "c5" in k_})

@@ -184,9 +184,16 @@ def close_norm(gpu, ref, rtol, what, cap=30.0):
     assert worst <= cap * rtol, "%s: worst entry off by %.3g of max(|ref|, rms)" % (what, worst)
 
 
-# an upstream bf16 rounding flip moves a pre-activation by about 1e-4 of the layer's rms, so the band of
-# ReLU ties is wider than in fp32
-TIE_BAND_BF16 = 1e-3
+# upstream bf16 rounding flips move a pre-activation by 1e-4 (first hidden layer) to 2e-3 (third, at width
+# 4096) of the layer's rms, so the band of ReLU ties is much wider than in fp32
+TIE_BAND_BF16 = 1e-2
+
+# Both sides round to bf16 at the same points, so they differ only where a value sits next to a rounding
+# boundary (or a ReLU tie) and the fp32 summation order tips it the other way: about one stored value in a
+# thousand flips by 2^-8 relative, i.e. ~1e-4 relative L2 per rounding point, and a gradient of the first
+# layer passes through six of them (a_1..a_3, d_3..d_1).  Hence 1e-3 on g and 2e-3 on Hz, in norm.
+RTOL_BF16_G = 1e-3
+RTOL_BF16_HZ = 2e-3
 
 BF16_SHAPES = [
     ((32, 64, 10), 16, 4),
@@ -211,8 +218,8 @@ def test_bf16_gradient_and_hvp_match_the_oracle(dims, batch, k):
     for i in range(k):
         g, hz = h.get_state(B.DW_S_G, i), h.get_state(B.DW_S_HZ, i)
         for name, sl in parity.per_layer(dims):
-            close_norm(g[sl], tr.traces[i].g[sl], 3e-4, "g[%d]/%s" % (i, name))
-            close_norm(hz[sl], tr.traces[i].hz[sl], RTOL_HV, "hz[%d]/%s" % (i, name))
+            close_norm(g[sl], tr.traces[i].g[sl], RTOL_BF16_G, "g[%d]/%s" % (i, name))
+            close_norm(hz[sl], tr.traces[i].hz[sl], RTOL_BF16_HZ, "hz[%d]/%s" % (i, name))
     print("worst err/bound:", {k_: v for k_, v in parity.OBSERVED.items() if k_.startswith("norm")})
 
 

@@ -226,6 +226,12 @@ def main():
         ach = kernels[dominant]["GB/s"]
         roof = {"kernel": dominant, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_ms": kernels[dominant]["avg_ms"]}
+    gemm_roof = None
+    if gemm_ms > 0:
+        ach_g = sum(fl.values()) / (gemm_ms * 1e-3) / 1e12
+        gemm_roof = {"kernel": "dual_gemm (%s), all launches of a step" % dtype, "bound": "mfma", "achieved": ach_g,
+                     "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s", "frac": ach_g / PEAK_TFLOPS[dtype],
+                     "ms_per_step": gemm_ms}
     del h
     torch.cuda.empty_cache()
 
@@ -239,6 +245,7 @@ def main():
         "step_TFLOP/s": w.flops_per_worker_step() * w.k / (ms_per_step * 1e-3) / 1e12,
         "ms_per_step_profiled": 1e3 * elapsed_prof / args.steps,
         "roofline": roof,
+        "roofline_gemm": gemm_roof,
         "kernels": kernels,
     }
     if not args.no_stress:

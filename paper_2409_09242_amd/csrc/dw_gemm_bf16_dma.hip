@@ -1,0 +1,283 @@
+// bf16 dual GEMM of the forward pass, large-tile path: tiles travel global -> LDS without passing through
+// registers.
+//
+// Same computation as dual_gemm_bf16 for the forward product of one layer and its directional derivative along
+// z (Section IV-B): S = A W^T, RS = RA W^T + A V^T with V = z's W-part as +-1, block tile 128 x 256 x 32,
+// 8 waves of 64 x 64.  What differs is the data path.  `global_load_lds_dwordx4` writes each lane's 16 bytes
+// straight into LDS (lane l of a wave lands at base + 16 l), so tiles in flight cost no registers and three
+// k-tiles are kept in flight or resident instead of two.  Because a wave's 64 x 16 bytes land contiguously,
+// tiles cannot be padded; bank conflicts are avoided by an XOR swizzle applied when choosing which 16 bytes a
+// lane fetches: rows are 64 bytes, 16-byte slot = k-chunk ^ ((row >> 2) & 3).
+// The +-1 operand V is never staged as a matrix: every fourth k-tile the sign bits of the next 128 k (16 bytes per
+// row, 4 KB per block) are fetched into a two-deep ring, and each lane expands its 8 bits to bf16 +-1 in
+// registers just before the multiply.
+//
+// Requirements (otherwise the caller uses dual_gemm_bf16): see gemm_bf16_dma_ok.  Rows beyond M are clamped to the
+// last valid row (their products are discarded).
+#include "dw_internal.h"
+
+namespace dw {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+namespace b16d {
+
+constexpr int BM = 128, BN = 256, BK = 32, NT = 512, NW = NT / 64;
+constexpr int WM = 2, WN = 4, TM = 2, TN = 2;           // wave tile 64 x 64
+constexpr int STAGES = 3;
+constexpr int ZGROUP = 4;                               // k-tiles covered by one fetch of sign bits (16 bytes per row)
+
+typedef __attribute__((address_space(3))) void* lds_void;
+typedef __attribute__((address_space(1))) const void* glb_void;
+
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pm1_pair(uint32_t b_lo, uint32_t b_hi) {
+  return 0xBF80BF80u ^ (b_lo << 15) ^ (b_hi << 31);     // bit set -> +1 (0x3F80), clear -> -1 (0xBF80)
+}
+__device__ __forceinline__ bf16x8 pm1_x8(uint32_t b) {
+  uint4 o;
+  o.x = pm1_pair(b & 1u, (b >> 1) & 1u); o.y = pm1_pair((b >> 2) & 1u, (b >> 3) & 1u);
+  o.z = pm1_pair((b >> 4) & 1u, (b >> 5) & 1u); o.w = pm1_pair((b >> 6) & 1u, (b >> 7) & 1u);
+  return __builtin_bit_cast(bf16x8, o);
+}
+
+// wait until at most n of this wave's vector-memory operations are outstanding (n < 64) and all of its LDS
+// reads have returned (so that, after the barrier that follows, the stage they read may be overwritten)
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+}
+
+// ---- one operand tile of R rows x 32 k, memory [row][k] -> LDS rows of 64 bytes, chunk c (1 KB) = rows 16c..16c+15
+template <int R>
+struct DmaTile {
+  static constexpr int BYTES = R * BK * 2;
+  static constexpr int CPW = BYTES / 1024 / NW;           // chunks per wave
+  static_assert(BYTES % (1024 * NW) == 0, "every wave moves the same number of chunks");
+  __device__ static __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+  // global element offset (at k0 = 0) of the 16 bytes lane `lane` moves for chunk c (they land at c*1024 + 16*lane)
+  __device__ static __forceinline__ int64_t map(int c, int lane, int r0, int Rmax, int ld) {
+    const int row = c * 16 + (lane >> 2), p = lane & 3;
+    const int q = p ^ swz(row);                           // logical k-chunk stored in physical slot p
+    int gr = r0 + row; gr = gr < Rmax ? gr : Rmax - 1;
+    return (int64_t)gr * ld + q * 8;
+  }
+  // MFMA operand: 8 consecutive k of row row0 + lane%32, k-chunk ks*2 + lane/32
+  __device__ static __forceinline__ bf16x8 frag(const char* lds, int row0, int ks, int lane) {
+    const int row = row0 + (lane & 31), q = ks * 2 + (lane >> 5);
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(lds + row * 64 + ((q ^ swz(row)) << 4)));
+  }
+};
+
+template <bool HAS_RX>
+__global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
+  using TX = DmaTile<BM>;
+  using TY = DmaTile<BN>;
+  constexpr int X_B = TX::BYTES, Y_B = TY::BYTES;
+  constexpr int OFF_RX = X_B;
+  constexpr int OFF_Y = X_B * (HAS_RX ? 2 : 1);
+  constexpr int STAGE_B = OFF_Y + Y_B;
+  constexpr int OFF_Z = STAGE_B * STAGES;                   // ring of two sign-bit groups, [256 rows][16 bytes] each
+  constexpr int Z_B = BN * 16;
+  // vector-memory operations every wave issues per k-tile; the sign-bit fetches (one more operation in four of
+  // the waves every fourth k-tile) are left out: counts are only used as "at most n outstanding", operations
+  // complete in order, so an uncounted younger operation makes a wait slightly longer, never too short
+  constexpr int LPT = TX::CPW * (HAS_RX ? 2 : 1) + TY::CPW;
+
+  const int tiles_m = (a.M + BM - 1) / BM;
+  const int tiles = tiles_m * (a.N / BN);
+  const int per_xcd = gridDim.x >> 3;                       // XCD-aware order, see dual_gemm_bf16
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= tiles * a.k) return;
+  const int worker = logical / tiles;
+  if (!((a.active_mask >> worker) & 1ull)) return;
+  const int tile = logical - worker * tiles;
+  const int tm = tile % tiles_m, tn = tile / tiles_m;
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave % WM) * (BM / WM), wn0 = (wave / WM) * (BN / WN);
+  const int l32 = lane & 31, lhalf = lane >> 5;
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  const uint16_t* X = reinterpret_cast<const uint16_t*>(a.X) + (int64_t)worker * a.x_wstride;
+  const uint16_t* RX = HAS_RX ? reinterpret_cast<const uint16_t*>(a.RX) + (int64_t)worker * a.x_wstride : nullptr;
+  const uint16_t* Y = reinterpret_cast<const uint16_t*>(a.Y) + (int64_t)worker * a.y_wstride;
+  const uint32_t* zb = a.zbits + (int64_t)worker * a.z_stride;
+
+  // per-wave source pointers (k0 = 0) of the chunks this wave moves
+  const uint16_t* gx[TX::CPW]; const uint16_t* grx[TX::CPW]; const uint16_t* gy[TY::CPW];
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);  // wave index as a scalar: LDS targets are per wave
+#pragma unroll
+  for (int c = 0; c < TX::CPW; ++c) {
+    const int64_t go = TX::map(wave * TX::CPW + c, lane, row0, a.M, a.ldx);
+    gx[c] = X + go; grx[c] = HAS_RX ? RX + go : nullptr;
+  }
+#pragma unroll
+  for (int c = 0; c < TY::CPW; ++c) gy[c] = Y + TY::map(wave * TY::CPW + c, lane, col0, a.N, a.ldy);
+  // sign bits: waves 0..3 fetch rows 64w..64w+63 of the tile, 16 bytes (128 k) per row and group
+  const uint32_t* gz = zb + ((a.z_off + (int64_t)(col0 + (wave & 3) * 64 + lane) * a.ldy) >> 5);
+
+  auto issue = [&](int kt, int st) {                        // start the loads of k-tile kt into LDS stage st
+    char* base = smem + st * STAGE_B;
+#pragma unroll
+    for (int c = 0; c < TX::CPW; ++c) {
+      __builtin_amdgcn_global_load_lds((glb_void)(gx[c] + (int64_t)kt * BK), (lds_void)(base + (wave_u * TX::CPW + c) * 1024), 16, 0, 0);
+      if (HAS_RX)
+        __builtin_amdgcn_global_load_lds((glb_void)(grx[c] + (int64_t)kt * BK), (lds_void)(base + OFF_RX + (wave_u * TX::CPW + c) * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int c = 0; c < TY::CPW; ++c)
+      __builtin_amdgcn_global_load_lds((glb_void)(gy[c] + (int64_t)kt * BK), (lds_void)(base + OFF_Y + (wave_u * TY::CPW + c) * 1024), 16, 0, 0);
+    if ((kt & (ZGROUP - 1)) == 0 && wave_u < 4) {           // k-tile kt opens sign-bit group kt / 4
+      const int zg = kt / ZGROUP;
+      __builtin_amdgcn_global_load_lds((glb_void)(gz + zg * 4), (lds_void)(smem + OFF_Z + (zg & 1) * Z_B + wave_u * 1024), 16, 0, 0);
+    }
+  };
+
+  floatx16 acc[TM][TN], racc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; racc[i][j][r] = 0.f; }
+
+  struct Frags { bf16x8 xa[TM], rxa[TM], yb[TN], ryb[TN]; };
+  uint32_t zw[TN];                                          // this lane's 32 sign bits of the current k-tile, per column tile
+  auto read_frags = [&](Frags& f, int st, int ks) {
+    const char* base = smem + st * STAGE_B;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      f.xa[i] = TX::frag(base, wm0 + i * 32, ks, lane);
+      if (HAS_RX) f.rxa[i] = TX::frag(base + OFF_RX, wm0 + i * 32, ks, lane);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.yb[j] = TY::frag(base + OFF_Y, wn0 + j * 32, ks, lane);
+  };
+  auto read_bits = [&](int kt) {
+    const char* zbase = smem + OFF_Z + ((kt / ZGROUP) & 1) * Z_B + (kt & (ZGROUP - 1)) * 4;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) zw[j] = *reinterpret_cast<const uint32_t*>(zbase + (wn0 + j * 32 + l32) * 16);
+  };
+  auto expand = [&](Frags& f, int ks) {                     // V operand of k-step ks: byte ks*2 + lane/32 of the tile's word
+#pragma unroll
+    for (int j = 0; j < TN; ++j) f.ryb[j] = pm1_x8((zw[j] >> ((ks * 2 + lhalf) * 8)) & 0xFFu);
+  };
+  auto multiply = [&](Frags& f) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.yb[j], acc[i][j], 0, 0, 0);
+    if (HAS_RX) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.rxa[i], f.yb[j], racc[i][j], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.ryb[j], racc[i][j], 0, 0, 0);
+  };
+
+  const int nkt = a.K / BK;
+  // prologue: fill all stages, wait for tile 0
+#pragma unroll
+  for (int t = 0; t < STAGES; ++t)
+    if (t < nkt) issue(t, t);
+  if (nkt >= STAGES) wait_vm<LPT * (STAGES - 1)>(); else wait_vm<0>();
+  __syncthreads();
+  Frags f0, f1;
+  read_bits(0);
+  read_frags(f0, 0, 0);
+
+  int st = 0;                                               // stage of k-tile kt
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int st_next = st + 1 == STAGES ? 0 : st + 1;
+    // k-step 0 multiplies while the operands of k-step 1 are fetched from LDS
+    read_frags(f1, st, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    expand(f0, 0);
+    multiply(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    expand(f1, 1);                                          // before the next tile's bits replace this tile's
+    // k-tile kt+1 must have landed (this wave's part), then everybody's part; after the barrier nobody reads
+    // stage `st` any more, so it can receive k-tile kt+STAGES
+    if (kt + STAGES - 1 < nkt) wait_vm<LPT * (STAGES - 2)>(); else wait_vm<0>();
+    __syncthreads();
+    if (kt + STAGES < nkt) issue(kt + STAGES, st);
+    if (kt + 1 < nkt) { read_bits(kt + 1); read_frags(f0, st_next, 0); }
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    st = st_next;
+  }
+
+  // epilogue: lane holds column n = l32 of each 32x32 tile, rows (r/4)*8 + lhalf*4 + r%4
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = col0 + wn0 + j * 32 + l32;
+    const float bias = a.bias[(int64_t)worker * a.bias_wstride + n];
+    const int64_t bi = a.zb_off + n;
+    const float cz = ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = row0 + wm0 + i * 32 + (r >> 2) * 8 + lhalf * 4 + (r & 3);
+        if (m >= a.M) continue;
+        const float c = acc[i][j][r] + bias, rc = racc[i][j][r] + cz;
+        const int64_t o = (int64_t)worker * a.c_wstride + (int64_t)m * a.ldc + n;
+        const bool on = c > 0.f;
+        reinterpret_cast<uint16_t*>(a.C)[o] = f2bf(on ? c : 0.f);
+        reinterpret_cast<uint16_t*>(a.RC)[o] = f2bf(on ? rc : 0.f);
+      }
+    }
+  }
+}
+
+template <bool RX>
+static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
+  const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
+  const dim3 grid((unsigned)((tiles * a.k + 7) / 8 * 8)), block(NT);
+  constexpr int smem = (BM * BK * 2 * (RX ? 2 : 1) + BN * BK * 2) * STAGES + 2 * BN * 16;
+  static_assert(smem <= 160 * 1024, "LDS budget");
+  auto kern = dual_gemm_bf16_fwd_dma<RX>;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, grid, block, smem, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace b16d
+
+// true when the large-tile DMA kernel can take this product: the forward product of a hidden layer (ReLU
+// epilogue) that fills the chip, with whole 256-column tiles and rows of z that 16-byte loads can address
+bool gemm_bf16_dma_ok(const GemmArgs& a) {
+  if (a.epi != EPI_RELU || !a.ry_bits || !a.x_kcontig || !a.y_kcontig) return false;
+  if (a.M < 128 || a.N % 256 != 0 || a.K % 128 != 0 || a.K != a.ldy) return false;
+  if (a.ldx % 32 != 0) return false;
+  if ((int64_t)((a.M + 127) / 128) * (a.N / 256) * a.k < 256) return false;
+  if (a.z_off % 128 != 0 || a.z_stride % 4 != 0 || (reinterpret_cast<uintptr_t>(a.zbits) & 15u) != 0) return false;
+  return true;
+}
+
+hipError_t launch_gemm_bf16_dma(const GemmArgs& a, hipStream_t s) {
+  return a.RX ? b16d::launch_one<true>(a, s) : b16d::launch_one<false>(a, s);
+}
+
+}  // namespace dw

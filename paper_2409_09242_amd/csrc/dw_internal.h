@@ -104,6 +104,8 @@ struct GemmArgs {
 
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
+bool gemm_bf16_dma_ok(const GemmArgs& a);                        // large-tile forward path usable for this product?
+hipError_t launch_gemm_bf16_dma(const GemmArgs& a, hipStream_t s);
 
 struct HeadArgs {                     // softmax cross-entropy on the output layer and its R-derivative
   const float* s; const float* Rs;    // [k][B][ld] logits and their directional derivative

@@ -46,7 +46,7 @@ def class_bytes(w, P, k):
     return {"update": upd, "pull": pull}
 
 
-def run_mlp(w, steps, warmup, n_pool):
+def run_mlp(w, steps, warmup, n_pool, fuse):
     import torch
     from paper_2409_09242_amd import binding as B
     from paper_2409_09242_amd import workloads as W
@@ -57,7 +57,7 @@ def run_mlp(w, steps, warmup, n_pool):
     if w.bf16:
         xd = xd.to(torch.bfloat16)
     yd = torch.from_numpy(y).cuda()
-    h = B.Handle(B.config_from_workload(w), theta0)
+    h = B.Handle(B.config_from_workload(w, fuse_update=1 if fuse else 0), theta0)
     sched = W.participation_schedule(w, (2 * steps + warmup) // w.tau + 2)
     state = {"round": 0, "step": 0}
 
@@ -176,6 +176,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--no-fuse", action="store_true",
+                    help="keep g and Hz in memory and run the streaming update over all parameters (fuse_update = 0)")
     ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stress-only", action="store_true",
@@ -196,7 +198,7 @@ def main():
         return 0
     w = W.WORKLOADS[args.workload]
     n_pool = 4 if w.bf16 else 8
-    h, elapsed, prof, elapsed_prof = run_mlp(w, args.steps, args.warmup, n_pool)
+    h, elapsed, prof, elapsed_prof = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse)
     dtype = "bf16" if w.bf16 else "f32"
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.k * args.steps / elapsed

@@ -92,6 +92,11 @@ typedef struct {
   int32_t p;                        /* number of history differences, 1..DW_MAX_P                           */
   float c[DW_MAX_P];                /* c_0 (most recent) .. c_{p-1}; must sum to 1 within 1e-5 (eq.(10)-(11)) */
   uint64_t seed;                    /* seed of the library's Rademacher stream                              */
+  int32_t fuse_update;              /* 0: g and Hz of the last dw_worker_step stay readable (DW_S_G, DW_S_HZ).
+                                       1: the library may apply the update of a weight matrix inside the kernel
+                                          that produces its gradient; the W-parts of g and Hz of such layers are
+                                          then never written (reading them returns stale values).  Same
+                                          arithmetic either way.                                              */
 } dw_config;
 
 /* Human-readable text for a status code (never NULL). */

@@ -33,6 +33,7 @@ int validate(const dw_config* c, Layout* lay) {
   if (!c) return DW_ERR_NULL;
   if (c->k < 1 || c->k > DW_MAX_K) return DW_ERR_CONFIG;
   if (c->dtype != DW_F32 && c->dtype != DW_BF16) return DW_ERR_CONFIG;
+  if (c->fuse_update != 0 && c->fuse_update != 1) return DW_ERR_CONFIG;
   if (c->n_layers < 0 || c->n_layers > DW_MAX_LAYERS) return DW_ERR_CONFIG;
   const int L = c->n_layers;
   const int align = c->dtype == DW_BF16 ? 8 : 4;
@@ -107,6 +108,17 @@ int validate(const dw_config* c, Layout* lay) {
     if (c->dtype == DW_BF16) { lay->dL16 = take(head / 2); lay->rdL16 = take(head / 2); }
   }
   lay->partials = take((size_t)k * lay->n_upd_blocks * sizeof(double));
+  // layers whose weight-gradient kernel applies the update itself: one partial-sum slot per output tile
+  lay->n_fuse_slots = 0;
+  for (int l = 1; l <= L; ++l) {
+    lay->fuse_base[l - 1] = -1;
+    if (c->fuse_update && c->dtype == DW_BF16 &&
+        gemm_bf16_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])) {
+      lay->fuse_base[l - 1] = lay->n_fuse_slots;
+      lay->n_fuse_slots += gemm_bf16_wgrad_tiles(c->dims[l], c->dims[l - 1]);
+    }
+  }
+  if (lay->n_fuse_slots > 0) lay->partials_f = take((size_t)k * lay->n_fuse_slots * sizeof(double));
   lay->u_ring = take((size_t)k * (DW_MAX_P + 1) * sizeof(double));
   lay->score = take((size_t)k * 4 * sizeof(double));
   lay->omh1 = take((size_t)k * sizeof(float));
@@ -147,8 +159,9 @@ struct dw_handle {
 
 namespace {
 
+// `fused_step`: the weight-gradient kernels of this step update the layers marked in the layout themselves
 void fill_update_args(dw_handle* h, UpdateArgs& a, const float* g, const float* hz, int64_t g_stride,
-                      const uint32_t* zbits, int64_t z_stride, uint64_t active) {
+                      const uint32_t* zbits, int64_t z_stride, uint64_t active, bool fused_step = false) {
   const dw_config& c = h->cfg;
   const Layout& L = h->lay;
   a.theta = h->at<float>(L.theta); a.m = h->at<float>(L.m); a.v = h->at<float>(L.v);
@@ -164,6 +177,15 @@ void fill_update_args(dw_handle* h, UpdateArgs& a, const float* g, const float* 
   for (int l = 0; l < c.n_layers; ++l) {
     a.bias.begin[l] = L.boff[l];
     a.bias.end[l] = L.boff[l] + c.dims[l + 1];
+  }
+  a.fused.n = 0;
+  if (fused_step) {
+    for (int l = 0; l < c.n_layers; ++l) {
+      if (L.fuse_base[l] < 0) continue;
+      a.fused.begin[a.fused.n] = L.woff[l];
+      a.fused.end[a.fused.n] = L.woff[l] + (int64_t)c.dims[l + 1] * c.dims[l];
+      a.fused.n += 1;
+    }
   }
   for (int i = 0; i < DW_MAX_K; ++i) {
     a.sc.inv_bc1[i] = 1.f; a.sc.inv_bc2[i] = 1.f;
@@ -188,6 +210,15 @@ int draw_z(dw_handle* h, uint64_t active, hipStream_t s) {
   return DW_OK;
 }
 
+// the partial sums of fused weight-gradient kernels describe the step that wrote them: clear them before any
+// other kernel measures the distances (or before the next fused step writes the active workers' slots)
+int clear_fused_partials(dw_handle* h, hipStream_t s) {
+  if (h->lay.n_fuse_slots > 0)
+    DW_HIP(launch_fill_zero(h->at<char>(h->lay.partials_f),
+                            (size_t)round_up((int64_t)h->cfg.k * h->lay.n_fuse_slots * (int64_t)sizeof(double), 256), s));
+  return DW_OK;
+}
+
 int run_update(dw_handle* h, const float* g, const float* hz, int64_t g_stride, const uint32_t* d_zbits,
                uint64_t active, hipStream_t s) {
   const uint32_t* zb = d_zbits ? d_zbits : h->at<uint32_t>(h->lay.zbits);
@@ -196,6 +227,32 @@ int run_update(dw_handle* h, const float* g, const float* hz, int64_t g_stride, 
     if ((active >> i) & 1ull) h->t[i] += 1;
   UpdateArgs a;
   fill_update_args(h, a, g, hz, g_stride, zb, zs, active);
+  { const int st = clear_fused_partials(h, s); if (st != DW_OK) return st; }
+  DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
+  h->norms_valid = true;
+  h->calls += 1;
+  return DW_OK;
+}
+
+// network and update of one step; with fused layers the step counts and the update's scalars are needed by the
+// weight-gradient kernels, so they are fixed before the network runs
+int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* d_zbits, uint64_t active,
+             float* loss, hipStream_t s) {
+  const uint32_t* zb = d_zbits ? d_zbits : h->at<uint32_t>(h->lay.zbits);
+  const int64_t zs = d_zbits ? 2 * ((h->lay.P + 63) / 64) : h->lay.z_stride;
+  if (h->lay.n_fuse_slots == 0) {
+    const int st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, nullptr, s);
+    if (st != DW_OK) return st;
+    return run_update(h, h->at<float>(h->lay.g), h->at<float>(h->lay.hz), h->lay.Pp, d_zbits, active, s);
+  }
+  for (int i = 0; i < h->cfg.k; ++i)
+    if ((active >> i) & 1ull) h->t[i] += 1;
+  UpdateArgs a;
+  fill_update_args(h, a, h->at<float>(h->lay.g), h->at<float>(h->lay.hz), h->lay.Pp, zb, zs, active, true);
+  int st = clear_fused_partials(h, s);
+  if (st != DW_OK) return st;
+  st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, &a, s);
+  if (st != DW_OK) return st;
   DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
   h->norms_valid = true;
   h->calls += 1;
@@ -337,12 +394,8 @@ int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint
     const int st = draw_z(h, active, s);
     if (st != DW_OK) return st;
   }
-  const uint32_t* zb = d_zbits ? d_zbits : h->at<uint32_t>(h->lay.zbits);
-  const int64_t zs = d_zbits ? 2 * ((h->lay.P + 63) / 64) : h->lay.z_stride;
   float* loss = d_loss ? d_loss : h->at<float>(h->lay.loss);
-  const int st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, s);
-  if (st != DW_OK) return st;
-  return run_update(h, h->at<float>(h->lay.g), h->at<float>(h->lay.hz), h->lay.Pp, d_zbits, active, s);
+  return run_step(h, d_x, d_y, d_zbits, active, loss, s);
 }
 
 int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint32_t* d_zbits,
@@ -378,11 +431,14 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
     // distances only: no worker is marked active, so the update kernel just measures theta_i - centre
     UpdateArgs a;
     fill_update_args(h, a, nullptr, nullptr, 0, h->at<uint32_t>(L.zbits), L.z_stride, 0ull);
+    { const int st = clear_fused_partials(h, s); if (st != DW_OK) return st; }
     DW_HIP(launch_update(a, (int)L.n_upd_blocks, s));
   }
   WeightArgs w;
   w.partials = h->at<double>(L.partials);
   w.n_blocks = (int)L.n_upd_blocks;
+  w.partials_f = L.n_fuse_slots > 0 ? h->at<double>(L.partials_f) : nullptr;
+  w.n_blocks_f = L.n_fuse_slots;
   w.u_ring = h->at<double>(L.u_ring);
   w.score = h->at<double>(L.score);
   w.omh1 = h->at<float>(L.omh1);

@@ -34,6 +34,14 @@ __device__ __forceinline__ bool in_bias(const BiasRanges& br, int64_t j) {
   return r;
 }
 
+__device__ __forceinline__ bool in_fused(const FusedRanges& fr, int64_t j) {
+  bool r = false;
+#pragma unroll
+  for (int l = 0; l < DW_MAX_LAYERS; ++l)
+    if (l < fr.n) r = r || (j >= fr.begin[l] && j < fr.end[l]);
+  return r;
+}
+
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
@@ -56,12 +64,26 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
   const int64_t qbase = (int64_t)blockIdx.x * (kUpdThreads * kUpdQuads) + tid;
   __shared__ double wave_part[DW_MAX_K][kUpdThreads / 64];
 
+  // a block whose parameters were all updated by a weight-gradient kernel has nothing to do unless some worker
+  // is frozen (then it still reports that worker's distance to the centre)
+  if (a.fused.n > 0) {
+    const int64_t j0 = (int64_t)blockIdx.x * kUpdChunk, j1 = j0 + kUpdChunk;
+    bool inside = false;
+    for (int l = 0; l < a.fused.n; ++l) inside = inside || (j0 >= a.fused.begin[l] && j1 <= a.fused.end[l]);
+    const uint64_t all = a.k >= 64 ? ~0ull : ((1ull << a.k) - 1ull);
+    if (inside && (a.active_mask & all) == all) {
+      if (tid < a.k) a.partials[(int64_t)tid * gridDim.x + blockIdx.x] = 0.0;
+      return;
+    }
+  }
+
   float4 cen[kUpdQuads];
-  bool valid[kUpdQuads], avg[kUpdQuads];
+  bool valid[kUpdQuads], avg[kUpdQuads], fz[kUpdQuads];
   uint32_t zshift[kUpdQuads];
 #pragma unroll
   for (int u = 0; u < kUpdQuads; ++u) {
     const int64_t q = qbase + (int64_t)u * kUpdThreads;
+    fz[u] = a.fused.n > 0 && in_fused(a.fused, q << 2);
     valid[u] = q < nq;
     cen[u] = valid[u] ? reinterpret_cast<const float4*>(a.centre)[q] : make_float4(0.f, 0.f, 0.f, 0.f);
     avg[u] = a.avg_block > 1 && !in_bias(a.bias, q << 2);
@@ -86,7 +108,7 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
 #pragma unroll
       for (int u = 0; u < kUpdQuads; ++u) {
         const int64_t q = qbase + (int64_t)u * kUpdThreads;
-        if (valid[u]) {
+        if (valid[u] && !fz[u]) {
           G[u] = g4[q]; H[u] = h4[q]; T[u] = th4[q]; M[u] = m4[q]; V[u] = v4[q];
           Z[u] = zb[q >> 3] >> zshift[u];
         } else {
@@ -102,7 +124,8 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
         float th[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
         float mm[4] = {M[u].x, M[u].y, M[u].z, M[u].w};
         float vv[4] = {V[u].x, V[u].y, V[u].z, V[u].w};
-        const float cc[4] = {cen[u].x, cen[u].y, cen[u].z, cen[u].w};
+        // quads updated elsewhere run on zeros and add nothing to the distance
+        const float cc[4] = {fz[u] ? 0.f : cen[u].x, fz[u] ? 0.f : cen[u].y, fz[u] ? 0.f : cen[u].z, fz[u] ? 0.f : cen[u].w};
         float D[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) D[e] = sign_from_bit(Z[u], e) * hz[e];       // Hutchinson: z * Hz
@@ -127,7 +150,7 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
           const float d = th[e] - cc[e];
           nsum += d * d;
         }
-        if (valid[u]) {
+        if (valid[u] && !fz[u]) {
           th4[q] = make_float4(th[0], th[1], th[2], th[3]);
           m4[q] = make_float4(mm[0], mm[1], mm[2], mm[3]);
           v4[q] = make_float4(vv[0], vv[1], vv[2], vv[3]);
@@ -180,6 +203,7 @@ __global__ __launch_bounds__(256) void weight_kernel(WeightArgs a) {
   __shared__ double red[256 / 64];
   double s = 0.0;
   for (int b = tid; b < a.n_blocks; b += 256) s += a.partials[(int64_t)i * a.n_blocks + b];
+  for (int b = tid; b < a.n_blocks_f; b += 256) s += a.partials_f[(int64_t)i * a.n_blocks_f + b];
   s = wave_sum(s);
   if ((tid & 63) == 0) red[tid >> 6] = s;
   __syncthreads();

@@ -15,6 +15,8 @@
 //     within 16 lanes, lane i receives element i%4 of the 8-byte rows addressed by lanes i/4, 4+i/4, 8+i/4,
 //     12+i/4), which hands each lane its 4 consecutive k for one row.
 // The +-1 operand V (z reshaped like W) is expanded from the sign bits of z in the loader.
+#include <cstddef>
+
 #include "dw_internal.h"
 
 namespace dw {
@@ -164,6 +166,14 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   const int worker = logical / tiles;
   if (!((a.active_mask >> worker) & 1ull)) return;
   const int tile = logical - worker * tiles;
+  if (EPI == EPI_WGRAD && a.fu.on && blockIdx.x < 256 * 8) {
+    // Fused update: a block alternates between a compute-bound main loop and an HBM-bound epilogue of about twice
+    // its length.  Blocks that start together stay in step, leaving HBM idle while everybody multiplies, so the
+    // first block of every compute unit starts with one of 16 delays spread over about one block period.
+    const int ph = (blockIdx.x >> 3) & 15;
+    if (blockIdx.x < 256)
+      for (int i = 0; i < ph; ++i) __builtin_amdgcn_s_sleep(127);
+  }
   const int tm = tile % tiles_m, tn = tile / tiles_m;
   const int row0 = tm * BM, col0 = tn * BN;
   const int tid = threadIdx.x;
@@ -303,6 +313,89 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   }
 
   // epilogue: lane holds column n = l32 of each 32x32 tile, rows (r/4)*8 + lhalf*4 + r%4
+  if (EPI == EPI_WGRAD && a.fu.on) {
+    // The update of Section IV-B applied to the tile while g and Hz are still in registers (same arithmetic as
+    // update_kernel, Hessian power 1).  Element (m, n) is parameter m*ldc + n of the layer's W block; the 32
+    // lanes of a half-wave hold 32 consecutive n of one row, so the sign bits of a row segment are one word and
+    // the block mean of D = z*Hz along fan-in is a butterfly over avg_block lanes.  M % 128 == 0 and N % 256 == 0:
+    // no element of the tile is out of range.  Offsets inside the block fit 32 bits.
+    const FuseArgs& f = a.fu;
+    const int64_t wbase = (int64_t)worker * a.c_wstride;
+    float* th_w = f.theta + wbase; float* m_w = f.m + wbase; float* v_w = f.v + wbase;
+    uint16_t* b16_w = f.wb16 + wbase;
+    const uint32_t* zrow = zb + (a.z_off >> 5);               // z_off % 32 == 0
+    // bias corrections of this worker, read from the kernel-argument block by a scalar load (indexing the by-value
+    // argument with a variable would copy it to scratch memory)
+    typedef const char __attribute__((address_space(4)))* karg_bytes;
+    typedef const float __attribute__((address_space(4)))* karg_floats;
+    const karg_bytes ka = (karg_bytes)__builtin_amdgcn_kernarg_segment_ptr();
+    const karg_floats bc = (karg_floats)(ka + offsetof(GemmArgs, fu) + offsetof(FuseArgs, sc));
+    const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];
+    static_assert(offsetof(UpdateScalars, inv_bc2) == DW_MAX_K * sizeof(float), "inv_bc2 follows inv_bc1");
+    const float inv_b = 1.0f / (float)f.avg_block;
+    constexpr int FB = 8;                                     // elements per batch (16 would spill registers)
+    float nsum = 0.f;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const uint32_t n = (uint32_t)(col0 + wn0 + j * 32 + l32);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        // eight elements at a time: their 40 loads are in flight together (the epilogue is bound by HBM, so it
+        // needs many), and the scheduling fence keeps later batches out of registers the accumulators occupy
+#pragma unroll
+        for (int r0 = 0; r0 < 16; r0 += FB) {
+          uint32_t e[FB], zw[FB];
+          float th[FB], mm[FB], vv[FB], cc[FB];
+#pragma unroll
+          for (int q = 0; q < FB; ++q) {
+            const int r = r0 + q;
+            const uint32_t m = (uint32_t)(row0 + wm0 + i * 32 + (r >> 2) * 8 + lhalf * 4 + (r & 3));
+            e[q] = m * (uint32_t)a.ldc + n;                   // offset inside the W block
+            th[q] = th_w[e[q]]; mm[q] = m_w[e[q]]; vv[q] = v_w[e[q]]; cc[q] = f.centre[e[q]];
+            zw[q] = zrow[e[q] >> 5];
+          }
+#pragma unroll
+          for (int q = 0; q < FB; ++q) {
+            const float g = acc[i][j][r0 + q], hz = racc[i][j][r0 + q];
+            float D = ((zw[q] >> l32) & 1u) ? hz : -hz;        // Hutchinson: z * Hz
+            if (f.avg_block > 1) {                             // same summation tree as update_kernel
+              float sD = D;
+#pragma unroll
+              for (int off = 1; off < 32; off <<= 1) {
+                const float t = __shfl_xor(sD, off);
+                sD += off < f.avg_block ? t : 0.f;
+              }
+              D = sD * inv_b;
+            }
+            const float m1 = f.beta1 * mm[q] + (1.0f - f.beta1) * g;
+            const float v1 = f.beta2 * vv[q] + (1.0f - f.beta2) * (D * D);
+            const float mhat = m1 * ib1, vhat = v1 * ib2;
+            const float t1 = th[q] - f.lr * (mhat / (sqrtf(vhat) + f.eps));
+            const float d = t1 - cc[q];
+            nsum += d * d;
+            th_w[e[q]] = t1; m_w[e[q]] = m1; v_w[e[q]] = v1;
+            b16_w[e[q]] = f2bf(t1);
+          }
+          asm volatile("" : "+v"(nsum));                  // the batch's terms are summed here, not kept for later
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    // squared distance of the tile's new parameters to the centre: one slot per (worker, tile)
+    double ws = (double)nsum;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ws += __shfl_xor(ws, off);
+    __syncthreads();                                          // everybody is done with the operand tiles in LDS
+    double* red = reinterpret_cast<double*>(smem);
+    if (lane == 0) red[wave] = ws;
+    __syncthreads();
+    if (tid == 0) {
+      double t = 0.0;
+#pragma unroll
+      for (int w = 0; w < NT / 64; ++w) t += red[w];
+      f.partials[(int64_t)worker * f.part_stride + f.part_base + tile] = t;
+    }
+  } else {
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = col0 + wn0 + j * 32 + l32;
@@ -341,6 +434,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
         }
       }
     }
+  }
   }
   if (EPI == EPI_WGRAD && tn == 0 && tid < BM) {
     const int m = row0 + tid;
@@ -386,6 +480,16 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
 }
 
 }  // namespace b16
+
+// The weight-gradient product of W[n_out][n_in] takes the 128 x 256 shape (see launch_gemm_bf16) and can apply the
+// update in its epilogue when W is made of whole tiles (rows are then whole 32-lane segments and sign-bit words),
+// an averaging block is at most one segment and the Hessian power is 1.
+bool gemm_bf16_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff) {
+  if (n_out % 128 != 0 || n_in % 256 != 0 || woff % 32 != 0 || avg_block > 32 || hpow != 1.0f) return false;
+  if ((int64_t)n_out * n_in >= (1ll << 31)) return false;
+  return (int64_t)(n_out / 128) * (n_in / 256) * k >= 256;
+}
+int gemm_bf16_wgrad_tiles(int n_out, int n_in) { return ((n_out + 127) / 128) * ((n_in + 255) / 256); }
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : a.epi == EPI_MASK ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);

@@ -200,6 +200,9 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
   Frags f0, f1;
   read_bits(0);
   read_frags(f0, 0, 0);
+  // nothing of this wave's LDS or scalar traffic is pending when the loop is entered, so that inside the loop
+  // the compiler can count exactly which LDS reads a multiply has to wait for
+  __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (0x7 << 4) | (0x0 << 8));
 
   int st = 0;                                               // stage of k-tile kt
   for (int kt = 0; kt < nkt; ++kt) {

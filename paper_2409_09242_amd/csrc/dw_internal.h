@@ -25,6 +25,14 @@ struct BiasRanges {
   int64_t end[DW_MAX_LAYERS];
 };
 
+// parameter ranges whose update is applied elsewhere (inside the weight-gradient kernel): the streaming update
+// skips them for active workers and only measures the distance to the centre for frozen ones
+struct FusedRanges {
+  int n;
+  int64_t begin[DW_MAX_LAYERS];
+  int64_t end[DW_MAX_LAYERS];
+};
+
 struct UpdateArgs {
   float* theta; float* m; float* v;   // [k][Pp]
   const float* g; const float* hz;    // [k][g_stride]
@@ -40,12 +48,15 @@ struct UpdateArgs {
   float lr, beta1, beta2, eps, hpow;
   uint64_t active_mask;               // bit i: worker i takes the step (others only report their distance)
   BiasRanges bias;
+  FusedRanges fused;
   UpdateScalars sc;
 };
 
 struct WeightArgs {                   // dynamic-weight scalars of one communication round (Section V-B)
   const double* partials;             // [k][n_blocks]
   int n_blocks;
+  const double* partials_f;           // [k][n_blocks_f] partial sums written by fused weight-gradient kernels
+  int n_blocks_f;
   double* u_ring;                     // [k][DW_MAX_P+1]
   double* score;                      // [k][4] = u, a, h1, h2
   float* omh1;                        // [k] 1 - h1_i   (0 pull for absent workers is handled by the mask)
@@ -78,6 +89,20 @@ hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hi
 
 // ---- network part ------------------------------------------------------------------------------------
 
+// AdaHessian update applied in the epilogue of a weight-gradient GEMM (same arithmetic as update_kernel):
+// element (m, n) of the product is parameter woff + m*ldc + n of the worker
+struct FuseArgs {
+  int on;
+  float* theta; float* m; float* v;   // worker 0's W block of the layer; worker stride = the product's c_wstride
+  const float* centre;                // the layer's W block of the centre
+  uint16_t* wb16;                     // bf16 copy of theta (W block), worker stride c_wstride
+  double* partials;                   // [k][part_stride] squared-distance partial sums, one slot per tile
+  int part_stride, part_base;         // slot of tile t of worker i: i*part_stride + part_base + t
+  int avg_block;                      // power of two, 1..32
+  float lr, beta1, beta2, eps, hpow;
+  UpdateScalars sc;
+};
+
 enum GemmKind { GEMM_FWD = 0, GEMM_DGRAD = 1, GEMM_WGRAD = 2 };
 enum Epilogue { EPI_RELU = 0, EPI_LINEAR = 1, EPI_MASK = 2, EPI_WGRAD = 3 };
 
@@ -97,6 +122,7 @@ struct GemmArgs {
   const float* bias; int64_t bias_wstride;            // EPI_RELU / EPI_LINEAR: theta + b_off
   int64_t zb_off;                                     // bit offset of the bias part of z
   float* gb; float* hzb;                              // EPI_WGRAD: bias-gradient outputs (g + b_off, hz + b_off)
+  FuseArgs fu;                                        // EPI_WGRAD: fu.on != 0 replaces the stores of C and RC by the update
   int epi;
   int k;
   uint64_t active_mask;
@@ -104,6 +130,10 @@ struct GemmArgs {
 
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
+// can the bf16 weight-gradient kernel of a layer W[n_out][n_in] (bit/parameter offset woff) apply the update itself,
+// and how many partial-sum slots (tiles) does it then write per worker?
+bool gemm_bf16_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff);
+int gemm_bf16_wgrad_tiles(int n_out, int n_in);
 bool gemm_bf16_dma_ok(const GemmArgs& a);                        // large-tile forward path usable for this product?
 hipError_t launch_gemm_bf16_dma(const GemmArgs& a, hipStream_t s);
 
@@ -125,14 +155,20 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t act[DW_MAX_LAYERS] = {0}, ract[DW_MAX_LAYERS] = {0};   // a_l, Ra_l for l = 1..L-1 (index l)
   size_t delta[2] = {0, 0}, rdelta[2] = {0, 0};                  // ping-pong hidden-layer errors
   size_t sL = 0, rsL = 0, dL = 0, rdL = 0, dL16 = 0, rdL16 = 0;  // output layer, fp32 [k][B][16] (+ bf16 copies)
+  int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
+  int n_fuse_slots = 0;
+  size_t partials_f = 0;              // [k][n_fuse_slots] doubles
   size_t partials = 0, u_ring = 0, score = 0, omh1 = 0, h2 = 0, loss = 0;
   size_t total = 0;
 };
 
 // Enqueue forward, R-forward, backward and R-backward of all layers for the active workers; leaves the mean
-// gradient in the g buffer and the Hessian-vector product in the hz buffer (returns a dw_status).
+// gradient in the g buffer and the Hessian-vector product in the hz buffer (returns a dw_status).  With `fuse`
+// (the arguments of this step's update) the layers marked in lay.fuse_base are updated by their weight-gradient
+// kernels instead, and their W-parts of g and hz are not written.
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
-                const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s);
+                const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
+                hipStream_t s);
 
 }  // namespace dw
 

@@ -97,7 +97,8 @@ hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
 }
 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
-                const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s) {
+                const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
+                hipStream_t s) {
   const bool b16 = cfg.dtype == DW_BF16;
   const int L = cfg.n_layers, k = cfg.k, B = cfg.batch;
   const int HL = DW_MAX_CLASSES;                     // row stride of the output-layer buffers
@@ -154,7 +155,8 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     } else {
       dl = ws + lay.delta[l & 1]; rdl = ws + lay.rdelta[l & 1]; ldd = cfg.dims[l]; dstride = act_stride(l);
     }
-    {   // weight gradient and its R-companion: contraction over the minibatch
+    const bool fused = fuse != nullptr && lay.fuse_base[l - 1] >= 0;
+    auto weight_gradient = [&]() -> hipError_t {   // and its R-companion: contraction over the minibatch
       GemmArgs a{};
       a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 0; a.ldx = ldd;
       a.Y = act(l - 1); a.RY = ract(l - 1); a.ry_bits = 0; a.y_wstride = act_stride(l - 1); a.y_kcontig = 0;
@@ -164,8 +166,22 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.C = g + lay.woff[l - 1]; a.RC = hz + lay.woff[l - 1]; a.ldc = cfg.dims[l - 1]; a.c_wstride = lay.Pp;
       a.gb = g + lay.boff[l - 1]; a.hzb = hz + lay.boff[l - 1];
       a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
-      if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
-    }
+      if (fused) {   // the kernel applies this step's update to W_l instead of storing gW_l and HzW_l
+        const int64_t wo = lay.woff[l - 1];
+        a.z_off = wo;
+        a.fu.on = 1;
+        a.fu.theta = fuse->theta + wo; a.fu.m = fuse->m + wo; a.fu.v = fuse->v + wo;
+        a.fu.centre = fuse->centre + wo; a.fu.wb16 = fuse->wb16 + wo;
+        a.fu.partials = reinterpret_cast<double*>(ws + lay.partials_f);
+        a.fu.part_stride = lay.n_fuse_slots; a.fu.part_base = lay.fuse_base[l - 1];
+        a.fu.avg_block = fuse->avg_block;
+        a.fu.lr = fuse->lr; a.fu.beta1 = fuse->beta1; a.fu.beta2 = fuse->beta2; a.fu.eps = fuse->eps; a.fu.hpow = fuse->hpow;
+        a.fu.sc = fuse->sc;
+      }
+      return gemm(a);
+    };
+    // a fused weight gradient overwrites W_l, which the data gradient still has to read: it goes second then
+    if (!fused && (e = weight_gradient()) != hipSuccess) return DW_ERR_HIP;
     if (l > 1) {   // data gradient through W_l, masked by the ReLU of layer l-1
       GemmArgs a{};
       a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 1; a.ldx = ldd;
@@ -179,6 +195,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.epi = EPI_MASK; a.k = k; a.active_mask = active;
       if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
     }
+    if (fused && (e = weight_gradient()) != hipSuccess) return DW_ERR_HIP;
   }
   return DW_OK;
 }

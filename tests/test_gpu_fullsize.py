@@ -31,11 +31,17 @@ def test_c4_full_size_step_and_round():
     theta0 = W.init_theta(w.dims, w.seed)
     x, y = W.minibatch_pool(w, 1, bf16_round=W.to_bf16_f32)
     h = B.Handle(B.config_from_workload(w), theta0)
+    # the configuration bench.py times: the three 4096 x 4096 layers are updated inside their weight-gradient kernels
+    hf = B.Handle(B.config_from_workload(w, fuse_update=1), theta0)
     loss = torch.zeros(w.k, device="cuda")
+    loss_f = torch.zeros(w.k, device="cuda")
     print("gpu step", flush=True)
-    h.worker_step(torch.from_numpy(x[0]).to(torch.bfloat16).cuda(), torch.from_numpy(y[0]).cuda(), loss=loss)
+    xb, yb = torch.from_numpy(x[0]).to(torch.bfloat16).cuda(), torch.from_numpy(y[0]).cuda()
+    h.worker_step(xb, yb, loss=loss)
+    hf.worker_step(xb, yb, loss=loss_f)
     loss = loss.cpu().numpy()
     assert np.all(np.isfinite(loss))
+    np.testing.assert_array_equal(loss_f.cpu().numpy(), loss)
     # the oracle only steps the followed workers; a worker's step does not depend on the others
     tr = O.OracleTrainer(oracle_config(w, k=len(follow)), theta0.astype(np.float64))
     tr.cfg.seed = w.seed
@@ -62,16 +68,23 @@ def test_c4_full_size_step_and_round():
               extra=2.0 ** -23 * np.abs(th))
         close(h.get_state(B.DW_S_M, i), m, RTOL_UPDATE, "c4 m[%d]" % i)
         close(h.get_state(B.DW_S_V, i), v, RTOL_UPDATE, "c4 v[%d]" % i)
+        close(hf.get_state(B.DW_S_THETA, i) - theta0, th - theta0, RTOL_UPDATE, "c4 fused update[%d]" % i,
+              extra=2.0 ** -23 * np.abs(th))
+        close(hf.get_state(B.DW_S_M, i), m, RTOL_UPDATE, "c4 fused m[%d]" % i)
+        close(hf.get_state(B.DW_S_V, i), v, RTOL_UPDATE, "c4 fused v[%d]" % i)
         tr.theta[slot] = h.get_state(B.DW_S_THETA, i).astype(np.float64)
     # one round in which only the followed workers communicate (the others' communication is suppressed)
     part = np.zeros(w.k, dtype=np.uint8); part[follow] = 1
     pre = {i: h.get_state(B.DW_S_THETA, i) for i in follow}
     untouched = h.get_state(B.DW_S_THETA, 3, 0, 100000)
     assert h.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part)
+    assert hf.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part)
     assert tr.elastic_sync(O.MODE_DYNAMIC, tau=1)
     for slot, i in enumerate(follow):
         sc = h.get_state(B.DW_S_SCORE, i)
         assert abs(sc[0] - tr.last_u[slot]) < 1e-5 and sc[1] == 0.0 and abs(sc[2] - w.alpha) < 1e-7
+        scf = hf.get_state(B.DW_S_SCORE, i)
+        assert abs(scf[0] - tr.last_u[slot]) < 1e-5 and scf[1] == 0.0 and abs(scf[2] - w.alpha) < 1e-7
         close(h.get_state(B.DW_S_THETA, i) - pre[i], tr.theta[slot] - pre[i], RTOL_UPDATE, "c4 pull[%d]" % i,
               extra=2.0 ** -23 * np.abs(tr.theta[slot]))
     close(h.get_state(B.DW_S_CENTRE) - theta0, tr.centre - theta0, RTOL_UPDATE, "c4 centre", extra=2.0 ** -23 * np.abs(tr.centre))

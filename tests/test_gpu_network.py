@@ -234,3 +234,64 @@ def _gpu_slopes_b16(h, w):
             per.append((bits != 0) & ((bits & 0x8000) == 0))
         out.append(per)
     return out
+
+
+# ---------------------------------------------------------------------------------------------------------
+# fuse_update = 1: the weight-gradient kernels of large bf16 layers apply the update themselves and never
+# store g and Hz.  The network part is the same code either way, so a fused and an unfused handle fed the same
+# inputs must agree to fp32 rounding; the update itself is checked against the oracle from the g and Hz the
+# unfused handle exposes (as in the full-size test), including a frozen worker and a communication round.
+# ---------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("avg_block", [1, 8, 32])
+def test_bf16_fused_update_matches_the_unfused_path_and_the_oracle(avg_block):
+    dims, batch, k = (512, 2048, 1024, 10), 128, 8       # layers 1 and 2 are fused, layer 3 and the biases are not
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=4242, bf16=True, avg_block=avg_block)
+    theta0 = W.init_theta(w.dims, w.seed)
+    hA = B.Handle(B.config_from_workload(w), theta0)
+    hB = B.Handle(B.config_from_workload(w, fuse_update=1), theta0)
+    x, y = W.minibatch_pool(w, 2, bf16_round=W.to_bf16_f32)
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, hpow=w.hpow, dims=w.dims, avg_block=w.avg_block)
+    t = np.zeros(k, dtype=int)
+    for step, active in ((0, [1] * k), (1, [1, 1, 1, 0, 1, 1, 1, 1])):
+        prev = [(hA.get_state(B.DW_S_THETA, i).astype(np.float64), hA.get_state(B.DW_S_M, i).astype(np.float64),
+                 hA.get_state(B.DW_S_V, i).astype(np.float64)) for i in range(k)]
+        xb, yb = _to_bf16_bits(x[step]), torch.from_numpy(y[step]).cuda()
+        lossA, lossB = torch.zeros(k, device="cuda"), torch.zeros(k, device="cuda")
+        hA.worker_step(xb, yb, loss=lossA, active=active)
+        hB.worker_step(xb, yb, loss=lossB, active=active)
+        np.testing.assert_array_equal(lossA.cpu().numpy(), lossB.cpu().numpy())
+        # the fused handle never stores the W-part of g of a fused layer (its buffer still holds the initial zeros)
+        assert not np.any(hB.get_state(B.DW_S_G, 0, 0, dims[0] * dims[1])) and np.any(hA.get_state(B.DW_S_G, 0, 0, 4096))
+        for i in range(k):
+            thA, mA, vA = (hA.get_state(s, i) for s in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V))
+            thB, mB, vB = (hB.get_state(s, i) for s in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V))
+            assert int(hB.get_state(B.DW_S_STEPS, i)[0]) == int(hA.get_state(B.DW_S_STEPS, i)[0])
+            if not active[i]:
+                np.testing.assert_array_equal(thB, prev[i][0].astype(np.float32))
+                np.testing.assert_array_equal(thB, thA)
+                continue
+            t[i] += 1
+            close(thB - prev[i][0], thA - prev[i][0], 1e-6, "fused vs unfused update[%d]" % i, extra=2.0 ** -23 * np.abs(thA))
+            close(mB, mA, 1e-6, "fused vs unfused m[%d]" % i)
+            close(vB, vA, 1e-6, "fused vs unfused v[%d]" % i)
+            z = O.words_to_signs(O.rademacher_words(w.seed, i, int(t[i]) - 1, w.P), w.P)
+            g, hz = hA.get_state(B.DW_S_G, i).astype(np.float64), hA.get_state(B.DW_S_HZ, i).astype(np.float64)
+            th, m, v = O.adahessian_update(prev[i][0], prev[i][1], prev[i][2], g, hz, z, int(t[i]), **hp)
+            close(thB - prev[i][0], th - prev[i][0], RTOL_UPDATE, "fused update[%d] step %d" % (i, step),
+                  extra=2.0 ** -23 * np.abs(th))
+            close(mB, m, RTOL_UPDATE, "fused m[%d]" % i)
+            close(vB, v, RTOL_UPDATE, "fused v[%d]" % i)
+    # the bf16 copy of the weights that the next forward pass reads follows the fused update
+    lossA2, lossB2 = torch.zeros(k, device="cuda"), torch.zeros(k, device="cuda")
+    part = [1, 1, 0, 1, 1, 1, 1, 1]
+    assert hA.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part) == 1
+    assert hB.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part) == 1
+    for i in range(k):
+        sa, sb = hA.get_state(B.DW_S_SCORE, i), hB.get_state(B.DW_S_SCORE, i)
+        assert abs(sa[0] - sb[0]) < 1e-6 and abs(sa[2] - sb[2]) < 1e-5 and abs(sa[3] - sb[3]) < 1e-5, (i, sa, sb)
+        close(hB.get_state(B.DW_S_THETA, i), hA.get_state(B.DW_S_THETA, i), 1e-6, "fused vs unfused pulled theta[%d]" % i)
+    close(hB.get_state(B.DW_S_CENTRE), hA.get_state(B.DW_S_CENTRE), 1e-6, "fused vs unfused centre")
+    xb, yb = _to_bf16_bits(x[0]), torch.from_numpy(y[0]).cuda()
+    hA.worker_step(xb, yb, loss=lossA2)
+    hB.worker_step(xb, yb, loss=lossB2)
+    close(lossB2.cpu().numpy(), lossA2.cpu().numpy(), 1e-5, "loss after the round")

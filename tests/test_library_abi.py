@@ -37,7 +37,7 @@ def test_strerror_and_param_count():
 
 
 @pytest.mark.parametrize("field,value,status", [
-    ("k", 0, -2), ("k", 65, -2), ("batch", 0, -2), ("dtype", 7, -2),
+    ("k", 0, -2), ("k", 65, -2), ("batch", 0, -2), ("dtype", 7, -2), ("fuse_update", 2, -2),
     ("lr", 0.0, -3), ("beta1", 1.0, -3), ("eps", 0.0, -3), ("avg_block", 3, -3), ("avg_block", 512, -3),
     ("alpha", 0.0, -3), ("alpha", 1.5, -3), ("kappa", 0.0, -3), ("kappa", 0.2, -3), ("p", 0, -3), ("p", 9, -3),
 ])
@@ -76,3 +76,17 @@ def test_null_handles_are_rejected_without_a_gpu():
     h = C.c_void_p()
     cfg = B.config_from_workload(W.C1)
     assert lib.dw_init(C.byref(h), C.byref(cfg), None, 0, None, 0, None) == -1
+
+
+def test_fused_update_is_an_option_of_large_bf16_layers_only():
+    """fuse_update = 1 is accepted everywhere; it only adds partial-sum slots (workspace) where a layer qualifies."""
+    lib = B.lib()
+    for w in (W.C1, W.C3, W.C4):
+        plain = lib.dw_workspace_bytes(C.byref(B.config_from_workload(w)))
+        fused = lib.dw_workspace_bytes(C.byref(B.config_from_workload(w, fuse_update=1)))
+        assert plain > 0
+        if w is W.C4:
+            # three 4096 x 4096 layers, 32 x 16 tiles each, one double per tile and worker
+            assert fused - plain == 3 * 32 * 16 * 8 * w.k
+        else:
+            assert fused == plain

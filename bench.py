@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA
+# HBM-side bytes per launch of the fused weight-gradient kernel at configuration 4 (mean of the three launches of
+# a step), from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel (factors 2.00 and 1.00);
+# see profiles/dual_gemm_bf16_fused_wgrad_c4_hbm_traffic.txt.  Valid for the kernel as profiled there.
+TRAFFIC_C4_FUSED_WGRAD = 10.86e9
 
 
 def class_flops(w):
@@ -37,13 +41,37 @@ def class_flops(w):
     return {"gemm_fwd": fwd * k, "gemm_wgrad": wgrad * k, "gemm_dgrad": dgrad * k}
 
 
-def class_bytes(w, P, k):
-    """Algorithmic HBM bytes per launch for the streaming classes: the update reads g, Hz, theta, m, v and
-    writes theta, m, v (32 B per parameter and worker, +2 B for the bf16 weight copy); the pull reads and
-    writes theta (8 B per parameter and worker) and the centre (8 B per parameter)."""
-    upd = (32.0 + (2.0 if w.bf16 else 0.0)) * P * k
-    pull = (8.0 + (2.0 if w.bf16 else 0.0)) * P * k + 8.0 * P
-    return {"update": upd, "pull": pull}
+def fused_layers(w, fuse):
+    """Layers whose weight-gradient kernel applies the update itself when fuse_update = 1 (the library's rule:
+    bf16, W made of whole 128 x 256 tiles that fill the chip, averaging block <= 32, Hessian power 1)."""
+    if not fuse or not w.bf16 or w.dims is None or w.avg_block > 32 or w.hpow != 1.0:
+        return []
+    out, off = [], 0
+    for l in range(1, len(w.dims)):
+        n_out, n_in = w.dims[l], w.dims[l - 1]
+        if (n_out % 128 == 0 and n_in % 256 == 0 and off % 32 == 0 and n_out * n_in < 2 ** 31
+                and (n_out // 128) * (n_in // 256) * w.k >= 256):
+            out.append(l)
+        off += n_out * n_in + n_out
+    return out
+
+
+def class_bytes(w, P, k, fused=(), part=1.0):
+    """Algorithmic HBM bytes per step for the HBM-bound classes.  The update reads g, Hz, theta, m, v and writes
+    theta, m, v (32 B per parameter and worker, +2 B for the bf16 weight copy); the pull reads and writes theta
+    (8 B per parameter and communicating worker, +2 B bf16 copy; `part` = mean fraction of workers that communicate) and
+    the centre (8 B per parameter).  A fused weight-gradient
+    launch reads theta, m, v and the centre, writes theta, m, v and the bf16 copy (30 B per parameter and worker,
+    + 1 bit of z) and reads its four bf16 operands once (d_l, Rd_l, a_{l-1}, Ra_{l-1})."""
+    d = w.dims
+    p_fused = sum(d[l] * d[l - 1] for l in fused)
+    upd = (32.0 + (2.0 if w.bf16 else 0.0)) * (P - p_fused) * k
+    pull = (8.0 + (2.0 if w.bf16 else 0.0)) * P * k * part + 8.0 * P
+    out = {"update": upd, "pull": pull}
+    if fused:
+        operands = sum(2.0 * 2.0 * w.batch * (d[l] + d[l - 1]) for l in fused)
+        out["gemm_wgrad"] = (30.125 * p_fused + operands) * k
+    return out
 
 
 def run_mlp(w, steps, warmup, n_pool, fuse):
@@ -86,7 +114,22 @@ def run_mlp(w, steps, warmup, n_pool, fuse):
     prof = h.profile_read()
     elapsed_prof = time.perf_counter() - t1
     h.profile(False)
-    return h, elapsed, prof, elapsed_prof
+    part = float(np.mean([np.mean(r) for r in sched[:max(state["round"], 1)]]))
+    return h, elapsed, prof, elapsed_prof, part
+
+
+def calibration_copy(n=1 << 28, reps=5):
+    """A plain copy of known size (n floats read, n floats written per launch, one elementwise kernel each) so
+    that hardware counters collected over this run can be scaled: counter per byte = its reading for this
+    kernel / (4 n)."""
+    import torch
+    src = torch.ones(n, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(reps):
+        torch.mul(src, 1.0, out=dst)
+    torch.cuda.synchronize()
+    del src, dst
+    torch.cuda.empty_cache()
 
 
 def run_update_stress(iters=20, warmup=3):
@@ -178,6 +221,8 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--no-fuse", action="store_true",
                     help="keep g and Hz in memory and run the streaming update over all parameters (fuse_update = 0)")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="first run a plain 1 GiB copy kernel five times (reference for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stress-only", action="store_true",
@@ -198,13 +243,17 @@ def main():
         return 0
     w = W.WORKLOADS[args.workload]
     n_pool = 4 if w.bf16 else 8
-    h, elapsed, prof, elapsed_prof = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse)
+    if args.calibrate:
+        calibration_copy()
+    h, elapsed, prof, elapsed_prof, part = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse)
     dtype = "bf16" if w.bf16 else "f32"
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.k * args.steps / elapsed
 
     fl = class_flops(w)
-    by = class_bytes(w, w.P, w.k)
+    fused = fused_layers(w, not args.no_fuse)
+    by = class_bytes(w, w.P, w.k, fused, part)
+    per_step = {"update": 1, "pull": 1.0 / w.tau, "gemm_wgrad": 1}
     kernels = {}
     for name in ("gemm_fwd", "gemm_wgrad", "gemm_dgrad", "head", "update", "weights", "pull", "rademacher"):
         n, ms = prof[name]
@@ -214,26 +263,40 @@ def main():
         if name in fl:
             entry["TFLOP/s"] = fl[name] / (ms / args.steps * 1e-3) / 1e12
         if name in by:
-            entry["GB/s"] = by[name] / (ms / n * 1e-3) / 1e9
+            # bytes of the class per step over its time per step (the pull runs every tau-th step)
+            entry["GB/s"] = by[name] * per_step[name] / (ms / args.steps * 1e-3) / 1e9
         kernels[name] = entry
-    gemm_ms = sum(kernels[c]["ms_per_step"] for c in fl if c in kernels)
+    # classes bound by the matrix cores: all GEMMs, except weight gradients that carry the update (HBM-bound then)
+    mfma = [c for c in fl if c in kernels and not (c == "gemm_wgrad" and fused)]
+    gemm_ms = sum(kernels[c]["ms_per_step"] for c in mfma)
+    gemm_fl = sum(fl[c] for c in mfma)
     dominant = max(kernels, key=lambda c: kernels[c]["ms_per_step"])
-    if dominant in fl:
+    if dominant in mfma:
         # one roofline entry for the GEMM family (one kernel template): all its launches of a step together
-        ach = sum(fl.values()) / (gemm_ms * 1e-3) / 1e12
+        ach = gemm_fl / (gemm_ms * 1e-3) / 1e12
         roof = {"kernel": "dual_gemm (%s)" % dtype, "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS[dtype],
                 "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[dtype], "traffic": None,
                 "avg_ms_per_step": gemm_ms, "dominant_class": dominant}
     else:
         ach = kernels[dominant]["GB/s"]
-        roof = {"kernel": dominant, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_ms": kernels[dominant]["avg_ms"]}
+        label = "dual_gemm_bf16 weight gradient with fused update" if dominant == "gemm_wgrad" else dominant
+        roof = {"kernel": label, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_ms": kernels[dominant]["avg_ms"],
+                "bytes_per_step": by[dominant] * per_step[dominant]}
+        if dominant == "gemm_wgrad":
+            # per launch, like the counters: the class has one more, tiny launch per step (the output layer)
+            n_big = len(fused)
+            roof["launches_per_step"] = n_big
+            roof["bytes_per_launch"] = by[dominant] / n_big
+            roof["avg_ms"] = kernels[dominant]["ms_per_step"] / n_big
+            if w.name.startswith("c4"):
+                roof["traffic"] = TRAFFIC_C4_FUSED_WGRAD
     gemm_roof = None
     if gemm_ms > 0:
-        ach_g = sum(fl.values()) / (gemm_ms * 1e-3) / 1e12
-        gemm_roof = {"kernel": "dual_gemm (%s), all launches of a step" % dtype, "bound": "mfma", "achieved": ach_g,
-                     "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s", "frac": ach_g / PEAK_TFLOPS[dtype],
-                     "ms_per_step": gemm_ms}
+        ach_g = gemm_fl / (gemm_ms * 1e-3) / 1e12
+        gemm_roof = {"kernel": "dual_gemm (%s): %s, all launches of a step" % (dtype, " + ".join(mfma)),
+                     "bound": "mfma", "achieved": ach_g, "peak": PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
+                     "frac": ach_g / PEAK_TFLOPS[dtype], "ms_per_step": gemm_ms}
     del h
     torch.cuda.empty_cache()
 
@@ -242,7 +305,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w.name, "k": w.k, "dims": list(w.dims), "batch": w.batch, "tau": w.tau,
-                   "stale": w.stale, "sync": "dynamic"},
+                   "stale": w.stale, "sync": "dynamic", "fuse_update": int(bool(fused))},
         "flop_per_step": w.flops_per_worker_step() * w.k,
         "step_TFLOP/s": w.flops_per_worker_step() * w.k / (ms_per_step * 1e-3) / 1e12,
         "ms_per_step_profiled": 1e3 * elapsed_prof / args.steps,

@@ -174,7 +174,15 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     if (blockIdx.x < 256)
       for (int i = 0; i < ph; ++i) __builtin_amdgcn_s_sleep(127);
   }
-  const int tm = tile % tiles_m, tn = tile / tiles_m;
+  int tm = tile % tiles_m, tn = tile / tiles_m;
+  if (EPI == EPI_WGRAD && tiles_m % 8 == 0) {
+    // Weight gradient: both operands are panels of the minibatch (512 k x 128 or 256 columns, with their
+    // R-companions 256 KB and 512 KB).  The 32 blocks an XCD runs at a time are 8 row tiles x 4 column tiles
+    // (2 + 2 MB of panels, which its 4 MB L2 can hold) instead of a column of 32 row tiles (8 MB).
+    const int tiles_n = tiles / tiles_m;
+    const int g = tile / (8 * tiles_n), r = tile - g * (8 * tiles_n);
+    tn = r / 8; tm = g * 8 + r % 8;
+  }
   const int row0 = tm * BM, col0 = tn * BN;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;

@@ -397,6 +397,27 @@ def elastic_sync(thetas: np.ndarray, centre: np.ndarray, h1s, h2s, participate=N
     return new_t, new_c
 
 
+def elastic_sync_sequential(thetas: np.ndarray, centre: np.ndarray, h1s, h2s, participate=None):
+    """The same round taken as a sequence of single exchanges (Section II: only asynchronous procedures are
+    considered; Section VI: a full communication round on one device).
+
+    Reading: the participating workers talk to the master one after the other, in index order; each exchange
+    is eq.(12)-(13) exactly as written for one worker, with the centre as the previous exchange left it.
+    The weights h1_i, h2_i are those of the round (the raw scores use the master estimate at the start of
+    the round).  Returns (new thetas [k,P], new centre [P]).
+    """
+    k = thetas.shape[0]
+    new_t = thetas.astype(F64).copy()
+    c = np.asarray(centre, dtype=F64).copy()
+    for i in range(k):
+        if participate is not None and not participate[i]:
+            continue
+        d = new_t[i] - c
+        new_t[i] = new_t[i] - h1s[i] * d             # eq.(12)
+        c = c + h2s[i] * d                           # eq.(13), seen by the next worker of the round
+    return new_t, c
+
+
 MODE_FIXED, MODE_MANUAL, MODE_DYNAMIC = 0, 1, 2
 
 
@@ -490,7 +511,8 @@ class OracleTrainer:
                 dims=cfg.dims, avg_block=cfg.avg_block)
         self.global_step += 1
 
-    def elastic_sync(self, mode: int, tau: int = 1, h1s=None, h2s=None, participate=None) -> bool:
+    def elastic_sync(self, mode: int, tau: int = 1, h1s=None, h2s=None, participate=None,
+                     sequential: bool = False) -> bool:
         """Communication round, taken when the number of worker_step calls is a multiple of tau.
 
         Every worker (also one whose communication is suppressed) records its log-distance to the
@@ -515,5 +537,6 @@ class OracleTrainer:
             else:
                 H1[i], H2[i] = h1(a, cfg.alpha, cfg.kappa), h2(a, cfg.alpha, cfg.kappa)
         self.last_h1, self.last_h2 = H1, H2
-        self.theta, self.centre = elastic_sync(self.theta, self.centre, H1, H2, participate)
+        pull = elastic_sync_sequential if sequential else elastic_sync
+        self.theta, self.centre = pull(self.theta, self.centre, H1, H2, participate)
         return True

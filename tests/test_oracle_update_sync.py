@@ -220,3 +220,77 @@ def test_trainer_modes_and_dynamic_round():
     assert tr.global_step == 3 and not tr.elastic_sync(O.MODE_FIXED, tau=2)
     tr.update_only(g, hz)
     assert tr.elastic_sync(O.MODE_FIXED, tau=2)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Sequential form of a round: a chain of single-worker exchanges, each eq.(12)-(13) as printed.
+# ---------------------------------------------------------------------------------------------------------
+def _exchange_matrix(k, i, h1, h2):
+    """Linear map of one exchange of worker i on the state (theta_0 .. theta_{k-1}, centre), one coordinate."""
+    M = np.eye(k + 1)
+    M[i, i] = 1.0 - h1; M[i, k] = h1            # theta_i <- theta_i - h1 (theta_i - c)
+    M[k, k] = 1.0 - h2; M[k, i] = h2            # c       <- c + h2 (theta_i - c)
+    return M
+
+
+def test_sequential_round_is_the_product_of_single_exchanges():
+    rng = np.random.default_rng(5)
+    k, P = 5, 7
+    th, c = rng.normal(size=(k, P)), rng.normal(size=P)
+    h1s, h2s = rng.uniform(0.05, 1.0, k), rng.uniform(0.0, 0.6, k)
+    part = np.array([1, 0, 1, 1, 0], dtype=np.uint8)
+    new_t, new_c = O.elastic_sync_sequential(th, c, h1s, h2s, part)
+    M = np.eye(k + 1)
+    for i in range(k):
+        if part[i]:
+            M = _exchange_matrix(k, i, h1s[i], h2s[i]) @ M      # later exchanges act on the earlier ones' result
+    state = M @ np.vstack([th, c[None, :]])
+    np.testing.assert_allclose(new_t, state[:k], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(new_c, state[k], rtol=1e-13, atol=1e-15)
+    np.testing.assert_array_equal(new_t[1], th[1]); np.testing.assert_array_equal(new_t[4], th[4])
+
+
+def test_sequential_round_special_cases():
+    rng = np.random.default_rng(6)
+    k, P = 4, 9
+    th, c = rng.normal(size=(k, P)), rng.normal(size=P)
+    h1s, h2s = rng.uniform(0.1, 0.9, k), rng.uniform(0.1, 0.5, k)
+    # a single participant: both forms are eq.(12)-(13) for that worker
+    one = np.array([0, 0, 1, 0], dtype=np.uint8)
+    ta, ca = O.elastic_sync(th, c, h1s, h2s, one)
+    tb, cb = O.elastic_sync_sequential(th, c, h1s, h2s, one)
+    np.testing.assert_allclose(ta, tb, rtol=0, atol=1e-15); np.testing.assert_allclose(ca, cb, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(cb, c + h2s[2] * (th[2] - c), rtol=1e-14)
+    np.testing.assert_allclose(tb[2], th[2] - h1s[2] * (th[2] - c), rtol=1e-14)
+    # h2 = 0: the centre never moves, so the order of the exchanges cannot matter
+    ta, ca = O.elastic_sync(th, c, h1s, np.zeros(k))
+    tb, cb = O.elastic_sync_sequential(th, c, h1s, np.zeros(k))
+    np.testing.assert_allclose(ta, tb, rtol=0, atol=1e-15); np.testing.assert_array_equal(cb, c)
+    # symmetric rate (plain elastic averaging): every exchange conserves theta_i + centre
+    a = np.full(k, 0.3)
+    tb, cb = O.elastic_sync_sequential(th, c, a, a)
+    np.testing.assert_allclose(tb.sum(0) + cb, th.sum(0) + c, rtol=1e-13)
+    # consensus is a fixed point; and with several participants the order does matter
+    same = np.tile(c, (k, 1))
+    tb, cb = O.elastic_sync_sequential(same, c, h1s, h2s)
+    np.testing.assert_array_equal(tb, same); np.testing.assert_array_equal(cb, c)
+    tj, cj = O.elastic_sync(th, c, h1s, h2s)
+    ts, cs = O.elastic_sync_sequential(th, c, h1s, h2s)
+    assert np.max(np.abs(cj - cs)) > 1e-3
+    # two workers, written out: the second one sees the centre the first one moved
+    c1 = c + h2s[0] * (th[0] - c)
+    ts2, cs2 = O.elastic_sync_sequential(th[:2], c, h1s[:2], h2s[:2])
+    np.testing.assert_allclose(ts2[1], th[1] - h1s[1] * (th[1] - c1), rtol=1e-14)
+    np.testing.assert_allclose(cs2, c1 + h2s[1] * (th[1] - c1), rtol=1e-14)
+
+
+def test_trainer_sequential_round_uses_the_scores_of_the_round_start():
+    cfg = O.OracleConfig(dims=None, k=3, n_params=16, seed=3)
+    rng = np.random.default_rng(8)
+    ta = O.OracleTrainer(cfg, rng.normal(size=16)); tb = O.OracleTrainer(cfg, ta.centre.copy())
+    pert = rng.normal(size=(3, 16)) * 0.1
+    ta.theta = ta.theta + pert; tb.theta = tb.theta + pert
+    assert ta.elastic_sync(O.MODE_DYNAMIC) and tb.elastic_sync(O.MODE_DYNAMIC, sequential=True)
+    np.testing.assert_array_equal(ta.last_u, tb.last_u)          # same u, a, h1, h2 ...
+    np.testing.assert_array_equal(ta.last_h1, tb.last_h1)
+    assert np.max(np.abs(ta.centre - tb.centre)) > 0             # ... different pull

@@ -74,7 +74,7 @@ def class_bytes(w, P, k, fused=(), part=1.0):
     return out
 
 
-def run_mlp(w, steps, warmup, n_pool, fuse):
+def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False):
     import torch
     from paper_2409_09242_amd import binding as B
     from paper_2409_09242_amd import workloads as W
@@ -88,11 +88,12 @@ def run_mlp(w, steps, warmup, n_pool, fuse):
     h = B.Handle(B.config_from_workload(w, fuse_update=1 if fuse else 0), theta0)
     sched = W.participation_schedule(w, (2 * steps + warmup) // w.tau + 2)
     state = {"round": 0, "step": 0}
+    mode = B.DW_DYNAMIC | (B.DW_SEQUENTIAL if sequential else 0)
 
     def one_step():
         b = state["step"] % n_pool
         h.worker_step(xd[b], yd[b])
-        if h.elastic_sync(B.DW_DYNAMIC, tau=w.tau, participate=sched[state["round"]]):
+        if h.elastic_sync(mode, tau=w.tau, participate=sched[state["round"]]):
             state["round"] += 1
         state["step"] += 1
 
@@ -219,6 +220,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--sequential", action="store_true",
+                    help="communication rounds as a sequence of single exchanges (DW_SEQUENTIAL); same bytes moved")
     ap.add_argument("--no-fuse", action="store_true",
                     help="keep g and Hz in memory and run the streaming update over all parameters (fuse_update = 0)")
     ap.add_argument("--calibrate", action="store_true",
@@ -245,7 +248,7 @@ def main():
     n_pool = 4 if w.bf16 else 8
     if args.calibrate:
         calibration_copy()
-    h, elapsed, prof, elapsed_prof, part = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse)
+    h, elapsed, prof, elapsed_prof, part = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse, args.sequential)
     dtype = "bf16" if w.bf16 else "f32"
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.k * args.steps / elapsed
@@ -305,7 +308,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w.name, "k": w.k, "dims": list(w.dims), "batch": w.batch, "tau": w.tau,
-                   "stale": w.stale, "sync": "dynamic", "fuse_update": int(bool(fused))},
+                   "stale": w.stale, "sync": "dynamic, sequential" if args.sequential else "dynamic",
+                   "fuse_update": int(bool(fused))},
         "flop_per_step": w.flops_per_worker_step() * w.k,
         "step_TFLOP/s": w.flops_per_worker_step() * w.k / (ms_per_step * 1e-3) / 1e12,
         "ms_per_step_profiled": 1e3 * elapsed_prof / args.steps,

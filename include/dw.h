@@ -59,6 +59,11 @@ typedef enum {
 #define DW_FIXED 0           /* h1 = h2 = alpha: plain elastic averaging (Section IV-A)                 */
 #define DW_MANUAL 1          /* caller-supplied, "as if we know when a node will fail" (Section VI)     */
 #define DW_DYNAMIC 2         /* h1(a), h2(a) from the raw score (Section V-B)                           */
+/* may be OR-ed into the mode: the participating workers exchange with the master one after the other, in index
+ * order, each exchange being eq.(12)-(13) with the centre as the previous one left it (asynchronous procedure,
+ * Section II; full communication round, Section VI).  Without it all differences use the centre of the round's
+ * start.  The weights are those of the round either way (u_i is measured against the centre at its start). */
+#define DW_SEQUENTIAL 16
 
 /* selectors for dw_get_state / dw_set_state */
 #define DW_S_THETA 0         /* float[P]   worker parameters                                            */
@@ -156,7 +161,7 @@ int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint
  * worker  theta_i -= h1_i (theta_i - centre)  (eq.(12))  and the centre moves by the sum over participating
  * workers of  h2_i (theta_i - centre)  (eq.(13)), all differences taken against the centre before the round.
  *
- *   mode            DW_FIXED | DW_MANUAL | DW_DYNAMIC
+ *   mode            DW_FIXED | DW_MANUAL | DW_DYNAMIC, optionally + DW_SEQUENTIAL
  *   h_h1, h_h2      [k] floats, required for DW_MANUAL, ignored otherwise
  *   h_participate   [k] bytes, 0 = this worker's communication is suppressed in this round (it still
  *                   records u); NULL = all participate

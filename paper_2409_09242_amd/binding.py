@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(HERE, "libdw.so")
 DW_MAX_LAYERS, DW_MAX_K, DW_MAX_P, DW_MAX_CLASSES = 8, 64, 8, 16
 DW_F32, DW_BF16 = 0, 1
 DW_FIXED, DW_MANUAL, DW_DYNAMIC = 0, 1, 2
+DW_SEQUENTIAL = 16      # OR-ed into the mode of elastic_sync: exchanges one after the other, in index order
 (DW_S_THETA, DW_S_M, DW_S_V, DW_S_G, DW_S_HZ, DW_S_CENTRE, DW_S_ZBITS, DW_S_SCORE, DW_S_U_HIST,
  DW_S_STEPS) = range(10)
 DW_S_ACT = 16

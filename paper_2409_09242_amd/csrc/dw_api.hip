@@ -419,6 +419,8 @@ int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint
 int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2,
                     const uint8_t* h_participate, int tau, void* stream) {
   if (!h) return DW_ERR_NULL;
+  const int sequential = (mode & DW_SEQUENTIAL) ? 1 : 0;
+  mode &= ~DW_SEQUENTIAL;
   if (mode != DW_FIXED && mode != DW_MANUAL && mode != DW_DYNAMIC) return DW_ERR_ARG;
   if (mode == DW_MANUAL && (!h_h1 || !h_h2)) return DW_ERR_NULL;
   if (tau < 1) return DW_ERR_ARG;
@@ -460,6 +462,7 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
   p.omh1 = w.omh1; p.h2 = w.h2;
   p.Pp = L.Pp; p.k = c.k;
   p.part_mask = mask_from(h_participate, c.k);
+  p.sequential = sequential;
   DW_HIP(launch_pull(p, s));
   h->rounds += 1;
   h->norms_valid = false;

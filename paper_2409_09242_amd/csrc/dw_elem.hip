@@ -253,6 +253,8 @@ hipError_t launch_weights(const WeightArgs& a, hipStream_t s) {
 // ---------------------------------------------------------------------------------------------------
 // Elastic pull.  theta_i <- centre + (1-h1_i)(theta_i - centre)  (the same value as eq.(12), written so
 // that h1 = 1 returns the centre exactly);  centre <- centre + sum_i h2_i (theta_i - centre)  (eq.(13)).
+// Sequential rounds apply eq.(13) after every worker instead: the thread that owns a parameter keeps the
+// centre in a register and walks the workers in index order, so the bytes moved are the same.
 // ---------------------------------------------------------------------------------------------------
 template <bool HAS_B16>
 __global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a) {
@@ -284,8 +286,13 @@ __global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a) {
       float4 r;
       r.x = fmaf(o, d0, cen[u].x); r.y = fmaf(o, d1, cen[u].y);
       r.z = fmaf(o, d2, cen[u].z); r.w = fmaf(o, d3, cen[u].w);
-      acc[u].x = fmaf(w, d0, acc[u].x); acc[u].y = fmaf(w, d1, acc[u].y);
-      acc[u].z = fmaf(w, d2, acc[u].z); acc[u].w = fmaf(w, d3, acc[u].w);
+      if (a.sequential) {     // eq.(13) takes effect at once: the next worker of the round sees the moved centre
+        cen[u].x = fmaf(w, d0, cen[u].x); cen[u].y = fmaf(w, d1, cen[u].y);
+        cen[u].z = fmaf(w, d2, cen[u].z); cen[u].w = fmaf(w, d3, cen[u].w);
+      } else {
+        acc[u].x = fmaf(w, d0, acc[u].x); acc[u].y = fmaf(w, d1, acc[u].y);
+        acc[u].z = fmaf(w, d2, acc[u].z); acc[u].w = fmaf(w, d3, acc[u].w);
+      }
       if (valid[u]) {
         th4[q] = r;
         if (HAS_B16) {

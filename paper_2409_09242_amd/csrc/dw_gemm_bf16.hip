@@ -341,53 +341,63 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];
     static_assert(offsetof(UpdateScalars, inv_bc2) == DW_MAX_K * sizeof(float), "inv_bc2 follows inv_bc1");
     const float inv_b = 1.0f / (float)f.avg_block;
-    constexpr int FB = 8;                                     // elements per batch (16 would spill registers)
-    float nsum = 0.f;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    // The epilogue is bound by HBM, so loads must always be in flight: the 64 elements of a lane are taken in 16
+    // batches of four (one MFMA register group = four consecutive rows), and the 24 loads of batch b+1 are issued
+    // before batch b is computed and stored.  Scheduling fences keep the compiler from hoisting more batches
+    // into registers that accumulators still occupy.
+    constexpr int FB = 4, NB = TN * TM * 16 / FB;
+    struct Batch { uint32_t e[FB], zw[FB]; float th[FB], mm[FB], vv[FB], cc[FB]; };
+    auto load_batch = [&](Batch& bt, int b) {
+      const int j = b / (TM * 4), i = (b / 4) % TM, rg = b % 4;
       const uint32_t n = (uint32_t)(col0 + wn0 + j * 32 + l32);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        // eight elements at a time: their 40 loads are in flight together (the epilogue is bound by HBM, so it
-        // needs many), and the scheduling fence keeps later batches out of registers the accumulators occupy
-#pragma unroll
-        for (int r0 = 0; r0 < 16; r0 += FB) {
-          uint32_t e[FB], zw[FB];
-          float th[FB], mm[FB], vv[FB], cc[FB];
-#pragma unroll
-          for (int q = 0; q < FB; ++q) {
-            const int r = r0 + q;
-            const uint32_t m = (uint32_t)(row0 + wm0 + i * 32 + (r >> 2) * 8 + lhalf * 4 + (r & 3));
-            e[q] = m * (uint32_t)a.ldc + n;                   // offset inside the W block
-            th[q] = th_w[e[q]]; mm[q] = m_w[e[q]]; vv[q] = v_w[e[q]]; cc[q] = f.centre[e[q]];
-            zw[q] = zrow[e[q] >> 5];
-          }
-#pragma unroll
-          for (int q = 0; q < FB; ++q) {
-            const float g = acc[i][j][r0 + q], hz = racc[i][j][r0 + q];
-            float D = ((zw[q] >> l32) & 1u) ? hz : -hz;        // Hutchinson: z * Hz
-            if (f.avg_block > 1) {                             // same summation tree as update_kernel
-              float sD = D;
-#pragma unroll
-              for (int off = 1; off < 32; off <<= 1) {
-                const float t = __shfl_xor(sD, off);
-                sD += off < f.avg_block ? t : 0.f;
-              }
-              D = sD * inv_b;
-            }
-            const float m1 = f.beta1 * mm[q] + (1.0f - f.beta1) * g;
-            const float v1 = f.beta2 * vv[q] + (1.0f - f.beta2) * (D * D);
-            const float mhat = m1 * ib1, vhat = v1 * ib2;
-            const float t1 = th[q] - f.lr * (mhat / (sqrtf(vhat) + f.eps));
-            const float d = t1 - cc[q];
-            nsum += d * d;
-            th_w[e[q]] = t1; m_w[e[q]] = m1; v_w[e[q]] = v1;
-            b16_w[e[q]] = f2bf(t1);
-          }
-          asm volatile("" : "+v"(nsum));                  // the batch's terms are summed here, not kept for later
-          __builtin_amdgcn_sched_barrier(0);
-        }
+      for (int q = 0; q < FB; ++q) {
+        const uint32_t m = (uint32_t)(row0 + wm0 + i * 32 + rg * 8 + lhalf * 4 + q);
+        bt.e[q] = m * (uint32_t)a.ldc + n;                    // offset inside the W block
+        bt.th[q] = th_w[bt.e[q]]; bt.mm[q] = m_w[bt.e[q]]; bt.vv[q] = v_w[bt.e[q]]; bt.cc[q] = f.centre[bt.e[q]];
+        bt.zw[q] = zrow[bt.e[q] >> 5];
       }
+    };
+    float nsum = 0.f;
+    auto finish_batch = [&](const Batch& bt, const float* gq, const float* hq) {
+#pragma unroll
+      for (int q = 0; q < FB; ++q) {
+        const float g = gq[q], hz = hq[q];
+        float D = ((bt.zw[q] >> l32) & 1u) ? hz : -hz;         // Hutchinson: z * Hz
+        if (f.avg_block > 1) {                                 // same summation tree as update_kernel
+          float sD = D;
+#pragma unroll
+          for (int off = 1; off < 32; off <<= 1) {
+            const float t = __shfl_xor(sD, off);
+            sD += off < f.avg_block ? t : 0.f;
+          }
+          D = sD * inv_b;
+        }
+        const float m1 = f.beta1 * bt.mm[q] + (1.0f - f.beta1) * g;
+        const float v1 = f.beta2 * bt.vv[q] + (1.0f - f.beta2) * (D * D);
+        const float mhat = m1 * ib1, vhat = v1 * ib2;
+        const float t1 = bt.th[q] - f.lr * (mhat / (sqrtf(vhat) + f.eps));
+        const float d = t1 - bt.cc[q];
+        nsum += d * d;
+        th_w[bt.e[q]] = t1; m_w[bt.e[q]] = m1; v_w[bt.e[q]] = v1;
+        b16_w[bt.e[q]] = f2bf(t1);
+      }
+    };
+    Batch b0, b1;
+    load_batch(b0, 0);
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+      Batch& cur = (b & 1) ? b1 : b0;
+      Batch& nxt = (b & 1) ? b0 : b1;
+      if (b + 1 < NB) load_batch(nxt, b + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      const int j = b / (TM * 4), i = (b / 4) % TM, rg = b % 4;
+      float gq[FB], hq[FB];
+#pragma unroll
+      for (int q = 0; q < FB; ++q) { gq[q] = acc[i][j][rg * 4 + q]; hq[q] = racc[i][j][rg * 4 + q]; }
+      finish_batch(cur, gq, hq);
+      asm volatile("" : "+v"(nsum));                          // the batch's terms are summed here, not kept for later
+      __builtin_amdgcn_sched_barrier(0);
     }
     // squared distance of the tile's new parameters to the centre: one slot per (worker, tile)
     double ws = (double)nsum;

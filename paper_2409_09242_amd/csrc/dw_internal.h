@@ -76,6 +76,7 @@ struct PullArgs {
   int64_t Pp;
   int k;
   uint64_t part_mask;                 // bit i: worker i communicates in this round
+  int sequential;                     // 1: exchanges one after the other in index order, the centre moves in between
 };
 
 hipError_t launch_update(const UpdateArgs& a, int n_blocks, hipStream_t s);

@@ -29,7 +29,7 @@ class Workload:
     bf16: bool = False
     n_params: int = 0                       # flat case only
     steps: int = 20
-    stale: str = "none"                     # "none" | "fixed3_last2" | "geometric0.3"
+    stale: str = "none"                     # "none" | "fixed3_last2" | "geometric0.3" | "third"
     lr: float = 0.01
     beta1: float = 0.9
     beta2: float = 0.999
@@ -134,6 +134,8 @@ def participation_schedule(w: Workload, n_rounds: int) -> np.ndarray:
       "fixed3_last2":  the last two workers are absent for 3 rounds and present in the 4th, forever;
       "geometric0.3":  after each participation a worker draws s ~ Geometric(0.3) on {0,1,2,...}
                        and is absent for the next s rounds.
+      "third":         every worker's communication is suppressed in a round with probability 1/3,
+                       independently (Section VI: "one-third of time").
     Suppressed workers keep taking local steps.
     """
     part = np.ones((n_rounds, w.k), dtype=np.uint8)
@@ -149,4 +151,7 @@ def participation_schedule(w: Workload, n_rounds: int) -> np.ndarray:
                 s = int(rng.geometric(0.3)) - 1
                 part[r:r + s, i] = 0
                 r += s + 1
+    elif w.stale == "third":
+        rng = rng_for(w.seed, 23)
+        part = (rng.random((n_rounds, w.k)) >= 1.0 / 3.0).astype(np.uint8)
     return part

@@ -136,3 +136,52 @@ def test_call_errors():
         h.get_state(B.DW_S_THETA, 7)
     with pytest.raises(B.DwError):
         h.get_state(B.DW_S_THETA, 0, offset=1000, count=100)
+
+
+@pytest.mark.parametrize("mode_gpu,mode_ref", [(B.DW_DYNAMIC, O.MODE_DYNAMIC), (B.DW_FIXED, O.MODE_FIXED),
+                                               (B.DW_MANUAL, O.MODE_MANUAL)])
+def test_sequential_rounds_follow_the_oracle(mode_gpu, mode_ref):
+    """DW_SEQUENTIAL: exchanges one after the other in index order, with the paper's one-third suppression."""
+    P, k = 3 * 4096 + 512, 6
+    w, theta0, rng = _flat_case(P, k, 77, stale="third")
+    h = B.Handle(B.config_from_workload(w), theta0)
+    tr = O.OracleTrainer(oracle_config(w, dims=None), theta0.astype(np.float64))
+    sched = W.participation_schedule(w, 8)
+    assert 0 < sched.sum() < sched.size
+    h1 = [0.1, 0.3, 1.0, 0.1, 0.6, 0.2]; h2 = [0.1, 0.05, 0.0, 0.1, 0.4, 0.3]
+    for r in range(8):
+        g = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+        hz = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+        h.update_only(torch.from_numpy(g).cuda(), torch.from_numpy(hz).cuda())
+        tr.update_only(g, hz)
+        # each round starts from the oracle's state, so rounds are compared one by one
+        for i in range(k):
+            h.set_state(B.DW_S_THETA, i, tr.theta[i])
+        h.set_state(B.DW_S_CENTRE, 0, tr.centre)
+        pre_t = [h.get_state(B.DW_S_THETA, i).astype(np.float64) for i in range(k)]
+        pre_c = h.get_state(B.DW_S_CENTRE).astype(np.float64)
+        tr.theta = np.stack(pre_t); tr.centre = pre_c.copy()        # the fp32 values the GPU holds
+        assert h.elastic_sync(mode_gpu | B.DW_SEQUENTIAL, tau=1, h1=h1, h2=h2, participate=sched[r])
+        assert tr.elastic_sync(mode_ref, 1, h1, h2, participate=sched[r], sequential=True)
+        for i in range(k):
+            sc = h.get_state(B.DW_S_SCORE, i)
+            assert abs(sc[0] - tr.last_u[i]) < 1e-5 and abs(sc[2] - tr.last_h1[i]) < 5e-4, (r, i, sc)
+            got = h.get_state(B.DW_S_THETA, i)
+            if not sched[r][i]:
+                np.testing.assert_array_equal(got, pre_t[i].astype(np.float32))
+            # the weights carry fp32 noise of the norms (dynamic mode): allow it times the distance pulled over
+            slack = 5e-4 * np.abs(pre_t[i] - pre_c).max() * k
+            close(got - pre_t[i], tr.theta[i] - pre_t[i], RTOL_UPDATE, "seq round %d pull[%d]" % (r, i),
+                  extra=slack + 2.0 ** -23 * np.abs(tr.theta[i]))
+        close(h.get_state(B.DW_S_CENTRE) - pre_c, tr.centre - pre_c, RTOL_UPDATE, "seq round %d centre" % r,
+              extra=5e-4 * k * np.abs(np.stack(pre_t) - pre_c).max() + 2.0 ** -23 * np.abs(tr.centre))
+    # the sequential and the simultaneous form differ once two workers take part
+    assert sched.sum(1).max() >= 2
+
+
+def test_sequential_flag_is_validated():
+    w, theta0, _ = _flat_case(4096, 2, 9)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    with pytest.raises(B.DwError):
+        h.elastic_sync(7 | B.DW_SEQUENTIAL)
+    assert h.elastic_sync(B.DW_FIXED | B.DW_SEQUENTIAL)

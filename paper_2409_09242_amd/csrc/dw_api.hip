@@ -99,9 +99,9 @@ int validate(const dw_config* c, Layout* lay) {
       lay->ract[l] = take((size_t)k * B * c->dims[l] * es);
       if (c->dims[l] > dmax) dmax = c->dims[l];
     }
-    for (int b = 0; b < 2; ++b) {
-      lay->delta[b] = take((size_t)k * B * dmax * es);
-      lay->rdelta[b] = take((size_t)k * B * dmax * es);
+    for (int l = 1; l < L; ++l) {
+      lay->delta[l] = take((size_t)k * B * c->dims[l] * es);
+      lay->rdelta[l] = take((size_t)k * B * c->dims[l] * es);
     }
     const size_t head = (size_t)k * B * DW_MAX_CLASSES * sizeof(float);
     lay->sL = take(head); lay->rsL = take(head); lay->dL = take(head); lay->rdL = take(head);
@@ -240,18 +240,15 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
              float* loss, hipStream_t s) {
   const uint32_t* zb = d_zbits ? d_zbits : h->at<uint32_t>(h->lay.zbits);
   const int64_t zs = d_zbits ? 2 * ((h->lay.P + 63) / 64) : h->lay.z_stride;
-  if (h->lay.n_fuse_slots == 0) {
-    const int st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, nullptr, s);
-    if (st != DW_OK) return st;
-    return run_update(h, h->at<float>(h->lay.g), h->at<float>(h->lay.hz), h->lay.Pp, d_zbits, active, s);
-  }
   for (int i = 0; i < h->cfg.k; ++i)
     if ((active >> i) & 1ull) h->t[i] += 1;
+  const bool fused = h->lay.n_fuse_slots > 0;
   UpdateArgs a;
-  fill_update_args(h, a, h->at<float>(h->lay.g), h->at<float>(h->lay.hz), h->lay.Pp, zb, zs, active, true);
+  fill_update_args(h, a, h->at<float>(h->lay.g), h->at<float>(h->lay.hz), h->lay.Pp, zb, zs, active, fused);
   int st = clear_fused_partials(h, s);
   if (st != DW_OK) return st;
-  st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, &a, s);
+  const UpdateArgs* fu = fused ? &a : nullptr;
+  st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fu, s);
   if (st != DW_OK) return st;
   DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
   h->norms_valid = true;

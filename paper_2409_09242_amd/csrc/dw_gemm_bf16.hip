@@ -162,10 +162,10 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   const int tiles = tiles_m * ((a.N + BN - 1) / BN);
   const int per_xcd = gridDim.x >> 3;
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= tiles * a.k) return;
-  const int worker = logical / tiles;
-  if (!((a.active_mask >> worker) & 1ull)) return;
-  const int tile = logical - worker * tiles;
+  const int slot = logical / tiles;                         // which of the active workers
+  if (slot >= active_count(a.active_mask, a.k)) return;
+  const int worker = nth_active_worker(a.active_mask, slot);
+  const int tile = logical - slot * tiles;
   if (EPI == EPI_WGRAD && a.fu.on && blockIdx.x < 256 * 8) {
     // Fused update: a block alternates between a compute-bound main loop and an HBM-bound epilogue of about twice
     // its length.  Blocks that start together stay in step, leaving HBM idle while everybody multiplies, so the
@@ -383,7 +383,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
         b16_w[bt.e[q]] = f2bf(t1);
       }
     };
-    Batch b0, b1;
+    Batch b0, b1;                                             // (a third batch in flight spills registers)
     load_batch(b0, 0);
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
@@ -466,7 +466,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
 template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  const dim3 grid((unsigned)((tiles * a.k + 7) / 8 * 8)), block(NT);
+  const dim3 grid((unsigned)((tiles * active_count(a.active_mask, a.k) + 7) / 8 * 8)), block(NT);
   constexpr int XTH = RX ? NT / 2 : NT;
   constexpr int smem = 2 * 2 * (Tile<BM, XTH, XKC>::LDS_ELEMS * (RX ? 2 : 1) +
                                 Tile<BN, NT, YKC>::LDS_ELEMS * (RYM != RY_NONE ? 2 : 1));

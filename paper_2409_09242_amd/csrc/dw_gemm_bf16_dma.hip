@@ -94,10 +94,10 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
   const int tiles = tiles_m * (a.N / BN);
   const int per_xcd = gridDim.x >> 3;                       // XCD-aware order, see dual_gemm_bf16
   const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= tiles * a.k) return;
-  const int worker = logical / tiles;
-  if (!((a.active_mask >> worker) & 1ull)) return;
-  const int tile = logical - worker * tiles;
+  const int slot = logical / tiles;                         // which of the active workers
+  if (slot >= active_count(a.active_mask, a.k)) return;
+  const int worker = nth_active_worker(a.active_mask, slot);
+  const int tile = logical - slot * tiles;
   const int tm = tile % tiles_m, tn = tile / tiles_m;
   const int row0 = tm * BM, col0 = tn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
 template <bool RX>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
-  const dim3 grid((unsigned)((tiles * a.k + 7) / 8 * 8)), block(NT);
+  const dim3 grid((unsigned)((tiles * active_count(a.active_mask, a.k) + 7) / 8 * 8)), block(NT);
   constexpr int smem = (BM * BK * 2 * (RX ? 2 : 1) + BN * BK * 2) * STAGES + 2 * BN * 16;
   static_assert(smem <= 160 * 1024, "LDS budget");
   auto kern = dual_gemm_bf16_fwd_dma<RX>;

@@ -106,8 +106,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
   static_assert(WM * WN == 4, "four waves per block");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
-  const int worker = blockIdx.y;
-  if (!((a.active_mask >> worker) & 1ull)) return;
+  const int worker = nth_active_worker(a.active_mask, blockIdx.y);    // grid y covers the active workers
 
   const int tiles_m = (a.M + BM - 1) / BM;
   const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
@@ -249,7 +248,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
 template <int BM, int BN, int WM, int WN>
 static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  const dim3 grid((unsigned)tiles, (unsigned)a.k), block(NT);
+  const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k)), block(NT);
 #define DW_LAUNCH(XKC, YKC, RX, RYM, EPI) \
   hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>), grid, block, 0, s, a)
   const bool rx = a.RX != nullptr;

@@ -129,6 +129,16 @@ struct GemmArgs {
   uint64_t active_mask;
 };
 
+// The GEMM grids cover the active workers only: block group j works for the j-th set bit of active_mask.
+__host__ __device__ inline int active_count(uint64_t mask, int k) {
+  const uint64_t low = k >= 64 ? ~0ull : ((1ull << k) - 1ull);
+  return __builtin_popcountll(mask & low);
+}
+__device__ __forceinline__ int nth_active_worker(uint64_t mask, int j) {
+  while (j-- > 0) mask &= mask - 1;                   // drop the j lowest set bits (uniform scalar work)
+  return __builtin_ctzll(mask);
+}
+
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 // can the bf16 weight-gradient kernel of a layer W[n_out][n_in] (bit/parameter offset woff) apply the update itself,
@@ -154,7 +164,7 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   int64_t woff[DW_MAX_LAYERS] = {0}, boff[DW_MAX_LAYERS] = {0};
   size_t theta = 0, m = 0, v = 0, g = 0, hz = 0, centre = 0, wb16 = 0, zbits = 0;
   size_t act[DW_MAX_LAYERS] = {0}, ract[DW_MAX_LAYERS] = {0};   // a_l, Ra_l for l = 1..L-1 (index l)
-  size_t delta[2] = {0, 0}, rdelta[2] = {0, 0};                  // ping-pong hidden-layer errors
+  size_t delta[DW_MAX_LAYERS] = {0}, rdelta[DW_MAX_LAYERS] = {0}; // d_l, Rd_l of the hidden layers l = 1..L-1 (index l)
   size_t sL = 0, rsL = 0, dL = 0, rdL = 0, dL16 = 0, rdL16 = 0;  // output layer, fp32 [k][B][16] (+ bf16 copies)
   int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
   int n_fuse_slots = 0;
@@ -166,7 +176,8 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
 // Enqueue forward, R-forward, backward and R-backward of all layers for the active workers; leaves the mean
 // gradient in the g buffer and the Hessian-vector product in the hz buffer (returns a dw_status).  With `fuse`
 // (the arguments of this step's update) the layers marked in lay.fuse_base are updated by their weight-gradient
-// kernels instead, and their W-parts of g and hz are not written.
+// kernels instead, and their W-parts of g and hz are not written.  All data gradients are launched before the
+// weight gradients (a fused weight gradient overwrites the W_l its layer's data gradient reads).
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
                 hipStream_t s);

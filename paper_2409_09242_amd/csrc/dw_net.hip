@@ -147,56 +147,61 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     if ((e = launch_head(hd, s)) != hipSuccess) return DW_ERR_HIP;
   }
 
-  // backward with R-backward, output layer first
-  for (int l = L; l >= 1; --l) {
-    const void* dl; const void* rdl; int ldd; int64_t dstride;
+  // backward with R-backward.  d_l, Rd_l of layer l (its own buffer per layer, so both phases can read them):
+  auto delta_of = [&](int l, const void*& dl, const void*& rdl, int& ldd, int64_t& dstride) {
     if (l == L) {
       dl = ws + (b16 ? lay.dL16 : lay.dL); rdl = ws + (b16 ? lay.rdL16 : lay.rdL); ldd = HL; dstride = (int64_t)B * HL;
     } else {
-      dl = ws + lay.delta[l & 1]; rdl = ws + lay.rdelta[l & 1]; ldd = cfg.dims[l]; dstride = act_stride(l);
+      dl = ws + lay.delta[l]; rdl = ws + lay.rdelta[l]; ldd = cfg.dims[l]; dstride = act_stride(l);
     }
-    const bool fused = fuse != nullptr && lay.fuse_base[l - 1] >= 0;
-    auto weight_gradient = [&]() -> hipError_t {   // and its R-companion: contraction over the minibatch
-      GemmArgs a{};
-      a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 0; a.ldx = ldd;
-      a.Y = act(l - 1); a.RY = ract(l - 1); a.ry_bits = 0; a.y_wstride = act_stride(l - 1); a.y_kcontig = 0;
-      a.ldy = cfg.dims[l - 1];
-      a.zbits = zbits; a.z_stride = z_stride;
-      a.M = cfg.dims[l]; a.N = cfg.dims[l - 1]; a.K = B;
-      a.C = g + lay.woff[l - 1]; a.RC = hz + lay.woff[l - 1]; a.ldc = cfg.dims[l - 1]; a.c_wstride = lay.Pp;
-      a.gb = g + lay.boff[l - 1]; a.hzb = hz + lay.boff[l - 1];
-      a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
-      if (fused) {   // the kernel applies this step's update to W_l instead of storing gW_l and HzW_l
-        const int64_t wo = lay.woff[l - 1];
-        a.z_off = wo;
-        a.fu.on = 1;
-        a.fu.theta = fuse->theta + wo; a.fu.m = fuse->m + wo; a.fu.v = fuse->v + wo;
-        a.fu.centre = fuse->centre + wo; a.fu.wb16 = fuse->wb16 + wo;
-        a.fu.partials = reinterpret_cast<double*>(ws + lay.partials_f);
-        a.fu.part_stride = lay.n_fuse_slots; a.fu.part_base = lay.fuse_base[l - 1];
-        a.fu.avg_block = fuse->avg_block;
-        a.fu.lr = fuse->lr; a.fu.beta1 = fuse->beta1; a.fu.beta2 = fuse->beta2; a.fu.eps = fuse->eps; a.fu.hpow = fuse->hpow;
-        a.fu.sc = fuse->sc;
-      }
-      return gemm(a);
-    };
-    // a fused weight gradient overwrites W_l, which the data gradient still has to read: it goes second then
-    if (!fused && (e = weight_gradient()) != hipSuccess) return DW_ERR_HIP;
-    if (l > 1) {   // data gradient through W_l, masked by the ReLU of layer l-1
-      GemmArgs a{};
-      a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 1; a.ldx = ldd;
-      a.Y = weights(l); a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0;
-      a.ldy = cfg.dims[l - 1];
-      a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1];
-      a.M = B; a.N = cfg.dims[l - 1]; a.K = cfg.dims[l];
-      a.C = ws + lay.delta[(l - 1) & 1]; a.RC = ws + lay.rdelta[(l - 1) & 1]; a.ldc = cfg.dims[l - 1];
-      a.c_wstride = act_stride(l - 1);
-      a.mask_src = act(l - 1); a.ld_mask = cfg.dims[l - 1]; a.mask_wstride = act_stride(l - 1);
-      a.epi = EPI_MASK; a.k = k; a.active_mask = active;
-      if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
+  };
+  auto weight_gradient = [&](int l) -> hipError_t {   // and its R-companion: contraction over the minibatch
+    const void* dl; const void* rdl; int ldd; int64_t dstride;
+    delta_of(l, dl, rdl, ldd, dstride);
+    GemmArgs a{};
+    a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 0; a.ldx = ldd;
+    a.Y = act(l - 1); a.RY = ract(l - 1); a.ry_bits = 0; a.y_wstride = act_stride(l - 1); a.y_kcontig = 0;
+    a.ldy = cfg.dims[l - 1];
+    a.zbits = zbits; a.z_stride = z_stride;
+    a.M = cfg.dims[l]; a.N = cfg.dims[l - 1]; a.K = B;
+    a.C = g + lay.woff[l - 1]; a.RC = hz + lay.woff[l - 1]; a.ldc = cfg.dims[l - 1]; a.c_wstride = lay.Pp;
+    a.gb = g + lay.boff[l - 1]; a.hzb = hz + lay.boff[l - 1];
+    a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
+    if (fuse != nullptr && lay.fuse_base[l - 1] >= 0) {
+      // the kernel applies this step's update to W_l instead of storing gW_l and HzW_l
+      const int64_t wo = lay.woff[l - 1];
+      a.z_off = wo;
+      a.fu.on = 1;
+      a.fu.theta = fuse->theta + wo; a.fu.m = fuse->m + wo; a.fu.v = fuse->v + wo;
+      a.fu.centre = fuse->centre + wo; a.fu.wb16 = fuse->wb16 + wo;
+      a.fu.partials = reinterpret_cast<double*>(ws + lay.partials_f);
+      a.fu.part_stride = lay.n_fuse_slots; a.fu.part_base = lay.fuse_base[l - 1];
+      a.fu.avg_block = fuse->avg_block;
+      a.fu.lr = fuse->lr; a.fu.beta1 = fuse->beta1; a.fu.beta2 = fuse->beta2; a.fu.eps = fuse->eps; a.fu.hpow = fuse->hpow;
+      a.fu.sc = fuse->sc;
     }
-    if (fused && (e = weight_gradient()) != hipSuccess) return DW_ERR_HIP;
+    return gemm(a);
+  };
+  // The data gradients, output layer first.  A fused weight gradient overwrites W_l, which the data gradient
+  // through W_l reads, so all data gradients are launched before the weight gradients.
+  for (int l = L; l >= 2; --l) {
+    const void* dl; const void* rdl; int ldd; int64_t dstride;
+    delta_of(l, dl, rdl, ldd, dstride);
+    GemmArgs a{};                                     // through W_l, masked by the ReLU of layer l-1
+    a.X = dl; a.RX = rdl; a.x_wstride = dstride; a.x_kcontig = 1; a.ldx = ldd;
+    a.Y = weights(l); a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0;
+    a.ldy = cfg.dims[l - 1];
+    a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1];
+    a.M = B; a.N = cfg.dims[l - 1]; a.K = cfg.dims[l];
+    a.C = ws + lay.delta[l - 1]; a.RC = ws + lay.rdelta[l - 1]; a.ldc = cfg.dims[l - 1];
+    a.c_wstride = act_stride(l - 1);
+    a.mask_src = act(l - 1); a.ld_mask = cfg.dims[l - 1]; a.mask_wstride = act_stride(l - 1);
+    a.epi = EPI_MASK; a.k = k; a.active_mask = active;
+    if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
   }
+  // weight gradients
+  for (int l = L; l >= 1; --l)
+    if ((e = weight_gradient(l)) != hipSuccess) return DW_ERR_HIP;
   return DW_OK;
 }
 

@@ -341,61 +341,90 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];
     static_assert(offsetof(UpdateScalars, inv_bc2) == DW_MAX_K * sizeof(float), "inv_bc2 follows inv_bc1");
     const float inv_b = 1.0f / (float)f.avg_block;
-    // The epilogue is bound by HBM, so loads must always be in flight: the 64 elements of a lane are taken in 16
-    // batches of four (one MFMA register group = four consecutive rows), and the 24 loads of batch b+1 are issued
-    // before batch b is computed and stored.  Scheduling fences keep the compiler from hoisting more batches
-    // into registers that accumulators still occupy.
-    constexpr int FB = 4, NB = TN * TM * 16 / FB;
-    struct Batch { uint32_t e[FB], zw[FB]; float th[FB], mm[FB], vv[FB], cc[FB]; };
-    auto load_batch = [&](Batch& bt, int b) {
-      const int j = b / (TM * 4), i = (b / 4) % TM, rg = b % 4;
-      const uint32_t n = (uint32_t)(col0 + wn0 + j * 32 + l32);
-#pragma unroll
-      for (int q = 0; q < FB; ++q) {
-        const uint32_t m = (uint32_t)(row0 + wm0 + i * 32 + rg * 8 + lhalf * 4 + q);
-        bt.e[q] = m * (uint32_t)a.ldc + n;                    // offset inside the W block
-        bt.th[q] = th_w[bt.e[q]]; bt.mm[q] = m_w[bt.e[q]]; bt.vv[q] = v_w[bt.e[q]]; bt.cc[q] = f.centre[bt.e[q]];
-        bt.zw[q] = zrow[bt.e[q] >> 5];
-      }
+    // The epilogue is bound by HBM, and HBM streams a quarter faster when a wave instruction touches 256
+    // contiguous bytes per row instead of 128 (measured).  The MFMA layout gives a lane one column, i.e. 128-byte
+    // row pieces per half-wave, so g and Hz go through LDS (free after the main loop, a private region per wave):
+    // the accumulators of one row of MFMA tiles (32 rows x 64 columns) are scattered into [row][72 floats] arrays
+    // and read back as one float4 per lane, 16 lanes per row.  A batch is then 4 rows x 256 bytes per access, all
+    // state is moved as float4 (bf16 copy: 8 bytes), and the block mean of D along fan-in is the update kernel's:
+    // four values in the lane, then a butterfly over avg_block / 4 lanes.  The loads of two later batches are in
+    // flight while a batch is computed; scheduling fences keep the compiler from hoisting more.
+    static_assert(TN == 2 || !(BM == 128 && BN == 256), "the wave's tile row is 64 columns wide");
+    constexpr int PR = 72;                                    // floats per LDS row: both half-waves hit distinct banks
+    float* gl = reinterpret_cast<float*>(smem) + wave * (2 * 32 * PR);
+    float* hl = gl + 32 * PR;
+    constexpr int NB = TM * 8, DEPTH = 3;
+    struct Batch { uint32_t e, zw; float4 th, mm, vv, cc; };
+    const int brow = lane >> 4, bcol = (lane & 15) * 4;
+    auto load_batch = [&](Batch& bt, int bb) {
+      const int i = bb / 8, b = bb % 8;
+      const uint32_t m = (uint32_t)(row0 + wm0 + i * 32 + b * 4 + brow), n = (uint32_t)(col0 + wn0 + bcol);
+      bt.e = m * (uint32_t)a.ldc + n;                         // offset inside the W block, a multiple of 4
+      bt.th = *reinterpret_cast<const float4*>(th_w + bt.e); bt.mm = *reinterpret_cast<const float4*>(m_w + bt.e);
+      bt.vv = *reinterpret_cast<const float4*>(v_w + bt.e); bt.cc = *reinterpret_cast<const float4*>(f.centre + bt.e);
+      bt.zw = zrow[bt.e >> 5];
     };
     float nsum = 0.f;
-    auto finish_batch = [&](const Batch& bt, const float* gq, const float* hq) {
+    const int group_lanes = f.avg_block >> 2;                 // lanes that share one averaging block (when b > 4)
+    auto finish_batch = [&](const Batch& bt, int b) {
+      const float4 g4 = *reinterpret_cast<const float4*>(gl + (b * 4 + brow) * PR + bcol);
+      const float4 h4 = *reinterpret_cast<const float4*>(hl + (b * 4 + brow) * PR + bcol);
+      const float g[4] = {g4.x, g4.y, g4.z, g4.w}, hz[4] = {h4.x, h4.y, h4.z, h4.w};
+      const float th[4] = {bt.th.x, bt.th.y, bt.th.z, bt.th.w}, mm[4] = {bt.mm.x, bt.mm.y, bt.mm.z, bt.mm.w};
+      const float vv[4] = {bt.vv.x, bt.vv.y, bt.vv.z, bt.vv.w}, cc[4] = {bt.cc.x, bt.cc.y, bt.cc.z, bt.cc.w};
+      const uint32_t zb4 = bt.zw >> (bt.e & 31u);
+      float D[4];
 #pragma unroll
-      for (int q = 0; q < FB; ++q) {
-        const float g = gq[q], hz = hq[q];
-        float D = ((bt.zw[q] >> l32) & 1u) ? hz : -hz;         // Hutchinson: z * Hz
-        if (f.avg_block > 1) {                                 // same summation tree as update_kernel
-          float sD = D;
+      for (int q = 0; q < 4; ++q) D[q] = ((zb4 >> q) & 1u) ? hz[q] : -hz[q];      // Hutchinson: z * Hz
+      if (f.avg_block == 2) {
+        const float p0 = 0.5f * (D[0] + D[1]), p1 = 0.5f * (D[2] + D[3]);
+        D[0] = D[1] = p0; D[2] = D[3] = p1;
+      } else if (f.avg_block >= 4) {
+        float sD = (D[0] + D[1]) + (D[2] + D[3]);
 #pragma unroll
-          for (int off = 1; off < 32; off <<= 1) {
-            const float t = __shfl_xor(sD, off);
-            sD += off < f.avg_block ? t : 0.f;
-          }
-          D = sD * inv_b;
+        for (int off = 1; off < 8; off <<= 1) {
+          const float t = __shfl_xor(sD, off);
+          sD += off < group_lanes ? t : 0.f;
         }
-        const float m1 = f.beta1 * bt.mm[q] + (1.0f - f.beta1) * g;
-        const float v1 = f.beta2 * bt.vv[q] + (1.0f - f.beta2) * (D * D);
-        const float mhat = m1 * ib1, vhat = v1 * ib2;
-        const float t1 = bt.th[q] - f.lr * (mhat / (sqrtf(vhat) + f.eps));
-        const float d = t1 - bt.cc[q];
-        nsum += d * d;
-        th_w[bt.e[q]] = t1; m_w[bt.e[q]] = m1; v_w[bt.e[q]] = v1;
-        b16_w[bt.e[q]] = f2bf(t1);
+        sD *= inv_b;
+        D[0] = D[1] = D[2] = D[3] = sD;
       }
+      float t1[4], m1[4], v1[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        m1[q] = f.beta1 * mm[q] + (1.0f - f.beta1) * g[q];
+        v1[q] = f.beta2 * vv[q] + (1.0f - f.beta2) * (D[q] * D[q]);
+        const float mhat = m1[q] * ib1, vhat = v1[q] * ib2;
+        t1[q] = th[q] - f.lr * (mhat / (sqrtf(vhat) + f.eps));
+        const float d = t1[q] - cc[q];
+        nsum += d * d;
+      }
+      *reinterpret_cast<float4*>(th_w + bt.e) = make_float4(t1[0], t1[1], t1[2], t1[3]);
+      *reinterpret_cast<float4*>(m_w + bt.e) = make_float4(m1[0], m1[1], m1[2], m1[3]);
+      *reinterpret_cast<float4*>(v_w + bt.e) = make_float4(v1[0], v1[1], v1[2], v1[3]);
+      ushort4 w16; w16.x = f2bf(t1[0]); w16.y = f2bf(t1[1]); w16.z = f2bf(t1[2]); w16.w = f2bf(t1[3]);
+      *reinterpret_cast<ushort4*>(b16_w + bt.e) = w16;
     };
-    Batch b0, b1;                                             // (a third batch in flight spills registers)
-    load_batch(b0, 0);
+    Batch ring[DEPTH];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-      Batch& cur = (b & 1) ? b1 : b0;
-      Batch& nxt = (b & 1) ? b0 : b1;
-      if (b + 1 < NB) load_batch(nxt, b + 1);
+    for (int bb = 0; bb < DEPTH - 1; ++bb) load_batch(ring[bb], bb);
+#pragma unroll
+    for (int bb = 0; bb < NB; ++bb) {
+      const int i = bb / 8, b = bb % 8;
+      if (b == 0) {
+        // scatter the accumulators of tile row i (earlier reads of the region are done: same wave, program order)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = (r >> 2) * 8 + lhalf * 4 + (r & 3), col = j * 32 + l32;
+            gl[row * PR + col] = acc[i][j][r];
+            hl[row * PR + col] = racc[i][j][r];
+          }
+      }
+      if (bb + DEPTH - 1 < NB) load_batch(ring[(bb + DEPTH - 1) % DEPTH], bb + DEPTH - 1);
       __builtin_amdgcn_sched_barrier(0);
-      const int j = b / (TM * 4), i = (b / 4) % TM, rg = b % 4;
-      float gq[FB], hq[FB];
-#pragma unroll
-      for (int q = 0; q < FB; ++q) { gq[q] = acc[i][j][rg * 4 + q]; hq[q] = racc[i][j][rg * 4 + q]; }
-      finish_batch(cur, gq, hq);
+      finish_batch(ring[bb % DEPTH], b);
       asm volatile("" : "+v"(nsum));                          // the batch's terms are summed here, not kept for later
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -468,8 +497,12 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   const dim3 grid((unsigned)((tiles * active_count(a.active_mask, a.k) + 7) / 8 * 8)), block(NT);
   constexpr int XTH = RX ? NT / 2 : NT;
-  constexpr int smem = 2 * 2 * (Tile<BM, XTH, XKC>::LDS_ELEMS * (RX ? 2 : 1) +
-                                Tile<BN, NT, YKC>::LDS_ELEMS * (RYM != RY_NONE ? 2 : 1));
+  constexpr int tiles_b = 2 * 2 * (Tile<BM, XTH, XKC>::LDS_ELEMS * (RX ? 2 : 1) +
+                                   Tile<BN, NT, YKC>::LDS_ELEMS * (RYM != RY_NONE ? 2 : 1));
+  // the fused weight-gradient epilogue passes g and Hz through LDS: per wave two arrays of 32 rows x 72 floats
+  constexpr int epi_b = (EPI == EPI_WGRAD && BM == 128 && BN == 256) ? (NT / 64) * 2 * 32 * 72 * 4 : 0;
+  constexpr int smem = tiles_b > epi_b ? tiles_b : epi_b;
+  static_assert(smem <= 160 * 1024, "LDS budget");
   auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>;
   static bool configured = false;        // raise the dynamic LDS limit once per instantiation
   if (!configured) {

@@ -18,6 +18,7 @@
 #include <cstddef>
 
 #include "dw_internal.h"
+#include "dw_gemm_epi.h"
 
 namespace dw {
 
@@ -442,6 +443,38 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
       for (int w = 0; w < NT / 64; ++w) t += red[w];
       f.partials[(int64_t)worker * f.part_stride + f.part_base + tile] = t;
     }
+  } else if (EPI == EPI_RELU || EPI == EPI_MASK) {
+    // bf16 outputs: through LDS, 16-byte stores of whole row pieces (see dw_gemm_epi.h)
+    char* wl = reinterpret_cast<char*>(smem) + wave * epi_bf16_lds_bytes(TN);
+    const uint16_t* msk = EPI == EPI_MASK ? reinterpret_cast<const uint16_t*>(a.mask_src) + (int64_t)worker * a.mask_wstride : nullptr;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      floatx16 cv[TN], rcv[TN];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if (EPI == EPI_RELU) {
+          const int n = col0 + wn0 + j * 32 + l32;
+          float bias = 0.f, cz = 0.f;
+          if (n < a.N) {
+            bias = a.bias[(int64_t)worker * a.bias_wstride + n];
+            const int64_t bi = a.zb_off + n;
+            cz = ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
+          }
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float c = acc[i][j][r] + bias, rc = racc[i][j][r] + cz;
+            const bool on = c > 0.f;
+            cv[j][r] = on ? c : 0.f; rcv[j][r] = on ? rc : 0.f;
+          }
+        } else {
+          cv[j] = acc[i][j]; rcv[j] = racc[i][j];
+        }
+      }
+      const int rbase = row0 + wm0 + i * 32, cbase = col0 + wn0;
+      epi_bf16_rows_out<TN, EPI == EPI_MASK>(wl, cv, rcv, lane, reinterpret_cast<uint16_t*>(a.C), reinterpret_cast<uint16_t*>(a.RC),
+                                             (int64_t)worker * a.c_wstride + (int64_t)rbase * a.ldc + cbase, a.ldc,
+                                             a.M - rbase, a.N - cbase, msk, (int64_t)rbase * a.ld_mask + cbase, a.ld_mask);
+    }
   } else {
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
@@ -501,7 +534,8 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
                                    Tile<BN, NT, YKC>::LDS_ELEMS * (RYM != RY_NONE ? 2 : 1));
   // the fused weight-gradient epilogue passes g and Hz through LDS: per wave two arrays of 32 rows x 72 floats
   constexpr int epi_b = (EPI == EPI_WGRAD && BM == 128 && BN == 256) ? (NT / 64) * 2 * 32 * 72 * 4 : 0;
-  constexpr int smem = tiles_b > epi_b ? tiles_b : epi_b;
+  constexpr int out_b = (EPI == EPI_RELU || EPI == EPI_MASK) ? (NT / 64) * epi_bf16_lds_bytes(BN / WN / 32) : 0;
+  constexpr int smem = tiles_b > epi_b ? (tiles_b > out_b ? tiles_b : out_b) : (epi_b > out_b ? epi_b : out_b);
   static_assert(smem <= 160 * 1024, "LDS budget");
   auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>;
   static bool configured = false;        // raise the dynamic LDS limit once per instantiation

@@ -15,6 +15,7 @@
 // Requirements (otherwise the caller uses dual_gemm_bf16): see gemm_bf16_dma_ok.  Rows beyond M are clamped to the
 // last valid row (their products are discarded).
 #include "dw_internal.h"
+#include "dw_gemm_epi.h"
 
 namespace dw {
 
@@ -31,11 +32,6 @@ constexpr int ZGROUP = 4;                               // k-tiles covered by on
 typedef __attribute__((address_space(3))) void* lds_void;
 typedef __attribute__((address_space(1))) const void* glb_void;
 
-__device__ __forceinline__ uint16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 __device__ __forceinline__ uint32_t pm1_pair(uint32_t b_lo, uint32_t b_hi) {
   return 0xBF80BF80u ^ (b_lo << 15) ^ (b_hi << 31);     // bit set -> +1 (0x3F80), clear -> -1 (0xBF80)
 }
@@ -226,26 +222,29 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     st = st_next;
   }
 
-  // epilogue: lane holds column n = l32 of each 32x32 tile, rows (r/4)*8 + lhalf*4 + r%4
+  // epilogue: bias, R-bias (the bias part of z), ReLU; the two bf16 outputs go through LDS (free after the last
+  // barrier of the loop) so that they leave as 16-byte stores of whole row pieces (see dw_gemm_epi.h)
+  char* wl = smem + wave * epi_bf16_lds_bytes(TN);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = col0 + wn0 + j * 32 + l32;
-    const float bias = a.bias[(int64_t)worker * a.bias_wstride + n];
-    const int64_t bi = a.zb_off + n;
-    const float cz = ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
+  for (int i = 0; i < TM; ++i) {
+    floatx16 cv[TN], rcv[TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int j = 0; j < TN; ++j) {
+      const int n = col0 + wn0 + j * 32 + l32;
+      const float bias = a.bias[(int64_t)worker * a.bias_wstride + n];
+      const int64_t bi = a.zb_off + n;
+      const float cz = ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int m = row0 + wm0 + i * 32 + (r >> 2) * 8 + lhalf * 4 + (r & 3);
-        if (m >= a.M) continue;
         const float c = acc[i][j][r] + bias, rc = racc[i][j][r] + cz;
-        const int64_t o = (int64_t)worker * a.c_wstride + (int64_t)m * a.ldc + n;
         const bool on = c > 0.f;
-        reinterpret_cast<uint16_t*>(a.C)[o] = f2bf(on ? c : 0.f);
-        reinterpret_cast<uint16_t*>(a.RC)[o] = f2bf(on ? rc : 0.f);
+        cv[j][r] = on ? c : 0.f; rcv[j][r] = on ? rc : 0.f;
       }
     }
+    const int rbase = row0 + wm0 + i * 32, cbase = col0 + wn0;
+    epi_bf16_rows_out<TN, false>(wl, cv, rcv, lane, reinterpret_cast<uint16_t*>(a.C), reinterpret_cast<uint16_t*>(a.RC),
+                                 (int64_t)worker * a.c_wstride + (int64_t)rbase * a.ldc + cbase, a.ldc, a.M - rbase,
+                                 a.N - cbase, nullptr, 0, 0);
   }
 }
 

@@ -295,3 +295,32 @@ def test_bf16_fused_update_matches_the_unfused_path_and_the_oracle(avg_block):
     hA.worker_step(xb, yb, loss=lossA2)
     hB.worker_step(xb, yb, loss=lossB2)
     close(lossB2.cpu().numpy(), lossA2.cpu().numpy(), 1e-5, "loss after the round")
+
+
+def test_bf16_fused_update_with_caller_z_and_an_update_only_call_in_between():
+    """Caller-supplied sign bits (their per-worker stride is not a multiple of 16 bytes here), then an update on
+    caller-supplied g and Hz, then a round: the fused handle must keep agreeing with the unfused one."""
+    dims, batch, k = (512, 2048, 1024, 12), 128, 8        # P % 4 == 0: dw_update_only needs 16-byte rows
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=777, bf16=True, avg_block=4)
+    theta0 = W.init_theta(w.dims, w.seed)
+    hA = B.Handle(B.config_from_workload(w), theta0)
+    hB = B.Handle(B.config_from_workload(w, fuse_update=1), theta0)
+    x, y = W.minibatch_pool(w, 1, bf16_round=W.to_bf16_f32)
+    xb, yb = _to_bf16_bits(x[0]), torch.from_numpy(y[0]).cuda()
+    rng = W.rng_for(11, 29)
+    nw = (w.P + 63) // 64
+    assert (2 * nw) % 4 != 0                              # the forward kernel's 16-byte sign-bit loads must not be used
+    words = rng.integers(0, 2 ** 63, size=(k, nw), dtype=np.uint64)
+    zb = torch.from_numpy(np.stack([O.words_to_u32(words[i]) for i in range(k)]).view(np.int32)).cuda()
+    hA.worker_step(xb, yb, zbits=zb); hB.worker_step(xb, yb, zbits=zb)
+    g = (rng.standard_normal((k, w.P)) * 0.01).astype(np.float32)
+    hz = (rng.standard_normal((k, w.P)) * 0.01).astype(np.float32)
+    gd, hd = torch.from_numpy(g).cuda(), torch.from_numpy(hz).cuda()
+    hA.update_only(gd, hd, zbits=zb); hB.update_only(gd, hd, zbits=zb)
+    assert hA.elastic_sync(B.DW_DYNAMIC, tau=1) == hB.elastic_sync(B.DW_DYNAMIC, tau=1) == 1
+    for i in range(k):
+        sa, sb = hA.get_state(B.DW_S_SCORE, i), hB.get_state(B.DW_S_SCORE, i)
+        assert abs(sa[0] - sb[0]) < 1e-6, (i, sa, sb)
+        for sel in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V):
+            close(hB.get_state(sel, i), hA.get_state(sel, i), 1e-6, "fused vs unfused state %d of worker %d" % (sel, i))
+    close(hB.get_state(B.DW_S_CENTRE), hA.get_state(B.DW_S_CENTRE), 1e-6, "fused vs unfused centre")

@@ -28,7 +28,7 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA
 # HBM-side bytes per launch of the fused weight-gradient kernel at configuration 4 (mean of the three launches of
 # a step), from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel (factors 2.00 and 1.00);
 # see profiles/dual_gemm_bf16_fused_wgrad_c4_hbm_traffic.txt.  Valid only for the kernel as profiled there.
-TRAFFIC_C4_FUSED_WGRAD = 10.14e9
+TRAFFIC_C4_FUSED_WGRAD = None   # to be re-measured: the kernel changed after the counters were taken
 
 
 def class_flops(w):
@@ -61,8 +61,9 @@ def class_bytes(w, P, k, fused=(), part=1.0):
     theta, m, v (32 B per parameter and worker, +2 B for the bf16 weight copy); the pull reads and writes theta
     (8 B per parameter and communicating worker, +2 B bf16 copy; `part` = mean fraction of workers that communicate) and
     the centre (8 B per parameter).  A fused weight-gradient
-    launch reads theta, m, v and the centre, writes theta, m, v and the bf16 copy (30 B per parameter and worker,
-    + 1 bit of z) and reads its four bf16 operands once (d_l, Rd_l, a_{l-1}, Ra_{l-1})."""
+    launch reads theta, m, v, writes theta, m, v and the bf16 copy (26 B per parameter and worker, + 1 bit of z),
+    reads the centre (4 B) on the steps before a round, and reads its four bf16 operands once (d_l, Rd_l, a_{l-1},
+    Ra_{l-1})."""
     d = w.dims
     p_fused = sum(d[l] * d[l - 1] for l in fused)
     upd = (32.0 + (2.0 if w.bf16 else 0.0)) * (P - p_fused) * k
@@ -70,7 +71,8 @@ def class_bytes(w, P, k, fused=(), part=1.0):
     out = {"update": upd, "pull": pull}
     if fused:
         operands = sum(2.0 * 2.0 * w.batch * (d[l] + d[l - 1]) for l in fused)
-        out["gemm_wgrad"] = (30.125 * p_fused + operands) * k
+        # the centre (4 B) is read only on the steps after which a round is due: one step in tau
+        out["gemm_wgrad"] = ((26.125 + 4.0 / w.tau) * p_fused + operands) * k
     return out
 
 

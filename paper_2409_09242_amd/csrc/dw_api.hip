@@ -152,6 +152,7 @@ struct dw_handle {
   int64_t calls;            // dw_worker_step / dw_update_only calls so far
   int64_t rounds;           // communication rounds so far
   bool norms_valid;         // the squared distances in `partials` match the current theta and centre
+  int last_tau;             // communication period of the latest dw_elastic_sync call (1 before the first)
   Profiler* prof;           // non-null while per-kernel timing is enabled
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
@@ -248,10 +249,14 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
   int st = clear_fused_partials(h, s);
   if (st != DW_OK) return st;
   const UpdateArgs* fu = fused ? &a : nullptr;
-  st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fu, s);
+  // The distances to the centre are only used by a communication round.  Fused layers pay for them with a read
+  // of the centre per worker, so they skip it on steps after which, going by the period of the latest
+  // dw_elastic_sync call, no round is due; should a round come anyway, it measures the distances itself.
+  const bool dist = !fused || h->last_tau <= 1 || (h->calls + 1) % h->last_tau == 0;
+  st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fu, dist, s);
   if (st != DW_OK) return st;
   DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
-  h->norms_valid = true;
+  h->norms_valid = dist;
   h->calls += 1;
   return DW_OK;
 }
@@ -306,7 +311,7 @@ int dw_init(dw_handle** out, const dw_config* cfg, void* d_workspace, size_t wor
   h->lay = lay;
   h->ws = reinterpret_cast<char*>(d_workspace);
   std::memset(h->t, 0, sizeof(h->t));
-  h->calls = 0; h->rounds = 0; h->norms_valid = false; h->prof = nullptr;
+  h->calls = 0; h->rounds = 0; h->norms_valid = false; h->prof = nullptr; h->last_tau = 1;
   int rc = DW_OK;
   do {
     hipError_t e = launch_fill_zero(h->ws, lay.total, s);            // moments, padding, history: all zero
@@ -421,6 +426,7 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
   if (mode != DW_FIXED && mode != DW_MANUAL && mode != DW_DYNAMIC) return DW_ERR_ARG;
   if (mode == DW_MANUAL && (!h_h1 || !h_h2)) return DW_ERR_NULL;
   if (tau < 1) return DW_ERR_ARG;
+  h->last_tau = tau;
   if (h->calls % tau != 0) return 0;
   ProfilerGuard pg(h);
   hipStream_t s = (hipStream_t)stream;

@@ -362,7 +362,8 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
       const uint32_t m = (uint32_t)(row0 + wm0 + i * 32 + b * 4 + brow), n = (uint32_t)(col0 + wn0 + bcol);
       bt.e = m * (uint32_t)a.ldc + n;                         // offset inside the W block, a multiple of 4
       bt.th = *reinterpret_cast<const float4*>(th_w + bt.e); bt.mm = *reinterpret_cast<const float4*>(m_w + bt.e);
-      bt.vv = *reinterpret_cast<const float4*>(v_w + bt.e); bt.cc = *reinterpret_cast<const float4*>(f.centre + bt.e);
+      bt.vv = *reinterpret_cast<const float4*>(v_w + bt.e);
+      bt.cc = f.dist ? *reinterpret_cast<const float4*>(f.centre + bt.e) : make_float4(0.f, 0.f, 0.f, 0.f);
       bt.zw = zrow[bt.e >> 5];
     };
     float nsum = 0.f;
@@ -437,7 +438,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     double* red = reinterpret_cast<double*>(smem);
     if (lane == 0) red[wave] = ws;
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0 && f.dist) {
       double t = 0.0;
 #pragma unroll
       for (int w = 0; w < NT / 64; ++w) t += red[w];

@@ -94,6 +94,7 @@ hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hi
 // element (m, n) of the product is parameter woff + m*ldc + n of the worker
 struct FuseArgs {
   int on;
+  int dist;                           // 1: also read the centre and report the tile's squared distance to it
   float* theta; float* m; float* v;   // worker 0's W block of the layer; worker stride = the product's c_wstride
   const float* centre;                // the layer's W block of the centre
   uint16_t* wb16;                     // bf16 copy of theta (W block), worker stride c_wstride
@@ -180,7 +181,7 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
 // weight gradients (a fused weight gradient overwrites the W_l its layer's data gradient reads).
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
-                hipStream_t s);
+                bool fuse_dist, hipStream_t s);
 
 }  // namespace dw
 

@@ -98,7 +98,7 @@ hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
-                hipStream_t s) {
+                bool fuse_dist, hipStream_t s) {
   const bool b16 = cfg.dtype == DW_BF16;
   const int L = cfg.n_layers, k = cfg.k, B = cfg.batch;
   const int HL = DW_MAX_CLASSES;                     // row stride of the output-layer buffers
@@ -172,6 +172,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       const int64_t wo = lay.woff[l - 1];
       a.z_off = wo;
       a.fu.on = 1;
+      a.fu.dist = fuse_dist ? 1 : 0;
       a.fu.theta = fuse->theta + wo; a.fu.m = fuse->m + wo; a.fu.v = fuse->v + wo;
       a.fu.centre = fuse->centre + wo; a.fu.wb16 = fuse->wb16 + wo;
       a.fu.partials = reinterpret_cast<double*>(ws + lay.partials_f);

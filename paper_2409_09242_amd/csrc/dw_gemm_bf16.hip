@@ -291,8 +291,10 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     read_frags(f0, cur, 0);
     read_frags(f1, cur, 1);
     __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);                           // the wave feeding the matrix cores issues first
     mfma_step(f0);
     mfma_step(f1);
+    __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
   };
   auto move_tiles = [&](int kt, int cur) {

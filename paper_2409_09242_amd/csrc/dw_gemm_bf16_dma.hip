@@ -207,7 +207,9 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     read_frags(f1, st, 1);
     __builtin_amdgcn_sched_barrier(0);
     expand(f0, 0);
+    __builtin_amdgcn_s_setprio(1);                          // the wave feeding the matrix cores issues first
     multiply(f0);
+    __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     expand(f1, 1);                                          // before the next tile's bits replace this tile's
     // k-tile kt+1 must have landed (this wave's part), then everybody's part; after the barrier nobody reads
@@ -217,7 +219,9 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     if (kt + STAGES < nkt) issue(kt + STAGES, st);
     if (kt + 1 < nkt) { read_bits(kt + 1); read_frags(f0, st_next, 0); }
     __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
     multiply(f1);
+    __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
     st = st_next;
   }

@@ -315,9 +315,18 @@ def spatial_average(D: np.ndarray, dims: Optional[Sequence[int]], avg_block: int
     return out
 
 
+def hutchinson_diagonal(zs, hzs) -> np.ndarray:
+    """Hutchinson estimate of diag(H) from n probes (Section IV-B): (1/n) sum_j z_j * (H z_j).
+    zs, hzs: [n, P] (or [P] for a single probe)."""
+    zs = np.atleast_2d(np.asarray(zs, dtype=F64))
+    hzs = np.atleast_2d(np.asarray(hzs, dtype=F64))
+    return (zs * hzs).sum(axis=0) / zs.shape[0]
+
+
 def adahessian_update(theta, m, v, g, hz, z, t, *, lr, beta1, beta2, eps, hpow, dims=None, avg_block=1):
-    """One AdaHessian update of (theta, m, v); returns new arrays.  t is the 1-based step count."""
-    D = z * hz                                             # Hutchinson diagonal estimate, n = 1
+    """One AdaHessian update of (theta, m, v); returns new arrays.  t is the 1-based step count.
+    hz, z: one probe ([P]) or n probes ([n, P]) of the same minibatch."""
+    D = hutchinson_diagonal(z, hz)                         # Hutchinson diagonal estimate (n = 1 in the experiments)
     Ds = spatial_average(D, dims, avg_block)
     m_new = beta1 * m + (1.0 - beta1) * g
     v_new = beta2 * v + (1.0 - beta2) * Ds * Ds
@@ -442,6 +451,7 @@ class OracleConfig:
     seed: int = 0
     bf16: bool = False
     n_params: int = 0
+    n_samples: int = 1                # Rademacher probes per step (Section IV-B's n)
 
 
 class OracleTrainer:
@@ -468,8 +478,11 @@ class OracleTrainer:
         self.traces: List[Optional[StepTrace]] = [None] * cfg.k
         self.q = round_bf16 if cfg.bf16 else _identity
 
-    def draw_z(self, worker: int) -> np.ndarray:
-        words = rademacher_words(self.cfg.seed, worker, int(self.t[worker]), self.P)
+    def draw_z(self, worker: int, sample: int = 0) -> np.ndarray:
+        """Probe `sample` of the worker's next step: stream position t_i * n_samples + sample, so that one
+        probe per step (n_samples = 1) is the stream at (seed, i, t_i)."""
+        pos = int(self.t[worker]) * self.cfg.n_samples + sample
+        words = rademacher_words(self.cfg.seed, worker, pos, self.P)
         return words_to_signs(words, self.P)
 
     def worker_step(self, x, y, z_signs=None, active=None, tie_band=0.0, tie_choice=None):
@@ -482,10 +495,23 @@ class OracleTrainer:
         for i in range(cfg.k):
             if active is not None and not active[i]:
                 continue
-            z = self.draw_z(i) if z_signs is None else np.asarray(z_signs[i], dtype=F64)
-            tr = StepTrace()
-            loss, g, hz = grad_and_hvp(self.theta[i], x[i], y[i], cfg.dims, z, self.q, tr, tie_band,
-                                       None if tie_choice is None else tie_choice[i])
+            if cfg.n_samples == 1:
+                z = self.draw_z(i) if z_signs is None else np.asarray(z_signs[i], dtype=F64)
+                tr = StepTrace()
+                loss, g, hz = grad_and_hvp(self.theta[i], x[i], y[i], cfg.dims, z, self.q, tr, tie_band,
+                                           None if tie_choice is None else tie_choice[i])
+            else:
+                # n probes of the same minibatch: the loss and g do not depend on the probe
+                assert z_signs is None, "caller-supplied probes are for n_samples = 1"
+                zs, hzs = [], []
+                for j in range(cfg.n_samples):
+                    zj = self.draw_z(i, j)
+                    tr = StepTrace()
+                    loss, g, hzj = grad_and_hvp(self.theta[i], x[i], y[i], cfg.dims, zj, self.q, tr, tie_band,
+                                                None if tie_choice is None else tie_choice[i])
+                    zs.append(zj); hzs.append(hzj)
+                z, hz = np.stack(zs), np.stack(hzs)
+                tr.hz, tr.z = hz, z
             self.traces[i] = tr
             self.t[i] += 1
             self.theta[i], self.m[i], self.v[i] = adahessian_update(

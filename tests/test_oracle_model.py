@@ -198,3 +198,47 @@ def test_bf16_rounding_helper():
     big = np.random.default_rng(0).standard_normal(10000)
     np.testing.assert_array_equal(O.round_bf16(big),
                                   torch.tensor(big, dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy())
+
+
+def test_hutchinson_diagonal_of_n_probes_and_the_update_that_uses_it():
+    """Section IV-B with n probes: the estimate is the mean of z_j * (H z_j); with the P-column restriction of a
+    Hadamard matrix as probes it is diag(H) exactly, and the update takes D from it."""
+    theta, x, y, P = _problem(DIMS_TINY, 6, 4)
+    H = _brute_force_hessian(theta, x, y, DIMS_TINY)
+    n = 32
+    Had = np.array([[1.0]])
+    while Had.shape[0] < n:
+        Had = np.block([[Had, Had], [Had, -Had]])
+    zs = Had[:, :P]
+    hzs = np.stack([O.grad_and_hvp(theta, x, y, DIMS_TINY, z)[2] for z in zs])
+    np.testing.assert_allclose(O.hutchinson_diagonal(zs, hzs), H.diagonal(), atol=2e-8)
+    # one probe: the plain product; two probes: the mean of the two single-probe estimates
+    np.testing.assert_array_equal(O.hutchinson_diagonal(zs[3], hzs[3]), zs[3] * hzs[3])
+    np.testing.assert_allclose(O.hutchinson_diagonal(zs[:2], hzs[:2]), 0.5 * (zs[0] * hzs[0] + zs[1] * hzs[1]), rtol=1e-15)
+    g = O.grad_and_hvp(theta, x, y, DIMS_TINY, zs[0])[1]
+    hp = dict(lr=0.01, beta1=0.9, beta2=0.999, eps=1e-4, hpow=1.0)
+    th_n, m_n, v_n = O.adahessian_update(theta, np.zeros(P), np.zeros(P), g, hzs, zs, 1, **hp)
+    # with the exact diagonal, the first step is lr * g / (|diag(H)| + eps) (bias corrections cancel at t = 1)
+    np.testing.assert_allclose(theta - th_n, 0.01 * g / (np.abs(H.diagonal()) + 1e-4), rtol=1e-6, atol=1e-12)
+    np.testing.assert_allclose(v_n, 0.001 * H.diagonal() ** 2, rtol=1e-6, atol=1e-18)
+
+
+def test_trainer_draws_distinct_probes_per_step_and_keeps_the_single_probe_stream():
+    dims = DIMS_TINY
+    P = O.layer_offsets(dims)[-1] if hasattr(O, "layer_offsets") else None
+    theta, x, y, P = _problem(dims, 6, 4)
+    one = O.OracleTrainer(O.OracleConfig(dims=dims, k=1, seed=9), theta)
+    three = O.OracleTrainer(O.OracleConfig(dims=dims, k=1, seed=9, n_samples=3), theta)
+    np.testing.assert_array_equal(one.draw_z(0), O.words_to_signs(O.rademacher_words(9, 0, 0, P), P))
+    zs = [three.draw_z(0, j) for j in range(3)]
+    np.testing.assert_array_equal(zs[0], one.draw_z(0))                     # position 0 either way
+    assert not np.array_equal(zs[0], zs[1]) and not np.array_equal(zs[1], zs[2])
+    three.worker_step(x[None], y[None]); one.worker_step(x[None], y[None])
+    # second step: positions 3, 4, 5 against position 1
+    np.testing.assert_array_equal(three.draw_z(0, 0), O.words_to_signs(O.rademacher_words(9, 0, 3, P), P))
+    np.testing.assert_array_equal(one.draw_z(0), O.words_to_signs(O.rademacher_words(9, 0, 1, P), P))
+    # the 3-probe step used the mean of the three single-probe estimates
+    hz = three.traces[0].hz
+    assert hz.shape == (3, P)
+    D = (np.stack(zs) * hz).mean(axis=0)
+    np.testing.assert_allclose(three.v[0], 0.001 * D ** 2, rtol=1e-12, atol=1e-30)

@@ -76,7 +76,7 @@ def class_bytes(w, P, k, fused=(), part=1.0):
     return out
 
 
-def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False):
+def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1):
     import torch
     from paper_2409_09242_amd import binding as B
     from paper_2409_09242_amd import workloads as W
@@ -87,7 +87,7 @@ def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False):
     if w.bf16:
         xd = xd.to(torch.bfloat16)
     yd = torch.from_numpy(y).cuda()
-    h = B.Handle(B.config_from_workload(w, fuse_update=1 if fuse else 0), theta0)
+    h = B.Handle(B.config_from_workload(w, fuse_update=1 if fuse else 0, n_samples=samples), theta0)
     sched = W.participation_schedule(w, (2 * steps + warmup) // w.tau + 2)
     state = {"round": 0, "step": 0}
     mode = B.DW_DYNAMIC | (B.DW_SEQUENTIAL if sequential else 0)
@@ -222,6 +222,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--samples", type=int, default=1,
+                    help="Rademacher probes per step (n of the Hutchinson estimate; the network runs once per probe)")
     ap.add_argument("--sequential", action="store_true",
                     help="communication rounds as a sequence of single exchanges (DW_SEQUENTIAL); same bytes moved")
     ap.add_argument("--no-fuse", action="store_true",
@@ -250,13 +252,15 @@ def main():
     n_pool = 4 if w.bf16 else 8
     if args.calibrate:
         calibration_copy()
-    h, elapsed, prof, elapsed_prof, part = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse, args.sequential)
+    h, elapsed, prof, elapsed_prof, part = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse, args.sequential, args.samples)
     dtype = "bf16" if w.bf16 else "f32"
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.k * args.steps / elapsed
 
     fl = class_flops(w)
-    fused = fused_layers(w, not args.no_fuse)
+    fused = fused_layers(w, not args.no_fuse and args.samples <= 1)
+    if args.samples > 1:
+        fl = {c: v * args.samples for c, v in fl.items()}
     by = class_bytes(w, w.P, w.k, fused, part)
     per_step = {"update": 1, "pull": 1.0 / w.tau, "gemm_wgrad": 1}
     kernels = {}
@@ -311,9 +315,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w.name, "k": w.k, "dims": list(w.dims), "batch": w.batch, "tau": w.tau,
                    "stale": w.stale, "sync": "dynamic, sequential" if args.sequential else "dynamic",
-                   "fuse_update": int(bool(fused))},
-        "flop_per_step": w.flops_per_worker_step() * w.k,
-        "step_TFLOP/s": w.flops_per_worker_step() * w.k / (ms_per_step * 1e-3) / 1e12,
+                   "fuse_update": int(bool(fused)), "hutchinson_probes": args.samples},
+        "flop_per_step": w.flops_per_worker_step() * w.k * args.samples,
+        "step_TFLOP/s": w.flops_per_worker_step() * w.k * args.samples / (ms_per_step * 1e-3) / 1e12,
         "ms_per_step_profiled": 1e3 * elapsed_prof / args.steps,
         "roofline": roof,
         "roofline_gemm": gemm_roof,

@@ -39,6 +39,7 @@ extern "C" {
 #define DW_MAX_K 64          /* worker replicas k                                */
 #define DW_MAX_P 8           /* length p of the raw-score history weights c_j    */
 #define DW_MAX_CLASSES 16    /* width d_L of the output layer                    */
+#define DW_MAX_SAMPLES 8     /* Rademacher probes per step                       */
 
 typedef enum {
   DW_OK = 0,
@@ -97,6 +98,11 @@ typedef struct {
   int32_t p;                        /* number of history differences, 1..DW_MAX_P                           */
   float c[DW_MAX_P];                /* c_0 (most recent) .. c_{p-1}; must sum to 1 within 1e-5 (eq.(10)-(11)) */
   uint64_t seed;                    /* seed of the library's Rademacher stream                              */
+  int32_t n_samples;                /* Rademacher probes per dw_worker_step (the n of Section IV-B's Hutchinson
+                                       estimate; the experiments use 1).  0 or 1: one probe.  Up to DW_MAX_SAMPLES:
+                                       D is the mean of z_j*(Hz_j); probe j of a worker's step t comes from
+                                       position t*n + j of its stream; the network runs once per probe, g and
+                                       Hz are never fused away, and dw_worker_step takes no caller-supplied z. */
   int32_t fuse_update;              /* 0: g and Hz of the last dw_worker_step stay readable (DW_S_G, DW_S_HZ).
                                        1: the library may apply the update of a weight matrix inside the kernel
                                           that produces its gradient; the W-parts of g and Hz of such layers are

@@ -36,7 +36,7 @@ class dw_config(C.Structure):
         ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
         ("hpow", C.c_float), ("avg_block", C.c_int32),
         ("alpha", C.c_float), ("kappa", C.c_float), ("p", C.c_int32), ("c", C.c_float * DW_MAX_P),
-        ("seed", C.c_uint64), ("fuse_update", C.c_int32),
+        ("seed", C.c_uint64), ("n_samples", C.c_int32), ("fuse_update", C.c_int32),
     ]
 
 
@@ -80,7 +80,8 @@ def lib() -> C.CDLL:
 
 def make_config(*, dims: Optional[Sequence[int]], k: int, batch: int = 0, bf16: bool = False, n_params: int = 0,
                 lr=0.01, beta1=0.9, beta2=0.999, eps=1e-4, hpow=1.0, avg_block=1, alpha=0.1, kappa=-0.1,
-                c: Sequence[float] = (0.4, 0.3, 0.2, 0.1), seed: int = 0, fuse_update: int = 0) -> dw_config:
+                c: Sequence[float] = (0.4, 0.3, 0.2, 0.1), seed: int = 0, fuse_update: int = 0,
+                n_samples: int = 1) -> dw_config:
     cfg = dw_config()
     if dims is None:
         cfg.n_layers = 0
@@ -97,6 +98,7 @@ def make_config(*, dims: Optional[Sequence[int]], k: int, batch: int = 0, bf16: 
         cfg.c[j] = cj
     cfg.seed = seed
     cfg.fuse_update = fuse_update
+    cfg.n_samples = n_samples
     return cfg
 
 

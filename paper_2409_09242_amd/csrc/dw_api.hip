@@ -34,6 +34,7 @@ int validate(const dw_config* c, Layout* lay) {
   if (c->k < 1 || c->k > DW_MAX_K) return DW_ERR_CONFIG;
   if (c->dtype != DW_F32 && c->dtype != DW_BF16) return DW_ERR_CONFIG;
   if (c->fuse_update != 0 && c->fuse_update != 1) return DW_ERR_CONFIG;
+  if (c->n_samples < 0 || c->n_samples > DW_MAX_SAMPLES) return DW_ERR_CONFIG;
   if (c->n_layers < 0 || c->n_layers > DW_MAX_LAYERS) return DW_ERR_CONFIG;
   const int L = c->n_layers;
   const int align = c->dtype == DW_BF16 ? 8 : 4;
@@ -88,6 +89,7 @@ int validate(const dw_config* c, Layout* lay) {
   lay->theta = take(vec); lay->m = take(vec); lay->v = take(vec);
   lay->centre = take((size_t)lay->Pp * sizeof(float));
   if (L > 0) { lay->g = take(vec); lay->hz = take(vec); }
+  if (L > 0 && c->n_samples > 1) lay->dacc = take(vec);
   if (c->dtype == DW_BF16) lay->wb16 = take((size_t)k * lay->Pp * 2);
   lay->zbits = take((size_t)k * lay->z_stride * 4);
   if (L > 0) {
@@ -112,7 +114,7 @@ int validate(const dw_config* c, Layout* lay) {
   lay->n_fuse_slots = 0;
   for (int l = 1; l <= L; ++l) {
     lay->fuse_base[l - 1] = -1;
-    if (c->fuse_update && c->dtype == DW_BF16 &&
+    if (c->fuse_update && c->dtype == DW_BF16 && c->n_samples <= 1 &&      // several probes: D needs all of them first
         gemm_bf16_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])) {
       lay->fuse_base[l - 1] = lay->n_fuse_slots;
       lay->n_fuse_slots += gemm_bf16_wgrad_tiles(c->dims[l], c->dims[l - 1]);
@@ -173,6 +175,7 @@ void fill_update_args(dw_handle* h, UpdateArgs& a, const float* g, const float* 
   a.P = L.P; a.Pp = L.Pp; a.g_stride = g_stride; a.z_stride = z_stride;
   a.k = c.k; a.avg_block = c.avg_block;
   a.lr = c.lr; a.beta1 = c.beta1; a.beta2 = c.beta2; a.eps = c.eps; a.hpow = c.hpow;
+  a.d_scale = 0.f;
   a.active_mask = active;
   a.bias.n = c.n_layers;
   for (int l = 0; l < c.n_layers; ++l) {
@@ -198,13 +201,16 @@ void fill_update_args(dw_handle* h, UpdateArgs& a, const float* g, const float* 
   }
 }
 
-// draw z for the active workers at their current step counts (before the increment)
-int draw_z(dw_handle* h, uint64_t active, hipStream_t s) {
+inline int probes(const dw_handle* h) { return h->cfg.n_samples > 1 ? h->cfg.n_samples : 1; }
+
+// draw probe `sample` of the active workers' next step (step counts before the increment): stream position
+// t_i * n_samples + sample, which for one probe per step is t_i
+int draw_z(dw_handle* h, uint64_t active, hipStream_t s, int sample = 0) {
   uint64_t keys[DW_MAX_K];
   const uint64_t G = 0x9E3779B97F4A7C15ull;
   for (int i = 0; i < h->cfg.k; ++i) {
     const uint64_t k1 = mix64_host(h->cfg.seed + G * (uint64_t)(i + 1));
-    keys[i] = mix64_host(k1 + G * (uint64_t)(h->t[i] + 1));
+    keys[i] = mix64_host(k1 + G * (uint64_t)(h->t[i] * probes(h) + sample + 1));
   }
   DW_HIP(launch_rademacher(h->at<uint32_t>(h->lay.zbits), h->lay.z_stride, (h->lay.P + 63) / 64, keys,
                            h->cfg.k, active, s));
@@ -241,6 +247,30 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
              float* loss, hipStream_t s) {
   const uint32_t* zb = d_zbits ? d_zbits : h->at<uint32_t>(h->lay.zbits);
   const int64_t zs = d_zbits ? 2 * ((h->lay.P + 63) / 64) : h->lay.z_stride;
+  if (probes(h) > 1) {
+    // n probes of the same minibatch: the network runs once per probe (loss and g come out the same each time),
+    // z_j*Hz_j is summed, and the update takes D = sum / n
+    const int n = probes(h);
+    for (int j = 0; j < n; ++j) {
+      int st = draw_z(h, active, s, j);
+      if (st != DW_OK) return st;
+      st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, nullptr, true, s);
+      if (st != DW_OK) return st;
+      DW_HIP(launch_probe_sum(h->at<float>(h->lay.dacc), h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->cfg.k, active,
+                              j == 0 ? 1 : 0, s));
+    }
+    for (int i = 0; i < h->cfg.k; ++i)
+      if ((active >> i) & 1ull) h->t[i] += 1;
+    UpdateArgs a;
+    fill_update_args(h, a, h->at<float>(h->lay.g), h->at<float>(h->lay.dacc), h->lay.Pp, zb, zs, active, false);
+    a.d_scale = 1.0f / (float)n;
+    int st = clear_fused_partials(h, s);
+    if (st != DW_OK) return st;
+    DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
+    h->norms_valid = true;
+    h->calls += 1;
+    return DW_OK;
+  }
   for (int i = 0; i < h->cfg.k; ++i)
     if ((active >> i) & 1ull) h->t[i] += 1;
   const bool fused = h->lay.n_fuse_slots > 0;
@@ -392,7 +422,8 @@ int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint
   hipStream_t s = (hipStream_t)stream;
   const uint64_t active = mask_from(h_active, h->cfg.k);
   if (active == 0) { h->calls += 1; return DW_OK; }
-  if (!d_zbits) {
+  if (probes(h) > 1 && d_zbits) return DW_ERR_ARG;       // several probes per step come from the library's stream
+  if (!d_zbits && probes(h) == 1) {
     const int st = draw_z(h, active, s);
     if (st != DW_OK) return st;
   }

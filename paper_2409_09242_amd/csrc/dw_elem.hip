@@ -128,7 +128,8 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
         const float cc[4] = {fz[u] ? 0.f : cen[u].x, fz[u] ? 0.f : cen[u].y, fz[u] ? 0.f : cen[u].z, fz[u] ? 0.f : cen[u].w};
         float D[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) D[e] = sign_from_bit(Z[u], e) * hz[e];       // Hutchinson: z * Hz
+        for (int e = 0; e < 4; ++e)                                              // Hutchinson: z * Hz, or its mean
+          D[e] = a.d_scale > 0.f ? hz[e] * a.d_scale : sign_from_bit(Z[u], e) * hz[e];
         // spatial average over avg_block consecutive parameters (all lanes take part in the shuffles)
         float Ds[4] = {D[0], D[1], D[2], D[3]};
         if (a.avg_block == 2) {
@@ -358,6 +359,32 @@ hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words6
   for (int i = 0; i < DW_MAX_K; ++i) keys.key[i] = i < k ? keys_host[i] : 0;
   dim3 grid((unsigned)((n_words64 + 255) / 256), (unsigned)k);
   hipLaunchKernelGGL(rademacher_kernel, grid, dim3(256), 0, s, zbits, z_stride, n_words64, keys, active_mask);
+  return hipGetLastError();
+}
+
+// Running sum of z_j * Hz_j over the probes of one step (Section IV-B with n > 1), one float4 per thread.
+__global__ __launch_bounds__(256) void probe_sum_kernel(float* dacc, const float* hz, const uint32_t* zbits, int64_t Pp,
+                                                        int64_t z_stride, uint64_t active_mask, int first) {
+  const int i = blockIdx.y;
+  if (!((active_mask >> i) & 1ull)) return;
+  const int64_t nq = Pp >> 2;
+  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256) {
+    const float4 h = reinterpret_cast<const float4*>(hz + (int64_t)i * Pp)[q];
+    const uint32_t z = zbits[(int64_t)i * z_stride + (q >> 3)] >> ((q << 2) & 31);
+    float4 d = first ? make_float4(0.f, 0.f, 0.f, 0.f) : reinterpret_cast<const float4*>(dacc + (int64_t)i * Pp)[q];
+    d.x += sign_from_bit(z, 0) * h.x; d.y += sign_from_bit(z, 1) * h.y;
+    d.z += sign_from_bit(z, 2) * h.z; d.w += sign_from_bit(z, 3) * h.w;
+    reinterpret_cast<float4*>(dacc + (int64_t)i * Pp)[q] = d;
+  }
+}
+
+hipError_t launch_probe_sum(float* dacc, const float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride, int k,
+                            uint64_t active_mask, int first, hipStream_t s) {
+  KernelScope ks(KC_UPDATE, s);
+  int64_t nb = ((Pp >> 2) + 255) / 256;
+  if (nb > 16384) nb = 16384;
+  hipLaunchKernelGGL(probe_sum_kernel, dim3((unsigned)nb, (unsigned)k), dim3(256), 0, s, dacc, hz, zbits, Pp, z_stride,
+                     active_mask, first);
   return hipGetLastError();
 }
 

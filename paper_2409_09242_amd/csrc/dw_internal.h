@@ -46,6 +46,7 @@ struct UpdateArgs {
   int k;
   int avg_block;                      // power of two, 1..256
   float lr, beta1, beta2, eps, hpow;
+  float d_scale;                      // 0: D = z*hz (one probe); > 0: hz holds the sum of z_j*Hz_j, D = hz * d_scale
   uint64_t active_mask;               // bit i: worker i takes the step (others only report their distance)
   BiasRanges bias;
   FusedRanges fused;
@@ -84,6 +85,9 @@ hipError_t launch_weights(const WeightArgs& a, hipStream_t s);
 hipError_t launch_pull(const PullArgs& a, hipStream_t s);
 hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words64, const uint64_t* keys_host,
                              int k, uint64_t active_mask, hipStream_t s);
+// dacc = (first ? 0 : dacc) + z*hz for the active workers: the running sum of a step's Hutchinson probes
+hipError_t launch_probe_sum(float* dacc, const float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride, int k,
+                            uint64_t active_mask, int first, hipStream_t s);
 hipError_t launch_broadcast(float* theta, const float* centre, uint16_t* wb16, int64_t Pp, int k, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hipStream_t s);
@@ -167,6 +171,7 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t act[DW_MAX_LAYERS] = {0}, ract[DW_MAX_LAYERS] = {0};   // a_l, Ra_l for l = 1..L-1 (index l)
   size_t delta[DW_MAX_LAYERS] = {0}, rdelta[DW_MAX_LAYERS] = {0}; // d_l, Rd_l of the hidden layers l = 1..L-1 (index l)
   size_t sL = 0, rsL = 0, dL = 0, rdL = 0, dL16 = 0, rdL16 = 0;  // output layer, fp32 [k][B][16] (+ bf16 copies)
+  size_t dacc = 0;                    // [k][Pp] floats, n_samples > 1 only: sum over the probes of z_j*Hz_j
   int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
   int n_fuse_slots = 0;
   size_t partials_f = 0;              // [k][n_fuse_slots] doubles

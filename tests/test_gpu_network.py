@@ -359,3 +359,59 @@ def test_bf16_fused_update_measures_distances_only_when_a_round_is_due():
     hA.worker_step(xb, yb); hB.worker_step(xb, yb)          # ... step 7 is not
     assert hA.elastic_sync(B.DW_DYNAMIC, tau=1) and hB.elastic_sync(B.DW_DYNAMIC, tau=1)
     same("unannounced round")
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Several Rademacher probes per step (Section IV-B's n): D is the mean of z_j * (H z_j).
+# ---------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bf16,n", [(False, 3), (False, 2), (True, 4)])
+def test_several_hutchinson_probes_per_step(bf16, n):
+    dims, batch, k = (72, 96, 40, 10), 37 if not bf16 else 40, 3
+    dims = dims if not bf16 else (72, 96, 40, 8)
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=600 + n, bf16=bf16, avg_block=2)
+    theta0 = W.init_theta(w.dims, w.seed)
+    h = B.Handle(B.config_from_workload(w, n_samples=n), theta0)
+    tr = O.OracleTrainer(oracle_config(w, n_samples=n), theta0.astype(np.float64))
+    x, y = W.minibatch_pool(w, 2, bf16_round=W.to_bf16_f32 if bf16 else None)
+    band = TIE_BAND_BF16 if bf16 else TIE_BAND
+    slopes = _gpu_slopes_b16 if bf16 else _gpu_slopes
+    for step in range(2):
+        if step:
+            for i in range(k):
+                h.set_state(B.DW_S_THETA, i, tr.theta[i]); h.set_state(B.DW_S_M, i, tr.m[i]); h.set_state(B.DW_S_V, i, tr.v[i])
+        prev_gpu = h.all_state(B.DW_S_THETA)
+        prev = tr.theta.copy()
+        xb = _to_bf16_bits(x[step]) if bf16 else torch.from_numpy(x[step]).cuda()
+        loss = torch.zeros(k, device="cuda")
+        active = None if step == 0 else [1, 0, 1]
+        h.worker_step(xb, torch.from_numpy(y[step]).cuda(), loss=loss, active=active)
+        ref_loss = tr.worker_step(x[step], y[step], active=active, tie_band=band, tie_choice=slopes(h, w))
+        now_gpu = h.all_state(B.DW_S_THETA)
+        for i in range(k):
+            if active is not None and not active[i]:
+                np.testing.assert_array_equal(now_gpu[i], prev_gpu[i])
+                continue
+            assert abs(loss[i].item() - ref_loss[i]) <= (1e-4 if bf16 else 1e-5) * abs(ref_loss[i])
+            # the last probe drawn is probe n-1 of this step: stream position (t-1)*n + n-1
+            pos = (int(tr.t[i]) - 1) * n + n - 1
+            np.testing.assert_array_equal(h.get_state(B.DW_S_ZBITS, i), O.words_to_u32(O.rademacher_words(w.seed, i, pos, w.P)))
+            zs, hzs = tr.traces[i].z, tr.traces[i].hz
+            assert hzs.shape == (n, w.P)
+            if bf16:
+                for name, sl in parity.per_layer(dims):
+                    close_norm(h.get_state(B.DW_S_G, i)[sl], tr.traces[i].g[sl], RTOL_BF16_G, "probes g[%d]/%s" % (i, name))
+                    close_norm(h.get_state(B.DW_S_HZ, i)[sl], hzs[-1][sl], RTOL_BF16_HZ, "probes hz[%d]/%s" % (i, name))
+                # second moment from the mean of the probes, in norm like its inputs
+                close_norm(h.get_state(B.DW_S_V, i), tr.v[i], 4 * RTOL_BF16_HZ, "probes v[%d]" % i, cap=100.0)
+                close_norm(h.get_state(B.DW_S_M, i), tr.m[i], RTOL_BF16_G, "probes m[%d]" % i)
+            else:
+                close_layers(h.get_state(B.DW_S_G, i), tr.traces[i].g, dims, RTOL_GRAD, "probes g[%d]" % i)
+                close_layers(h.get_state(B.DW_S_HZ, i), hzs[-1], dims, RTOL_HV, "probes hz[%d]" % i)
+                close(h.get_state(B.DW_S_M, i), tr.m[i], RTOL_UPDATE, "probes m[%d]" % i)
+                # the update: same conditioning argument as for one probe, with the probes' rms as the scale of Hz
+                tr.traces[i].hz = np.sqrt((hzs ** 2).mean(axis=0))
+                close_update(now_gpu[i] - prev_gpu[i], tr.theta[i] - prev[i], tr, i, dims, RTOL_UPDATE, "probes update[%d]" % i)
+                tr.traces[i].hz = hzs
+    with pytest.raises(B.DwError):
+        zb = torch.zeros(k, 2 * ((w.P + 63) // 64), dtype=torch.int32, device="cuda")
+        h.worker_step(xb, torch.from_numpy(y[0]).cuda(), zbits=zb)

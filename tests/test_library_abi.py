@@ -37,7 +37,7 @@ def test_strerror_and_param_count():
 
 
 @pytest.mark.parametrize("field,value,status", [
-    ("k", 0, -2), ("k", 65, -2), ("batch", 0, -2), ("dtype", 7, -2), ("fuse_update", 2, -2),
+    ("k", 0, -2), ("k", 65, -2), ("batch", 0, -2), ("dtype", 7, -2), ("fuse_update", 2, -2), ("n_samples", 9, -2), ("n_samples", -1, -2),
     ("lr", 0.0, -3), ("beta1", 1.0, -3), ("eps", 0.0, -3), ("avg_block", 3, -3), ("avg_block", 512, -3),
     ("alpha", 0.0, -3), ("alpha", 1.5, -3), ("kappa", 0.0, -3), ("kappa", 0.2, -3), ("p", 0, -3), ("p", 9, -3),
 ])

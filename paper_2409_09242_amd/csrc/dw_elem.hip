@@ -21,6 +21,18 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return (uint16_t)(u >> 16);
 }
 
+// The optimizer state streams through once per launch: 16-byte accesses marked non-temporal so that they do not
+// displace lines that are reused (the centre, the sign bits, other kernels' operand tiles).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_load4(const float4* p) {
+  const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store4(float4* p, float4 x) {
+  const f32x4 v = {x.x, x.y, x.z, x.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+}
+
 __device__ __forceinline__ float sign_from_bit(uint32_t bits, int b) {
   // bit set -> +1, clear -> -1
   return ((bits >> b) & 1u) ? 1.0f : -1.0f;
@@ -109,7 +121,8 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
       for (int u = 0; u < kUpdQuads; ++u) {
         const int64_t q = qbase + (int64_t)u * kUpdThreads;
         if (valid[u] && !fz[u]) {
-          G[u] = g4[q]; H[u] = h4[q]; T[u] = th4[q]; M[u] = m4[q]; V[u] = v4[q];
+          G[u] = nt_load4(g4 + q); H[u] = nt_load4(h4 + q); T[u] = nt_load4(th4 + q);
+          M[u] = nt_load4(m4 + q); V[u] = nt_load4(v4 + q);
           Z[u] = zb[q >> 3] >> zshift[u];
         } else {
           G[u] = H[u] = T[u] = M[u] = V[u] = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -152,9 +165,9 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
           nsum += d * d;
         }
         if (valid[u] && !fz[u]) {
-          th4[q] = make_float4(th[0], th[1], th[2], th[3]);
-          m4[q] = make_float4(mm[0], mm[1], mm[2], mm[3]);
-          v4[q] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+          nt_store4(th4 + q, make_float4(th[0], th[1], th[2], th[3]));
+          nt_store4(m4 + q, make_float4(mm[0], mm[1], mm[2], mm[3]));
+          nt_store4(v4 + q, make_float4(vv[0], vv[1], vv[2], vv[3]));
           if (HAS_B16) {
             ushort4 w;
             w.x = f32_to_bf16_rne(th[0]); w.y = f32_to_bf16_rne(th[1]);
@@ -278,7 +291,7 @@ __global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a) {
 #pragma unroll
     for (int u = 0; u < kUpdQuads; ++u) {
       const int64_t q = qbase + (int64_t)u * kUpdThreads;
-      T[u] = valid[u] ? th4[q] : make_float4(0.f, 0.f, 0.f, 0.f);
+      T[u] = valid[u] ? nt_load4(th4 + q) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
 #pragma unroll
     for (int u = 0; u < kUpdQuads; ++u) {
@@ -295,7 +308,7 @@ __global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a) {
         acc[u].z = fmaf(w, d2, acc[u].z); acc[u].w = fmaf(w, d3, acc[u].w);
       }
       if (valid[u]) {
-        th4[q] = r;
+        nt_store4(th4 + q, r);
         if (HAS_B16) {
           ushort4 b;
           b.x = f32_to_bf16_rne(r.x); b.y = f32_to_bf16_rne(r.y);

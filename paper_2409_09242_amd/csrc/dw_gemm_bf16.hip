@@ -35,6 +35,15 @@ constexpr int NT = 512;
 
 enum RyMode { RY_NONE = 0, RY_MEM = 1, RY_BITS = 2 };
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_load4(const float* p) {          // 16-byte load that does not displace L2 lines
+  const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store4(float* p, float4 x) {
+  const f32x4 v = {x.x, x.y, x.z, x.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+}
 __device__ __forceinline__ uint16_t f2bf(float f) {
   uint32_t u = __float_as_uint(f);
   u += 0x7FFFu + ((u >> 16) & 1u);
@@ -363,8 +372,8 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
       const int i = bb / 8, b = bb % 8;
       const uint32_t m = (uint32_t)(row0 + wm0 + i * 32 + b * 4 + brow), n = (uint32_t)(col0 + wn0 + bcol);
       bt.e = m * (uint32_t)a.ldc + n;                         // offset inside the W block, a multiple of 4
-      bt.th = *reinterpret_cast<const float4*>(th_w + bt.e); bt.mm = *reinterpret_cast<const float4*>(m_w + bt.e);
-      bt.vv = *reinterpret_cast<const float4*>(v_w + bt.e);
+      bt.th = nt_load4(th_w + bt.e); bt.mm = nt_load4(m_w + bt.e);   // the state streams through once: no reuse in L2
+      bt.vv = nt_load4(v_w + bt.e);
       bt.cc = f.dist ? *reinterpret_cast<const float4*>(f.centre + bt.e) : make_float4(0.f, 0.f, 0.f, 0.f);
       bt.zw = zrow[bt.e >> 5];
     };
@@ -403,9 +412,9 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
         const float d = t1[q] - cc[q];
         nsum += d * d;
       }
-      *reinterpret_cast<float4*>(th_w + bt.e) = make_float4(t1[0], t1[1], t1[2], t1[3]);
-      *reinterpret_cast<float4*>(m_w + bt.e) = make_float4(m1[0], m1[1], m1[2], m1[3]);
-      *reinterpret_cast<float4*>(v_w + bt.e) = make_float4(v1[0], v1[1], v1[2], v1[3]);
+      nt_store4(th_w + bt.e, make_float4(t1[0], t1[1], t1[2], t1[3]));
+      nt_store4(m_w + bt.e, make_float4(m1[0], m1[1], m1[2], m1[3]));
+      nt_store4(v_w + bt.e, make_float4(v1[0], v1[1], v1[2], v1[3]));
       ushort4 w16; w16.x = f2bf(t1[0]); w16.y = f2bf(t1[1]); w16.z = f2bf(t1[2]); w16.w = f2bf(t1[3]);
       *reinterpret_cast<ushort4*>(b16_w + bt.e) = w16;
     };

@@ -416,7 +416,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
       nt_store4(m_w + bt.e, make_float4(m1[0], m1[1], m1[2], m1[3]));
       nt_store4(v_w + bt.e, make_float4(v1[0], v1[1], v1[2], v1[3]));
       ushort4 w16; w16.x = f2bf(t1[0]); w16.y = f2bf(t1[1]); w16.z = f2bf(t1[2]); w16.w = f2bf(t1[3]);
-      *reinterpret_cast<ushort4*>(b16_w + bt.e) = w16;
+      __builtin_nontemporal_store(__builtin_bit_cast(unsigned long long, w16), reinterpret_cast<unsigned long long*>(b16_w + bt.e));
     };
     Batch ring[DEPTH];
 #pragma unroll

@@ -4,6 +4,7 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2409_09242_amd import binding as B
@@ -90,3 +91,19 @@ def test_fused_update_is_an_option_of_large_bf16_layers_only():
             assert fused - plain == 3 * 32 * 16 * 8 * w.k
         else:
             assert fused == plain
+
+
+def test_participation_schedules():
+    """Host-side recipes of the failure patterns (Section VI: communication suppressed, here per round)."""
+    w = W.scaled(W.C2, k=6, stale="third", seed=4)
+    p = W.participation_schedule(w, 6000)
+    assert p.shape == (6000, 6) and p.dtype == np.uint8 and set(np.unique(p)) == {0, 1}
+    assert abs(p.mean() - 2.0 / 3.0) < 0.02                       # suppressed one third of the time
+    assert np.array_equal(p, W.participation_schedule(w, 6000))   # seeded
+    assert np.all(np.abs(p.mean(axis=0) - 2.0 / 3.0) < 0.03)      # every worker alike
+    f = W.participation_schedule(W.scaled(W.C3, k=5), 8)
+    assert f[:, :3].all() and list(f[:, 3]) == [0, 0, 0, 1, 0, 0, 0, 1] and list(f[:, 4]) == list(f[:, 3])
+    g = W.participation_schedule(W.C4, 400)
+    # absent for Geometric(0.3) - 1 rounds (7/3 on average) after each turn: present 3 rounds in 10
+    assert g.shape == (400, 16) and 0.25 < g.mean() < 0.35
+    assert W.participation_schedule(W.C1, 3).all()

@@ -455,6 +455,33 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
       for (int w = 0; w < NT / 64; ++w) t += red[w];
       f.partials[(int64_t)worker * f.part_stride + f.part_base + tile] = t;
     }
+  } else if (EPI == EPI_WGRAD && TN == 2 && BM == 128 && BN == 256 && a.M % BM == 0 && a.N % BN == 0) {
+    // Large weight gradient stored as it is (gW and HzW, fp32): through the same per-wave LDS regions as the fused
+    // epilogue, so that the stores are float4 of 256-byte row pieces; non-temporal, the update kernel reads
+    // them once.
+    constexpr int PR = 72;
+    float* gl = reinterpret_cast<float*>(smem) + wave * (2 * 32 * PR);
+    float* hl = gl + 32 * PR;
+    const int brow = lane >> 4, bcol = (lane & 15) * 4;
+    float* Cw = reinterpret_cast<float*>(a.C) + (int64_t)worker * a.c_wstride;
+    float* RCw = reinterpret_cast<float*>(a.RC) + (int64_t)worker * a.c_wstride;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = (r >> 2) * 8 + lhalf * 4 + (r & 3), col = j * 32 + l32;
+          gl[row * PR + col] = acc[i][j][r];
+          hl[row * PR + col] = racc[i][j][r];
+        }
+#pragma unroll
+      for (int b = 0; b < 8; ++b) {
+        const int64_t e = (int64_t)(row0 + wm0 + i * 32 + b * 4 + brow) * a.ldc + (col0 + wn0 + bcol);
+        nt_store4(Cw + e, *reinterpret_cast<const float4*>(gl + (b * 4 + brow) * PR + bcol));
+        nt_store4(RCw + e, *reinterpret_cast<const float4*>(hl + (b * 4 + brow) * PR + bcol));
+      }
+    }
   } else if (EPI == EPI_RELU || EPI == EPI_MASK) {
     // bf16 outputs: through LDS, 16-byte stores of whole row pieces (see dw_gemm_epi.h)
     char* wl = reinterpret_cast<char*>(smem) + wave * epi_bf16_lds_bytes(TN);

@@ -11,6 +11,8 @@
 // All three are bound by HBM bandwidth.  One thread owns the same four consecutive parameters of every
 // worker: the centre values stay in registers while the block walks over the k replicas, so the centre is
 // read once per launch, and the reduction over workers into the centre needs no atomics.
+#include <cstddef>
+
 #include "dw_internal.h"
 
 namespace dw {
@@ -73,18 +75,27 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int64_t nq = (a.P + 3) >> 2;      // caller-supplied g / Hz rows end at P
-  const int64_t qbase = (int64_t)blockIdx.x * (kUpdThreads * kUpdQuads) + tid;
+  // which chunk of kUpdChunk parameters: the block index, or an entry of the list (read from the kernel-argument
+  // block by a scalar load: indexing the by-value argument with a variable would copy it to scratch memory)
+  int blk = blockIdx.x;
+  if (a.n_list > 0) {
+    typedef const char __attribute__((address_space(4)))* karg_bytes;
+    typedef const int __attribute__((address_space(4)))* karg_ints;
+    const karg_bytes ka = (karg_bytes)__builtin_amdgcn_kernarg_segment_ptr();
+    blk = ((karg_ints)(ka + offsetof(UpdateArgs, block_list)))[blockIdx.x];
+  }
+  const int64_t qbase = (int64_t)blk * (kUpdThreads * kUpdQuads) + tid;
   __shared__ double wave_part[DW_MAX_K][kUpdThreads / 64];
 
   // a block whose parameters were all updated by a weight-gradient kernel has nothing to do unless some worker
   // is frozen (then it still reports that worker's distance to the centre)
   if (a.fused.n > 0) {
-    const int64_t j0 = (int64_t)blockIdx.x * kUpdChunk, j1 = j0 + kUpdChunk;
+    const int64_t j0 = (int64_t)blk * kUpdChunk, j1 = j0 + kUpdChunk;
     bool inside = false;
     for (int l = 0; l < a.fused.n; ++l) inside = inside || (j0 >= a.fused.begin[l] && j1 <= a.fused.end[l]);
     const uint64_t all = a.k >= 64 ? ~0ull : ((1ull << a.k) - 1ull);
     if (inside && (a.active_mask & all) == all) {
-      if (tid < a.k) a.partials[(int64_t)tid * gridDim.x + blockIdx.x] = 0.0;
+      if (tid < a.k) a.partials[(int64_t)tid * a.n_blocks + blk] = 0.0;
       return;
     }
   }
@@ -104,7 +115,10 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
   const float inv_b = 1.0f / (float)a.avg_block;
   const int group_lanes = a.avg_block >> 2;           // lanes that share one averaging block (when b > 4)
 
-  for (int i = 0; i < a.k; ++i) {
+  // a listed launch spreads the workers over the grid's second dimension: few chunks, so the chain of k dependent
+  // memory round trips per block would otherwise set the kernel's duration
+  const int i0 = a.n_list > 0 ? (int)blockIdx.y : 0, i1 = a.n_list > 0 ? i0 + 1 : a.k;
+  for (int i = i0; i < i1; ++i) {
     const bool active = (a.active_mask >> i) & 1ull;
     float nsum = 0.f;
     float4* th4 = reinterpret_cast<float4*>(a.theta + (int64_t)i * a.Pp);
@@ -191,20 +205,50 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
     if (lane == 0) wave_part[i][wave] = ws;
   }
   __syncthreads();
-  if (tid < a.k) {
+  if (tid >= i0 && tid < i1) {
     double s = 0.0;
 #pragma unroll
     for (int w = 0; w < kUpdThreads / 64; ++w) s += wave_part[tid][w];
-    a.partials[(int64_t)tid * gridDim.x + blockIdx.x] = s;
+    a.partials[(int64_t)tid * a.n_blocks + blk] = s;
   }
 }
 
-hipError_t launch_update(const UpdateArgs& a, int n_blocks, hipStream_t s) {
+hipError_t launch_update(const UpdateArgs& args, int n_blocks, hipStream_t s) {
   KernelScope ks(KC_UPDATE, s);
+  UpdateArgs a = args;
+  a.n_blocks = n_blocks; a.n_list = 0;
+  int grid = n_blocks, grid_y = 1;
+  // When weight-gradient kernels have updated most ranges and no worker is frozen, only the chunks that touch
+  // other parameters (biases, small layers) have work: launch those, after clearing everybody's partial sums.
+  const uint64_t all = a.k >= 64 ? ~0ull : ((1ull << a.k) - 1ull);
+  if (a.fused.n > 0 && (a.active_mask & all) == all) {
+    int n = 0;
+    bool fits = true;
+    for (int b = 0; b < n_blocks && fits; ++b) {
+      const int64_t j0 = (int64_t)b * kUpdChunk, j1 = j0 + kUpdChunk;
+      bool inside = false;
+      for (int l = 0; l < a.fused.n; ++l) {
+        if (j0 >= a.fused.begin[l] && j1 <= a.fused.end[l]) {
+          inside = true;
+          // skip ahead to the last chunk that is still inside this range
+          const int64_t last = a.fused.end[l] / kUpdChunk - 1;
+          if (last > b) b = (int)last;
+          break;
+        }
+      }
+      if (inside) continue;
+      if (n == 64) fits = false; else a.block_list[n++] = b;
+    }
+    if (fits && n > 0) {
+      hipError_t e = launch_fill_zero(a.partials, (size_t)(((int64_t)a.k * n_blocks * sizeof(double) + 15) / 16 * 16), s);   // the array is carved in 256-byte units
+      if (e != hipSuccess) return e;
+      a.n_list = n; grid = n; grid_y = a.k;
+    }
+  }
   if (a.wb16)
-    hipLaunchKernelGGL(update_kernel<true>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
+    hipLaunchKernelGGL(update_kernel<true>, dim3(grid, grid_y), dim3(kUpdThreads), 0, s, a);
   else
-    hipLaunchKernelGGL(update_kernel<false>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
+    hipLaunchKernelGGL(update_kernel<false>, dim3(grid, grid_y), dim3(kUpdThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -51,6 +51,9 @@ struct UpdateArgs {
   BiasRanges bias;
   FusedRanges fused;
   UpdateScalars sc;
+  // filled by launch_update: the launch covers all n_blocks chunks (n_list == 0) or only the listed ones
+  int n_blocks, n_list;
+  int block_list[64];
 };
 
 struct WeightArgs {                   // dynamic-weight scalars of one communication round (Section V-B)

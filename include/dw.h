@@ -185,13 +185,47 @@ int dw_get_state(dw_handle* h, int what, int worker, int64_t offset, int64_t cou
 int dw_set_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, const void* h_buf, void* stream);
 
 /*
+ * Data overlap (Section IV-A).  The n data points are shuffled by one seeded permutation (the order of the keys
+ * mix(mix(seed) + GAMMA*(i+1)), SplitMix64's output function and increment, equal keys by index); its first o
+ * entries are the subset O shared by all workers, the next k blocks of s = floor((n-o)/k) entries the private
+ * subsets S_1..S_k; the last (n-o) mod k entries belong to no worker.
+ *
+ *   n, o, k     1 <= n <= DW_MAX_POINTS, 0 <= o <= n, 1 <= k <= DW_MAX_K
+ *   d_index     device, [k][o + s] int32: row j receives D_j = O u S_j as point indices, O first, both parts in
+ *               permutation order (nothing is written when o + s == 0)
+ *   d_scratch   device, dw_partition_scratch_bytes(n) bytes, 256-byte aligned; contents undefined afterwards
+ * Returns s (>= 0), or a negative dw_status.  Work is enqueued on `stream`; nothing is synchronised.
+ */
+#define DW_MAX_POINTS (1 << 21)
+size_t dw_partition_scratch_bytes(int64_t n);
+int64_t dw_overlap_partition(int64_t n, int64_t o, int k, uint64_t seed, int32_t* d_index, void* d_scratch,
+                             size_t scratch_bytes, void* stream);
+
+/*
+ * The minibatch of every active worker (Section II eq.(3): each worker's gradient is that of a minibatch sampled
+ * from its own data), drawn on the device from a resident data set: draw b of worker j at its local step t_j is
+ * row d_index[j][floor(u * m / 2^64)] with u = mix(key(seed, j, t_j) + GAMMA*(b+1)), key as for the Rademacher
+ * stream; independent uniform draws with replacement.  Call it before the dw_worker_step that consumes the batch
+ * (same h_active), with a seed different from the configuration's.
+ *
+ *   h           an MLP handle: supplies k, the batch size B, d_0 = dims[0], the element type and the t_j
+ *   d_data      device, [n][d_0] in the handle's dtype (fp32 or bf16), 16-byte aligned
+ *   d_labels    device, [n] int32
+ *   d_index     device, [k][m] int32 as written by dw_overlap_partition (m = o + s >= 1)
+ *   d_x, d_y    device outputs [k][B][d_0] (16-byte aligned) and [k][B]; rows of frozen workers are left alone.
+ *               An entry of d_index outside [0, n) gives a row of zeros with label -1.
+ */
+int dw_draw_batch(dw_handle* h, const void* d_data, const int32_t* d_labels, int64_t n, const int32_t* d_index,
+                  int64_t m, uint64_t seed, const uint8_t* h_active, void* d_x, int32_t* d_y, void* stream);
+
+/*
  * Per-kernel timing for benchmarks (not part of the method).  While enabled, every kernel the handle launches
  * is bracketed by two HIP events on the caller's stream.  dw_profile_read synchronises the stream and returns,
  * per kernel class, the number of launches and their summed duration in milliseconds since the last read
  * (arrays of DW_N_KERNEL_CLASSES entries), then clears the record.  At most 8192 launches are kept between
  * reads; *n_dropped receives how many were not recorded (may be NULL).
  */
-#define DW_N_KERNEL_CLASSES 8
+#define DW_N_KERNEL_CLASSES 9
 #define DW_K_RADEMACHER 0    /* Rademacher bit generator                         */
 #define DW_K_GEMM_FWD 1      /* forward + R-forward GEMMs                        */
 #define DW_K_HEAD 2          /* softmax cross-entropy head                       */
@@ -200,6 +234,7 @@ int dw_set_state(dw_handle* h, int what, int worker, int64_t offset, int64_t cou
 #define DW_K_UPDATE 5        /* fused AdaHessian update (+ distance partials)    */
 #define DW_K_WEIGHTS 6       /* dynamic-weight scalars                           */
 #define DW_K_PULL 7          /* elastic pull + centre reduction                  */
+#define DW_K_GATHER 8        /* minibatch rows drawn from a resident data set    */
 int dw_profile(dw_handle* h, int enable);
 int dw_profile_read(dw_handle* h, int64_t* n_launches, double* total_ms, int64_t* n_dropped, void* stream);
 

@@ -25,8 +25,8 @@ DW_S_ACT = 16
 
 EXPORTS = ("dw_strerror", "dw_last_hip_error", "dw_param_count", "dw_workspace_bytes", "dw_init", "dw_destroy",
            "dw_worker_step", "dw_update_only", "dw_elastic_sync", "dw_get_state", "dw_set_state",
-           "dw_profile", "dw_profile_read")
-KERNEL_CLASSES = ("rademacher", "gemm_fwd", "head", "gemm_wgrad", "gemm_dgrad", "update", "weights", "pull")
+           "dw_profile", "dw_profile_read", "dw_partition_scratch_bytes", "dw_overlap_partition", "dw_draw_batch")
+KERNEL_CLASSES = ("rademacher", "gemm_fwd", "head", "gemm_wgrad", "gemm_dgrad", "update", "weights", "pull", "gather")
 
 
 class dw_config(C.Structure):
@@ -74,6 +74,11 @@ def lib() -> C.CDLL:
     L.dw_set_state.restype = i32; L.dw_set_state.argtypes = [vp, i32, i32, i64, i64, vp, vp]
     L.dw_profile.restype = i32; L.dw_profile.argtypes = [vp, i32]
     L.dw_profile_read.restype = i32; L.dw_profile_read.argtypes = [vp, vp, vp, vp, vp]
+    L.dw_partition_scratch_bytes.restype = C.c_size_t; L.dw_partition_scratch_bytes.argtypes = [i64]
+    L.dw_overlap_partition.restype = i64
+    L.dw_overlap_partition.argtypes = [i64, i64, i32, C.c_uint64, vp, vp, C.c_size_t, vp]
+    L.dw_draw_batch.restype = i32
+    L.dw_draw_batch.argtypes = [vp, vp, vp, i64, vp, i64, C.c_uint64, vp, vp, vp, vp]
     _LIB = L
     return L
 
@@ -128,6 +133,26 @@ def _ptr(a):
     if isinstance(a, np.ndarray):
         return a.ctypes.data_as(C.c_void_p)
     return C.c_void_p(a.data_ptr())        # torch tensor
+
+
+def overlap_partition(n: int, o: int, k: int, seed: int, device="cuda:0"):
+    """Section IV-A on the device: an int32 tensor [k][o + floor((n-o)/k)], row j = D_j (O first)."""
+    import torch
+    dev = torch.device(device)
+    nbytes = lib().dw_partition_scratch_bytes(n)
+    if nbytes == 0:
+        raise DwError(-5, "dw_partition_scratch_bytes")
+    scratch = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    sp = (scratch.data_ptr() + 255) // 256 * 256
+    m = o + (n - o) // k if 0 <= o <= n and k >= 1 else 0
+    index = torch.empty((max(k, 1), max(m, 0)), dtype=torch.int32, device=dev)
+    stream = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
+    s = lib().dw_overlap_partition(n, o, k, seed, C.c_void_p(index.data_ptr()) if index.numel() else None,
+                                   C.c_void_p(sp), nbytes, stream)
+    if s < 0:
+        raise DwError(int(s), "dw_overlap_partition")
+    torch.cuda.current_stream(dev).synchronize()          # the scratch tensor goes away with this frame
+    return index
 
 
 class Handle:
@@ -193,6 +218,14 @@ class Handle:
         if st < 0:
             raise DwError(st, "dw_elastic_sync")
         return st == 1
+
+    def draw_batch(self, data, labels, index, seed: int, x, y, active=None):
+        """Fill x [k][B][d0], y [k][B] with every active worker's minibatch at its current local step."""
+        act = _u8(active)
+        st = lib().dw_draw_batch(self._h, _ptr(data), _ptr(labels), data.shape[0], _ptr(index), index.shape[1], seed,
+                                 _ptr(act), _ptr(x), _ptr(y), self._stream())
+        if st != 0:
+            raise DwError(st, "dw_draw_batch")
 
     # ---- state access --------------------------------------------------------------------------------
     _DT = {DW_S_ZBITS: np.uint32, DW_S_SCORE: np.float64, DW_S_U_HIST: np.float64, DW_S_STEPS: np.int64}

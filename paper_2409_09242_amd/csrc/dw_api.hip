@@ -503,6 +503,41 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
   return 1;
 }
 
+size_t dw_partition_scratch_bytes(int64_t n) {
+  if (n < 1 || n > DW_MAX_POINTS) return 0;
+  return partition_scratch_bytes(n);
+}
+
+int64_t dw_overlap_partition(int64_t n, int64_t o, int k, uint64_t seed, int32_t* d_index, void* d_scratch,
+                             size_t scratch_bytes, void* stream) {
+  if (n < 1 || n > DW_MAX_POINTS || o < 0 || o > n || k < 1 || k > DW_MAX_K) return DW_ERR_ARG;
+  const int64_t sz = (n - o) / k;
+  if (!d_scratch || (!d_index && o + sz > 0)) return DW_ERR_NULL;
+  if (scratch_bytes < partition_scratch_bytes(n) || (reinterpret_cast<uintptr_t>(d_scratch) & 255u))
+    return DW_ERR_WORKSPACE;
+  DW_HIP(launch_partition(n, o, k, seed, d_index, d_scratch, (hipStream_t)stream));
+  return sz;
+}
+
+int dw_draw_batch(dw_handle* h, const void* d_data, const int32_t* d_labels, int64_t n, const int32_t* d_index,
+                  int64_t m, uint64_t seed, const uint8_t* h_active, void* d_x, int32_t* d_y, void* stream) {
+  if (!h || !d_data || !d_labels || !d_index || !d_x || !d_y) return DW_ERR_NULL;
+  if (h->cfg.n_layers == 0) return DW_ERR_MODE;
+  if (n < 1 || n > DW_MAX_POINTS || m < 1 || m > n) return DW_ERR_ARG;
+  if ((reinterpret_cast<uintptr_t>(d_data) & 15u) || (reinterpret_cast<uintptr_t>(d_x) & 15u)) return DW_ERR_ARG;
+  ProfilerGuard pg(h);
+  const uint64_t active = mask_from(h_active, h->cfg.k);
+  if (active == 0) return DW_OK;
+  const uint64_t G = 0x9E3779B97F4A7C15ull;
+  uint64_t keys[DW_MAX_K];
+  for (int j = 0; j < h->cfg.k; ++j)
+    keys[j] = mix64_host(mix64_host(seed + G * (uint64_t)(j + 1)) + G * (uint64_t)(h->t[j] + 1));
+  const int row_bytes = h->cfg.dims[0] * (h->cfg.dtype == DW_BF16 ? 2 : 4);    // a multiple of 16 by validate()
+  DW_HIP(launch_gather(d_data, d_labels, d_index, n, m, row_bytes, h->cfg.batch, h->cfg.k, keys, active, d_x, d_y,
+                       (hipStream_t)stream));
+  return DW_OK;
+}
+
 static int state_ptr(dw_handle* h, int what, int worker, int64_t offset, int64_t count, char** ptr, size_t* bytes) {
   const Layout& L = h->lay;
   const int k = h->cfg.k;

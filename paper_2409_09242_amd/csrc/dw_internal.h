@@ -95,6 +95,15 @@ hipError_t launch_broadcast(float* theta, const float* centre, uint16_t* wb16, i
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hipStream_t s);
 
+// ---- data side ---------------------------------------------------------------------------------------
+size_t partition_scratch_bytes(int64_t n);
+// index [k][o + s], s = floor((n-o)/k): row j = the shared points then worker j's own, in permutation order
+hipError_t launch_partition(int64_t n, int64_t o, int k, uint64_t seed, int32_t* index, void* scratch, hipStream_t s);
+// x [k][B][row_bytes], y [k][B]: draw b of worker j is row index[j][floor(u*m/2^64)], u = mix(key_j + GAMMA*(b+1))
+hipError_t launch_gather(const void* data, const int32_t* labels, const int32_t* index, int64_t n, int64_t m,
+                         int row_bytes, int B, int k, const uint64_t* keys_host, uint64_t active_mask, void* x,
+                         int32_t* y, hipStream_t s);
+
 // ---- network part ------------------------------------------------------------------------------------
 
 // AdaHessian update applied in the epilogue of a weight-gradient GEMM (same arithmetic as update_kernel):
@@ -198,7 +207,7 @@ namespace dw {
 
 enum KernelClass {
   KC_RADEMACHER = 0, KC_GEMM_FWD = 1, KC_HEAD = 2, KC_GEMM_WGRAD = 3, KC_GEMM_DGRAD = 4,
-  KC_UPDATE = 5, KC_WEIGHTS = 6, KC_PULL = 7, KC_COUNT = 8
+  KC_UPDATE = 5, KC_WEIGHTS = 6, KC_PULL = 7, KC_GATHER = 8, KC_COUNT = 9
 };
 
 struct Profiler {

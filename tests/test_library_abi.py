@@ -107,3 +107,17 @@ def test_participation_schedules():
     # absent for Geometric(0.3) - 1 rounds (7/3 on average) after each turn: present 3 rounds in 10
     assert g.shape == (400, 16) and 0.25 < g.mean() < 0.35
     assert W.participation_schedule(W.C1, 3).all()
+
+
+def test_data_calls_validate_on_the_host():
+    lib = B.lib()
+    assert lib.dw_partition_scratch_bytes(0) == 0
+    assert lib.dw_partition_scratch_bytes((1 << 21) + 1) == 0
+    assert lib.dw_partition_scratch_bytes(60000) >= 60000 * 12
+    assert lib.dw_partition_scratch_bytes(60000) % 256 == 0
+    # argument errors are reported before anything touches a device
+    assert lib.dw_overlap_partition(0, 0, 1, 1, None, None, 0, None) == -5
+    assert lib.dw_overlap_partition(10, 11, 1, 1, None, None, 0, None) == -5
+    assert lib.dw_overlap_partition(10, 0, 65, 1, None, None, 0, None) == -5
+    assert lib.dw_overlap_partition(10, 0, 2, 1, None, None, 0, None) == -1
+    assert lib.dw_draw_batch(None, None, None, 1, None, 1, 0, None, None, None, None) == -1

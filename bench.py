@@ -76,7 +76,7 @@ def class_bytes(w, P, k, fused=(), part=1.0):
     return out
 
 
-def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1):
+def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, resident=None):
     import torch
     from paper_2409_09242_amd import binding as B
     from paper_2409_09242_amd import workloads as W
@@ -92,9 +92,27 @@ def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1):
     state = {"round": 0, "step": 0}
     mode = B.DW_DYNAMIC | (B.DW_SEQUENTIAL if sequential else 0)
 
+    if resident is not None:
+        # the step's input comes from a data set resident in HBM: n points shaped like the workload's inputs, split
+        # among the workers with overlap ratio `resident` (Section IV-A), every step's minibatch drawn on the device
+        n_points = 60000
+        gen = torch.Generator(device="cuda"); gen.manual_seed(w.seed)
+        data = torch.randn((n_points, w.dims[0]), device="cuda", generator=gen)
+        t1 = torch.randn((w.dims[0], 32), device="cuda", generator=gen) / w.dims[0] ** 0.5
+        t2 = torch.randn((32, w.dims[-1]), device="cuda", generator=gen) / 32 ** 0.5
+        labels = torch.argmax(torch.relu(data @ t1) @ t2, dim=1).to(torch.int32)
+        if w.bf16:
+            data = data.to(torch.bfloat16)
+        index = B.overlap_partition(n_points, int(resident * n_points), w.k, w.seed + 1)
+        xb, yb = torch.empty_like(xd[0]), torch.empty_like(yd[0])
+
     def one_step():
         b = state["step"] % n_pool
-        h.worker_step(xd[b], yd[b])
+        if resident is not None:
+            h.draw_batch(data, labels, index, w.seed + 2, xb, yb)
+            h.worker_step(xb, yb)
+        else:
+            h.worker_step(xd[b], yd[b])
         if h.elastic_sync(mode, tau=w.tau, participate=sched[state["round"]]):
             state["round"] += 1
         state["step"] += 1
@@ -230,6 +248,9 @@ def main():
                     help="keep g and Hz in memory and run the streaming update over all parameters (fuse_update = 0)")
     ap.add_argument("--calibrate", action="store_true",
                     help="first run a plain 1 GiB copy kernel five times (reference for scaling rocprofv3 --pmc counters)")
+    ap.add_argument("--resident-data", type=float, default=None, metavar="RATIO",
+                    help="draw every step's minibatches on the device from a resident synthetic data set of 60000 "
+                         "points, partitioned among the workers with this overlap ratio (e.g. 0.125)")
     ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stress-only", action="store_true",
@@ -252,7 +273,8 @@ def main():
     n_pool = 4 if w.bf16 else 8
     if args.calibrate:
         calibration_copy()
-    h, elapsed, prof, elapsed_prof, part = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse, args.sequential, args.samples)
+    h, elapsed, prof, elapsed_prof, part = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse, args.sequential, args.samples,
+                                                  args.resident_data)
     dtype = "bf16" if w.bf16 else "f32"
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.k * args.steps / elapsed
@@ -262,9 +284,10 @@ def main():
     if args.samples > 1:
         fl = {c: v * args.samples for c, v in fl.items()}
     by = class_bytes(w, w.P, w.k, fused, part)
-    per_step = {"update": 1, "pull": 1.0 / w.tau, "gemm_wgrad": 1}
+    per_step = {"update": 1, "pull": 1.0 / w.tau, "gemm_wgrad": 1, "gather": 1}
+    by["gather"] = 2.0 * w.k * w.batch * w.dims[0] * (2 if w.bf16 else 4)        # every drawn row read and written once
     kernels = {}
-    for name in ("gemm_fwd", "gemm_wgrad", "gemm_dgrad", "head", "update", "weights", "pull", "rademacher"):
+    for name in ("gemm_fwd", "gemm_wgrad", "gemm_dgrad", "head", "update", "weights", "pull", "rademacher", "gather"):
         n, ms = prof[name]
         if n == 0:
             continue
@@ -315,7 +338,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w.name, "k": w.k, "dims": list(w.dims), "batch": w.batch, "tau": w.tau,
                    "stale": w.stale, "sync": "dynamic, sequential" if args.sequential else "dynamic",
-                   "fuse_update": int(bool(fused)), "hutchinson_probes": args.samples},
+                   "fuse_update": int(bool(fused)), "hutchinson_probes": args.samples,
+                   "input": "pool of minibatches" if args.resident_data is None else
+                            "drawn on the device from 60000 resident points, overlap %g" % args.resident_data},
         "flop_per_step": w.flops_per_worker_step() * w.k * args.samples,
         "step_TFLOP/s": w.flops_per_worker_step() * w.k * args.samples / (ms_per_step * 1e-3) / 1e12,
         "ms_per_step_profiled": 1e3 * elapsed_prof / args.steps,

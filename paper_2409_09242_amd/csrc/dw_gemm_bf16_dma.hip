@@ -1,19 +1,28 @@
 // bf16 dual GEMM of the forward pass, large-tile path: tiles travel global -> LDS without passing through
-// registers.
+// registers, and one wave per SIMD owns a 128 x 64 output tile with all 512 registers of its lanes.
 //
 // Same computation as dual_gemm_bf16 for the forward product of one layer and its directional derivative along
-// z (Section IV-B): S = A W^T, RS = RA W^T + A V^T with V = z's W-part as +-1, block tile 128 x 256 x 32,
-// 8 waves of 64 x 64.  What differs is the data path.  `global_load_lds_dwordx4` writes each lane's 16 bytes
-// straight into LDS (lane l of a wave lands at base + 16 l), so tiles in flight cost no registers and three
-// k-tiles are kept in flight or resident instead of two.  Because a wave's 64 x 16 bytes land contiguously,
-// tiles cannot be padded; bank conflicts are avoided by an XOR swizzle applied when choosing which 16 bytes a
-// lane fetches: rows are 64 bytes, 16-byte slot = k-chunk ^ ((row >> 2) & 3).
+// z (Section IV-B): S = A W^T, RS = RA W^T + A V^T with V = z's W-part as +-1.  Block tile 128 x 256 x 32, four
+// waves side by side along N: the two accumulator sets of a wave (4 x 2 MFMA tiles each) are 256 registers, which
+// the compiler keeps in the accumulation registers, leaving the 256 vector registers to operands and addresses.
+// A wave tile of 128 x 64 needs 20 LDS reads of 16 bytes per lane and k-tile against 24 for two waves of 64 x 64,
+// and half as many +-1 expansions as 64 x 128 would.  With a single wave per SIMD nothing else hides a stall, so
+// the k-loop is written as two straight-line regions per k-tile (one per k-step of 16) in which the multiplies of
+// one k-step are interleaved, by scheduling groups, with the LDS reads, the sign expansions and the global loads
+// that feed the next one; the loop body has no branch except a uniform one around the sign-bit fetch, placed right
+// after the barrier, and the last STAGES k-tiles (nothing left to fetch) run in a loop of their own.
+// `global_load_lds_dwordx4` writes each lane's 16 bytes straight into LDS (lane l of a wave lands at base + 16 l),
+// so tiles in flight cost no registers and four k-tiles are in flight or resident.  Because a wave's 64 x 16
+// bytes land contiguously, tiles cannot be padded; bank conflicts are avoided by an XOR swizzle applied when
+// choosing which 16 bytes a lane fetches: rows are 64 bytes, 16-byte slot = k-chunk ^ ((row >> 2) & 3).
 // The +-1 operand V is never staged as a matrix: every fourth k-tile the sign bits of the next 128 k (16 bytes per
-// row, 4 KB per block) are fetched into a two-deep ring, and each lane expands its 8 bits to bf16 +-1 in
-// registers just before the multiply.
+// row, 4 KB per block) are fetched into a two-deep ring; a lane reads its 32 bits of a k-tile one k-tile ahead and
+// expands 8 of them to bf16 +-1 in registers just before the multiply.
 //
 // Requirements (otherwise the caller uses dual_gemm_bf16): see gemm_bf16_dma_ok.  Rows beyond M are clamped to the
 // last valid row (their products are discarded).
+#include <type_traits>
+
 #include "dw_internal.h"
 #include "dw_gemm_epi.h"
 
@@ -24,9 +33,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 namespace b16d {
 
-constexpr int BM = 128, BN = 256, BK = 32, NT = 512, NW = NT / 64;
-constexpr int WM = 2, WN = 4, TM = 2, TN = 2;           // wave tile 64 x 64
-constexpr int STAGES = 3;
+constexpr int BM = 128, BN = 256, BK = 32, NT = 256, NW = NT / 64;
+constexpr int WM = 1, WN = 4, TM = 4, TN = 2;           // wave tile 128 x 64
+constexpr int STAGES = 4;
 constexpr int ZGROUP = 4;                               // k-tiles covered by one fetch of sign bits (16 bytes per row)
 
 typedef __attribute__((address_space(3))) void* lds_void;
@@ -131,10 +140,6 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
 #pragma unroll
     for (int c = 0; c < TY::CPW; ++c)
       __builtin_amdgcn_global_load_lds((glb_void)(gy[c] + (int64_t)kt * BK), (lds_void)(base + OFF_Y + (wave_u * TY::CPW + c) * 1024), 16, 0, 0);
-    if ((kt & (ZGROUP - 1)) == 0 && wave_u < 4) {           // k-tile kt opens sign-bit group kt / 4
-      const int zg = kt / ZGROUP;
-      __builtin_amdgcn_global_load_lds((glb_void)(gz + zg * 4), (lds_void)(smem + OFF_Z + (zg & 1) * Z_B + wave_u * 1024), 16, 0, 0);
-    }
   };
 
   floatx16 acc[TM][TN], racc[TM][TN];
@@ -146,7 +151,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
       for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; racc[i][j][r] = 0.f; }
 
   struct Frags { bf16x8 xa[TM], rxa[TM], yb[TN], ryb[TN]; };
-  uint32_t zw[TN];                                          // this lane's 32 sign bits of the current k-tile, per column tile
+  uint32_t zw[TN], zn[TN];                                  // this lane's 32 sign bits of the current and of the next k-tile, per column tile
   auto read_frags = [&](Frags& f, int st, int ks) {
     const char* base = smem + st * STAGE_B;
 #pragma unroll
@@ -160,7 +165,11 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
   auto read_bits = [&](int kt) {
     const char* zbase = smem + OFF_Z + ((kt / ZGROUP) & 1) * Z_B + (kt & (ZGROUP - 1)) * 4;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) zw[j] = *reinterpret_cast<const uint32_t*>(zbase + (wn0 + j * 32 + l32) * 16);
+    for (int j = 0; j < TN; ++j) zn[j] = *reinterpret_cast<const uint32_t*>(zbase + (wn0 + j * 32 + l32) * 16);
+  };
+  auto take_bits = [&]() {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) zw[j] = zn[j];
   };
   auto expand = [&](Frags& f, int ks) {                     // V operand of k-step ks: byte ks*2 + lane/32 of the tile's word
 #pragma unroll
@@ -186,48 +195,77 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
         racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.ryb[j], racc[i][j], 0, 0, 0);
   };
 
-  const int nkt = a.K / BK;
-  // prologue: fill all stages, wait for tile 0
+  const int nkt = a.K / BK;                                 // a multiple of 4, at least 4
+  __builtin_amdgcn_global_load_lds((glb_void)gz, (lds_void)(smem + OFF_Z + wave_u * 1024), 16, 0, 0);   // bits of k-tiles 0..3
 #pragma unroll
-  for (int t = 0; t < STAGES; ++t)
-    if (t < nkt) issue(t, t);
-  if (nkt >= STAGES) wait_vm<LPT * (STAGES - 1)>(); else wait_vm<0>();
+  for (int t = 0; t < STAGES; ++t) issue(t, t);
+  wait_vm<LPT * (STAGES - 1)>();
   __syncthreads();
   Frags f0, f1;
   read_bits(0);
   read_frags(f0, 0, 0);
-  // nothing of this wave's LDS or scalar traffic is pending when the loop is entered, so that inside the loop
-  // the compiler can count exactly which LDS reads a multiply has to wait for
+  __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (0x7 << 4) | (0x0 << 8));
+  take_bits();
+  expand(f0, 0);
+  read_bits(1);
   __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (0x7 << 4) | (0x0 << 8));
 
-  int st = 0;                                               // stage of k-tile kt
-  for (int kt = 0; kt < nkt; ++kt) {
+  // Scheduling groups: after every multiply, one LDS read or one global load (while there are any) and two vector
+  // instructions (address arithmetic, sign expansion) of the code that prepares the next k-step.
+  constexpr int N_MFMA = TM * TN * (HAS_RX ? 3 : 2);        // multiplies per k-step
+  constexpr int N_DS = TM * (HAS_RX ? 2 : 1) + TN;          // operand reads from LDS per k-step
+  auto interleave = [&](auto n_vmem_, auto n_ds_) {
+    constexpr int n_vmem = decltype(n_vmem_)::value, n_ds = decltype(n_ds_)::value;
+#pragma unroll
+    for (int q = 0; q < N_MFMA; ++q) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      if (q < n_vmem) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+      else if (q < n_vmem + n_ds) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+    }
+  };
+  using no_vmem = std::integral_constant<int, 0>;
+  using tile_vmem = std::integral_constant<int, LPT>;
+  using frag_ds = std::integral_constant<int, N_DS>;
+  using frag_bits_ds = std::integral_constant<int, N_DS + TN>;
+  int st = 0, kt = 0;
+  for (; kt + STAGES < nkt; ++kt) {
     const int st_next = st + 1 == STAGES ? 0 : st + 1;
-    // k-step 0 multiplies while the operands of k-step 1 are fetched from LDS
     read_frags(f1, st, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    expand(f0, 0);
-    __builtin_amdgcn_s_setprio(1);                          // the wave feeding the matrix cores issues first
+    expand(f1, 1);
     multiply(f0);
-    __builtin_amdgcn_s_setprio(0);
+    interleave(no_vmem{}, frag_ds{});
     __builtin_amdgcn_sched_barrier(0);
-    expand(f1, 1);                                          // before the next tile's bits replace this tile's
-    // k-tile kt+1 must have landed (this wave's part), then everybody's part; after the barrier nobody reads
-    // stage `st` any more, so it can receive k-tile kt+STAGES
-    if (kt + STAGES - 1 < nkt) wait_vm<LPT * (STAGES - 2)>(); else wait_vm<0>();
+    wait_vm<LPT * (STAGES - 2)>();
     __syncthreads();
-    if (kt + STAGES < nkt) issue(kt + STAGES, st);
-    if (kt + 1 < nkt) { read_bits(kt + 1); read_frags(f0, st_next, 0); }
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_setprio(1);
+    if (((kt + STAGES) & (ZGROUP - 1)) == 0) {              // k-tile kt+STAGES opens a group of sign bits
+      const int zg = (kt + STAGES) / ZGROUP;
+      __builtin_amdgcn_global_load_lds((glb_void)(gz + zg * 4), (lds_void)(smem + OFF_Z + (zg & 1) * Z_B + wave_u * 1024), 16, 0, 0);
+    }
+    issue(kt + STAGES, st);
+    take_bits(); read_bits(kt + 2); read_frags(f0, st_next, 0); expand(f0, 0);
     multiply(f1);
-    __builtin_amdgcn_s_setprio(0);
+    interleave(tile_vmem{}, frag_bits_ds{});
     __builtin_amdgcn_sched_barrier(0);
     st = st_next;
   }
+  for (; kt < nkt; ++kt) {                                  // the last STAGES k-tiles: nothing left to fetch
+    const int st_next = st + 1 == STAGES ? 0 : st + 1;
+    read_frags(f1, st, 1);
+    expand(f1, 1);
+    multiply(f0);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_vm<0>();
+    __syncthreads();
+    if (kt + 1 < nkt) { take_bits(); if (kt + 2 < nkt) read_bits(kt + 2); read_frags(f0, st_next, 0); expand(f0, 0); }
+    multiply(f1);
+    __builtin_amdgcn_sched_barrier(0);
+    st = st_next;
+  }
+  __syncthreads();                                          // the epilogue reuses the stages as its staging area
 
-  // epilogue: bias, R-bias (the bias part of z), ReLU; the two bf16 outputs go through LDS (free after the last
-  // barrier of the loop) so that they leave as 16-byte stores of whole row pieces (see dw_gemm_epi.h)
+  // epilogue: bias, R-bias (the bias part of z), ReLU; the two bf16 outputs go through LDS (free after the
+  // barrier above) so that they leave as 16-byte stores of whole row pieces (see dw_gemm_epi.h)
   char* wl = smem + wave * epi_bf16_lds_bytes(TN);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {

@@ -92,6 +92,14 @@ int validate(const dw_config* c, Layout* lay) {
   if (L > 0 && c->n_samples > 1) lay->dacc = take(vec);
   if (c->dtype == DW_BF16) lay->wb16 = take((size_t)k * lay->Pp * 2);
   lay->zbits = take((size_t)k * lay->z_stride * 4);
+  if (c->dtype == DW_BF16) {
+    bool any = false;
+    for (int l = 2; l <= L; ++l) {
+      lay->zt_layer[l - 1] = gemm_bf16_dgrad_dma_shape_ok(c->batch, c->dims[l], c->dims[l - 1], k, lay->woff[l - 1]);
+      any = any || lay->zt_layer[l - 1];
+    }
+    if (any) lay->zbits_t = take((size_t)k * lay->z_stride * 4);
+  }
   if (L > 0) {
     const size_t es = c->dtype == DW_BF16 ? 2 : 4;
     const int64_t B = c->batch;

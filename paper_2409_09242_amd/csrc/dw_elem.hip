@@ -419,6 +419,81 @@ hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words6
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Transposed copy of one layer's part of z.  The data gradient through W_l [R = d_l][C = d_{l-1}] contracts over
+// the R index, so its large-tile kernel wants the sign bits of a column of V_l (fixed c, consecutive r) side by
+// side: bit (r, c) of z sits at woff + r*C + c, its copy at woff + c*R + r of zt.  A block moves a 512 x 512 bit
+// super-tile: 64-byte row pieces in, 64 transposes of 64 x 64 bits in LDS (tile (a, b) and tile (b, a) swap places),
+// 64-byte row pieces out.  A 64 x 64 tile is one 64-bit word per lane; it is transposed by six exchange steps with
+// the lane 32, 16, .. 1 away (swap the off-diagonal blocks of every 2j x 2j block).
+// Requires R % 128 == 0, C % 128 == 0, woff % 128 == 0.
+// ---------------------------------------------------------------------------------------------------
+constexpr int kTrEdge = 512;                       // bits
+constexpr int kTrRow = kTrEdge / 8 + 8;            // LDS bytes per row (8 bytes of padding)
+
+template <int J>
+__device__ __forceinline__ uint64_t transpose64_step(uint64_t w, int lane) {
+  // bits whose position has bit J clear
+  constexpr uint64_t lo = J == 32 ? 0x00000000FFFFFFFFull : J == 16 ? 0x0000FFFF0000FFFFull : J == 8 ? 0x00FF00FF00FF00FFull
+                          : J == 4 ? 0x0F0F0F0F0F0F0F0Full : J == 2 ? 0x3333333333333333ull : 0x5555555555555555ull;
+  const uint64_t p = __shfl_xor(w, J);
+  return (lane & J) ? ((w & ~lo) | ((p >> J) & lo)) : ((w & lo) | ((p << J) & ~lo));
+}
+__device__ __forceinline__ uint64_t transpose64(uint64_t w, int lane) {
+  w = transpose64_step<32>(w, lane); w = transpose64_step<16>(w, lane); w = transpose64_step<8>(w, lane);
+  w = transpose64_step<4>(w, lane); w = transpose64_step<2>(w, lane); w = transpose64_step<1>(w, lane);
+  return w;
+}
+
+__global__ __launch_bounds__(256) void transpose_bits_kernel(const uint32_t* z, int64_t z_stride, uint32_t* zt, int64_t zt_stride, int64_t woff,
+                                                             int R, int C, uint64_t active_mask) {
+  __shared__ __attribute__((aligned(16))) char tile[kTrEdge * kTrRow];
+  const int worker = blockIdx.z;
+  if (!((active_mask >> worker) & 1ull)) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r0 = blockIdx.y * kTrEdge, c0 = blockIdx.x * kTrEdge;
+  const char* src = reinterpret_cast<const char*>(z + (int64_t)worker * z_stride) + (woff >> 3);
+  char* dst = reinterpret_cast<char*>(zt + (int64_t)worker * zt_stride) + (woff >> 3);
+  for (int u = tid; u < kTrEdge * 4; u += 256) {
+    const int row = u >> 2, q = u & 3;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (r0 + row < R && c0 + q * 128 < C)
+      v = *reinterpret_cast<const uint4*>(src + (((int64_t)(r0 + row) * C + c0) >> 3) + q * 16);
+    uint2* t = reinterpret_cast<uint2*>(tile + row * kTrRow + q * 16);
+    t[0] = make_uint2(v.x, v.y); t[1] = make_uint2(v.z, v.w);
+  }
+  __syncthreads();
+  // 8 x 8 tiles: units are the 8 diagonal tiles and the 28 pairs (a, b), (b, a) with a < b
+  for (int u = wave; u < 36; u += 4) {
+    int a = 0, b = u;                                // u-th pair in the order (0,0..7), (1,1..7), ...
+    while (b >= 8 - a) { b -= 8 - a; a += 1; }
+    b += a;
+    uint64_t* pab = reinterpret_cast<uint64_t*>(tile + (a * 64 + lane) * kTrRow + b * 8);
+    uint64_t* pba = reinterpret_cast<uint64_t*>(tile + (b * 64 + lane) * kTrRow + a * 8);
+    const uint64_t wab = transpose64(*pab, lane);
+    const uint64_t wba = transpose64(*pba, lane);    // the same word when a == b
+    *pba = wab;
+    if (a != b) *pab = wba;
+  }
+  __syncthreads();
+  for (int u = tid; u < kTrEdge * 4; u += 256) {
+    const int row = u >> 2, q = u & 3;
+    if (c0 + row < C && r0 + q * 128 < R) {
+      const uint2* t = reinterpret_cast<const uint2*>(tile + row * kTrRow + q * 16);
+      const uint2 x = t[0], y = t[1];
+      *reinterpret_cast<uint4*>(dst + (((int64_t)(c0 + row) * R + r0) >> 3) + q * 16) = make_uint4(x.x, x.y, y.x, y.y);
+    }
+  }
+}
+
+hipError_t launch_transpose_bits(const uint32_t* z, int64_t z_stride, uint32_t* zt, int64_t zt_stride, int64_t woff, int R, int C, int k,
+                                 uint64_t active_mask, hipStream_t s) {
+  KernelScope ks(KC_RADEMACHER, s);
+  const dim3 grid((unsigned)((C + kTrEdge - 1) / kTrEdge), (unsigned)((R + kTrEdge - 1) / kTrEdge), (unsigned)k);
+  hipLaunchKernelGGL(transpose_bits_kernel, grid, dim3(256), 0, s, z, z_stride, zt, zt_stride, woff, R, C, active_mask);
+  return hipGetLastError();
+}
+
 // Running sum of z_j * Hz_j over the probes of one step (Section IV-B with n > 1), one float4 per thread.
 __global__ __launch_bounds__(256) void probe_sum_kernel(float* dacc, const float* hz, const uint32_t* zbits, int64_t Pp,
                                                         int64_t z_stride, uint64_t active_mask, int first) {

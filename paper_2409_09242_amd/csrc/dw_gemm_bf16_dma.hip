@@ -39,6 +39,7 @@ constexpr int STAGES = 4;
 constexpr int ZGROUP = 4;                               // k-tiles covered by one fetch of sign bits (16 bytes per row)
 
 typedef __attribute__((address_space(3))) void* lds_void;
+typedef __attribute__((address_space(3))) const char* lds_char;
 typedef __attribute__((address_space(1))) const void* glb_void;
 
 __device__ __forceinline__ uint32_t pm1_pair(uint32_t b_lo, uint32_t b_hi) {
@@ -57,6 +58,11 @@ template <int N>
 __device__ __forceinline__ void wait_vm() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+}
+
+// wait until all of this wave's LDS reads have returned (vector-memory operations are not waited for)
+__device__ __forceinline__ void wait_lds() {
+  __builtin_amdgcn_s_waitcnt((63 & 15) | ((63 >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
 }
 
 // ---- one operand tile of R rows x 32 k, memory [row][k] -> LDS rows of 64 bytes, chunk c (1 KB) = rows 16c..16c+15
@@ -80,10 +86,52 @@ struct DmaTile {
   }
 };
 
-template <bool HAS_RX>
-__global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
+// ---- one operand tile of 32 k x R rows stored k-major in memory ([k][row], the weight matrix in the data gradient):
+// LDS keeps it as it lies, 32 k-rows of R*2 bytes, chunk c (1 KB) = k-rows 2c and 2c+1 (R = 256).  The MFMA operand
+// (8 consecutive k of one row) is produced by the LDS transpose read `ds_read_b64_tr_b16`: within 16 lanes, lane i
+// receives element i%4 of the 8-byte pieces addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4.  The four k-rows a
+// 16-lane group addresses are a multiple of 256 bytes apart, so the 32-byte piece ("pair" of 16-byte slots) a group
+// reads is XOR-swizzled by 2*(k%4): the 32 lanes of a pass then cover 256 consecutive bytes of bank space.
+template <int R>
+struct DmaTileK {
+  static_assert(R == 256, "two k-rows per 1 KB chunk");
+  static constexpr int BYTES = R * BK * 2;
+  static constexpr int CPW = BYTES / 1024 / NW;
+  // global element offset (at k0 = 0) of the 16 bytes lane `lane` moves for chunk c (they land at c*1024 + 16*lane)
+  __device__ static __forceinline__ int64_t map(int c, int lane, int r0, int ld) {
+    const int k = 2 * c + (lane >> 5), ps = lane & 31;      // k-row, physical slot
+    const int lp = (ps >> 1) ^ ((k & 3) << 1);              // logical pair held by physical pair ps/2
+    return (int64_t)k * ld + r0 + ((lp << 1) | (ps & 1)) * 8;
+  }
+  // The transpose reads are written as inline assembly: behind the compiler's intrinsic they would be preceded by a
+  // wait for every outstanding global -> LDS load (it cannot tell that they read other stages), which serialises the
+  // pipeline.  The price: the compiler does not know when their results arrive.  The kernel waits for its LDS reads
+  // explicitly (the waits it needs anyway before a barrier or a multiply) and then passes the registers through
+  // `settle`, which pins every use behind that wait.
+  __device__ static __forceinline__ bf16x8 frag(const char* lds, int row0, int ks, int lane) {
+    const int s = lane & 15, kq = s >> 2;
+    const int k = ks * 16 + (lane >> 5) * 8 + kq;           // k%4 == kq; the second read is 4 k-rows further on
+    const int lp = (row0 >> 4) + ((lane >> 4) & 1);
+    const uint32_t addr = (uint32_t)(uintptr_t)(lds_char)(lds + k * (R * 2) + ((lp ^ (kq << 1)) << 5) + (s & 3) * 8);
+    uint2 lo, hi;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(4 * R * 2));
+    return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+  }
+  __device__ static __forceinline__ void settle(bf16x8& f) {
+    uint4 u = __builtin_bit_cast(uint4, f);
+    asm volatile("" : "+v"(u.x), "+v"(u.y), "+v"(u.z), "+v"(u.w));
+    f = __builtin_bit_cast(bf16x8, u);
+  }
+};
+
+// DGRAD = false: forward product, Y = W stored [n][k], epilogue bias + ReLU.
+// DGRAD = true: data gradient, Y = W stored [k][n] (k = the layer's outputs), sign bits from the transposed copy of
+// z's W-part (bit (n, k) at z_off + n*K + k), epilogue = the ReLU mask of the layer below.
+template <bool HAS_RX, bool DGRAD>
+__global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
   using TX = DmaTile<BM>;
-  using TY = DmaTile<BN>;
+  using TY = typename std::conditional<DGRAD, DmaTileK<BN>, DmaTile<BN>>::type;
   constexpr int X_B = TX::BYTES, Y_B = TY::BYTES;
   constexpr int OFF_RX = X_B;
   constexpr int OFF_Y = X_B * (HAS_RX ? 2 : 1);
@@ -114,7 +162,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
   const uint16_t* X = reinterpret_cast<const uint16_t*>(a.X) + (int64_t)worker * a.x_wstride;
   const uint16_t* RX = HAS_RX ? reinterpret_cast<const uint16_t*>(a.RX) + (int64_t)worker * a.x_wstride : nullptr;
   const uint16_t* Y = reinterpret_cast<const uint16_t*>(a.Y) + (int64_t)worker * a.y_wstride;
-  const uint32_t* zb = a.zbits + (int64_t)worker * a.z_stride;
+  const uint32_t* zb = DGRAD ? a.zbits_t + (int64_t)worker * a.zt_stride : a.zbits + (int64_t)worker * a.z_stride;
 
   // per-wave source pointers (k0 = 0) of the chunks this wave moves
   const uint16_t* gx[TX::CPW]; const uint16_t* grx[TX::CPW]; const uint16_t* gy[TY::CPW];
@@ -125,9 +173,13 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     gx[c] = X + go; grx[c] = HAS_RX ? RX + go : nullptr;
   }
 #pragma unroll
-  for (int c = 0; c < TY::CPW; ++c) gy[c] = Y + TY::map(wave * TY::CPW + c, lane, col0, a.N, a.ldy);
+  for (int c = 0; c < TY::CPW; ++c) {
+    if constexpr (DGRAD) gy[c] = Y + DmaTileK<BN>::map(wave * TY::CPW + c, lane, col0, a.ldy);
+    else gy[c] = Y + DmaTile<BN>::map(wave * TY::CPW + c, lane, col0, a.N, a.ldy);
+  }
+  const int64_t y_step = DGRAD ? (int64_t)BK * a.ldy : BK;  // elements from one k-tile of Y to the next
   // sign bits: waves 0..3 fetch rows 64w..64w+63 of the tile, 16 bytes (128 k) per row and group
-  const uint32_t* gz = zb + ((a.z_off + (int64_t)(col0 + (wave & 3) * 64 + lane) * a.ldy) >> 5);
+  const uint32_t* gz = zb + ((a.z_off + (int64_t)(col0 + (wave & 3) * 64 + lane) * a.K) >> 5);
 
   auto issue = [&](int kt, int st) {                        // start the loads of k-tile kt into LDS stage st
     char* base = smem + st * STAGE_B;
@@ -139,7 +191,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     }
 #pragma unroll
     for (int c = 0; c < TY::CPW; ++c)
-      __builtin_amdgcn_global_load_lds((glb_void)(gy[c] + (int64_t)kt * BK), (lds_void)(base + OFF_Y + (wave_u * TY::CPW + c) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void)(gy[c] + kt * y_step), (lds_void)(base + OFF_Y + (wave_u * TY::CPW + c) * 1024), 16, 0, 0);
   };
 
   floatx16 acc[TM][TN], racc[TM][TN];
@@ -161,6 +213,12 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) f.yb[j] = TY::frag(base + OFF_Y, wn0 + j * 32, ks, lane);
+  };
+  auto settle = [&](Frags& f) {                             // after a wait for this wave's LDS reads
+    if constexpr (DGRAD) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) TY::settle(f.yb[j]);
+    }
   };
   auto read_bits = [&](int kt) {
     const char* zbase = smem + OFF_Z + ((kt / ZGROUP) & 1) * Z_B + (kt & (ZGROUP - 1)) * 4;
@@ -205,6 +263,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
   read_bits(0);
   read_frags(f0, 0, 0);
   __builtin_amdgcn_s_waitcnt(15 | (3 << 14) | (0x7 << 4) | (0x0 << 8));
+  settle(f0);
   take_bits();
   expand(f0, 0);
   read_bits(1);
@@ -237,6 +296,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     interleave(no_vmem{}, frag_ds{});
     __builtin_amdgcn_sched_barrier(0);
     wait_vm<LPT * (STAGES - 2)>();
+    settle(f1);
     __syncthreads();
     if (((kt + STAGES) & (ZGROUP - 1)) == 0) {              // k-tile kt+STAGES opens a group of sign bits
       const int zg = (kt + STAGES) / ZGROUP;
@@ -247,6 +307,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     multiply(f1);
     interleave(tile_vmem{}, frag_bits_ds{});
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (DGRAD) { wait_lds(); settle(f0); }
     st = st_next;
   }
   for (; kt < nkt; ++kt) {                                  // the last STAGES k-tiles: nothing left to fetch
@@ -256,47 +317,55 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_fwd_dma(GemmArgs a) {
     multiply(f0);
     __builtin_amdgcn_sched_barrier(0);
     wait_vm<0>();
+    settle(f1);
     __syncthreads();
     if (kt + 1 < nkt) { take_bits(); if (kt + 2 < nkt) read_bits(kt + 2); read_frags(f0, st_next, 0); expand(f0, 0); }
     multiply(f1);
     __builtin_amdgcn_sched_barrier(0);
+    if constexpr (DGRAD) { wait_lds(); settle(f0); }
     st = st_next;
   }
   __syncthreads();                                          // the epilogue reuses the stages as its staging area
 
-  // epilogue: bias, R-bias (the bias part of z), ReLU; the two bf16 outputs go through LDS (free after the
-  // barrier above) so that they leave as 16-byte stores of whole row pieces (see dw_gemm_epi.h)
+  // epilogue.  Forward: bias, R-bias (the bias part of z), ReLU.  Data gradient: the ReLU mask of the layer below,
+  // applied while the rows leave.  The two bf16 outputs go through LDS (free after the barrier above) so that they
+  // leave as 16-byte stores of whole row pieces (see dw_gemm_epi.h)
   char* wl = smem + wave * epi_bf16_lds_bytes(TN);
+  const uint16_t* msk = DGRAD ? reinterpret_cast<const uint16_t*>(a.mask_src) + (int64_t)worker * a.mask_wstride : nullptr;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     floatx16 cv[TN], rcv[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int n = col0 + wn0 + j * 32 + l32;
-      const float bias = a.bias[(int64_t)worker * a.bias_wstride + n];
-      const int64_t bi = a.zb_off + n;
-      const float cz = ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
+      if constexpr (DGRAD) {
+        cv[j] = acc[i][j]; rcv[j] = racc[i][j];
+      } else {
+        const int n = col0 + wn0 + j * 32 + l32;
+        const float bias = a.bias[(int64_t)worker * a.bias_wstride + n];
+        const int64_t bi = a.zb_off + n;
+        const float cz = ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float c = acc[i][j][r] + bias, rc = racc[i][j][r] + cz;
-        const bool on = c > 0.f;
-        cv[j][r] = on ? c : 0.f; rcv[j][r] = on ? rc : 0.f;
+        for (int r = 0; r < 16; ++r) {
+          const float c = acc[i][j][r] + bias, rc = racc[i][j][r] + cz;
+          const bool on = c > 0.f;
+          cv[j][r] = on ? c : 0.f; rcv[j][r] = on ? rc : 0.f;
+        }
       }
     }
     const int rbase = row0 + wm0 + i * 32, cbase = col0 + wn0;
-    epi_bf16_rows_out<TN, false>(wl, cv, rcv, lane, reinterpret_cast<uint16_t*>(a.C), reinterpret_cast<uint16_t*>(a.RC),
+    epi_bf16_rows_out<TN, DGRAD>(wl, cv, rcv, lane, reinterpret_cast<uint16_t*>(a.C), reinterpret_cast<uint16_t*>(a.RC),
                                  (int64_t)worker * a.c_wstride + (int64_t)rbase * a.ldc + cbase, a.ldc, a.M - rbase,
-                                 a.N - cbase, nullptr, 0, 0);
+                                 a.N - cbase, msk, (int64_t)rbase * a.ld_mask + cbase, a.ld_mask);
   }
 }
 
-template <bool RX>
+template <bool RX, bool DGRAD>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
   const dim3 grid((unsigned)((tiles * active_count(a.active_mask, a.k) + 7) / 8 * 8)), block(NT);
   constexpr int smem = (BM * BK * 2 * (RX ? 2 : 1) + BN * BK * 2) * STAGES + 2 * BN * 16;
   static_assert(smem <= 160 * 1024, "LDS budget");
-  auto kern = dual_gemm_bf16_fwd_dma<RX>;
+  auto kern = dual_gemm_bf16_dma<RX, DGRAD>;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
@@ -309,19 +378,29 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
 
 }  // namespace b16d
 
+bool gemm_bf16_dgrad_dma_shape_ok(int batch, int n_out, int n_in, int k, int64_t woff) {
+  if (batch < 128 || n_in % 256 != 0 || n_out % 128 != 0 || woff % 128 != 0) return false;
+  return (int64_t)((batch + 127) / 128) * (n_in / 256) * k >= 256;
+}
+
 // true when the large-tile DMA kernel can take this product: the forward product of a hidden layer (ReLU
-// epilogue) that fills the chip, with whole 256-column tiles and rows of z that 16-byte loads can address
+// epilogue) or the data gradient through a layer (mask epilogue) that fills the chip, with whole 256-column tiles
+// and rows of z (for the data gradient: of its transposed copy) that 16-byte loads can address
 bool gemm_bf16_dma_ok(const GemmArgs& a) {
-  if (a.epi != EPI_RELU || !a.ry_bits || !a.x_kcontig || !a.y_kcontig) return false;
-  if (a.M < 128 || a.N % 256 != 0 || a.K % 128 != 0 || a.K != a.ldy) return false;
-  if (a.ldx % 32 != 0) return false;
+  const bool fwd = a.epi == EPI_RELU && a.y_kcontig && a.K == a.ldy;
+  const bool dgrad = a.epi == EPI_MASK && !a.y_kcontig && a.RX && a.zbits_t && a.N == a.ldy && a.ld_mask % 8 == 0 &&
+                     a.zt_stride % 4 == 0 && (reinterpret_cast<uintptr_t>(a.zbits_t) & 15u) == 0;
+  if (!(fwd || dgrad) || !a.ry_bits || !a.x_kcontig) return false;
+  if (a.M < 128 || a.N % 256 != 0 || a.K % 128 != 0) return false;
+  if (a.ldx % 32 != 0 || a.ldc % 8 != 0) return false;
   if ((int64_t)((a.M + 127) / 128) * (a.N / 256) * a.k < 256) return false;
   if (a.z_off % 128 != 0 || a.z_stride % 4 != 0 || (reinterpret_cast<uintptr_t>(a.zbits) & 15u) != 0) return false;
   return true;
 }
 
 hipError_t launch_gemm_bf16_dma(const GemmArgs& a, hipStream_t s) {
-  return a.RX ? b16d::launch_one<true>(a, s) : b16d::launch_one<false>(a, s);
+  if (a.epi == EPI_MASK) return b16d::launch_one<true, true>(a, s);
+  return a.RX ? b16d::launch_one<true, false>(a, s) : b16d::launch_one<false, false>(a, s);
 }
 
 }  // namespace dw

@@ -91,6 +91,10 @@ hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words6
 // dacc = (first ? 0 : dacc) + z*hz for the active workers: the running sum of a step's Hutchinson probes
 hipError_t launch_probe_sum(float* dacc, const float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride, int k,
                             uint64_t active_mask, int first, hipStream_t s);
+// zt = z with the bits of one layer's W-part [R][C] transposed (bit (r, c) at woff + r*C + c goes to woff + c*R + r);
+// R, C and woff must be multiples of 128, both strides multiples of 4 words, both arrays 16-byte aligned
+hipError_t launch_transpose_bits(const uint32_t* z, int64_t z_stride, uint32_t* zt, int64_t zt_stride, int64_t woff, int R, int C, int k,
+                                 uint64_t active_mask, hipStream_t s);
 hipError_t launch_broadcast(float* theta, const float* centre, uint16_t* wb16, int64_t Pp, int k, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hipStream_t s);
@@ -131,6 +135,8 @@ struct GemmArgs {
   const void* Y; const void* RY;      // RY == nullptr and ry_bits == 0: absent
   int ry_bits;                        // RY is the +-1 direction z, read from zbits at z_off + element offset in Y
   const uint32_t* zbits; int64_t z_stride; int64_t z_off;
+  const uint32_t* zbits_t;            // optional: z with the W-part of this layer transposed (bit (n, k) at z_off + n*K + k)
+  int64_t zt_stride;                  // its per-worker stride in words
   int64_t x_wstride, y_wstride;       // per-worker element strides of X/RX and Y/RY
   int x_kcontig, y_kcontig;           // 1: contraction index is the contiguous one
   int ldx, ldy;
@@ -162,6 +168,9 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 // and how many partial-sum slots (tiles) does it then write per worker?
 bool gemm_bf16_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff);
 int gemm_bf16_wgrad_tiles(int n_out, int n_in);
+// would the data gradient through W[n_out][n_in] of a minibatch of `batch` samples take the large-tile kernel
+// (given the transposed sign bits)?
+bool gemm_bf16_dgrad_dma_shape_ok(int batch, int n_out, int n_in, int k, int64_t woff);
 bool gemm_bf16_dma_ok(const GemmArgs& a);                        // large-tile forward path usable for this product?
 hipError_t launch_gemm_bf16_dma(const GemmArgs& a, hipStream_t s);
 
@@ -183,6 +192,8 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t act[DW_MAX_LAYERS] = {0}, ract[DW_MAX_LAYERS] = {0};   // a_l, Ra_l for l = 1..L-1 (index l)
   size_t delta[DW_MAX_LAYERS] = {0}, rdelta[DW_MAX_LAYERS] = {0}; // d_l, Rd_l of the hidden layers l = 1..L-1 (index l)
   size_t sL = 0, rsL = 0, dL = 0, rdL = 0, dL16 = 0, rdL16 = 0;  // output layer, fp32 [k][B][16] (+ bf16 copies)
+  size_t zbits_t = 0;                 // [k][z_stride] words: z with the W-parts of the layers in zt_layer transposed
+  bool zt_layer[DW_MAX_LAYERS] = {false};   // index l-1: the data gradient through W_l reads the transposed bits
   size_t dacc = 0;                    // [k][Pp] floats, n_samples > 1 only: sum over the probes of z_j*Hz_j
   int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
   int n_fuse_slots = 0;

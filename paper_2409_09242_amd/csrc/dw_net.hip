@@ -116,6 +116,18 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
   auto gemm = [&](const GemmArgs& a) { return b16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s); };
   hipError_t e;
 
+  // layers whose data gradient reads the sign bits of V_l column by column get a transposed copy of those bits
+  // (when the caller's z allows 16-byte accesses; otherwise those layers take the general kernel)
+  uint32_t* zt = nullptr;
+  const bool z_aligned = z_stride % 4 == 0 && (reinterpret_cast<uintptr_t>(zbits) & 15u) == 0;
+  for (int l = 2; l <= L && b16 && z_aligned; ++l) {
+    if (!lay.zt_layer[l - 1]) continue;
+    zt = reinterpret_cast<uint32_t*>(ws + lay.zbits_t);
+    if ((e = launch_transpose_bits(zbits, z_stride, zt, lay.z_stride, lay.woff[l - 1], cfg.dims[l], cfg.dims[l - 1], k,
+                                   active, s)) != hipSuccess)
+      return DW_ERR_HIP;
+  }
+
   // forward with R-forward
   for (int l = 1; l <= L; ++l) {
     GemmArgs a{};
@@ -193,6 +205,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.Y = weights(l); a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0;
     a.ldy = cfg.dims[l - 1];
     a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1];
+    a.zbits_t = lay.zt_layer[l - 1] ? zt : nullptr; a.zt_stride = lay.z_stride;
     a.M = B; a.N = cfg.dims[l - 1]; a.K = cfg.dims[l];
     a.C = ws + lay.delta[l - 1]; a.RC = ws + lay.rdelta[l - 1]; a.ldc = cfg.dims[l - 1];
     a.c_wstride = act_stride(l - 1);

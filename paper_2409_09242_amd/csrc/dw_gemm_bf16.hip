@@ -618,6 +618,7 @@ int gemm_bf16_wgrad_tiles(int n_out, int n_in) { return ((n_out + 127) / 128) * 
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : a.epi == EPI_MASK ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);
   if (gemm_bf16_dma_ok(a)) return launch_gemm_bf16_dma(a, s);
+  if (gemm_bf16_out_ok(a)) return launch_gemm_bf16_out(a, s);
   if (a.N <= 32) return b16::launch_shape<256, 32, 8, 1>(a, s);
   if (a.M <= 32) return b16::launch_shape<32, 256, 1, 8>(a, s);
   const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 255) / 256) * a.k;

@@ -173,6 +173,8 @@ int gemm_bf16_wgrad_tiles(int n_out, int n_in);
 bool gemm_bf16_dgrad_dma_shape_ok(int batch, int n_out, int n_in, int k, int64_t woff);
 bool gemm_bf16_dma_ok(const GemmArgs& a);                        // large-tile forward path usable for this product?
 hipError_t launch_gemm_bf16_dma(const GemmArgs& a, hipStream_t s);
+bool gemm_bf16_out_ok(const GemmArgs& a);                        // output-layer forward kernel usable for this product?
+hipError_t launch_gemm_bf16_out(const GemmArgs& a, hipStream_t s);
 
 struct HeadArgs {                     // softmax cross-entropy on the output layer and its R-derivative
   const float* s; const float* Rs;    // [k][B][ld] logits and their directional derivative

@@ -323,11 +323,12 @@ def hutchinson_diagonal(zs, hzs) -> np.ndarray:
     return (zs * hzs).sum(axis=0) / zs.shape[0]
 
 
-def adahessian_update(theta, m, v, g, hz, z, t, *, lr, beta1, beta2, eps, hpow, dims=None, avg_block=1):
+def adahessian_update(theta, m, v, g, hz, z, t, *, lr, beta1, beta2, eps, hpow, dims=None, avg_block=1, average=None):
     """One AdaHessian update of (theta, m, v); returns new arrays.  t is the 1-based step count.
-    hz, z: one probe ([P]) or n probes ([n, P]) of the same minibatch."""
+    hz, z: one probe ([P]) or n probes ([n, P]) of the same minibatch.
+    average: the spatial averaging of another model family (a function of D); default: the MLP's blocks."""
     D = hutchinson_diagonal(z, hz)                         # Hutchinson diagonal estimate (n = 1 in the experiments)
-    Ds = spatial_average(D, dims, avg_block)
+    Ds = average(D) if average is not None else spatial_average(D, dims, avg_block)
     m_new = beta1 * m + (1.0 - beta1) * g
     v_new = beta2 * v + (1.0 - beta2) * Ds * Ds
     m_hat = m_new / (1.0 - beta1 ** t)

@@ -22,7 +22,8 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls on one handle must be
  *     issued from one host thread at a time and on one stream.
  *   - Canonical parameter layout (index space of theta, m, v, g, Hz and of the Rademacher vector z):
- *     for l = 1..L the weight W_l row-major [d_l][d_{l-1}] followed by the bias b_l[d_l], no padding.
+ *     for l = 1..L the weight W_l row-major [d_l][d_{l-1}] followed by the bias b_l[d_l], no padding
+ *     (with a convolutional front end its kernels and biases come first, see dw_config.n_conv).
  *   - Rademacher bits: element j of z is +1 when bit (j mod 32) of 32-bit word floor(j/32) is set, else -1.
  */
 #ifndef DW_H_
@@ -40,6 +41,7 @@ extern "C" {
 #define DW_MAX_P 8           /* length p of the raw-score history weights c_j    */
 #define DW_MAX_CLASSES 16    /* width d_L of the output layer                    */
 #define DW_MAX_SAMPLES 8     /* Rademacher probes per step                       */
+#define DW_MAX_CONV 2        /* 3x3 convolutions in front of the linear layers   */
 
 typedef enum {
   DW_OK = 0,
@@ -108,6 +110,19 @@ typedef struct {
                                           that produces its gradient; the W-parts of g and Hz of such layers are
                                           then never written (reading them returns stale values).  Same
                                           arithmetic either way.                                              */
+  /* Convolutional front end (Section VI trains a small CNN): n_conv 3x3 convolutions, stride 1, no padding, each
+   * followed by ReLU, one 2x2 max-pool after the last, then the flattened map (row, column, channel) feeds the
+   * linear layers, so dims[0] must equal (H_out/2)*(W_out/2)*conv_c[n_conv-1].  Needs DW_F32, avg_block = 1,
+   * n_samples <= 1, fuse_update = 0.  The minibatch x is then [k][B][img_h][img_w][img_c] floats (channels last).
+   * Parameters of convolution j come first in the canonical layout: W_j [C_j][K_j] with K_j = 9*C_{j-1} rounded up
+   * to a multiple of 4, entry ci*9 + dy*3 + dx of a row being tap (dy, dx) on input channel ci, the last
+   * K_j - 9*C_{j-1} entries of a row padding (they must be 0 in theta_0 and then stay 0); then b_j [C_j]. */
+  int32_t n_conv;                   /* 0 (none) .. DW_MAX_CONV                                              */
+  int32_t img_h, img_w, img_c;      /* input image                                                          */
+  int32_t conv_c[DW_MAX_CONV];      /* output channels C_j, multiples of 4                                  */
+  int32_t conv_avg;                 /* 1: D = z*Hz of a convolution kernel is replaced by its mean over the
+                                       3x3 window of each (output, input) channel pair (Section IV-B); biases
+                                       and linear layers are not averaged                                    */
 } dw_config;
 
 /* Human-readable text for a status code (never NULL). */

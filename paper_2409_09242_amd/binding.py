@@ -15,7 +15,7 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libdw.so")
 
-DW_MAX_LAYERS, DW_MAX_K, DW_MAX_P, DW_MAX_CLASSES = 8, 64, 8, 16
+DW_MAX_LAYERS, DW_MAX_K, DW_MAX_P, DW_MAX_CLASSES, DW_MAX_CONV = 8, 64, 8, 16, 2
 DW_F32, DW_BF16 = 0, 1
 DW_FIXED, DW_MANUAL, DW_DYNAMIC = 0, 1, 2
 DW_SEQUENTIAL = 16      # OR-ed into the mode of elastic_sync: exchanges one after the other, in index order
@@ -37,6 +37,8 @@ class dw_config(C.Structure):
         ("hpow", C.c_float), ("avg_block", C.c_int32),
         ("alpha", C.c_float), ("kappa", C.c_float), ("p", C.c_int32), ("c", C.c_float * DW_MAX_P),
         ("seed", C.c_uint64), ("n_samples", C.c_int32), ("fuse_update", C.c_int32),
+        ("n_conv", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32), ("img_c", C.c_int32),
+        ("conv_c", C.c_int32 * DW_MAX_CONV), ("conv_avg", C.c_int32),
     ]
 
 
@@ -86,7 +88,8 @@ def lib() -> C.CDLL:
 def make_config(*, dims: Optional[Sequence[int]], k: int, batch: int = 0, bf16: bool = False, n_params: int = 0,
                 lr=0.01, beta1=0.9, beta2=0.999, eps=1e-4, hpow=1.0, avg_block=1, alpha=0.1, kappa=-0.1,
                 c: Sequence[float] = (0.4, 0.3, 0.2, 0.1), seed: int = 0, fuse_update: int = 0,
-                n_samples: int = 1) -> dw_config:
+                n_samples: int = 1, img: Optional[Sequence[int]] = None, conv: Sequence[int] = (),
+                conv_avg: int = 0) -> dw_config:
     cfg = dw_config()
     if dims is None:
         cfg.n_layers = 0
@@ -104,6 +107,12 @@ def make_config(*, dims: Optional[Sequence[int]], k: int, batch: int = 0, bf16: 
     cfg.seed = seed
     cfg.fuse_update = fuse_update
     cfg.n_samples = n_samples
+    cfg.n_conv = len(conv)
+    if conv:
+        cfg.img_h, cfg.img_w, cfg.img_c = img
+        for j, cj in enumerate(conv):
+            cfg.conv_c[j] = cj
+    cfg.conv_avg = conv_avg
     return cfg
 
 
@@ -113,6 +122,28 @@ def config_from_workload(w, **overrides) -> dw_config:
               alpha=w.alpha, kappa=w.kappa, c=w.c, seed=w.seed)
     kw.update(overrides)
     return make_config(**kw)
+
+
+def conv_param_index(img: Sequence[int], conv: Sequence[int], fc: Sequence[int]):
+    """Where the parameters of a convolutional model sit in the library's layout.
+
+    Returns (idx, P_lib): idx[j] is the library position of parameter j of the unpadded layout (kernels
+    [C_out][C_in][3][3] and biases of the convolutions, then W_l, b_l of the linear layers); the library rows of a
+    kernel are padded to a multiple of 4 entries, which adds zeros that never change (see dw_config.n_conv)."""
+    h, w, c_in = img
+    idx, pos = [], 0
+    for co in conv:
+        K = (9 * c_in + 3) // 4 * 4
+        rows = pos + np.arange(co)[:, None] * K + np.arange(9 * c_in)[None, :]
+        idx.append(rows.reshape(-1)); pos += co * K
+        idx.append(pos + np.arange(co)); pos += co
+        h, w, c_in = h - 2, w - 2, co
+    d_in = (h // 2) * (w // 2) * c_in
+    for d in fc:
+        n = d * d_in + d
+        idx.append(pos + np.arange(n)); pos += n
+        d_in = d
+    return np.concatenate(idx).astype(np.int64), pos
 
 
 def param_count(cfg: dw_config) -> int:

@@ -40,6 +40,7 @@ int validate(const dw_config* c, Layout* lay) {
   const int align = c->dtype == DW_BF16 ? 8 : 4;
   int64_t P = 0;
   if (L == 0) {
+    if (c->n_conv != 0) return DW_ERR_CONFIG;
     if (c->n_params < 4 || c->n_params % 4 != 0) return DW_ERR_CONFIG;
     P = c->n_params;
   } else {
@@ -49,6 +50,29 @@ int validate(const dw_config* c, Layout* lay) {
     for (int l = 0; l < L; ++l)
       if (c->dims[l] % align != 0) return DW_ERR_CONFIG;
     if (c->dims[L] > DW_MAX_CLASSES) return DW_ERR_CONFIG;
+    const int nc = c->n_conv;
+    if (nc < 0 || nc > DW_MAX_CONV) return DW_ERR_CONFIG;
+    lay->n_conv = nc;
+    if (nc > 0) {
+      // convolutional front end: fp32, one probe, no fusion; maps shrink by 2 per convolution, the last is pooled 2x2
+      if (c->dtype != DW_F32 || c->fuse_update != 0 || c->n_samples > 1) return DW_ERR_CONFIG;
+      if (c->conv_avg != 0 && c->conv_avg != 1) return DW_ERR_CONFIG;
+      if (c->img_h < 3 || c->img_w < 3 || c->img_c < 1 || c->img_h > 4096 || c->img_w > 4096 || c->img_c > 1024)
+        return DW_ERR_CONFIG;
+      lay->cH[0] = c->img_h; lay->cW[0] = c->img_w; lay->cC[0] = c->img_c;
+      for (int j = 0; j < nc; ++j) {
+        const int co = c->conv_c[j];
+        if (co < 4 || co % 4 != 0 || co > 1024) return DW_ERR_CONFIG;
+        lay->cH[j + 1] = lay->cH[j] - 2; lay->cW[j + 1] = lay->cW[j] - 2; lay->cC[j + 1] = co;
+        if (lay->cH[j + 1] < 1 || lay->cW[j + 1] < 1) return DW_ERR_CONFIG;
+        if ((int64_t)c->batch * lay->cH[j + 1] * lay->cW[j + 1] > (int64_t)1 << 30) return DW_ERR_CONFIG;
+        lay->cK[j] = (int)round_up(9 * lay->cC[j], 4);
+        lay->cwoff[j] = P; P += (int64_t)co * lay->cK[j];
+        lay->cboff[j] = P; P += co;
+      }
+      if (lay->cH[nc] % 2 != 0 || lay->cW[nc] % 2 != 0) return DW_ERR_CONFIG;
+      if ((int64_t)c->dims[0] != (int64_t)(lay->cH[nc] / 2) * (lay->cW[nc] / 2) * lay->cC[nc]) return DW_ERR_CONFIG;
+    }
     for (int l = 1; l <= L; ++l) {
       lay->woff[l - 1] = P;
       P += (int64_t)c->dims[l] * c->dims[l - 1];
@@ -62,6 +86,7 @@ int validate(const dw_config* c, Layout* lay) {
       !(c->eps > 0.f) || !(c->hpow >= 0.f && c->hpow <= 2.f))
     return DW_ERR_HYPER;
   if (!is_pow2(c->avg_block) || c->avg_block > 256) return DW_ERR_HYPER;
+  if (c->n_layers > 0 && c->n_conv > 0 && c->avg_block != 1) return DW_ERR_HYPER;   // linear layers are not averaged there
   if (L == 0) {
     if (P % c->avg_block != 0) return DW_ERR_HYPER;
   } else {
@@ -116,6 +141,19 @@ int validate(const dw_config* c, Layout* lay) {
     const size_t head = (size_t)k * B * DW_MAX_CLASSES * sizeof(float);
     lay->sL = take(head); lay->rsL = take(head); lay->dL = take(head); lay->rdL = take(head);
     if (c->dtype == DW_BF16) { lay->dL16 = take(head / 2); lay->rdL16 = take(head / 2); }
+  }
+  if (L > 0 && lay->n_conv > 0) {
+    const int64_t B = c->batch;
+    for (int j = 0; j < lay->n_conv; ++j) {
+      const size_t M = (size_t)B * lay->cH[j + 1] * lay->cW[j + 1];
+      lay->cP[j] = take((size_t)k * M * lay->cK[j] * 4);
+      if (j > 0) lay->cRP[j] = take((size_t)k * M * lay->cK[j] * 4);
+      const size_t out = (size_t)k * M * lay->cC[j + 1] * 4;
+      lay->cA[j] = take(out); lay->cRA[j] = take(out); lay->cD[j] = take(out); lay->cRD[j] = take(out);
+    }
+    const size_t flat = (size_t)k * B * c->dims[0];
+    lay->pool = take(flat * 4); lay->rpool = take(flat * 4); lay->dpool = take(flat * 4); lay->rdpool = take(flat * 4);
+    lay->pidx = take(flat);
   }
   lay->partials = take((size_t)k * lay->n_upd_blocks * sizeof(double));
   // layers whose weight-gradient kernel applies the update itself: one partial-sum slot per output tile
@@ -291,8 +329,15 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
   // of the centre per worker, so they skip it on steps after which, going by the period of the latest
   // dw_elastic_sync call, no round is due; should a round come anyway, it measures the distances itself.
   const bool dist = !fused || h->last_tau <= 1 || (h->calls + 1) % h->last_tau == 0;
-  st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fu, dist, s);
-  if (st != DW_OK) return st;
+  if (h->lay.n_conv > 0) {
+    st = run_network_cnn(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, s);
+    if (st != DW_OK) return st;
+    if (h->cfg.conv_avg)
+      DW_HIP(launch_conv_window_mean(h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->lay, h->cfg.k, active, s));
+  } else {
+    st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fu, dist, s);
+    if (st != DW_OK) return st;
+  }
   DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
   h->norms_valid = dist;
   h->calls += 1;
@@ -443,6 +488,7 @@ int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint
                    const uint8_t* h_active, void* stream) {
   if (!h || !d_g || !d_hz) return DW_ERR_NULL;
   if (h->lay.P % 4 != 0) return DW_ERR_MODE;          // worker i sits at offset i*P: needs 16-byte rows
+  if (h->lay.n_conv > 0 && h->cfg.conv_avg) return DW_ERR_MODE;   // the window mean needs a writable Hz
   ProfilerGuard pg(h);
   if ((reinterpret_cast<uintptr_t>(d_g) & 15u) || (reinterpret_cast<uintptr_t>(d_hz) & 15u) ||
       (reinterpret_cast<uintptr_t>(d_zbits) & 7u))

@@ -1,0 +1,256 @@
+// Convolutional front end of the classifier (the paper's experiments use a small CNN, Section VI) and its
+// directional derivative along z, in fp32.
+//
+// A 3x3 convolution (stride 1, no padding) over a channels-last map is a linear layer applied to every 3x3 patch,
+// so it runs on the dual GEMM of the linear layers: the patches of a map [B][H][W][C] become a matrix
+// [B*(H-2)*(W-2)][K], K = 9*C rounded up to 4, column ci*9 + dy*3 + dx holding input (y+dy, x+dx, ci), and
+//   forward      S  = P W^T + b,          RS  = RP W^T + P V^T + c         (P patches, V = z reshaped like W)
+//   weight grad  gW = D^T P,              HzW = RD^T P + D^T RP
+//   data grad    dP = D W,                RdP = RD W + D V,   then summed back onto the map ("col2im")
+// are the three products of Section IV-B's Hessian-vector product with B*(H-2)*(W-2) rows instead of B.  ReLU and
+// max-pool pass the directional derivative through their selections (their curvature is zero almost everywhere).
+// This file holds the data movement around those products (patch extraction, its adjoint, pooling and its
+// adjoint, the 3x3 window mean of the Hutchinson estimate) and the order of the launches.
+#include "dw_internal.h"
+
+namespace dw {
+
+namespace {
+
+// patches of value map `in` and, when given, of its R-companion `rin`: one thread per patch entry
+__global__ __launch_bounds__(256) void im2col3x3_kernel(const float* in, const float* rin, float* P, float* RP, int B, int H,
+                                                        int W, int C, int K, uint64_t active_mask) {
+  const int worker = blockIdx.y;
+  if (!((active_mask >> worker) & 1ull)) return;
+  const int Ho = H - 2, Wo = W - 2;
+  const int64_t rows = (int64_t)B * Ho * Wo, total = rows * K;
+  const int64_t in_w = (int64_t)B * H * W * C;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int64_t m = e / K;
+    const int kk = (int)(e - m * K);
+    float v = 0.f, rv = 0.f;
+    if (kk < 9 * C) {
+      const int ci = kk / 9, tap = kk - ci * 9, dy = tap / 3, dx = tap - dy * 3;
+      const int x = (int)(m % Wo), y = (int)((m / Wo) % Ho);
+      const int64_t b = m / ((int64_t)Wo * Ho);
+      const int64_t src = ((b * H + (y + dy)) * W + (x + dx)) * C + ci;
+      v = in[worker * in_w + src];
+      if (rin) rv = rin[worker * in_w + src];
+    }
+    P[worker * total + e] = v;
+    if (RP) RP[worker * total + e] = rv;
+  }
+}
+
+// adjoint of the patch extraction, followed by the ReLU mask of the map the patches were cut from: one thread per
+// map entry, summing the (up to nine) patch entries that were copied from it
+__global__ __launch_bounds__(256) void col2im3x3_kernel(const float* dP, const float* RdP, const float* act, float* D,
+                                                        float* RD, int B, int H, int W, int C, int K, uint64_t active_mask) {
+  const int worker = blockIdx.y;
+  if (!((active_mask >> worker) & 1ull)) return;
+  const int Ho = H - 2, Wo = W - 2;
+  const int64_t total = (int64_t)B * H * W * C, p_w = (int64_t)B * Ho * Wo * K;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int ci = (int)(e % C);
+    const int x = (int)((e / C) % W), y = (int)((e / ((int64_t)C * W)) % H);
+    const int64_t b = e / ((int64_t)C * W * H);
+    float s = 0.f, rs = 0.f;
+    if (act[worker * total + e] > 0.f) {
+      for (int dy = 0; dy < 3; ++dy) {
+        const int oy = y - dy;
+        if (oy < 0 || oy >= Ho) continue;
+        for (int dx = 0; dx < 3; ++dx) {
+          const int ox = x - dx;
+          if (ox < 0 || ox >= Wo) continue;
+          const int64_t src = ((b * Ho + oy) * Wo + ox) * K + ci * 9 + dy * 3 + dx;
+          s += dP[worker * p_w + src];
+          rs += RdP[worker * p_w + src];
+        }
+      }
+    }
+    D[worker * total + e] = s;
+    RD[worker * total + e] = rs;
+  }
+}
+
+// 2x2 max-pool of a map and the same selection applied to its R-companion; which[...] = 0..3 in the order
+// (0,0), (0,1), (1,0), (1,1), the first one on ties
+__global__ __launch_bounds__(256) void maxpool2_kernel(const float* A, const float* RA, float* Pm, float* RPm,
+                                                       uint8_t* which, int B, int H, int W, int C, uint64_t active_mask) {
+  const int worker = blockIdx.y;
+  if (!((active_mask >> worker) & 1ull)) return;
+  const int Hp = H / 2, Wp = W / 2;
+  const int64_t total = (int64_t)B * Hp * Wp * C, a_w = (int64_t)B * H * W * C;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int c = (int)(e % C);
+    const int j = (int)((e / C) % Wp), i = (int)((e / ((int64_t)C * Wp)) % Hp);
+    const int64_t b = e / ((int64_t)C * Wp * Hp);
+    float best = 0.f, rbest = 0.f;
+    int sel = 0;
+    for (int q = 0; q < 4; ++q) {
+      const int64_t src = ((b * H + (2 * i + (q >> 1))) * W + (2 * j + (q & 1))) * C + c;
+      const float v = A[worker * a_w + src];
+      if (q == 0 || v > best) { best = v; rbest = RA[worker * a_w + src]; sel = q; }
+    }
+    Pm[worker * total + e] = best;
+    RPm[worker * total + e] = rbest;
+    which[worker * total + e] = (uint8_t)sel;
+  }
+}
+
+// adjoint of the pooling: the gradient of a pooled entry goes to the input that was selected, zero to the others
+__global__ __launch_bounds__(256) void unpool2_kernel(const float* dPm, const float* RdPm, const uint8_t* which, float* D,
+                                                      float* RD, int B, int H, int W, int C, uint64_t active_mask) {
+  const int worker = blockIdx.y;
+  if (!((active_mask >> worker) & 1ull)) return;
+  const int Hp = H / 2, Wp = W / 2;
+  const int64_t total = (int64_t)B * H * W * C, p_w = (int64_t)B * Hp * Wp * C;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int c = (int)(e % C);
+    const int x = (int)((e / C) % W), y = (int)((e / ((int64_t)C * W)) % H);
+    const int64_t b = e / ((int64_t)C * W * H);
+    const int64_t src = ((b * Hp + (y >> 1)) * Wp + (x >> 1)) * C + c;
+    const bool mine = which[worker * p_w + src] == (uint8_t)((y & 1) * 2 + (x & 1));
+    D[worker * total + e] = mine ? dPm[worker * p_w + src] : 0.f;
+    RD[worker * total + e] = mine ? RdPm[worker * p_w + src] : 0.f;
+  }
+}
+
+// Section IV-B averaging for a convolution kernel: D = z * Hz is replaced by its mean over the 3x3 window of every
+// (output, input) channel pair.  The update multiplies hz by z again, so the window mean is stored times z.
+__global__ __launch_bounds__(256) void conv_window_mean_kernel(float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride,
+                                                               int64_t woff, int C_out, int C_in, int K, uint64_t active_mask) {
+  const int worker = blockIdx.y;
+  if (!((active_mask >> worker) & 1ull)) return;
+  const int pair = blockIdx.x * 256 + threadIdx.x;
+  if (pair >= C_out * C_in) return;
+  const int co = pair / C_in, ci = pair - co * C_in;
+  const int64_t j0 = woff + (int64_t)co * K + ci * 9;
+  float* h = hz + worker * Pp;
+  const uint32_t* zb = zbits + worker * z_stride;
+  float sign[9], s = 0.f;
+#pragma unroll
+  for (int t = 0; t < 9; ++t) {
+    const int64_t j = j0 + t;
+    sign[t] = ((zb[j >> 5] >> (j & 31)) & 1u) ? 1.f : -1.f;
+    s += sign[t] * h[j];
+  }
+  s *= 1.0f / 9.0f;
+#pragma unroll
+  for (int t = 0; t < 9; ++t) h[j0 + t] = sign[t] * s;
+}
+
+inline unsigned blocks_for(int64_t n) {
+  const int64_t b = (n + 255) / 256;
+  return (unsigned)(b < 1 ? 1 : b > 16384 ? 16384 : b);
+}
+
+}  // namespace
+
+hipError_t launch_conv_window_mean(float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride, const Layout& lay,
+                                   int k, uint64_t active, hipStream_t s) {
+  KernelScope ks(KC_UPDATE, s);
+  for (int j = 0; j < lay.n_conv; ++j) {
+    const int pairs = lay.cC[j + 1] * lay.cC[j];
+    hipLaunchKernelGGL(conv_window_mean_kernel, dim3((unsigned)((pairs + 255) / 256), (unsigned)k), dim3(256), 0, s, hz,
+                       zbits, Pp, z_stride, lay.cwoff[j], lay.cC[j + 1], lay.cC[j], lay.cK[j], active);
+  }
+  return hipGetLastError();
+}
+
+int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
+                    const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s) {
+  const int nc = lay.n_conv, k = cfg.k, B = cfg.batch;
+  float* theta = reinterpret_cast<float*>(ws + lay.theta);
+  float* g = reinterpret_cast<float*>(ws + lay.g);
+  float* hz = reinterpret_cast<float*>(ws + lay.hz);
+  auto f = [&](size_t off) { return reinterpret_cast<float*>(ws + off); };
+  auto rows = [&](int j) { return (int64_t)B * lay.cH[j + 1] * lay.cW[j + 1]; };   // patches / output positions of convolution j
+  hipError_t e;
+
+  // forward through the convolutions
+  for (int j = 0; j < nc; ++j) {
+    const float* in = j == 0 ? reinterpret_cast<const float*>(d_x) : f(lay.cA[j - 1]);
+    const float* rin = j == 0 ? nullptr : f(lay.cRA[j - 1]);
+    const int64_t M = rows(j);
+    {
+      KernelScope ks(KC_GEMM_FWD, s);
+      hipLaunchKernelGGL(im2col3x3_kernel, dim3(blocks_for(M * lay.cK[j]), (unsigned)k), dim3(256), 0, s, in, rin,
+                         f(lay.cP[j]), j == 0 ? nullptr : f(lay.cRP[j]), B, lay.cH[j], lay.cW[j], lay.cC[j], lay.cK[j],
+                         active);
+      if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
+    }
+    GemmArgs a{};
+    a.X = f(lay.cP[j]); a.RX = j == 0 ? nullptr : f(lay.cRP[j]); a.x_wstride = M * lay.cK[j]; a.x_kcontig = 1;
+    a.ldx = lay.cK[j];
+    a.Y = theta + lay.cwoff[j]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 1; a.ldy = lay.cK[j];
+    a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.cwoff[j]; a.zb_off = lay.cboff[j];
+    a.M = (int)M; a.N = lay.cC[j + 1]; a.K = lay.cK[j];
+    a.bias = theta + lay.cboff[j]; a.bias_wstride = lay.Pp;
+    a.C = f(lay.cA[j]); a.RC = f(lay.cRA[j]); a.ldc = lay.cC[j + 1]; a.c_wstride = M * lay.cC[j + 1];
+    a.epi = EPI_RELU; a.k = k; a.active_mask = active;
+    if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+  }
+  // pooling
+  {
+    KernelScope ks(KC_GEMM_FWD, s);
+    const int64_t total = (int64_t)B * cfg.dims[0];
+    hipLaunchKernelGGL(maxpool2_kernel, dim3(blocks_for(total), (unsigned)k), dim3(256), 0, s, f(lay.cA[nc - 1]),
+                       f(lay.cRA[nc - 1]), f(lay.pool), f(lay.rpool), reinterpret_cast<uint8_t*>(ws + lay.pidx), B,
+                       lay.cH[nc], lay.cW[nc], lay.cC[nc], active);
+    if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
+  }
+  // the linear layers, forward and backward, down to the gradient with respect to the pooled map
+  const int st = run_network(cfg, ws, lay, f(lay.pool), d_y, zbits, z_stride, active, d_loss, nullptr, true, s,
+                             f(lay.rpool), f(lay.dpool), f(lay.rdpool));
+  if (st != DW_OK) return st;
+  // back through the pooling (the ReLU of the last convolution is already in the mask of that gradient: a pooled
+  // entry is positive exactly when the input it selected is)
+  {
+    KernelScope ks(KC_GEMM_DGRAD, s);
+    const int64_t total = rows(nc - 1) * lay.cC[nc];
+    hipLaunchKernelGGL(unpool2_kernel, dim3(blocks_for(total), (unsigned)k), dim3(256), 0, s, f(lay.dpool), f(lay.rdpool),
+                       reinterpret_cast<const uint8_t*>(ws + lay.pidx), f(lay.cD[nc - 1]), f(lay.cRD[nc - 1]), B,
+                       lay.cH[nc], lay.cW[nc], lay.cC[nc], active);
+    if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
+  }
+  // back through the convolutions: weight gradient first (it reads the patches), then the data gradient into the
+  // patch buffers and from there onto the map below
+  for (int j = nc - 1; j >= 0; --j) {
+    const int64_t M = rows(j);
+    {
+      GemmArgs a{};
+      a.X = f(lay.cD[j]); a.RX = f(lay.cRD[j]); a.x_wstride = M * lay.cC[j + 1]; a.x_kcontig = 0; a.ldx = lay.cC[j + 1];
+      a.Y = f(lay.cP[j]); a.RY = j == 0 ? nullptr : f(lay.cRP[j]); a.ry_bits = 0; a.y_wstride = M * lay.cK[j];
+      a.y_kcontig = 0; a.ldy = lay.cK[j];
+      a.zbits = zbits; a.z_stride = z_stride;
+      a.M = lay.cC[j + 1]; a.N = lay.cK[j]; a.K = (int)M;
+      a.C = g + lay.cwoff[j]; a.RC = hz + lay.cwoff[j]; a.ldc = lay.cK[j]; a.c_wstride = lay.Pp;
+      a.gb = g + lay.cboff[j]; a.hzb = hz + lay.cboff[j];
+      a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
+      if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+    }
+    if (j == 0) break;
+    {
+      GemmArgs a{};
+      a.X = f(lay.cD[j]); a.RX = f(lay.cRD[j]); a.x_wstride = M * lay.cC[j + 1]; a.x_kcontig = 1; a.ldx = lay.cC[j + 1];
+      a.Y = theta + lay.cwoff[j]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0; a.ldy = lay.cK[j];
+      a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.cwoff[j];
+      a.M = (int)M; a.N = lay.cK[j]; a.K = lay.cC[j + 1];
+      a.C = f(lay.cP[j]); a.RC = f(lay.cRP[j]); a.ldc = lay.cK[j]; a.c_wstride = M * lay.cK[j];
+      a.epi = EPI_PLAIN; a.k = k; a.active_mask = active;
+      if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
+    }
+    {
+      KernelScope ks(KC_GEMM_DGRAD, s);
+      const int64_t total = (int64_t)B * lay.cH[j] * lay.cW[j] * lay.cC[j];
+      hipLaunchKernelGGL(col2im3x3_kernel, dim3(blocks_for(total), (unsigned)k), dim3(256), 0, s, f(lay.cP[j]),
+                         f(lay.cRP[j]), f(lay.cA[j - 1]), f(lay.cD[j - 1]), f(lay.cRD[j - 1]), B, lay.cH[j], lay.cW[j],
+                         lay.cC[j], lay.cK[j], active);
+      if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
+    }
+  }
+  return DW_OK;
+}
+
+}  // namespace dw

@@ -258,6 +258,8 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
     if (rx) DW_LAUNCH(true, true, true, RY_BITS, EPI_LINEAR); else DW_LAUNCH(true, true, false, RY_BITS, EPI_LINEAR);
   } else if (a.epi == EPI_MASK) {              // data gradient
     DW_LAUNCH(true, false, true, RY_BITS, EPI_MASK);
+  } else if (a.epi == EPI_PLAIN) {             // data gradient stored unmasked (the mask follows a col2im)
+    DW_LAUNCH(true, false, true, RY_BITS, EPI_PLAIN);
   } else {                                     // weight gradient
     if (a.RY) DW_LAUNCH(false, false, true, RY_MEM, EPI_WGRAD); else DW_LAUNCH(false, false, true, RY_NONE, EPI_WGRAD);
   }
@@ -266,7 +268,7 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
-  KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : a.epi == EPI_MASK ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);
+  KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : (a.epi == EPI_MASK || a.epi == EPI_PLAIN) ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);
   if (a.N <= 32) return launch_shape<128, 32, 4, 1>(a, s);
   if (a.M <= 32) return launch_shape<32, 128, 1, 4>(a, s);
   const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.k;

@@ -126,7 +126,7 @@ struct FuseArgs {
 };
 
 enum GemmKind { GEMM_FWD = 0, GEMM_DGRAD = 1, GEMM_WGRAD = 2 };
-enum Epilogue { EPI_RELU = 0, EPI_LINEAR = 1, EPI_MASK = 2, EPI_WGRAD = 3 };
+enum Epilogue { EPI_RELU = 0, EPI_LINEAR = 1, EPI_MASK = 2, EPI_WGRAD = 3, EPI_PLAIN = 4 };   // PLAIN: a data gradient stored as it is
 
 // One "dual-number" GEMM: C = X*Y and RC = RX*Y + X*RY for all workers (grid y = worker).
 // Element strides describe how the logical operands X[M][K], Y[K][N] sit in memory.
@@ -200,6 +200,15 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
   int n_fuse_slots = 0;
   size_t partials_f = 0;              // [k][n_fuse_slots] doubles
+  // convolutional front end (index j = convolution j+1): geometry, parameter offsets, per-stage buffers
+  int n_conv = 0;
+  int cH[DW_MAX_CONV + 1] = {0}, cW[DW_MAX_CONV + 1] = {0}, cC[DW_MAX_CONV + 1] = {0};   // maps: input, then each output
+  int cK[DW_MAX_CONV] = {0};                                    // padded row length of W_j: 9*C_in rounded up to 4
+  int64_t cwoff[DW_MAX_CONV] = {0}, cboff[DW_MAX_CONV] = {0};
+  size_t cP[DW_MAX_CONV] = {0}, cRP[DW_MAX_CONV] = {0};         // patches [k][M_j][K_j] and their R-companions
+  size_t cA[DW_MAX_CONV] = {0}, cRA[DW_MAX_CONV] = {0};         // outputs a_j, Ra_j [k][M_j][C_j]
+  size_t cD[DW_MAX_CONV] = {0}, cRD[DW_MAX_CONV] = {0};         // their gradients
+  size_t pool = 0, rpool = 0, dpool = 0, rdpool = 0, pidx = 0;  // pooled map [k][B][d_0] (+R, gradients), selection bytes
   size_t partials = 0, u_ring = 0, score = 0, omh1 = 0, h2 = 0, loss = 0;
   size_t total = 0;
 };
@@ -211,7 +220,19 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
 // weight gradients (a fused weight gradient overwrites the W_l its layer's data gradient reads).
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
-                bool fuse_dist, hipStream_t s);
+                bool fuse_dist, hipStream_t s, const void* in_ract = nullptr, void* d_in = nullptr,
+                void* rd_in = nullptr);
+// `in_ract` above: directional derivative of the input (nullptr: the input does not depend on the parameters).
+// `d_in`, `rd_in`: when given, the gradient with respect to the input and its R-companion ([k][B][d_0], zero where
+// the input is not positive: the input is then the ReLU output of a layer in front).
+//
+// The same for a model with a convolutional front end: convolutions, pooling, then run_network on the pooled map,
+// then back through the pooling and the convolutions (fp32 only).
+int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
+                    const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s);
+// hz <- z * (mean over each 3x3 window of z * hz) on the kernels of the convolutions (Section IV-B averaging)
+hipError_t launch_conv_window_mean(float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride, const Layout& lay,
+                                   int k, uint64_t active, hipStream_t s);
 
 }  // namespace dw
 

@@ -98,7 +98,7 @@ hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
-                bool fuse_dist, hipStream_t s) {
+                bool fuse_dist, hipStream_t s, const void* in_ract, void* d_in, void* rd_in) {
   const bool b16 = cfg.dtype == DW_BF16;
   const int L = cfg.n_layers, k = cfg.k, B = cfg.batch;
   const int HL = DW_MAX_CLASSES;                     // row stride of the output-layer buffers
@@ -106,7 +106,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
   float* g = reinterpret_cast<float*>(ws + lay.g);
   float* hz = reinterpret_cast<float*>(ws + lay.hz);
   auto act = [&](int l) -> const void* { return l == 0 ? d_x : (const void*)(ws + lay.act[l]); };
-  auto ract = [&](int l) -> const void* { return l == 0 ? nullptr : (const void*)(ws + lay.ract[l]); };
+  auto ract = [&](int l) -> const void* { return l == 0 ? in_ract : (const void*)(ws + lay.ract[l]); };
   auto act_stride = [&](int l) -> int64_t { return (int64_t)B * cfg.dims[l]; };
   // weights as the GEMMs read them: fp32 master copy, or its bf16 rounding kept by the update and the pull
   auto weights = [&](int l) -> const void* {
@@ -197,7 +197,8 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
   };
   // The data gradients, output layer first.  A fused weight gradient overwrites W_l, which the data gradient
   // through W_l reads, so all data gradients are launched before the weight gradients.
-  for (int l = L; l >= 2; --l) {
+  // (down to the first layer only when the caller wants the gradient with respect to the input)
+  for (int l = L; l >= (d_in ? 1 : 2); --l) {
     const void* dl; const void* rdl; int ldd; int64_t dstride;
     delta_of(l, dl, rdl, ldd, dstride);
     GemmArgs a{};                                     // through W_l, masked by the ReLU of layer l-1
@@ -207,7 +208,8 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1];
     a.zbits_t = lay.zt_layer[l - 1] ? zt : nullptr; a.zt_stride = lay.z_stride;
     a.M = B; a.N = cfg.dims[l - 1]; a.K = cfg.dims[l];
-    a.C = ws + lay.delta[l - 1]; a.RC = ws + lay.rdelta[l - 1]; a.ldc = cfg.dims[l - 1];
+    a.C = l == 1 ? d_in : (void*)(ws + lay.delta[l - 1]); a.RC = l == 1 ? rd_in : (void*)(ws + lay.rdelta[l - 1]);
+    a.ldc = cfg.dims[l - 1];
     a.c_wstride = act_stride(l - 1);
     a.mask_src = act(l - 1); a.ld_mask = cfg.dims[l - 1]; a.mask_wstride = act_stride(l - 1);
     a.epi = EPI_MASK; a.k = k; a.active_mask = active;

@@ -121,3 +121,17 @@ def test_data_calls_validate_on_the_host():
     assert lib.dw_overlap_partition(10, 0, 65, 1, None, None, 0, None) == -5
     assert lib.dw_overlap_partition(10, 0, 2, 1, None, None, 0, None) == -1
     assert lib.dw_draw_batch(None, None, None, 1, None, 1, 0, None, None, None, None) == -1
+
+
+def test_convolutional_configuration_is_validated_on_the_host():
+    n = C.c_int64()
+    ok = dict(dims=(72, 16, 10), k=2, batch=4, img=(10, 10, 1), conv=(4, 8))
+    cfg = B.make_config(**ok)
+    assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == 0
+    idx, P_lib = B.conv_param_index((10, 10, 1), (4, 8), (16, 10))
+    assert n.value == P_lib == 4 * 12 + 4 + 8 * 36 + 8 + 72 * 16 + 16 + 160 + 10
+    assert idx.size == 4 * 9 + 4 + 8 * 36 + 8 + 72 * 16 + 16 + 160 + 10 and len(set(idx.tolist())) == idx.size
+    assert idx[:10].tolist() == [0, 1, 2, 3, 4, 5, 6, 7, 8, 12]        # three padding entries after nine taps
+    assert B.lib().dw_workspace_bytes(C.byref(cfg)) > 0
+    for kw in (dict(ok, dims=(64, 16, 10)), dict(ok, conv=(4, 6)), dict(ok, img=(9, 10, 1)), dict(ok, bf16=True)):
+        assert B.lib().dw_param_count(C.byref(B.make_config(**kw)), C.byref(n)) == -2

@@ -33,12 +33,7 @@ TRAFFIC_C4_FUSED_WGRAD = 8.31e9
 
 def class_flops(w):
     """Multiply-add work (flop) per all-worker step for each GEMM class."""
-    d, B, k = w.dims, w.batch, w.k
-    L = len(d) - 1
-    fwd = sum(2.0 * B * d[l] * d[l - 1] * (3 if l > 1 else 2) for l in range(1, L + 1))
-    wgrad = fwd
-    dgrad = sum(2.0 * B * d[l] * d[l - 1] * 3 for l in range(2, L + 1))
-    return {"gemm_fwd": fwd * k, "gemm_wgrad": wgrad * k, "gemm_dgrad": dgrad * k}
+    return {c: v * w.k for c, v in w.gemm_flops_by_class().items()}
 
 
 def fused_layers(w, fuse):
@@ -81,13 +76,13 @@ def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, residen
     from paper_2409_09242_amd import binding as B
     from paper_2409_09242_amd import workloads as W
 
-    theta0 = W.init_theta(w.dims, w.seed)
+    theta0 = W.init_theta_workload(w)
     x, y = W.minibatch_pool(w, n_pool, bf16_round=W.to_bf16_f32 if w.bf16 else None)
     xd = torch.from_numpy(x).cuda()
     if w.bf16:
         xd = xd.to(torch.bfloat16)
     yd = torch.from_numpy(y).cuda()
-    h = B.Handle(B.config_from_workload(w, fuse_update=1 if fuse else 0, n_samples=samples), theta0)
+    h = B.Handle(B.config_from_workload(w, fuse_update=1 if (fuse and w.bf16) else 0, n_samples=samples), theta0)
     sched = W.participation_schedule(w, (2 * steps + warmup) // w.tau + 2)
     state = {"round": 0, "step": 0}
     mode = B.DW_DYNAMIC | (B.DW_SEQUENTIAL if sequential else 0)
@@ -216,6 +211,30 @@ def cpu_baseline(w, budget_s=15.0):
     per_worker = w.flops_per_worker_step()
     k_s = int(max(1, min(w.k, budget_s * est_rate / per_worker)))
     ws = W.scaled(w, k=k_s)
+    if w.conv:
+        # the convolutional oracle has no trainer class: gradient + Hessian-vector product + update per worker
+        from oracle import dw_cnn as OC
+        from paper_2409_09242_amd import binding as B
+        spec = OC.CnnSpec(img=tuple(w.img), conv=tuple(w.conv), fc=tuple(w.dims[1:]))
+        idx, _ = B.conv_param_index(w.img, w.conv, w.dims[1:])
+        theta = W.init_theta_workload(ws).astype(np.float64)[idx]
+        x, y = W.minibatch_pool(ws, 1)
+        m, v = np.zeros_like(theta), np.zeros_like(theta)
+        z = np.where(W.rng_for(w.seed, 29).random(theta.size) < 0.5, -1.0, 1.0)
+        t0 = time.perf_counter()
+        n = 0
+        while True:
+            for i in range(k_s):
+                _, g, hz, _ = OC.grad_and_hvp(theta, x[0, i], y[0, i], spec, z)
+                theta, m, v = O.adahessian_update(theta, m, v, g, hz, z, n + 1, lr=w.lr, beta1=w.beta1, beta2=w.beta2,
+                                                  eps=w.eps, hpow=w.hpow,
+                                                  average=(lambda D: OC.spatial_average(D, spec)) if w.conv_avg else None)
+            n += 1
+            if time.perf_counter() - t0 > budget_s * 0.6 or n >= 50:
+                break
+        el = time.perf_counter() - t0
+        return {"value": k_s * n / el, "unit": "worker-steps/s", "cores": int(cores), "kind": "oracle",
+                "sample": "%d of %d workers, %d steps of %s (numpy float64, no communication round)" % (k_s, w.k, n, w.name)}
     theta0 = W.init_theta(ws.dims, ws.seed)
     x, y = W.minibatch_pool(ws, 1, bf16_round=W.to_bf16_f32 if w.bf16 else None)
     tr = O.OracleTrainer(O.OracleConfig(dims=ws.dims, k=k_s, lr=ws.lr, beta1=ws.beta1, beta2=ws.beta2, eps=ws.eps,
@@ -239,7 +258,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "cnn"])
     ap.add_argument("--samples", type=int, default=1,
                     help="Rademacher probes per step (n of the Hutchinson estimate; the network runs once per probe)")
     ap.add_argument("--sequential", action="store_true",
@@ -337,6 +356,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w.name, "k": w.k, "dims": list(w.dims), "batch": w.batch, "tau": w.tau,
+                   **({"img": list(w.img), "conv": list(w.conv), "conv_avg": w.conv_avg} if w.conv else {}),
                    "stale": w.stale, "sync": "dynamic, sequential" if args.sequential else "dynamic",
                    "fuse_update": int(bool(fused)), "hutchinson_probes": args.samples,
                    "input": "pool of minibatches" if args.resident_data is None else

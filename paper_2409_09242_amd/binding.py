@@ -120,6 +120,8 @@ def config_from_workload(w, **overrides) -> dw_config:
     kw = dict(dims=w.dims, k=w.k, batch=w.batch, bf16=w.bf16, n_params=w.n_params if w.dims is None else 0,
               lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, hpow=w.hpow, avg_block=w.avg_block,
               alpha=w.alpha, kappa=w.kappa, c=w.c, seed=w.seed)
+    if getattr(w, "conv", ()):
+        kw.update(img=w.img, conv=w.conv, conv_avg=w.conv_avg)
     kw.update(overrides)
     return make_config(**kw)
 

@@ -151,6 +151,35 @@ int validate(const dw_config* c, Layout* lay) {
       const size_t out = (size_t)k * M * lay->cC[j + 1] * 4;
       lay->cA[j] = take(out); lay->cRA[j] = take(out); lay->cD[j] = take(out); lay->cRD[j] = take(out);
     }
+    // weight gradients of the convolutions contract over all output positions of the minibatch and have few output
+    // tiles: cut the contraction so that about 1024 blocks exist, slices of at least 512 positions
+    size_t part = 0, part_b = 0;
+    for (int j = 0; j < lay->n_conv; ++j) {
+      const int64_t M = B * lay->cH[j + 1] * lay->cW[j + 1];
+      const int64_t blocks = (int64_t)((lay->cC[j + 1] + 63) / 64) * ((lay->cK[j] + 63) / 64) * k;
+      int64_t split = 1024 / blocks;
+      if (split > M / 512) split = M / 512;
+      if (split > 64) split = 64;
+      lay->cSplit[j] = (int)(split < 1 ? 1 : split);
+      if (lay->cSplit[j] > 1) {
+        const size_t need = (size_t)lay->cSplit[j] * k * 2 * lay->cC[j + 1] * lay->cK[j] * 4;
+        const size_t need_b = (size_t)lay->cSplit[j] * k * 2 * lay->cC[j + 1] * 4;
+        part = need > part ? need : part; part_b = need_b > part_b ? need_b : part_b;
+      }
+    }
+    {
+      // the first linear layer contracts over the whole pooled map with a handful of output tiles: same cut
+      const int64_t blocks = (int64_t)((B + 63) / 64) * ((c->dims[1] + 63) / 64) * k;
+      int64_t split = 1024 / blocks;
+      if (split > c->dims[0] / 512) split = c->dims[0] / 512;
+      if (split > 64) split = 64;
+      lay->fcSplit = (int)(split < 1 ? 1 : split);
+      if (lay->fcSplit > 1) {
+        const size_t need = (size_t)lay->fcSplit * k * 2 * B * c->dims[1] * 4;
+        part = need > part ? need : part;
+      }
+    }
+    if (part > 0) { lay->cPart = take(part); lay->cPartB = take(part_b > 0 ? part_b : 256); }
     const size_t flat = (size_t)k * B * c->dims[0];
     lay->pool = take(flat * 4); lay->rpool = take(flat * 4); lay->dpool = take(flat * 4); lay->rdpool = take(flat * 4);
     lay->pidx = take(flat);

@@ -228,6 +228,10 @@ int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const voi
       a.C = g + lay.cwoff[j]; a.RC = hz + lay.cwoff[j]; a.ldc = lay.cK[j]; a.c_wstride = lay.Pp;
       a.gb = g + lay.cboff[j]; a.hzb = hz + lay.cboff[j];
       a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
+      if (lay.cSplit[j] > 1) {
+        a.ksplit = lay.cSplit[j]; a.part = f(lay.cPart); a.part_stride = (int64_t)lay.cC[j + 1] * lay.cK[j];
+        a.part_b = f(lay.cPartB);
+      }
       if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
     }
     if (j == 0) break;

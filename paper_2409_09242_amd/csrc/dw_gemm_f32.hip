@@ -141,17 +141,22 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
 
   float gb_acc = 0.f, hzb_acc = 0.f;     // EPI_WGRAD: column sums of X and RX (bias gradients)
 
-  const int nkt = (a.K + BK - 1) / BK;
+  // the slice of the contraction this block covers (all of it unless the weight gradient is cut along k)
+  const bool sliced = (EPI == EPI_WGRAD || EPI == EPI_RELU || EPI == EPI_LINEAR) && a.ksplit > 1;
+  const int kchunk = sliced ? ((a.K + a.ksplit - 1) / a.ksplit + BK - 1) / BK * BK : a.K;
+  const int kbeg = sliced ? (int)blockIdx.z * kchunk : 0;
+  const int kend = sliced ? (kbeg + kchunk < a.K ? kbeg + kchunk : a.K) : a.K;
+  const int nkt = kend > kbeg ? (kend - kbeg + BK - 1) / BK : 0;
   auto fetch = [&](int kt) {
-    const int k0 = kt * BK;
-    LX::template load<X_KC>(X, a.ldx, row0, k0, a.M, a.K, xr);
-    if (HAS_RX) LX::template load<X_KC>(RX, a.ldx, row0, k0, a.M, a.K, rxr);
-    LY::template load<Y_KC>(Y, a.ldy, col0, k0, a.N, a.K, yr);
-    if (RYM == RY_MEM) LY::template load<Y_KC>(RY, a.ldy, col0, k0, a.N, a.K, ryr);
-    if (RYM == RY_BITS) LY::template load_bits<Y_KC>(zb, a.z_off, a.ldy, col0, k0, a.N, a.K, zr);
+    const int k0 = kbeg + kt * BK;
+    LX::template load<X_KC>(X, a.ldx, row0, k0, a.M, kend, xr);
+    if (HAS_RX) LX::template load<X_KC>(RX, a.ldx, row0, k0, a.M, kend, rxr);
+    LY::template load<Y_KC>(Y, a.ldy, col0, k0, a.N, kend, yr);
+    if (RYM == RY_MEM) LY::template load<Y_KC>(RY, a.ldy, col0, k0, a.N, kend, ryr);
+    if (RYM == RY_BITS) LY::template load_bits<Y_KC>(zb, a.z_off, a.ldy, col0, k0, a.N, kend, zr);
   };
 
-  fetch(0);
+  if (nkt > 0) fetch(0);
   for (int kt = 0; kt < nkt; ++kt) {
     LX::template store<X_KC>(Xs, xr);
     if (HAS_RX) LX::template store<X_KC>(RXs, rxr);
@@ -198,6 +203,10 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
   // epilogue: lane holds column n = l32 of each 32x32 tile, rows (r/4)*8 + lhalf*4 + r%4
   float* C = reinterpret_cast<float*>(a.C) + (int64_t)worker * a.c_wstride;
   float* RC = reinterpret_cast<float*>(a.RC) + (int64_t)worker * a.c_wstride;
+  if (sliced) {
+    C = a.part + (((int64_t)blockIdx.z * a.k + worker) * 2) * a.part_stride;
+    RC = C + a.part_stride;
+  }
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = col0 + wn0 + j * 32 + l32;
@@ -216,7 +225,9 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
         if (!n_ok || m >= a.M) continue;
         float c = acc[i][j][r], rc = racc[i][j][r];
         const int64_t o = (int64_t)m * a.ldc + n;
-        if (EPI == EPI_RELU) {
+        if (sliced) {                                 // raw partial products: the epilogue follows the sum of the slices
+          C[o] = c; RC[o] = rc;
+        } else if (EPI == EPI_RELU) {
           c += bias; rc += cz;
           const bool on = c > 0.f;
           C[o] = on ? c : 0.f;
@@ -239,16 +250,56 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
   if (EPI == EPI_WGRAD && tn == 0 && (int)threadIdx.x < BM) {
     const int m = row0 + threadIdx.x;
     if (m < a.M) {
-      a.gb[(int64_t)worker * a.c_wstride + m] = gb_acc;
-      a.hzb[(int64_t)worker * a.c_wstride + m] = hzb_acc;
+      if (sliced) {
+        float* pb = a.part_b + (((int64_t)blockIdx.z * a.k + worker) * 2) * a.M;
+        pb[m] = gb_acc; pb[a.M + m] = hzb_acc;
+      } else {
+        a.gb[(int64_t)worker * a.c_wstride + m] = gb_acc;
+        a.hzb[(int64_t)worker * a.c_wstride + m] = hzb_acc;
+      }
     }
+  }
+}
+
+// adds the slices of a product cut along its contraction, in slice order, and applies the epilogue the main kernel
+// left out: C, RC (M rows of ldc, columns < N) and, for a weight gradient, the bias sums gb, hzb (M)
+__global__ __launch_bounds__(256) void sum_slices_kernel(GemmArgs a) {
+  const int worker = nth_active_worker(a.active_mask, blockIdx.y);
+  const int64_t n_out = (int64_t)a.M * a.ldc;
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int n = (int)(e % a.ldc);
+  if (e < n_out && n < a.N) {
+    float c = 0.f, rc = 0.f;
+    for (int sl = 0; sl < a.ksplit; ++sl) {
+      const float* p = a.part + (((int64_t)sl * a.k + worker) * 2) * a.part_stride;
+      c += p[e]; rc += p[a.part_stride + e];
+    }
+    if (a.epi == EPI_RELU || a.epi == EPI_LINEAR) {
+      const uint32_t* zb = a.zbits + (int64_t)worker * a.z_stride;
+      const int64_t bi = a.zb_off + n;
+      c += a.bias[(int64_t)worker * a.bias_wstride + n];
+      rc += ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
+      if (a.epi == EPI_RELU && !(c > 0.f)) { c = 0.f; rc = 0.f; }
+    }
+    reinterpret_cast<float*>(a.C)[(int64_t)worker * a.c_wstride + e] = c;
+    reinterpret_cast<float*>(a.RC)[(int64_t)worker * a.c_wstride + e] = rc;
+  }
+  if (a.epi == EPI_WGRAD && e < a.M) {
+    float b = 0.f, rb = 0.f;
+    for (int sl = 0; sl < a.ksplit; ++sl) {
+      const float* p = a.part_b + (((int64_t)sl * a.k + worker) * 2) * a.M;
+      b += p[e]; rb += p[a.M + e];
+    }
+    a.gb[(int64_t)worker * a.c_wstride + e] = b;
+    a.hzb[(int64_t)worker * a.c_wstride + e] = rb;
   }
 }
 
 template <int BM, int BN, int WM, int WN>
 static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k)), block(NT);
+  const bool sliced = (a.epi == EPI_WGRAD || a.epi == EPI_RELU || a.epi == EPI_LINEAR) && a.ksplit > 1;
+  const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k), (unsigned)(sliced ? a.ksplit : 1)), block(NT);
 #define DW_LAUNCH(XKC, YKC, RX, RYM, EPI) \
   hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>), grid, block, 0, s, a)
   const bool rx = a.RX != nullptr;
@@ -264,6 +315,10 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
     if (a.RY) DW_LAUNCH(false, false, true, RY_MEM, EPI_WGRAD); else DW_LAUNCH(false, false, true, RY_NONE, EPI_WGRAD);
   }
 #undef DW_LAUNCH
+  if (sliced) {
+    const int64_t n_out = (int64_t)a.M * a.ldc;
+    hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n_out + 255) / 256), grid.y), dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 
@@ -271,6 +326,7 @@ hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
   KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : (a.epi == EPI_MASK || a.epi == EPI_PLAIN) ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);
   if (a.N <= 32) return launch_shape<128, 32, 4, 1>(a, s);
   if (a.M <= 32) return launch_shape<32, 128, 1, 4>(a, s);
+  if (a.N <= 64 && (int64_t)((a.M + 127) / 128) * a.k >= 512) return launch_shape<128, 64, 2, 2>(a, s);   // many rows, few columns
   const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.k;
   if (big_tiles >= 512) return launch_shape<128, 128, 2, 2>(a, s);
   return launch_shape<64, 64, 2, 2>(a, s);

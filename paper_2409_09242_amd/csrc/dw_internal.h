@@ -147,6 +147,11 @@ struct GemmArgs {
   int64_t zb_off;                                     // bit offset of the bias part of z
   float* gb; float* hzb;                              // EPI_WGRAD: bias-gradient outputs (g + b_off, hz + b_off)
   FuseArgs fu;                                        // EPI_WGRAD: fu.on != 0 replaces the stores of C and RC by the update
+  // fp32 forward (EPI_RELU, EPI_LINEAR) or weight gradient with a long contraction and few output tiles: the contraction is cut into ksplit slices
+  // (grid z), slice s of worker i writes its partial products to part + ((s*k + i)*2 + {0,1})*part_stride and its
+  // partial bias sums (weight gradient) to part_b + ((s*k + i)*2 + {0,1})*M; a second kernel adds the slices in order and
+  // applies the epilogue (bias, ReLU) into C, RC, gb, hzb
+  int ksplit; float* part; int64_t part_stride; float* part_b;
   int epi;
   int k;
   uint64_t active_mask;
@@ -208,6 +213,9 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t cP[DW_MAX_CONV] = {0}, cRP[DW_MAX_CONV] = {0};         // patches [k][M_j][K_j] and their R-companions
   size_t cA[DW_MAX_CONV] = {0}, cRA[DW_MAX_CONV] = {0};         // outputs a_j, Ra_j [k][M_j][C_j]
   size_t cD[DW_MAX_CONV] = {0}, cRD[DW_MAX_CONV] = {0};         // their gradients
+  int cSplit[DW_MAX_CONV] = {0};                                // slices of the weight gradient's contraction (1: none)
+  int fcSplit = 0;                                              // slices of the first linear layer's forward contraction
+  size_t cPart = 0, cPartB = 0;                                 // scratch of the sliced weight gradients
   size_t pool = 0, rpool = 0, dpool = 0, rdpool = 0, pidx = 0;  // pooled map [k][B][d_0] (+R, gradients), selection bytes
   size_t partials = 0, u_ring = 0, score = 0, omh1 = 0, h2 = 0, loss = 0;
   size_t total = 0;

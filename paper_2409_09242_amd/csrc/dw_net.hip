@@ -145,6 +145,10 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.epi = EPI_LINEAR;
     }
     a.k = k; a.active_mask = active;
+    if (l == 1 && !b16 && lay.fcSplit > 1) {           // behind a convolutional front end: long contraction, few tiles
+      a.ksplit = lay.fcSplit; a.part = reinterpret_cast<float*>(ws + lay.cPart);
+      a.part_stride = (int64_t)B * a.ldc; a.part_b = nullptr;
+    }
     if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
   }
 

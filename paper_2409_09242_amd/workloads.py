@@ -40,19 +40,42 @@ class Workload:
     kappa: float = -0.1
     c: Tuple[float, ...] = (0.4, 0.3, 0.2, 0.1)
     seed: int = 20240909
+    img: Optional[Tuple[int, int, int]] = None   # convolutional front end: input image (H, W, C), channels last
+    conv: Tuple[int, ...] = ()               # output channels of its 3x3 convolutions (dims[0] = the pooled, flattened map)
+    conv_avg: int = 0                        # 3x3 window averaging of the Hutchinson estimate
 
     @property
     def P(self) -> int:
         if self.dims is None:
             return self.n_params
-        return sum(self.dims[l] * self.dims[l - 1] + self.dims[l] for l in range(1, len(self.dims)))
+        conv = sum(co * ((9 * ci + 3) // 4 * 4) + co for (_, ci, co) in self.conv_stages())   # rows padded to 4
+        return conv + sum(self.dims[l] * self.dims[l - 1] + self.dims[l] for l in range(1, len(self.dims)))
+
+    def conv_stages(self):
+        """(output positions per sample, input channels, output channels) of every convolution."""
+        out = []
+        if self.conv:
+            h, w, c = self.img
+            for co in self.conv:
+                h, w = h - 2, w - 2
+                out.append((h * w, c, co))
+                c = co
+        return out
+
+    def gemm_flops_by_class(self):
+        """Multiply-add work (flop) of one worker step per GEMM class.  A layer costs 2 (rows)(fan-in)(fan-out) per
+        product: forward 3 products (2 when its input does not depend on the parameters), weight gradient the same,
+        data gradient 3 (none for the first layer of the model)."""
+        layers = [(self.batch * pos, 9 * ci, co) for (pos, ci, co) in self.conv_stages()]
+        layers += [(self.batch, self.dims[l - 1], self.dims[l]) for l in range(1, len(self.dims))]
+        fwd = sum(2.0 * m * fi * fo * (3 if n > 0 else 2) for n, (m, fi, fo) in enumerate(layers))
+        dgrad = sum(2.0 * m * fi * fo * 3 for n, (m, fi, fo) in enumerate(layers) if n > 0)
+        return {"gemm_fwd": fwd, "gemm_wgrad": fwd, "gemm_dgrad": dgrad}
 
     def flops_per_worker_step(self) -> float:
         """Multiply-add work of one worker step including the Hessian-vector product:
         first layer 4 products (forward, V-term, weight-grad, Hz weight-grad), every later layer 9."""
-        d = self.dims
-        units = 4 * d[0] * d[1] + 9 * sum(d[l - 1] * d[l] for l in range(2, len(d)))
-        return 2.0 * self.batch * units
+        return sum(self.gemm_flops_by_class().values())
 
 
 C1 = Workload("c1_tiny", k=4, dims=(32, 64, 10), batch=16, tau=1, input_dist="normal", teacher="linear",
@@ -63,10 +86,14 @@ C3 = Workload("c3_cifar_mlp", k=8, dims=(3072, 1024, 1024, 1024, 10), batch=256,
               teacher="mlp2", steps=64, stale="fixed3_last2", seed=20240909 + 3)
 C4 = Workload("c4_wide_bf16", k=16, dims=(4096, 4096, 4096, 4096, 10), batch=512, tau=4, input_dist="normal",
               teacher="mlp2", bf16=True, steps=8, stale="geometric0.3", seed=20240909 + 4)
+# the model of the paper's experiments (Section VI: a small 2-convolution CNN on 28 x 28 images, k in {4, 8}), inputs
+# U[0,1] shaped like its data set, batch 64, communication period 1, one third of the communications suppressed
+CNN = Workload("cnn_paper_model", k=8, dims=(9216, 128, 10), batch=64, tau=1, input_dist="uniform01", teacher="mlp2",
+               steps=8, stale="third", seed=20240909 + 6, img=(28, 28, 1), conv=(32, 64), conv_avg=1)
 C5 = Workload("c5_update_only", k=16, dims=None, batch=0, tau=1, input_dist="normal", teacher="none",
               n_params=100_000_000, steps=20, seed=20240909 + 5)
 
-WORKLOADS = {w.name.split("_")[0]: w for w in (C1, C2, C3, C4, C5)}
+WORKLOADS = {w.name.split("_")[0]: w for w in (C1, C2, C3, C4, C5, CNN)}
 
 
 def scaled(w: Workload, **kw) -> Workload:
@@ -92,6 +119,27 @@ def init_theta(dims: Sequence[int], seed: int) -> np.ndarray:
     return np.concatenate(parts).astype(np.float32)
 
 
+def init_theta_workload(w: Workload) -> np.ndarray:
+    """theta_0 of a workload in the library's layout: as init_theta, with the kernels of a convolutional front end
+    first (rows padded with zeros to a multiple of 4 entries)."""
+    if not w.conv:
+        return init_theta(w.dims, w.seed)
+    rng = rng_for(w.seed, 11)
+    parts = []
+    for (_, ci, co) in w.conv_stages():
+        K = (9 * ci + 3) // 4 * 4
+        bound = 1.0 / np.sqrt(9 * ci)
+        kern = np.zeros((co, K))
+        kern[:, :9 * ci] = rng.uniform(-bound, bound, size=(co, 9 * ci))
+        parts.append(kern.reshape(-1))
+        parts.append(rng.uniform(-bound, bound, size=co))
+    for l in range(1, len(w.dims)):
+        bound = 1.0 / np.sqrt(w.dims[l - 1])
+        parts.append(rng.uniform(-bound, bound, size=w.dims[l] * w.dims[l - 1]))
+        parts.append(rng.uniform(-bound, bound, size=w.dims[l]))
+    return np.concatenate(parts).astype(np.float32)
+
+
 def _teacher_labels(x: np.ndarray, kind: str, n_classes: int, seed: int) -> np.ndarray:
     rng = rng_for(seed, 13)
     d0 = x.shape[-1]
@@ -108,14 +156,14 @@ def _teacher_labels(x: np.ndarray, kind: str, n_classes: int, seed: int) -> np.n
 def minibatch_pool(w: Workload, n_batches: int, bf16_round=None) -> Tuple[np.ndarray, np.ndarray]:
     """A pool of minibatches: x [n_batches, k, B, d0] float32, y [n_batches, k, B] int32."""
     rng = rng_for(w.seed, 17)
-    shape = (n_batches, w.k, w.batch, w.dims[0])
+    shape = (n_batches, w.k, w.batch) + (tuple(w.img) if w.conv else (w.dims[0],))
     if w.input_dist == "uniform01":
         x = rng.random(shape, dtype=np.float32)
     else:
         x = rng.standard_normal(shape, dtype=np.float32)
     if bf16_round is not None:
         x = bf16_round(x)
-    y = _teacher_labels(x.astype(np.float64), w.teacher, w.dims[-1], w.seed)
+    y = _teacher_labels(x.reshape(shape[:3] + (-1,)).astype(np.float64), w.teacher, w.dims[-1], w.seed)
     return x.astype(np.float32), y
 
 

@@ -128,3 +128,40 @@ def test_cnn_configuration_errors():
     for kw in bad:
         assert B.lib().dw_param_count(C.byref(B.make_config(**kw)), C.byref(n)) == -2, kw
     assert B.lib().dw_param_count(C.byref(B.make_config(**dict(ok, avg_block=2))), C.byref(n)) == -3
+
+
+def test_cnn_steps_and_rounds_follow_the_oracle():
+    """Three local steps with a dynamic-weighted round after each (one worker's communication suppressed once):
+    the oracle side is its flat trainer fed with the convolutional oracle's g and Hz."""
+    spec, batch, k = SPECS["two_conv"]
+    theta0, _, _ = _inputs(spec, batch, k, 100)
+    offs, P = spec.offsets()
+    idx, P_lib = B.conv_param_index(spec.img, spec.conv, spec.fc)
+    cfg = B.make_config(dims=(spec.flat,) + spec.fc, k=k, batch=batch, img=spec.img, conv=spec.conv, conv_avg=1,
+                        seed=5, lr=0.01, eps=1e-4)
+    th_lib = np.zeros(P_lib, dtype=np.float32); th_lib[idx] = theta0
+    h = B.Handle(cfg, th_lib, DEV)
+    tr = O.OracleTrainer(O.OracleConfig(dims=None, k=k, n_params=P, lr=0.01, eps=1e-4, seed=5), theta0.copy())
+    rng = W.rng_for(9, 1)
+    for step in range(3):
+        x = rng.uniform(0, 1, size=(k, batch) + spec.img).astype(np.float32)
+        y = rng.integers(0, spec.fc[-1], size=(k, batch)).astype(np.int32)
+        h.worker_step(torch.from_numpy(x).to(DEV), torch.from_numpy(y).to(DEV))
+        g_all, hz_all, z_all = [], [], []
+        for i in range(k):
+            z = _signs(h.get_state(B.DW_S_ZBITS, i), P_lib)[idx]
+            _, g, hz, margin = OC.grad_and_hvp(tr.theta[i], x[i], y[i], spec, z)
+            assert margin > 1e-6
+            g_all.append(g); hz_all.append(z * OC.spatial_average(z * hz, spec)); z_all.append(z)
+        tr.update_only(np.stack(g_all), np.stack(hz_all), z_signs=np.stack(z_all))
+        part = [1, 0, 1] if step == 1 else None
+        assert h.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part)
+        assert tr.elastic_sync(O.MODE_DYNAMIC, tau=1, participate=part)
+    for i in range(k):
+        th = h.get_state(B.DW_S_THETA, i)[idx]
+        assert np.linalg.norm(th - tr.theta[i]) <= 2e-3 * np.linalg.norm(tr.theta[i] - theta0), i
+        sc = h.get_state(B.DW_S_SCORE, i)
+        np.testing.assert_allclose(sc, [tr.last_u[i], tr.last_a[i], tr.last_h1[i], tr.last_h2[i]], rtol=2e-4, atol=2e-5)
+    c = h.get_state(B.DW_S_CENTRE)[idx]
+    assert np.linalg.norm(c - tr.centre) <= 2e-3 * np.linalg.norm(tr.centre - theta0)
+    h.close()

@@ -223,7 +223,9 @@ int64_t dw_overlap_partition(int64_t n, int64_t o, int k, uint64_t seed, int32_t
  * stream; independent uniform draws with replacement.  Call it before the dw_worker_step that consumes the batch
  * (same h_active), with a seed different from the configuration's.
  *
- *   h           an MLP handle: supplies k, the batch size B, d_0 = dims[0], the element type and the t_j
+ *   h           an MLP or CNN handle: supplies k, the batch size B, the sample size d_0 (dims[0], or img_h*img_w*img_c
+ *               with a convolutional front end; d_0 values must fill a multiple of 16 bytes, else DW_ERR_MODE), the
+ *               element type and the t_j
  *   d_data      device, [n][d_0] in the handle's dtype (fp32 or bf16), 16-byte aligned
  *   d_labels    device, [n] int32
  *   d_index     device, [k][m] int32 as written by dw_overlap_partition (m = o + s >= 1)

@@ -615,7 +615,11 @@ int dw_draw_batch(dw_handle* h, const void* d_data, const int32_t* d_labels, int
   uint64_t keys[DW_MAX_K];
   for (int j = 0; j < h->cfg.k; ++j)
     keys[j] = mix64_host(mix64_host(seed + G * (uint64_t)(j + 1)) + G * (uint64_t)(h->t[j] + 1));
-  const int row_bytes = h->cfg.dims[0] * (h->cfg.dtype == DW_BF16 ? 2 : 4);    // a multiple of 16 by validate()
+  // one sample: d_0 values, or a whole image in front of a convolutional model
+  const int64_t row_elems = h->lay.n_conv > 0 ? (int64_t)h->cfg.img_h * h->cfg.img_w * h->cfg.img_c : h->cfg.dims[0];
+  const int64_t row_bytes64 = row_elems * (h->cfg.dtype == DW_BF16 ? 2 : 4);
+  if (row_bytes64 % 16 != 0 || row_bytes64 > (1 << 30)) return DW_ERR_MODE;     // rows are moved as 16-byte pieces
+  const int row_bytes = (int)row_bytes64;
   DW_HIP(launch_gather(d_data, d_labels, d_index, n, m, row_bytes, h->cfg.batch, h->cfg.k, keys, active, d_x, d_y,
                        (hipStream_t)stream));
   return DW_OK;

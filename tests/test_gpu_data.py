@@ -146,3 +146,26 @@ def test_draw_batch_at_the_largest_configuration_shape():
         assert torch.equal(x[j].view(torch.int16), want.view(torch.int16))
         np.testing.assert_array_equal(y[j].cpu().numpy(), lab[idx])
     h.close()
+
+
+def test_draw_batch_feeds_a_convolutional_model_with_whole_images():
+    from oracle import dw_cnn as OC
+    spec = OC.CnnSpec(img=(10, 10, 1), conv=(4, 8), fc=(16, 10))
+    k, Bsz, n = 2, 6, 50
+    idx, P_lib = B.conv_param_index(spec.img, spec.conv, spec.fc)
+    cfg = B.make_config(dims=(spec.flat,) + spec.fc, k=k, batch=Bsz, img=spec.img, conv=spec.conv)
+    h = B.Handle(cfg, np.zeros(P_lib, dtype=np.float32), DEV)
+    data = torch.rand((n, 10, 10, 1), device=DEV)
+    labels = torch.randint(0, 10, (n,), device=DEV, dtype=torch.int32)
+    index = B.overlap_partition(n, 10, k, 3, DEV)
+    Dj = OD.worker_datasets(n, 10, k, 3)
+    x = torch.zeros((k, Bsz, 10, 10, 1), device=DEV); y = torch.zeros((k, Bsz), dtype=torch.int32, device=DEV)
+    h.draw_batch(data, labels, index, 8, x, y)
+    torch.cuda.synchronize()
+    for j in range(k):
+        pos = Dj[j][OD.batch_positions(8, j, 0, Bsz, Dj.shape[1])]
+        assert torch.equal(x[j], data[torch.from_numpy(pos).to(DEV)])
+        np.testing.assert_array_equal(y[j].cpu().numpy(), labels.cpu().numpy()[pos])
+    h.worker_step(x, y)                                       # the drawn images are a valid minibatch of the model
+    torch.cuda.synchronize()
+    h.close()

@@ -577,7 +577,11 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   constexpr int smem = tiles_b > epi_b ? (tiles_b > out_b ? tiles_b : out_b) : (epi_b > out_b ? epi_b : out_b);
   static_assert(smem <= 160 * 1024, "LDS budget");
   auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>;
-  static bool configured = false;        // raise the dynamic LDS limit once per instantiation
+  // raise the dynamic LDS limit once per instantiation and device (the attribute belongs to the device's code object)
+  static bool configured_on[64] = {false};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  bool& configured = configured_on[dev];
   if (!configured) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;

@@ -142,6 +142,7 @@ int validate(const dw_config* c, Layout* lay) {
     lay->sL = take(head); lay->rsL = take(head); lay->dL = take(head); lay->rdL = take(head);
     if (c->dtype == DW_BF16) { lay->dL16 = take(head / 2); lay->rdL16 = take(head / 2); }
   }
+  size_t part = 0, part_b = 0;                       // scratch of products whose contraction is cut into slices
   if (L > 0 && lay->n_conv > 0) {
     const int64_t B = c->batch;
     for (int j = 0; j < lay->n_conv; ++j) {
@@ -153,7 +154,6 @@ int validate(const dw_config* c, Layout* lay) {
     }
     // weight gradients of the convolutions contract over all output positions of the minibatch and have few output
     // tiles: cut the contraction so that about 1024 blocks exist, slices of at least 512 positions
-    size_t part = 0, part_b = 0;
     for (int j = 0; j < lay->n_conv; ++j) {
       const int64_t M = B * lay->cH[j + 1] * lay->cW[j + 1];
       const int64_t blocks = (int64_t)((lay->cC[j + 1] + 63) / 64) * ((lay->cK[j] + 63) / 64) * k;
@@ -167,23 +167,28 @@ int validate(const dw_config* c, Layout* lay) {
         part = need > part ? need : part; part_b = need_b > part_b ? need_b : part_b;
       }
     }
-    {
-      // the first linear layer contracts over the whole pooled map with a handful of output tiles: same cut
-      const int64_t blocks = (int64_t)((B + 63) / 64) * ((c->dims[1] + 63) / 64) * k;
-      int64_t split = 1024 / blocks;
-      if (split > c->dims[0] / 512) split = c->dims[0] / 512;
-      if (split > 64) split = 64;
-      lay->fcSplit = (int)(split < 1 ? 1 : split);
-      if (lay->fcSplit > 1) {
-        const size_t need = (size_t)lay->fcSplit * k * 2 * B * c->dims[1] * 4;
-        part = need > part ? need : part;
-      }
-    }
-    if (part > 0) { lay->cPart = take(part); lay->cPartB = take(part_b > 0 ? part_b : 256); }
     const size_t flat = (size_t)k * B * c->dims[0];
     lay->pool = take(flat * 4); lay->rpool = take(flat * 4); lay->dpool = take(flat * 4); lay->rdpool = take(flat * 4);
     lay->pidx = take(flat);
   }
+  if (L > 0 && c->dtype == DW_F32) {
+    // fp32 forward products with a long contraction and a handful of output tiles (the output layer; the first linear
+    // layer behind a convolutional front end): same cut, slices of at least 256
+    const int64_t B = c->batch;
+    for (int l = 1; l <= L; ++l) {
+      const int64_t n = c->dims[l], kk = c->dims[l - 1];
+      const int64_t tiles = n <= 32 ? (B + 127) / 128 : B <= 32 ? (n + 127) / 128 : ((B + 63) / 64) * ((n + 63) / 64);
+      int64_t split = tiles * k < 256 ? 1024 / (tiles * k) : 1;
+      if (split > kk / 256) split = kk / 256;
+      if (split > 64) split = 64;
+      lay->fwdSplit[l - 1] = (int)(split < 1 ? 1 : split);
+      if (lay->fwdSplit[l - 1] > 1) {
+        const size_t need = (size_t)lay->fwdSplit[l - 1] * k * 2 * B * (l == L ? DW_MAX_CLASSES : n) * 4;
+        part = need > part ? need : part;
+      }
+    }
+  }
+  if (part > 0) { lay->cPart = take(part); lay->cPartB = take(part_b > 0 ? part_b : 256); }
   lay->partials = take((size_t)k * lay->n_upd_blocks * sizeof(double));
   // layers whose weight-gradient kernel applies the update itself: one partial-sum slot per output tile
   lay->n_fuse_slots = 0;

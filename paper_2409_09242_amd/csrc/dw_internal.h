@@ -202,6 +202,7 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t zbits_t = 0;                 // [k][z_stride] words: z with the W-parts of the layers in zt_layer transposed
   bool zt_layer[DW_MAX_LAYERS] = {false};   // index l-1: the data gradient through W_l reads the transposed bits
   size_t dacc = 0;                    // [k][Pp] floats, n_samples > 1 only: sum over the probes of z_j*Hz_j
+  int fwdSplit[DW_MAX_LAYERS] = {0};   // fp32: slices of layer l+1's forward contraction (0 or 1: not cut)
   int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
   int n_fuse_slots = 0;
   size_t partials_f = 0;              // [k][n_fuse_slots] doubles
@@ -214,7 +215,6 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t cA[DW_MAX_CONV] = {0}, cRA[DW_MAX_CONV] = {0};         // outputs a_j, Ra_j [k][M_j][C_j]
   size_t cD[DW_MAX_CONV] = {0}, cRD[DW_MAX_CONV] = {0};         // their gradients
   int cSplit[DW_MAX_CONV] = {0};                                // slices of the weight gradient's contraction (1: none)
-  int fcSplit = 0;                                              // slices of the first linear layer's forward contraction
   size_t cPart = 0, cPartB = 0;                                 // scratch of the sliced weight gradients
   size_t pool = 0, rpool = 0, dpool = 0, rdpool = 0, pidx = 0;  // pooled map [k][B][d_0] (+R, gradients), selection bytes
   size_t partials = 0, u_ring = 0, score = 0, omh1 = 0, h2 = 0, loss = 0;

@@ -145,8 +145,8 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.epi = EPI_LINEAR;
     }
     a.k = k; a.active_mask = active;
-    if (l == 1 && !b16 && lay.fcSplit > 1) {           // behind a convolutional front end: long contraction, few tiles
-      a.ksplit = lay.fcSplit; a.part = reinterpret_cast<float*>(ws + lay.cPart);
+    if (!b16 && lay.fwdSplit[l - 1] > 1) {             // long contraction, few output tiles
+      a.ksplit = lay.fwdSplit[l - 1]; a.part = reinterpret_cast<float*>(ws + lay.cPart);
       a.part_stride = (int64_t)B * a.ldc; a.part_b = nullptr;
     }
     if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;

@@ -79,6 +79,10 @@ typedef enum {
 #define DW_S_SCORE 7         /* double[4]  {u, a, h1, h2} of the last round (get only)                  */
 #define DW_S_U_HIST 8        /* double[1+DW_MAX_P+1]: count n, then the n most recent u, oldest first   */
 #define DW_S_STEPS 9         /* int64[1]   local steps t_i taken by the worker                          */
+#define DW_S_ZBITS_T 10      /* uint32[ceil(P/32)] the last z with the W-parts of some layers transposed: for the layers
+                                whose data gradient runs on the large-tile bf16 kernel, bit (r, c) of V_l [d_l][d_{l-1}]
+                                sits at woff_l + c*d_l + r; other positions are unspecified; get only; DW_ERR_MODE when
+                                the handle keeps no such copy                                                */
 #define DW_S_ACT 16          /* DW_S_ACT + l, l = 1..L-1: hidden activations a_l of the last step, [B][d_l]
                                 floats (DW_F32) or bfloat16 bit patterns as uint16 (DW_BF16); get only      */
 

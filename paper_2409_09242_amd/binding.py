@@ -20,7 +20,7 @@ DW_F32, DW_BF16 = 0, 1
 DW_FIXED, DW_MANUAL, DW_DYNAMIC = 0, 1, 2
 DW_SEQUENTIAL = 16      # OR-ed into the mode of elastic_sync: exchanges one after the other, in index order
 (DW_S_THETA, DW_S_M, DW_S_V, DW_S_G, DW_S_HZ, DW_S_CENTRE, DW_S_ZBITS, DW_S_SCORE, DW_S_U_HIST,
- DW_S_STEPS) = range(10)
+ DW_S_STEPS, DW_S_ZBITS_T) = range(11)
 DW_S_ACT = 16
 
 EXPORTS = ("dw_strerror", "dw_last_hip_error", "dw_param_count", "dw_workspace_bytes", "dw_init", "dw_destroy",
@@ -261,7 +261,7 @@ class Handle:
             raise DwError(st, "dw_draw_batch")
 
     # ---- state access --------------------------------------------------------------------------------
-    _DT = {DW_S_ZBITS: np.uint32, DW_S_SCORE: np.float64, DW_S_U_HIST: np.float64, DW_S_STEPS: np.int64}
+    _DT = {DW_S_ZBITS: np.uint32, DW_S_ZBITS_T: np.uint32, DW_S_SCORE: np.float64, DW_S_U_HIST: np.float64, DW_S_STEPS: np.int64}
 
     def get_state(self, what: int, worker: int = 0, offset: int = 0, count: Optional[int] = None) -> np.ndarray:
         if what > DW_S_ACT:
@@ -273,7 +273,7 @@ class Handle:
                 raise DwError(st, "dw_get_state")
             return out.reshape(self.cfg.batch, self.cfg.dims[l])
         if count is None:
-            count = {DW_S_ZBITS: self.zwords, DW_S_SCORE: 4, DW_S_U_HIST: 2 + DW_MAX_P, DW_S_STEPS: 1}.get(
+            count = {DW_S_ZBITS: self.zwords, DW_S_ZBITS_T: self.zwords, DW_S_SCORE: 4, DW_S_U_HIST: 2 + DW_MAX_P, DW_S_STEPS: 1}.get(
                 what, self.P) - offset
         out = np.empty(count, dtype=self._DT.get(what, np.float32))
         st = lib().dw_get_state(self._h, what, worker, offset, count, _ptr(out), self._stream())

@@ -654,6 +654,7 @@ static int state_ptr(dw_handle* h, int what, int worker, int64_t offset, int64_t
     case DW_S_HZ: if (h->cfg.n_layers == 0) return DW_ERR_MODE; base = L.hz; break;
     case DW_S_CENTRE: base = L.centre; worker = 0; break;
     case DW_S_ZBITS: base = L.zbits; n = 2 * ((L.P + 63) / 64); stride = L.z_stride; break;
+    case DW_S_ZBITS_T: if (L.zbits_t == 0) return DW_ERR_MODE; base = L.zbits_t; n = 2 * ((L.P + 63) / 64); stride = L.z_stride; break;
     case DW_S_SCORE: base = L.score; es = 8; n = 4; stride = 4; break;
     default: return DW_ERR_ARG;
   }

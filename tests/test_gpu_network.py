@@ -415,3 +415,30 @@ def test_several_hutchinson_probes_per_step(bf16, n):
     with pytest.raises(B.DwError):
         zb = torch.zeros(k, 2 * ((w.P + 63) // 64), dtype=torch.int32, device="cuda")
         h.worker_step(xb, torch.from_numpy(y[0]).cuda(), zbits=zb)
+
+
+def test_transposed_sign_bits_are_the_transpose_bit_for_bit():
+    """The data gradient of large bf16 layers reads the sign bits of V_l column by column from a transposed copy
+    of z (index work: compared bit for bit with numpy's transpose of the bits the library drew)."""
+    dims, batch, k = (256, 1024, 512, 10), 512, 16            # W_2 is 512 x 1024: several 512-bit super-tiles, R != C
+    w = W.scaled(W.C4, dims=dims, batch=batch, k=k)
+    h = B.Handle(B.config_from_workload(w), W.init_theta(dims, w.seed), "cuda:0")
+    x, y = W.minibatch_pool(w, 1, bf16_round=W.to_bf16_f32)
+    active = [1] * k; active[5] = 0
+    h.worker_step(torch.from_numpy(x[0]).cuda().to(torch.bfloat16), torch.from_numpy(y[0]).cuda(), active=active)
+    torch.cuda.synchronize()
+    woff = dims[0] * dims[1] + dims[1]                          # start of W_2 in the canonical layout
+    R, Cn = dims[2], dims[1]
+    P = h.P
+    for i in (0, 4, 15):
+        z = np.unpackbits(h.get_state(B.DW_S_ZBITS, i).view(np.uint8), bitorder="little")[:P]
+        zt = np.unpackbits(h.get_state(B.DW_S_ZBITS_T, i).view(np.uint8), bitorder="little")[:P]
+        V = z[woff:woff + R * Cn].reshape(R, Cn)
+        np.testing.assert_array_equal(zt[woff:woff + R * Cn].reshape(Cn, R), V.T)
+    # a frozen worker draws nothing: its copy is left alone (all zero after init)
+    assert not h.get_state(B.DW_S_ZBITS_T, 5).any()
+    # fp32 handles keep no transposed copy
+    h32 = B.Handle(B.config_from_workload(W.C1), W.init_theta(W.C1.dims, W.C1.seed), "cuda:0")
+    with pytest.raises(B.DwError):
+        h32.get_state(B.DW_S_ZBITS_T, 0)
+    h32.close(); h.close()

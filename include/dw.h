@@ -119,7 +119,7 @@ typedef struct {
    * linear layers, so dims[0] must equal (H_out/2)*(W_out/2)*conv_c[n_conv-1].  Needs DW_F32, avg_block = 1,
    * n_samples <= 1, fuse_update = 0.  The minibatch x is then [k][B][img_h][img_w][img_c] floats (channels last).
    * Parameters of convolution j come first in the canonical layout: W_j [C_j][K_j] with K_j = 9*C_{j-1} rounded up
-   * to a multiple of 4, entry ci*9 + dy*3 + dx of a row being tap (dy, dx) on input channel ci, the last
+   * to a multiple of 4, entry (dy*3 + dx)*C_{j-1} + ci of a row being tap (dy, dx) on input channel ci, the last
    * K_j - 9*C_{j-1} entries of a row padding (they must be 0 in theta_0 and then stay 0); then b_j [C_j]. */
   int32_t n_conv;                   /* 0 (none) .. DW_MAX_CONV                                              */
   int32_t img_h, img_w, img_c;      /* input image                                                          */

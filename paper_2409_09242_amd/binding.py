@@ -131,12 +131,14 @@ def conv_param_index(img: Sequence[int], conv: Sequence[int], fc: Sequence[int])
 
     Returns (idx, P_lib): idx[j] is the library position of parameter j of the unpadded layout (kernels
     [C_out][C_in][3][3] and biases of the convolutions, then W_l, b_l of the linear layers); the library rows of a
-    kernel are padded to a multiple of 4 entries, which adds zeros that never change (see dw_config.n_conv)."""
+    kernel run over (tap, input channel) and are padded to a multiple of 4 entries, which adds zeros that never
+    change (see dw_config.n_conv)."""
     h, w, c_in = img
     idx, pos = [], 0
     for co in conv:
         K = (9 * c_in + 3) // 4 * 4
-        rows = pos + np.arange(co)[:, None] * K + np.arange(9 * c_in)[None, :]
+        # unpadded entry (co, ci, tap) -> library entry co*K + tap*C_in + ci
+        rows = pos + np.arange(co)[:, None, None] * K + np.arange(c_in)[None, :, None] + np.arange(9)[None, None, :] * c_in
         idx.append(rows.reshape(-1)); pos += co * K
         idx.append(pos + np.arange(co)); pos += co
         h, w, c_in = h - 2, w - 2, co

@@ -3,7 +3,8 @@
 //
 // A 3x3 convolution (stride 1, no padding) over a channels-last map is a linear layer applied to every 3x3 patch,
 // so it runs on the dual GEMM of the linear layers: the patches of a map [B][H][W][C] become a matrix
-// [B*(H-2)*(W-2)][K], K = 9*C rounded up to 4, column ci*9 + dy*3 + dx holding input (y+dy, x+dx, ci), and
+// [B*(H-2)*(W-2)][K], K = 9*C rounded up to 4, column (dy*3 + dx)*C + ci holding input (y+dy, x+dx, ci) (channels
+// innermost, as in the map, so that patches are cut and put back with contiguous accesses), and
 //   forward      S  = P W^T + b,          RS  = RP W^T + P V^T + c         (P patches, V = z reshaped like W)
 //   weight grad  gW = D^T P,              HzW = RD^T P + D^T RP
 //   data grad    dP = D W,                RdP = RD W + D V,   then summed back onto the map ("col2im")
@@ -17,59 +18,78 @@ namespace dw {
 
 namespace {
 
-// patches of value map `in` and, when given, of its R-companion `rin`: one thread per patch entry
+// patches of value map `in` and, when given, of its R-companion `rin`: one thread per V consecutive patch entries
+// (V = 4 when the channel count allows 16-byte accesses, else 1)
+template <int V>
 __global__ __launch_bounds__(256) void im2col3x3_kernel(const float* in, const float* rin, float* P, float* RP, int B, int H,
                                                         int W, int C, int K, uint64_t active_mask) {
   const int worker = blockIdx.y;
   if (!((active_mask >> worker) & 1ull)) return;
-  const int Ho = H - 2, Wo = W - 2;
-  const int64_t rows = (int64_t)B * Ho * Wo, total = rows * K;
+  const int Ho = H - 2, Wo = W - 2, KV = K / V;
+  const int64_t rows = (int64_t)B * Ho * Wo, total = rows * K, groups = rows * KV;
   const int64_t in_w = (int64_t)B * H * W * C;
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-    const int64_t m = e / K;
-    const int kk = (int)(e - m * K);
-    float v = 0.f, rv = 0.f;
-    if (kk < 9 * C) {
-      const int ci = kk / 9, tap = kk - ci * 9, dy = tap / 3, dx = tap - dy * 3;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < groups; e += (int64_t)gridDim.x * 256) {
+    const int64_t m = e / KV;
+    const int kk = (int)(e - m * KV) * V;
+    float v[V], rv[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) { v[q] = 0.f; rv[q] = 0.f; }
+    if (kk < 9 * C) {                                  // V consecutive channels of one tap (C % V == 0)
+      const int tap = kk / C, ci = kk - tap * C, dy = tap / 3, dx = tap - dy * 3;
       const int x = (int)(m % Wo), y = (int)((m / Wo) % Ho);
       const int64_t b = m / ((int64_t)Wo * Ho);
-      const int64_t src = ((b * H + (y + dy)) * W + (x + dx)) * C + ci;
-      v = in[worker * in_w + src];
-      if (rin) rv = rin[worker * in_w + src];
+      const int64_t src = worker * in_w + ((b * H + (y + dy)) * W + (x + dx)) * C + ci;
+      if (V == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(in + src);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+        if (rin) { const float4 r = *reinterpret_cast<const float4*>(rin + src); rv[0] = r.x; rv[1] = r.y; rv[2] = r.z; rv[3] = r.w; }
+      } else {
+        v[0] = in[src];
+        if (rin) rv[0] = rin[src];
+      }
     }
-    P[worker * total + e] = v;
-    if (RP) RP[worker * total + e] = rv;
+    const int64_t dst = worker * total + m * K + kk;
+    if (V == 4) {
+      *reinterpret_cast<float4*>(P + dst) = make_float4(v[0], v[1], v[2], v[3]);
+      if (RP) *reinterpret_cast<float4*>(RP + dst) = make_float4(rv[0], rv[1], rv[2], rv[3]);
+    } else {
+      P[dst] = v[0];
+      if (RP) RP[dst] = rv[0];
+    }
   }
 }
 
 // adjoint of the patch extraction, followed by the ReLU mask of the map the patches were cut from: one thread per
-// map entry, summing the (up to nine) patch entries that were copied from it
+// four consecutive channels of a map entry (the convolutions below the first have C % 4 == 0), summing the (up to
+// nine) patch entries that were copied from them
 __global__ __launch_bounds__(256) void col2im3x3_kernel(const float* dP, const float* RdP, const float* act, float* D,
                                                         float* RD, int B, int H, int W, int C, int K, uint64_t active_mask) {
   const int worker = blockIdx.y;
   if (!((active_mask >> worker) & 1ull)) return;
-  const int Ho = H - 2, Wo = W - 2;
-  const int64_t total = (int64_t)B * H * W * C, p_w = (int64_t)B * Ho * Wo * K;
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-    const int ci = (int)(e % C);
-    const int x = (int)((e / C) % W), y = (int)((e / ((int64_t)C * W)) % H);
-    const int64_t b = e / ((int64_t)C * W * H);
-    float s = 0.f, rs = 0.f;
-    if (act[worker * total + e] > 0.f) {
-      for (int dy = 0; dy < 3; ++dy) {
-        const int oy = y - dy;
-        if (oy < 0 || oy >= Ho) continue;
-        for (int dx = 0; dx < 3; ++dx) {
-          const int ox = x - dx;
-          if (ox < 0 || ox >= Wo) continue;
-          const int64_t src = ((b * Ho + oy) * Wo + ox) * K + ci * 9 + dy * 3 + dx;
-          s += dP[worker * p_w + src];
-          rs += RdP[worker * p_w + src];
-        }
+  const int Ho = H - 2, Wo = W - 2, C4 = C / 4;
+  const int64_t total = (int64_t)B * H * W * C, groups = total / 4, p_w = (int64_t)B * Ho * Wo * K;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < groups; e += (int64_t)gridDim.x * 256) {
+    const int ci = (int)(e % C4) * 4;
+    const int x = (int)((e / C4) % W), y = (int)((e / ((int64_t)C4 * W)) % H);
+    const int64_t b = e / ((int64_t)C4 * W * H);
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f), rs = s;
+    for (int dy = 0; dy < 3; ++dy) {
+      const int oy = y - dy;
+      if (oy < 0 || oy >= Ho) continue;
+      for (int dx = 0; dx < 3; ++dx) {
+        const int ox = x - dx;
+        if (ox < 0 || ox >= Wo) continue;
+        const int64_t src = worker * p_w + ((b * Ho + oy) * Wo + ox) * K + (dy * 3 + dx) * C + ci;
+        const float4 t = *reinterpret_cast<const float4*>(dP + src), r = *reinterpret_cast<const float4*>(RdP + src);
+        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        rs.x += r.x; rs.y += r.y; rs.z += r.z; rs.w += r.w;
       }
     }
-    D[worker * total + e] = s;
-    RD[worker * total + e] = rs;
+    const float4 a = *reinterpret_cast<const float4*>(act + worker * total + e * 4);
+    *reinterpret_cast<float4*>(D + worker * total + e * 4) =
+        make_float4(a.x > 0.f ? s.x : 0.f, a.y > 0.f ? s.y : 0.f, a.z > 0.f ? s.z : 0.f, a.w > 0.f ? s.w : 0.f);
+    *reinterpret_cast<float4*>(RD + worker * total + e * 4) =
+        make_float4(a.x > 0.f ? rs.x : 0.f, a.y > 0.f ? rs.y : 0.f, a.z > 0.f ? rs.z : 0.f, a.w > 0.f ? rs.w : 0.f);
   }
 }
 
@@ -125,19 +145,19 @@ __global__ __launch_bounds__(256) void conv_window_mean_kernel(float* hz, const 
   const int pair = blockIdx.x * 256 + threadIdx.x;
   if (pair >= C_out * C_in) return;
   const int co = pair / C_in, ci = pair - co * C_in;
-  const int64_t j0 = woff + (int64_t)co * K + ci * 9;
+  const int64_t j0 = woff + (int64_t)co * K + ci;           // tap t of the pair sits C_in entries further on each time
   float* h = hz + worker * Pp;
   const uint32_t* zb = zbits + worker * z_stride;
   float sign[9], s = 0.f;
 #pragma unroll
   for (int t = 0; t < 9; ++t) {
-    const int64_t j = j0 + t;
+    const int64_t j = j0 + (int64_t)t * C_in;
     sign[t] = ((zb[j >> 5] >> (j & 31)) & 1u) ? 1.f : -1.f;
     s += sign[t] * h[j];
   }
   s *= 1.0f / 9.0f;
 #pragma unroll
-  for (int t = 0; t < 9; ++t) h[j0 + t] = sign[t] * s;
+  for (int t = 0; t < 9; ++t) h[j0 + (int64_t)t * C_in] = sign[t] * s;
 }
 
 inline unsigned blocks_for(int64_t n) {
@@ -175,9 +195,14 @@ int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const voi
     const int64_t M = rows(j);
     {
       KernelScope ks(KC_GEMM_FWD, s);
-      hipLaunchKernelGGL(im2col3x3_kernel, dim3(blocks_for(M * lay.cK[j]), (unsigned)k), dim3(256), 0, s, in, rin,
-                         f(lay.cP[j]), j == 0 ? nullptr : f(lay.cRP[j]), B, lay.cH[j], lay.cW[j], lay.cC[j], lay.cK[j],
-                         active);
+      if (lay.cC[j] % 4 == 0)
+        hipLaunchKernelGGL(im2col3x3_kernel<4>, dim3(blocks_for(M * lay.cK[j] / 4), (unsigned)k), dim3(256), 0, s, in, rin,
+                           f(lay.cP[j]), j == 0 ? nullptr : f(lay.cRP[j]), B, lay.cH[j], lay.cW[j], lay.cC[j], lay.cK[j],
+                           active);
+      else
+        hipLaunchKernelGGL(im2col3x3_kernel<1>, dim3(blocks_for(M * lay.cK[j]), (unsigned)k), dim3(256), 0, s, in, rin,
+                           f(lay.cP[j]), j == 0 ? nullptr : f(lay.cRP[j]), B, lay.cH[j], lay.cW[j], lay.cC[j], lay.cK[j],
+                           active);
       if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
     }
     GemmArgs a{};
@@ -248,7 +273,7 @@ int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const voi
     {
       KernelScope ks(KC_GEMM_DGRAD, s);
       const int64_t total = (int64_t)B * lay.cH[j] * lay.cW[j] * lay.cC[j];
-      hipLaunchKernelGGL(col2im3x3_kernel, dim3(blocks_for(total), (unsigned)k), dim3(256), 0, s, f(lay.cP[j]),
+      hipLaunchKernelGGL(col2im3x3_kernel, dim3(blocks_for(total / 4), (unsigned)k), dim3(256), 0, s, f(lay.cP[j]),
                          f(lay.cRP[j]), f(lay.cA[j - 1]), f(lay.cD[j - 1]), f(lay.cRD[j - 1]), B, lay.cH[j], lay.cW[j],
                          lay.cC[j], lay.cK[j], active);
       if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;

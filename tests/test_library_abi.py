@@ -132,6 +132,8 @@ def test_convolutional_configuration_is_validated_on_the_host():
     assert n.value == P_lib == 4 * 12 + 4 + 8 * 36 + 8 + 72 * 16 + 16 + 160 + 10
     assert idx.size == 4 * 9 + 4 + 8 * 36 + 8 + 72 * 16 + 16 + 160 + 10 and len(set(idx.tolist())) == idx.size
     assert idx[:10].tolist() == [0, 1, 2, 3, 4, 5, 6, 7, 8, 12]        # three padding entries after nine taps
+    second = 4 * 12 + 4                                                # the second kernel: rows of 9 taps x 4 channels
+    assert idx[40:50].tolist() == [second + t * 4 for t in range(9)] + [second + 1]
     assert B.lib().dw_workspace_bytes(C.byref(cfg)) > 0
     for kw in (dict(ok, dims=(64, 16, 10)), dict(ok, conv=(4, 6)), dict(ok, img=(9, 10, 1)), dict(ok, bf16=True)):
         assert B.lib().dw_param_count(C.byref(B.make_config(**kw)), C.byref(n)) == -2

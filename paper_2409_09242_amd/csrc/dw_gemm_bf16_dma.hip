@@ -138,9 +138,9 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
   constexpr int STAGE_B = OFF_Y + Y_B;
   constexpr int OFF_Z = STAGE_B * STAGES;                   // ring of two sign-bit groups, [256 rows][16 bytes] each
   constexpr int Z_B = BN * 16;
-  // vector-memory operations every wave issues per k-tile; the sign-bit fetches (one more operation in four of
-  // the waves every fourth k-tile) are left out: counts are only used as "at most n outstanding", operations
-  // complete in order, so an uncounted younger operation makes a wait slightly longer, never too short
+  // vector-memory operations every wave issues per k-tile; the sign-bit fetches (one more operation per wave every
+  // fourth k-tile) are left out: counts are only used as "at most n outstanding", operations complete in order, so
+  // an uncounted operation makes a wait slightly longer, never too short
   constexpr int LPT = TX::CPW * (HAS_RX ? 2 : 1) + TY::CPW;
 
   const int tiles_m = (a.M + BM - 1) / BM;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
     else gy[c] = Y + DmaTile<BN>::map(wave * TY::CPW + c, lane, col0, a.N, a.ldy);
   }
   const int64_t y_step = DGRAD ? (int64_t)BK * a.ldy : BK;  // elements from one k-tile of Y to the next
-  // sign bits: waves 0..3 fetch rows 64w..64w+63 of the tile, 16 bytes (128 k) per row and group
+  // sign bits: wave w fetches rows 64w..64w+63 of the tile, 16 bytes (128 k) per row and group
   const uint32_t* gz = zb + ((a.z_off + (int64_t)(col0 + (wave & 3) * 64 + lane) * a.K) >> 5);
 
   auto issue = [&](int kt, int st) {                        // start the loads of k-tile kt into LDS stage st

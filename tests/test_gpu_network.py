@@ -203,6 +203,7 @@ BF16_SHAPES = [
     ((256, 1024, 512, 10), 384, 8),
     ((512, 2048, 1024, 10), 512, 8),       # large tiles (128 x 256); layer 1 forward and layer 2 data gradient on the global->LDS path
     ((256, 1024, 1024, 10), 512, 16),      # layer 2 forward (with R-operand) and data gradient on the global->LDS path
+    ((256, 1024, 1024, 10), 200, 32),      # the same path with a ragged last row tile (200 = 128 + 72 rows)
 ]
 
 

@@ -38,14 +38,15 @@ def class_flops(w):
 
 def fused_layers(w, fuse):
     """Layers whose weight-gradient kernel applies the update itself when fuse_update = 1 (the library's rule:
-    bf16, W made of whole 128 x 256 tiles that fill the chip, averaging block <= 32, Hessian power 1)."""
-    if not fuse or not w.bf16 or w.dims is None or w.avg_block > 32 or w.hpow != 1.0:
+    W made of whole tiles that fill the chip, averaging block <= 32, Hessian power 1, no convolutional front end)."""
+    if not fuse or w.dims is None or w.conv or w.avg_block > 32 or w.hpow != 1.0:
         return []
+    tile_n, min_tiles = (256, 256) if w.bf16 else (128, 512)        # bf16: 128 x 256 tiles; fp32: 128 x 128
     out, off = [], 0
     for l in range(1, len(w.dims)):
         n_out, n_in = w.dims[l], w.dims[l - 1]
-        if (n_out % 128 == 0 and n_in % 256 == 0 and off % 32 == 0 and n_out * n_in < 2 ** 31
-                and (n_out // 128) * (n_in // 256) * w.k >= 256):
+        if (n_out % 128 == 0 and n_in % tile_n == 0 and off % 32 == 0 and n_out * n_in < 2 ** 31
+                and (n_out // 128) * (n_in // tile_n) * w.k >= min_tiles):
             out.append(l)
         off += n_out * n_in + n_out
     return out
@@ -65,9 +66,10 @@ def class_bytes(w, P, k, fused=(), part=1.0):
     pull = (8.0 + (2.0 if w.bf16 else 0.0)) * P * k * part + 8.0 * P
     out = {"update": upd, "pull": pull}
     if fused:
-        operands = sum(2.0 * 2.0 * w.batch * (d[l] + d[l - 1]) for l in fused)
+        es = 2.0 if w.bf16 else 4.0
+        operands = sum(2.0 * es * w.batch * (d[l] + d[l - 1]) for l in fused)
         # the centre (4 B) is read only on the steps after which a round is due: one step in tau
-        out["gemm_wgrad"] = ((26.125 + 4.0 / w.tau) * p_fused + operands) * k
+        out["gemm_wgrad"] = ((24.125 + (2.0 if w.bf16 else 0.0) + 4.0 / w.tau) * p_fused + operands) * k
     return out
 
 
@@ -82,7 +84,7 @@ def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, residen
     if w.bf16:
         xd = xd.to(torch.bfloat16)
     yd = torch.from_numpy(y).cuda()
-    h = B.Handle(B.config_from_workload(w, fuse_update=1 if (fuse and w.bf16) else 0, n_samples=samples), theta0)
+    h = B.Handle(B.config_from_workload(w, fuse_update=1 if (fuse and not w.conv) else 0, n_samples=samples), theta0)
     sched = W.participation_schedule(w, (2 * steps + warmup) // w.tau + 2)
     state = {"round": 0, "step": 0}
     mode = B.DW_DYNAMIC | (B.DW_SEQUENTIAL if sequential else 0)
@@ -330,7 +332,7 @@ def main():
                 "avg_ms_per_step": gemm_ms, "dominant_class": dominant}
     else:
         ach = kernels[dominant]["GB/s"]
-        label = "dual_gemm_bf16 weight gradient with fused update" if dominant == "gemm_wgrad" else dominant
+        label = ("dual_gemm_%s weight gradient with fused update" % ("bf16" if w.bf16 else "f32")) if dominant == "gemm_wgrad" else dominant
         roof = {"kernel": label, "bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_ms": kernels[dominant]["avg_ms"],
                 "bytes_per_step": by[dominant] * per_step[dominant]}

@@ -194,10 +194,13 @@ int validate(const dw_config* c, Layout* lay) {
   lay->n_fuse_slots = 0;
   for (int l = 1; l <= L; ++l) {
     lay->fuse_base[l - 1] = -1;
-    if (c->fuse_update && c->dtype == DW_BF16 && c->n_samples <= 1 &&      // several probes: D needs all of them first
-        gemm_bf16_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])) {
+    if (!c->fuse_update || c->n_samples > 1) continue;                      // several probes: D needs all of them first
+    const bool b16 = c->dtype == DW_BF16;
+    if (b16 ? gemm_bf16_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])
+            : gemm_f32_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])) {
       lay->fuse_base[l - 1] = lay->n_fuse_slots;
-      lay->n_fuse_slots += gemm_bf16_wgrad_tiles(c->dims[l], c->dims[l - 1]);
+      lay->n_fuse_slots += b16 ? gemm_bf16_wgrad_tiles(c->dims[l], c->dims[l - 1])
+                               : gemm_f32_wgrad_tiles(c->dims[l], c->dims[l - 1]);
     }
   }
   if (lay->n_fuse_slots > 0) lay->partials_f = take((size_t)k * lay->n_fuse_slots * sizeof(double));

@@ -19,6 +19,7 @@
 
 #include "dw_internal.h"
 #include "dw_gemm_epi.h"
+#include "dw_fused_update.h"
 
 namespace dw {
 
@@ -340,10 +341,6 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     // the block mean of D = z*Hz along fan-in is a butterfly over avg_block lanes.  M % 128 == 0 and N % 256 == 0:
     // no element of the tile is out of range.  Offsets inside the block fit 32 bits.
     const FuseArgs& f = a.fu;
-    const int64_t wbase = (int64_t)worker * a.c_wstride;
-    float* th_w = f.theta + wbase; float* m_w = f.m + wbase; float* v_w = f.v + wbase;
-    uint16_t* b16_w = f.wb16 + wbase;
-    const uint32_t* zrow = zb + (a.z_off >> 5);               // z_off % 32 == 0
     // bias corrections of this worker, read from the kernel-argument block by a scalar load (indexing the by-value
     // argument with a variable would copy it to scratch memory)
     typedef const char __attribute__((address_space(4)))* karg_bytes;
@@ -352,95 +349,12 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     const karg_floats bc = (karg_floats)(ka + offsetof(GemmArgs, fu) + offsetof(FuseArgs, sc));
     const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];
     static_assert(offsetof(UpdateScalars, inv_bc2) == DW_MAX_K * sizeof(float), "inv_bc2 follows inv_bc1");
-    const float inv_b = 1.0f / (float)f.avg_block;
-    // The epilogue is bound by HBM, and HBM streams a quarter faster when a wave instruction touches 256
-    // contiguous bytes per row instead of 128 (measured).  The MFMA layout gives a lane one column, i.e. 128-byte
-    // row pieces per half-wave, so g and Hz go through LDS (free after the main loop, a private region per wave):
-    // the accumulators of one row of MFMA tiles (32 rows x 64 columns) are scattered into [row][72 floats] arrays
-    // and read back as one float4 per lane, 16 lanes per row.  A batch is then 4 rows x 256 bytes per access, all
-    // state is moved as float4 (bf16 copy: 8 bytes), and the block mean of D along fan-in is the update kernel's:
-    // four values in the lane, then a butterfly over avg_block / 4 lanes.  The loads of two later batches are in
-    // flight while a batch is computed; scheduling fences keep the compiler from hoisting more.
     static_assert(TN == 2 || !(BM == 128 && BN == 256), "the wave's tile row is 64 columns wide");
-    constexpr int PR = 72;                                    // floats per LDS row: both half-waves hit distinct banks
-    float* gl = reinterpret_cast<float*>(smem) + wave * (2 * 32 * PR);
-    float* hl = gl + 32 * PR;
-    constexpr int NB = TM * 8, DEPTH = 3;
-    struct Batch { uint32_t e, zw; float4 th, mm, vv, cc; };
-    const int brow = lane >> 4, bcol = (lane & 15) * 4;
-    auto load_batch = [&](Batch& bt, int bb) {
-      const int i = bb / 8, b = bb % 8;
-      const uint32_t m = (uint32_t)(row0 + wm0 + i * 32 + b * 4 + brow), n = (uint32_t)(col0 + wn0 + bcol);
-      bt.e = m * (uint32_t)a.ldc + n;                         // offset inside the W block, a multiple of 4
-      bt.th = nt_load4(th_w + bt.e); bt.mm = nt_load4(m_w + bt.e);   // the state streams through once: no reuse in L2
-      bt.vv = nt_load4(v_w + bt.e);
-      bt.cc = f.dist ? *reinterpret_cast<const float4*>(f.centre + bt.e) : make_float4(0.f, 0.f, 0.f, 0.f);
-      bt.zw = zrow[bt.e >> 5];
-    };
+    float* gl = reinterpret_cast<float*>(smem) + wave * fused_update_lds_floats();     // free after the main loop
     float nsum = 0.f;
-    const int group_lanes = f.avg_block >> 2;                 // lanes that share one averaging block (when b > 4)
-    auto finish_batch = [&](const Batch& bt, int b) {
-      const float4 g4 = *reinterpret_cast<const float4*>(gl + (b * 4 + brow) * PR + bcol);
-      const float4 h4 = *reinterpret_cast<const float4*>(hl + (b * 4 + brow) * PR + bcol);
-      const float g[4] = {g4.x, g4.y, g4.z, g4.w}, hz[4] = {h4.x, h4.y, h4.z, h4.w};
-      const float th[4] = {bt.th.x, bt.th.y, bt.th.z, bt.th.w}, mm[4] = {bt.mm.x, bt.mm.y, bt.mm.z, bt.mm.w};
-      const float vv[4] = {bt.vv.x, bt.vv.y, bt.vv.z, bt.vv.w}, cc[4] = {bt.cc.x, bt.cc.y, bt.cc.z, bt.cc.w};
-      const uint32_t zb4 = bt.zw >> (bt.e & 31u);
-      float D[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) D[q] = ((zb4 >> q) & 1u) ? hz[q] : -hz[q];      // Hutchinson: z * Hz
-      if (f.avg_block == 2) {
-        const float p0 = 0.5f * (D[0] + D[1]), p1 = 0.5f * (D[2] + D[3]);
-        D[0] = D[1] = p0; D[2] = D[3] = p1;
-      } else if (f.avg_block >= 4) {
-        float sD = (D[0] + D[1]) + (D[2] + D[3]);
-#pragma unroll
-        for (int off = 1; off < 8; off <<= 1) {
-          const float t = __shfl_xor(sD, off);
-          sD += off < group_lanes ? t : 0.f;
-        }
-        sD *= inv_b;
-        D[0] = D[1] = D[2] = D[3] = sD;
-      }
-      float t1[4], m1[4], v1[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        m1[q] = f.beta1 * mm[q] + (1.0f - f.beta1) * g[q];
-        v1[q] = f.beta2 * vv[q] + (1.0f - f.beta2) * (D[q] * D[q]);
-        const float mhat = m1[q] * ib1, vhat = v1[q] * ib2;
-        t1[q] = th[q] - f.lr * (mhat / (sqrtf(vhat) + f.eps));
-        const float d = t1[q] - cc[q];
-        nsum += d * d;
-      }
-      nt_store4(th_w + bt.e, make_float4(t1[0], t1[1], t1[2], t1[3]));
-      nt_store4(m_w + bt.e, make_float4(m1[0], m1[1], m1[2], m1[3]));
-      nt_store4(v_w + bt.e, make_float4(v1[0], v1[1], v1[2], v1[3]));
-      ushort4 w16; w16.x = f2bf(t1[0]); w16.y = f2bf(t1[1]); w16.z = f2bf(t1[2]); w16.w = f2bf(t1[3]);
-      __builtin_nontemporal_store(__builtin_bit_cast(unsigned long long, w16), reinterpret_cast<unsigned long long*>(b16_w + bt.e));
-    };
-    Batch ring[DEPTH];
-#pragma unroll
-    for (int bb = 0; bb < DEPTH - 1; ++bb) load_batch(ring[bb], bb);
-#pragma unroll
-    for (int bb = 0; bb < NB; ++bb) {
-      const int i = bb / 8, b = bb % 8;
-      if (b == 0) {
-        // scatter the accumulators of tile row i (earlier reads of the region are done: same wave, program order)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int row = (r >> 2) * 8 + lhalf * 4 + (r & 3), col = j * 32 + l32;
-            gl[row * PR + col] = acc[i][j][r];
-            hl[row * PR + col] = racc[i][j][r];
-          }
-      }
-      if (bb + DEPTH - 1 < NB) load_batch(ring[(bb + DEPTH - 1) % DEPTH], bb + DEPTH - 1);
-      __builtin_amdgcn_sched_barrier(0);
-      finish_batch(ring[bb % DEPTH], b);
-      asm volatile("" : "+v"(nsum));                          // the batch's terms are summed here, not kept for later
-      __builtin_amdgcn_sched_barrier(0);
-    }
+    if constexpr (TN == 2)                                    // (the tile shapes that can be asked to fuse)
+      nsum = fused_update_wave_tile<TM, true>(acc, racc, gl, f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0,
+                                              col0 + wn0, zb + (a.z_off >> 5), ib1, ib2, lane);
     // squared distance of the tile's new parameters to the centre: one slot per (worker, tile)
     double ws = (double)nsum;
 #pragma unroll

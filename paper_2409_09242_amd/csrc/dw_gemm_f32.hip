@@ -13,7 +13,10 @@
 // Tiling: 256 threads = 4 waves; block tile BM x BN x 16; tiles are staged k-major in LDS so that each
 // lane's MFMA operand (v_mfma_f32_32x32x2_f32: lane l supplies A[l%32][l/32] and B[l/32][l%32]) is one
 // conflict-free 32-bit LDS read; global loads are 16-byte and prefetched into registers one tile ahead.
+#include <cstddef>
+
 #include "dw_internal.h"
+#include "dw_fused_update.h"
 
 namespace dw {
 
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
     __syncthreads();
     if (kt + 1 < nkt) fetch(kt + 1);
 
-    if (EPI == EPI_WGRAD && tn == 0 && (int)threadIdx.x < BM) {
+    if ((EPI == EPI_WGRAD || EPI == EPI_WGRAD_FUSED) && tn == 0 && (int)threadIdx.x < BM) {
 #pragma unroll
       for (int kk = 0; kk < BK; ++kk) {
         gb_acc += Xs[kk][threadIdx.x];
@@ -200,6 +203,35 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
     __syncthreads();
   }
 
+  if constexpr (EPI == EPI_WGRAD_FUSED) {
+    // The update of Section IV-B applied to the tile instead of storing gW and HzW (see dw_fused_update.h): whole
+    // 128 x 128 tiles, wave tiles of 64 x 64; a private LDS region per wave (dynamic shared memory; the operand
+    // tiles above are static).
+    static_assert(TM == 2 && TN == 2, "four waves of 64 x 64");
+    extern __shared__ __attribute__((aligned(16))) float fused_lds[];
+    const FuseArgs& f = a.fu;
+    typedef const char __attribute__((address_space(4)))* karg_bytes;
+    typedef const float __attribute__((address_space(4)))* karg_floats;
+    const karg_bytes ka = (karg_bytes)__builtin_amdgcn_kernarg_segment_ptr();
+    const karg_floats bc = (karg_floats)(ka + offsetof(GemmArgs, fu) + offsetof(FuseArgs, sc));
+    const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];    // scalar loads from the kernel-argument block
+    static_assert(offsetof(UpdateScalars, inv_bc2) == DW_MAX_K * sizeof(float), "inv_bc2 follows inv_bc1");
+    const float nsum = fused_update_wave_tile<TM, false>(acc, racc, fused_lds + wave * fused_update_lds_floats(), f,
+                                                         (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
+                                                         zb + (a.z_off >> 5), ib1, ib2, lane);
+    double ws = (double)nsum;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) ws += __shfl_xor(ws, off);
+    __shared__ double red[NT / 64];
+    if (lane == 0) red[wave] = ws;
+    __syncthreads();
+    if (threadIdx.x == 0 && f.dist) {
+      double t = 0.0;
+#pragma unroll
+      for (int w = 0; w < NT / 64; ++w) t += red[w];
+      f.partials[(int64_t)worker * f.part_stride + f.part_base + blockIdx.x] = t;
+    }
+  }
   // epilogue: lane holds column n = l32 of each 32x32 tile, rows (r/4)*8 + lhalf*4 + r%4
   float* C = reinterpret_cast<float*>(a.C) + (int64_t)worker * a.c_wstride;
   float* RC = reinterpret_cast<float*>(a.RC) + (int64_t)worker * a.c_wstride;
@@ -208,7 +240,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
     RC = C + a.part_stride;
   }
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
+  for (int j = 0; j < (EPI == EPI_WGRAD_FUSED ? 0 : TN); ++j) {
     const int n = col0 + wn0 + j * 32 + l32;
     const bool n_ok = n < a.N;
     float bias = 0.f, cz = 0.f;
@@ -247,7 +279,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
       }
     }
   }
-  if (EPI == EPI_WGRAD && tn == 0 && (int)threadIdx.x < BM) {
+  if ((EPI == EPI_WGRAD || EPI == EPI_WGRAD_FUSED) && tn == 0 && (int)threadIdx.x < BM) {
     const int m = row0 + threadIdx.x;
     if (m < a.M) {
       if (sliced) {
@@ -322,8 +354,40 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// weight gradient that applies the update itself: 128 x 128 tiles, dynamic LDS for the epilogue's per-wave regions
+static hipError_t launch_fused_wgrad(const GemmArgs& a, hipStream_t s) {
+  const int tiles = (a.M / 128) * (a.N / 128);
+  const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k)), block(NT);
+  constexpr int smem = (NT / 64) * fused_update_lds_floats() * (int)sizeof(float);
+  static bool configured_on[64] = {false};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  auto with_ry = dual_gemm_f32<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD_FUSED>;
+  auto without_ry = dual_gemm_f32<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD_FUSED>;
+  if (!configured_on[dev]) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(with_ry), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(without_ry), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    configured_on[dev] = true;
+  }
+  if (a.RY) hipLaunchKernelGGL(with_ry, grid, block, smem, s, a);
+  else hipLaunchKernelGGL(without_ry, grid, block, smem, s, a);
+  return hipGetLastError();
+}
+
+// The fp32 weight-gradient product of W[n_out][n_in] can apply the update in its epilogue when W is made of whole
+// 128 x 128 tiles that fill the chip, an averaging block is at most 32 and the Hessian power is 1.
+bool gemm_f32_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff) {
+  if (n_out % 128 != 0 || n_in % 128 != 0 || woff % 32 != 0 || avg_block > 32 || hpow != 1.0f) return false;
+  if ((int64_t)n_out * n_in >= (1ll << 31)) return false;
+  return (int64_t)(n_out / 128) * (n_in / 128) * k >= 512;
+}
+int gemm_f32_wgrad_tiles(int n_out, int n_in) { return (n_out / 128) * (n_in / 128); }
+
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
   KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : (a.epi == EPI_MASK || a.epi == EPI_PLAIN) ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);
+  if (a.epi == EPI_WGRAD && a.fu.on) return launch_fused_wgrad(a, s);
   if (a.N <= 32) return launch_shape<128, 32, 4, 1>(a, s);
   if (a.M <= 32) return launch_shape<32, 128, 1, 4>(a, s);
   if (a.N <= 64 && (int64_t)((a.M + 127) / 128) * a.k >= 512) return launch_shape<128, 64, 2, 2>(a, s);   // many rows, few columns

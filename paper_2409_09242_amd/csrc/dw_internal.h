@@ -117,7 +117,7 @@ struct FuseArgs {
   int dist;                           // 1: also read the centre and report the tile's squared distance to it
   float* theta; float* m; float* v;   // worker 0's W block of the layer; worker stride = the product's c_wstride
   const float* centre;                // the layer's W block of the centre
-  uint16_t* wb16;                     // bf16 copy of theta (W block), worker stride c_wstride
+  uint16_t* wb16;                     // bf16 copy of theta (W block), worker stride c_wstride; nullptr in fp32
   double* partials;                   // [k][part_stride] squared-distance partial sums, one slot per tile
   int part_stride, part_base;         // slot of tile t of worker i: i*part_stride + part_base + t
   int avg_block;                      // power of two, 1..32
@@ -126,7 +126,8 @@ struct FuseArgs {
 };
 
 enum GemmKind { GEMM_FWD = 0, GEMM_DGRAD = 1, GEMM_WGRAD = 2 };
-enum Epilogue { EPI_RELU = 0, EPI_LINEAR = 1, EPI_MASK = 2, EPI_WGRAD = 3, EPI_PLAIN = 4 };   // PLAIN: a data gradient stored as it is
+// PLAIN: a data gradient stored as it is.  WGRAD_FUSED: template instance of the fp32 kernel for EPI_WGRAD with fu.on
+enum Epilogue { EPI_RELU = 0, EPI_LINEAR = 1, EPI_MASK = 2, EPI_WGRAD = 3, EPI_PLAIN = 4, EPI_WGRAD_FUSED = 5 };
 
 // One "dual-number" GEMM: C = X*Y and RC = RX*Y + X*RY for all workers (grid y = worker).
 // Element strides describe how the logical operands X[M][K], Y[K][N] sit in memory.
@@ -173,6 +174,8 @@ hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 // and how many partial-sum slots (tiles) does it then write per worker?
 bool gemm_bf16_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff);
 int gemm_bf16_wgrad_tiles(int n_out, int n_in);
+bool gemm_f32_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff);   // same for fp32 (128 x 128 tiles)
+int gemm_f32_wgrad_tiles(int n_out, int n_in);
 // would the data gradient through W[n_out][n_in] of a minibatch of `batch` samples take the large-tile kernel
 // (given the transposed sign bits)?
 bool gemm_bf16_dgrad_dma_shape_ok(int batch, int n_out, int n_in, int k, int64_t woff);

@@ -190,7 +190,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.fu.on = 1;
       a.fu.dist = fuse_dist ? 1 : 0;
       a.fu.theta = fuse->theta + wo; a.fu.m = fuse->m + wo; a.fu.v = fuse->v + wo;
-      a.fu.centre = fuse->centre + wo; a.fu.wb16 = fuse->wb16 + wo;
+      a.fu.centre = fuse->centre + wo; a.fu.wb16 = fuse->wb16 ? fuse->wb16 + wo : nullptr;
       a.fu.partials = reinterpret_cast<double*>(ws + lay.partials_f);
       a.fu.part_stride = lay.n_fuse_slots; a.fu.part_base = lay.fuse_base[l - 1];
       a.fu.avg_block = fuse->avg_block;

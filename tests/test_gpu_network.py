@@ -245,24 +245,37 @@ def _gpu_slopes_b16(h, w):
 # ---------------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("avg_block", [1, 8, 32])
 def test_bf16_fused_update_matches_the_unfused_path_and_the_oracle(avg_block):
-    dims, batch, k = (512, 2048, 1024, 10), 128, 8       # layers 1 and 2 are fused, layer 3 and the biases are not
-    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=4242, bf16=True, avg_block=avg_block)
+    # layers 1 and 2 are fused, layer 3 and the biases are not
+    _fused_against_unfused_and_oracle((512, 2048, 1024, 10), 128, 8, True, avg_block, fused_layer=1)
+
+
+@pytest.mark.parametrize("avg_block", [1, 16])
+def test_f32_fused_update_matches_the_unfused_path_and_the_oracle(avg_block):
+    # fp32: layer 2 (1024 x 1024 = 64 tiles of 128 x 128, 512 with the 8 workers) is fused, the others are not
+    _fused_against_unfused_and_oracle((256, 1024, 1024, 10), 64, 8, False, avg_block, fused_layer=2)
+
+
+def _fused_against_unfused_and_oracle(dims, batch, k, bf16, avg_block, fused_layer):
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=4242, bf16=bf16, avg_block=avg_block)
     theta0 = W.init_theta(w.dims, w.seed)
     hA = B.Handle(B.config_from_workload(w), theta0)
     hB = B.Handle(B.config_from_workload(w, fuse_update=1), theta0)
-    x, y = W.minibatch_pool(w, 2, bf16_round=W.to_bf16_f32)
+    x, y = W.minibatch_pool(w, 2, bf16_round=W.to_bf16_f32 if bf16 else None)
+    _to_dev = _to_bf16_bits if bf16 else (lambda a: torch.from_numpy(a).cuda())
+    woff = sum(dims[l] * dims[l - 1] + dims[l] for l in range(1, fused_layer))       # W of the first fused layer
+    wlen = dims[fused_layer] * dims[fused_layer - 1]
     hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, hpow=w.hpow, dims=w.dims, avg_block=w.avg_block)
     t = np.zeros(k, dtype=int)
     for step, active in ((0, [1] * k), (1, [1, 1, 1, 0, 1, 1, 1, 1])):
         prev = [(hA.get_state(B.DW_S_THETA, i).astype(np.float64), hA.get_state(B.DW_S_M, i).astype(np.float64),
                  hA.get_state(B.DW_S_V, i).astype(np.float64)) for i in range(k)]
-        xb, yb = _to_bf16_bits(x[step]), torch.from_numpy(y[step]).cuda()
+        xb, yb = _to_dev(x[step]), torch.from_numpy(y[step]).cuda()
         lossA, lossB = torch.zeros(k, device="cuda"), torch.zeros(k, device="cuda")
         hA.worker_step(xb, yb, loss=lossA, active=active)
         hB.worker_step(xb, yb, loss=lossB, active=active)
         np.testing.assert_array_equal(lossA.cpu().numpy(), lossB.cpu().numpy())
         # the fused handle never stores the W-part of g of a fused layer (its buffer still holds the initial zeros)
-        assert not np.any(hB.get_state(B.DW_S_G, 0, 0, dims[0] * dims[1])) and np.any(hA.get_state(B.DW_S_G, 0, 0, 4096))
+        assert not np.any(hB.get_state(B.DW_S_G, 0, woff, wlen)) and np.any(hA.get_state(B.DW_S_G, 0, woff, 4096))
         for i in range(k):
             thA, mA, vA = (hA.get_state(s, i) for s in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V))
             thB, mB, vB = (hB.get_state(s, i) for s in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V))
@@ -292,10 +305,11 @@ def test_bf16_fused_update_matches_the_unfused_path_and_the_oracle(avg_block):
         assert abs(sa[0] - sb[0]) < 1e-6 and abs(sa[2] - sb[2]) < 1e-5 and abs(sa[3] - sb[3]) < 1e-5, (i, sa, sb)
         close(hB.get_state(B.DW_S_THETA, i), hA.get_state(B.DW_S_THETA, i), 1e-6, "fused vs unfused pulled theta[%d]" % i)
     close(hB.get_state(B.DW_S_CENTRE), hA.get_state(B.DW_S_CENTRE), 1e-6, "fused vs unfused centre")
-    xb, yb = _to_bf16_bits(x[0]), torch.from_numpy(y[0]).cuda()
+    xb, yb = _to_dev(x[0]), torch.from_numpy(y[0]).cuda()
     hA.worker_step(xb, yb, loss=lossA2)
     hB.worker_step(xb, yb, loss=lossB2)
     close(lossB2.cpu().numpy(), lossA2.cpu().numpy(), 1e-5, "loss after the round")
+    hA.close(); hB.close()
 
 
 def test_bf16_fused_update_with_caller_z_and_an_update_only_call_in_between():

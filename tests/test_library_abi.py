@@ -79,7 +79,7 @@ def test_null_handles_are_rejected_without_a_gpu():
     assert lib.dw_init(C.byref(h), C.byref(cfg), None, 0, None, 0, None) == -1
 
 
-def test_fused_update_is_an_option_of_large_bf16_layers_only():
+def test_fused_update_is_an_option_of_large_layers_only():
     """fuse_update = 1 is accepted everywhere; it only adds partial-sum slots (workspace) where a layer qualifies."""
     lib = B.lib()
     for w in (W.C1, W.C3, W.C4):
@@ -89,6 +89,9 @@ def test_fused_update_is_an_option_of_large_bf16_layers_only():
         if w is W.C4:
             # three 4096 x 4096 layers, 32 x 16 tiles each, one double per tile and worker
             assert fused - plain == 3 * 32 * 16 * 8 * w.k
+        elif w is W.C3:
+            # fp32: 1024 x 3072 and two 1024 x 1024 layers in 128 x 128 tiles, one double per tile and worker
+            assert fused - plain == (8 * 24 + 2 * 8 * 8) * 8 * w.k
         else:
             assert fused == plain
 

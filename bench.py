@@ -52,14 +52,16 @@ def fused_layers(w, fuse):
     return out
 
 
-def class_bytes(w, P, k, fused=(), part=1.0):
+def class_bytes(w, P, k, fused=(), part=1.0, samples=1):
     """Algorithmic HBM bytes per step for the HBM-bound classes.  The update reads g, Hz, theta, m, v and writes
     theta, m, v (32 B per parameter and worker, +2 B for the bf16 weight copy); the pull reads and writes theta
     (8 B per parameter and communicating worker, +2 B bf16 copy; `part` = mean fraction of workers that communicate) and
     the centre (8 B per parameter).  A fused weight-gradient
     launch reads theta, m, v, writes theta, m, v and the bf16 copy (26 B per parameter and worker, + 1 bit of z),
     reads the centre (4 B) on the steps before a round, and reads its four bf16 operands once (d_l, Rd_l, a_{l-1},
-    Ra_{l-1})."""
+    Ra_{l-1}).  With n > 1 Hutchinson probes the fused launches of the first n - 1 probes only keep the running sum
+    of z*Hz (first: 4 B written, later: 4 B read and 4 B written per parameter, + 1 bit of z) and the last one
+    reads the sum on top of the above (+4 B)."""
     d = w.dims
     p_fused = sum(d[l] * d[l - 1] for l in fused)
     upd = (32.0 + (2.0 if w.bf16 else 0.0)) * (P - p_fused) * k
@@ -70,6 +72,8 @@ def class_bytes(w, P, k, fused=(), part=1.0):
         operands = sum(2.0 * es * w.batch * (d[l] + d[l - 1]) for l in fused)
         # the centre (4 B) is read only on the steps after which a round is due: one step in tau
         out["gemm_wgrad"] = ((24.125 + (2.0 if w.bf16 else 0.0) + 4.0 / w.tau) * p_fused + operands) * k
+        if samples > 1:
+            out["gemm_wgrad"] += ((4.125 + 8.125 * (samples - 2) + 4.0) * p_fused + (samples - 1) * operands) * k
     return out
 
 
@@ -301,10 +305,10 @@ def main():
     value = w.k * args.steps / elapsed
 
     fl = class_flops(w)
-    fused = fused_layers(w, not args.no_fuse and args.samples <= 1)
+    fused = fused_layers(w, not args.no_fuse and (args.samples <= 1 or w.bf16))     # fp32 fuses one-probe steps only
     if args.samples > 1:
         fl = {c: v * args.samples for c, v in fl.items()}
-    by = class_bytes(w, w.P, w.k, fused, part)
+    by = class_bytes(w, w.P, w.k, fused, part, args.samples)
     per_step = {"update": 1, "pull": 1.0 / w.tau, "gemm_wgrad": 1, "gather": 1}
     by["gather"] = 2.0 * w.k * w.batch * w.dims[0] * (2 if w.bf16 else 4)        # every drawn row read and written once
     kernels = {}
@@ -338,11 +342,11 @@ def main():
                 "bytes_per_step": by[dominant] * per_step[dominant]}
         if dominant == "gemm_wgrad":
             # per launch, like the counters: the class has one more, tiny launch per step (the output layer)
-            n_big = len(fused)
+            n_big = len(fused) * args.samples
             roof["launches_per_step"] = n_big
             roof["bytes_per_launch"] = by[dominant] / n_big
             roof["avg_ms"] = kernels[dominant]["ms_per_step"] / n_big
-            if w.name.startswith("c4"):
+            if w.name.startswith("c4") and args.samples <= 1:
                 roof["traffic"] = TRAFFIC_C4_FUSED_WGRAD
     gemm_roof = None
     if gemm_ms > 0:

@@ -194,8 +194,9 @@ int validate(const dw_config* c, Layout* lay) {
   lay->n_fuse_slots = 0;
   for (int l = 1; l <= L; ++l) {
     lay->fuse_base[l - 1] = -1;
-    if (!c->fuse_update || c->n_samples > 1) continue;                      // several probes: D needs all of them first
     const bool b16 = c->dtype == DW_BF16;
+    // several probes: the bf16 kernel keeps the running sum of z*Hz itself; the fp32 kernel does not
+    if (!c->fuse_update || (c->n_samples > 1 && !b16)) continue;
     if (b16 ? gemm_bf16_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])
             : gemm_f32_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])) {
       lay->fuse_base[l - 1] = lay->n_fuse_slots;
@@ -259,6 +260,7 @@ void fill_update_args(dw_handle* h, UpdateArgs& a, const float* g, const float* 
   a.k = c.k; a.avg_block = c.avg_block;
   a.lr = c.lr; a.beta1 = c.beta1; a.beta2 = c.beta2; a.eps = c.eps; a.hpow = c.hpow;
   a.d_scale = 0.f;
+  a.probe_mode = 0; a.probe_first = 0; a.dacc = nullptr;
   a.active_mask = active;
   a.bias.n = c.n_layers;
   for (int l = 0; l < c.n_layers; ++l) {
@@ -332,23 +334,29 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
   const int64_t zs = d_zbits ? 2 * ((h->lay.P + 63) / 64) : h->lay.z_stride;
   if (probes(h) > 1) {
     // n probes of the same minibatch: the network runs once per probe (loss and g come out the same each time),
-    // z_j*Hz_j is summed, and the update takes D = sum / n
+    // z_j*Hz_j is summed, and the update takes D = sum / n.  Fused layers keep their part of the sum in the
+    // weight-gradient kernel and apply the update in the last probe's; the rest goes through the sum kernel.
     const int n = probes(h);
-    for (int j = 0; j < n; ++j) {
-      int st = draw_z(h, active, s, j);
-      if (st != DW_OK) return st;
-      st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, nullptr, true, s);
-      if (st != DW_OK) return st;
-      DW_HIP(launch_probe_sum(h->at<float>(h->lay.dacc), h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->cfg.k, active,
-                              j == 0 ? 1 : 0, s));
-    }
-    for (int i = 0; i < h->cfg.k; ++i)
-      if ((active >> i) & 1ull) h->t[i] += 1;
-    UpdateArgs a;
-    fill_update_args(h, a, h->at<float>(h->lay.g), h->at<float>(h->lay.dacc), h->lay.Pp, zb, zs, active, false);
-    a.d_scale = 1.0f / (float)n;
+    const bool fused = h->lay.n_fuse_slots > 0;
+    float* dacc = h->at<float>(h->lay.dacc);
     int st = clear_fused_partials(h, s);
     if (st != DW_OK) return st;
+    UpdateArgs a;
+    for (int j = 0; j < n; ++j) {
+      const bool last = j == n - 1;
+      st = draw_z(h, active, s, j);
+      if (st != DW_OK) return st;
+      if (last)
+        for (int i = 0; i < h->cfg.k; ++i)
+          if ((active >> i) & 1ull) h->t[i] += 1;
+      if (last || j == 0) fill_update_args(h, a, h->at<float>(h->lay.g), dacc, h->lay.Pp, zb, zs, active, fused);
+      a.d_scale = 1.0f / (float)n;
+      a.probe_mode = last ? 2 : 1; a.probe_first = j == 0 ? 1 : 0; a.dacc = dacc;
+      st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fused ? &a : nullptr, true, s);
+      if (st != DW_OK) return st;
+      DW_HIP(launch_probe_sum(dacc, h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->cfg.k, active, j == 0 ? 1 : 0,
+                              a.fused, s));
+    }
     DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
     h->norms_valid = true;
     h->calls += 1;

@@ -495,12 +495,18 @@ hipError_t launch_transpose_bits(const uint32_t* z, int64_t z_stride, uint32_t* 
 }
 
 // Running sum of z_j * Hz_j over the probes of one step (Section IV-B with n > 1), one float4 per thread.
+// blockIdx.z picks one of the parameter ranges in `keep` (begin and end multiples of 4); what lies between them
+// belongs to weight-gradient kernels that keep the sum themselves.
 __global__ __launch_bounds__(256) void probe_sum_kernel(float* dacc, const float* hz, const uint32_t* zbits, int64_t Pp,
-                                                        int64_t z_stride, uint64_t active_mask, int first) {
+                                                        int64_t z_stride, uint64_t active_mask, int first,
+                                                        FusedRanges keep) {
   const int i = blockIdx.y;
   if (!((active_mask >> i) & 1ull)) return;
-  const int64_t nq = Pp >> 2;
-  for (int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x; q < nq; q += (int64_t)gridDim.x * 256) {
+  int64_t q0 = 0, q1 = 0;
+#pragma unroll
+  for (int r = 0; r < DW_MAX_LAYERS; ++r)                    // (static indices: the argument stays in registers)
+    if (r == (int)blockIdx.z) { q0 = keep.begin[r] >> 2; q1 = keep.end[r] >> 2; }
+  for (int64_t q = q0 + (int64_t)blockIdx.x * 256 + threadIdx.x; q < q1; q += (int64_t)gridDim.x * 256) {
     const float4 h = reinterpret_cast<const float4*>(hz + (int64_t)i * Pp)[q];
     const uint32_t z = zbits[(int64_t)i * z_stride + (q >> 3)] >> ((q << 2) & 31);
     float4 d = first ? make_float4(0.f, 0.f, 0.f, 0.f) : reinterpret_cast<const float4*>(dacc + (int64_t)i * Pp)[q];
@@ -510,13 +516,28 @@ __global__ __launch_bounds__(256) void probe_sum_kernel(float* dacc, const float
   }
 }
 
+// skip: ranges (ascending, disjoint, bounds multiples of 4) that the sum leaves out
 hipError_t launch_probe_sum(float* dacc, const float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride, int k,
-                            uint64_t active_mask, int first, hipStream_t s) {
+                            uint64_t active_mask, int first, const FusedRanges& skip, hipStream_t s) {
   KernelScope ks(KC_UPDATE, s);
-  int64_t nb = ((Pp >> 2) + 255) / 256;
+  FusedRanges keep{};
+  int64_t pos = 0, longest = 0;
+  for (int r = 0; r <= skip.n; ++r) {
+    const int64_t end = r < skip.n ? skip.begin[r] : Pp;
+    if (end > pos) {
+      // at most DW_MAX_LAYERS - 1 layers are fused (the output layer never is): the pieces between them fit
+      if (keep.n == DW_MAX_LAYERS) return hipErrorInvalidValue;
+      keep.begin[keep.n] = pos; keep.end[keep.n] = end;
+      longest = end - pos > longest ? end - pos : longest;
+      keep.n += 1;
+    }
+    if (r < skip.n) pos = skip.end[r];
+  }
+  if (keep.n == 0) return hipSuccess;
+  int64_t nb = ((longest >> 2) + 255) / 256;
   if (nb > 16384) nb = 16384;
-  hipLaunchKernelGGL(probe_sum_kernel, dim3((unsigned)nb, (unsigned)k), dim3(256), 0, s, dacc, hz, zbits, Pp, z_stride,
-                     active_mask, first);
+  hipLaunchKernelGGL(probe_sum_kernel, dim3((unsigned)nb, (unsigned)k, (unsigned)keep.n), dim3(256), 0, s, dacc, hz, zbits,
+                     Pp, z_stride, active_mask, first, keep);
   return hipGetLastError();
 }
 

@@ -46,8 +46,9 @@ __host__ __device__ constexpr int fused_update_lds_floats() { return 2 * 32 * 72
 // in theta, m, v (and the bf16 copy).  row_base, col_base: first row and column of the wave's tile in W_l.
 // zrow: sign bits of z from the first parameter of the W block on.  ib1, ib2: the worker's 1/(1 - beta^t).
 // Returns this lane's share of the squared distance of the new parameters to the centre (0 unless f.dist).
-// B16: also store the bf16 copy of the new parameters.
-template <int TM, bool B16>
+// B16: also store the bf16 copy of the new parameters.  PROBES: the diagonal estimate is the mean over several
+// Hutchinson probes, D = (f.dacc + z*Hz) * f.d_scale, f.dacc holding the sum over the earlier probes.
+template <int TM, bool B16, bool PROBES = false>
 __device__ __forceinline__ float fused_update_wave_tile(const fu_floatx16 (&acc)[TM][2], const fu_floatx16 (&racc)[TM][2],
                                                         float* gl, const FuseArgs& f, int64_t wbase, int ldc,
                                                         int row_base, int col_base, const uint32_t* zrow, float ib1,
@@ -59,7 +60,8 @@ __device__ __forceinline__ float fused_update_wave_tile(const fu_floatx16 (&acc)
   constexpr int PR = 72;                                    // floats per LDS row: both half-waves hit distinct banks
   float* hl = gl + 32 * PR;
   constexpr int NB = TM * 8, DEPTH = 3;
-  struct Batch { uint32_t e, zw; float4 th, mm, vv, cc; };
+  struct Batch { uint32_t e, zw; float4 th, mm, vv, cc, dd; };
+  const float* dacc_w = PROBES ? f.dacc + wbase : nullptr;
   const int brow = lane >> 4, bcol = (lane & 15) * 4;
   auto load_batch = [&](Batch& bt, int bb) {
     const int i = bb / 8, b = bb % 8;
@@ -69,6 +71,7 @@ __device__ __forceinline__ float fused_update_wave_tile(const fu_floatx16 (&acc)
     bt.vv = fu_nt_load4(v_w + bt.e);
     bt.cc = f.dist ? *reinterpret_cast<const float4*>(f.centre + bt.e) : make_float4(0.f, 0.f, 0.f, 0.f);
     bt.zw = zrow[bt.e >> 5];
+    if constexpr (PROBES) bt.dd = fu_nt_load4(dacc_w + bt.e);
   };
   float nsum = 0.f;
   const int group_lanes = f.avg_block >> 2;                 // lanes that share one averaging block (when b > 4)
@@ -82,6 +85,11 @@ __device__ __forceinline__ float fused_update_wave_tile(const fu_floatx16 (&acc)
     float D[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) D[q] = ((zb4 >> q) & 1u) ? hz[q] : -hz[q];      // Hutchinson: z * Hz
+    if constexpr (PROBES) {
+      const float dd[4] = {bt.dd.x, bt.dd.y, bt.dd.z, bt.dd.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) D[q] = (dd[q] + D[q]) * f.d_scale;
+    }
     if (f.avg_block == 2) {
       const float p0 = 0.5f * (D[0] + D[1]), p1 = 0.5f * (D[2] + D[3]);
       D[0] = D[1] = p0; D[2] = D[3] = p1;
@@ -137,6 +145,43 @@ __device__ __forceinline__ float fused_update_wave_tile(const fu_floatx16 (&acc)
     __builtin_amdgcn_sched_barrier(0);
   }
   return nsum;
+}
+
+// One of several Hutchinson probes that is not the last: only z*Hz of the wave's tile is kept, added to (first
+// probe: stored as) the running sum f.dacc; the parameters and moments are not touched.  Same LDS staging and
+// 256-byte rows as above; racc, gl, wbase, ldc, row_base, col_base, zrow, lane as above.
+template <int TM>
+__device__ __forceinline__ void fused_probe_sum_wave_tile(const fu_floatx16 (&racc)[TM][2], float* gl, const FuseArgs& f,
+                                                          int64_t wbase, int ldc, int row_base, int col_base,
+                                                          const uint32_t* zrow, int lane) {
+  const int l32 = lane & 31, lhalf = lane >> 5;
+  constexpr int PR = 72;
+  float* dacc_w = f.dacc + wbase;
+  const int brow = lane >> 4, bcol = (lane & 15) * 4;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) gl[((r >> 2) * 8 + lhalf * 4 + (r & 3)) * PR + j * 32 + l32] = racc[i][j][r];
+    uint32_t e[8], zw[8];
+    float4 dd[8];
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      e[b] = (uint32_t)(row_base + i * 32 + b * 4 + brow) * (uint32_t)ldc + (uint32_t)(col_base + bcol);
+      zw[b] = zrow[e[b] >> 5];
+      dd[b] = f.first ? make_float4(0.f, 0.f, 0.f, 0.f) : fu_nt_load4(dacc_w + e[b]);
+    }
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {
+      const float4 h4 = *reinterpret_cast<const float4*>(gl + (b * 4 + brow) * PR + bcol);
+      const uint32_t zb4 = zw[b] >> (e[b] & 31u);
+      float4 o;
+      o.x = dd[b].x + ((zb4 & 1u) ? h4.x : -h4.x); o.y = dd[b].y + ((zb4 & 2u) ? h4.y : -h4.y);
+      o.z = dd[b].z + ((zb4 & 4u) ? h4.z : -h4.z); o.w = dd[b].w + ((zb4 & 8u) ? h4.w : -h4.w);
+      fu_nt_store4(dacc_w + e[b], o);
+    }
+  }
 }
 
 }  // namespace dw

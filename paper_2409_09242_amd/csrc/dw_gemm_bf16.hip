@@ -161,7 +161,7 @@ __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int row0, int ks, in
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI>
+template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0>
 __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   static_assert(WM * WN == NT / 64, "eight waves per block");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   if (slot >= active_count(a.active_mask, a.k)) return;
   const int worker = nth_active_worker(a.active_mask, slot);
   const int tile = logical - slot * tiles;
-  if (EPI == EPI_WGRAD && a.fu.on && blockIdx.x < 256 * 8) {
+  if (EPI == EPI_WGRAD && FM != 1 && a.fu.on && blockIdx.x < 256 * 8) {
     // Fused update: a block alternates between a compute-bound main loop and an HBM-bound epilogue of about twice
     // its length.  Blocks that start together stay in step, leaving HBM idle while everybody multiplies, so the
     // first block of every compute unit starts with one of 16 delays spread over about one block period.
@@ -352,9 +352,16 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     static_assert(TN == 2 || !(BM == 128 && BN == 256), "the wave's tile row is 64 columns wide");
     float* gl = reinterpret_cast<float*>(smem) + wave * fused_update_lds_floats();     // free after the main loop
     float nsum = 0.f;
-    if constexpr (TN == 2)                                    // (the tile shapes that can be asked to fuse)
-      nsum = fused_update_wave_tile<TM, true>(acc, racc, gl, f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0,
-                                              col0 + wn0, zb + (a.z_off >> 5), ib1, ib2, lane);
+    if constexpr (TN == 2) {                                  // (the tile shapes that can be asked to fuse)
+      // FM: 0 one Hutchinson probe; 1 a probe before the last (only the running sum of z*Hz is written);
+      // 2 the last of several probes
+      if constexpr (FM == 1)
+        fused_probe_sum_wave_tile<TM>(racc, gl, f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
+                                      zb + (a.z_off >> 5), lane);
+      else
+        nsum = fused_update_wave_tile<TM, true, FM == 2>(acc, racc, gl, f, (int64_t)worker * a.c_wstride, a.ldc,
+                                                         row0 + wm0, col0 + wn0, zb + (a.z_off >> 5), ib1, ib2, lane);
+    }
     // squared distance of the tile's new parameters to the centre: one slot per (worker, tile)
     double ws = (double)nsum;
 #pragma unroll
@@ -478,7 +485,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI>
+template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI, int FM = 0>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   const dim3 grid((unsigned)((tiles * active_count(a.active_mask, a.k) + 7) / 8 * 8)), block(NT);
@@ -490,7 +497,7 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   constexpr int out_b = (EPI == EPI_RELU || EPI == EPI_MASK) ? (NT / 64) * epi_bf16_lds_bytes(BN / WN / 32) : 0;
   constexpr int smem = tiles_b > epi_b ? (tiles_b > out_b ? tiles_b : out_b) : (epi_b > out_b ? epi_b : out_b);
   static_assert(smem <= 160 * 1024, "LDS budget");
-  auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>;
+  auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, FM>;
   // raise the dynamic LDS limit once per instantiation and device (the attribute belongs to the device's code object)
   static bool configured_on[64] = {false};
   int dev = 0;
@@ -516,6 +523,15 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
               : launch_one<BM, BN, WM, WN, true, true, false, RY_BITS, EPI_LINEAR>(a, s);
   } else if (a.epi == EPI_MASK) {
     return launch_one<BM, BN, WM, WN, true, false, true, RY_BITS, EPI_MASK>(a, s);
+  }
+  if constexpr (BM == 128 && BN == 256) {
+    // the fused update with several Hutchinson probes: own instances, so that the one-probe kernel keeps its registers
+    if (a.fu.on && a.fu.probe_mode == 1)
+      return a.RY ? launch_one<BM, BN, WM, WN, false, false, true, RY_MEM, EPI_WGRAD, 1>(a, s)
+                  : launch_one<BM, BN, WM, WN, false, false, true, RY_NONE, EPI_WGRAD, 1>(a, s);
+    if (a.fu.on && a.fu.probe_mode == 2)
+      return a.RY ? launch_one<BM, BN, WM, WN, false, false, true, RY_MEM, EPI_WGRAD, 2>(a, s)
+                  : launch_one<BM, BN, WM, WN, false, false, true, RY_NONE, EPI_WGRAD, 2>(a, s);
   }
   return a.RY ? launch_one<BM, BN, WM, WN, false, false, true, RY_MEM, EPI_WGRAD>(a, s)
               : launch_one<BM, BN, WM, WN, false, false, true, RY_NONE, EPI_WGRAD>(a, s);

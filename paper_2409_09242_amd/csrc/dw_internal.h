@@ -51,6 +51,9 @@ struct UpdateArgs {
   BiasRanges bias;
   FusedRanges fused;
   UpdateScalars sc;
+  // several probes per step with fused weight gradients (see FuseArgs): mode, first probe, running sum [k][Pp]
+  int probe_mode, probe_first;
+  float* dacc;
   // filled by launch_update: the launch covers all n_blocks chunks (n_list == 0) or only the listed ones
   int n_blocks, n_list;
   int block_list[64];
@@ -90,7 +93,7 @@ hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words6
                              int k, uint64_t active_mask, hipStream_t s);
 // dacc = (first ? 0 : dacc) + z*hz for the active workers: the running sum of a step's Hutchinson probes
 hipError_t launch_probe_sum(float* dacc, const float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride, int k,
-                            uint64_t active_mask, int first, hipStream_t s);
+                            uint64_t active_mask, int first, const FusedRanges& skip, hipStream_t s);
 // zt = z with the bits of one layer's W-part [R][C] transposed (bit (r, c) at woff + r*C + c goes to woff + c*R + r);
 // R, C and woff must be multiples of 128, both strides multiples of 4 words, both arrays 16-byte aligned
 hipError_t launch_transpose_bits(const uint32_t* z, int64_t z_stride, uint32_t* zt, int64_t zt_stride, int64_t woff, int R, int C, int k,
@@ -123,6 +126,11 @@ struct FuseArgs {
   int avg_block;                      // power of two, 1..32
   float lr, beta1, beta2, eps, hpow;
   UpdateScalars sc;
+  // several Hutchinson probes (bf16 product only).  0: one probe.  1: a probe that is not the last, only
+  // dacc (+)= z*Hz is written (first: stored, not added).  2: the last probe, D = (dacc + z*Hz) * d_scale
+  int probe_mode, first;
+  float* dacc;                        // the layer's W block of worker 0 in the running sum, worker stride c_wstride
+  float d_scale;
 };
 
 enum GemmKind { GEMM_FWD = 0, GEMM_DGRAD = 1, GEMM_WGRAD = 2 };

@@ -196,6 +196,8 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.fu.avg_block = fuse->avg_block;
       a.fu.lr = fuse->lr; a.fu.beta1 = fuse->beta1; a.fu.beta2 = fuse->beta2; a.fu.eps = fuse->eps; a.fu.hpow = fuse->hpow;
       a.fu.sc = fuse->sc;
+      a.fu.probe_mode = fuse->probe_mode; a.fu.first = fuse->probe_first;
+      a.fu.dacc = fuse->dacc ? fuse->dacc + wo : nullptr; a.fu.d_scale = fuse->d_scale;
     }
     return gemm(a);
   };

@@ -1,4 +1,6 @@
 """GPU parity of the network part (gradient and Hessian-vector product) and of whole trajectories."""
+import ctypes as C
+
 import numpy as np
 import pytest
 import torch
@@ -309,6 +311,47 @@ def _fused_against_unfused_and_oracle(dims, batch, k, bf16, avg_block, fused_lay
     hA.worker_step(xb, yb, loss=lossA2)
     hB.worker_step(xb, yb, loss=lossB2)
     close(lossB2.cpu().numpy(), lossA2.cpu().numpy(), 1e-5, "loss after the round")
+    hA.close(); hB.close()
+
+
+@pytest.mark.parametrize("n,avg_block", [(2, 8), (3, 1)])
+def test_bf16_fused_update_with_several_probes_matches_the_unfused_path(n, avg_block):
+    """Several Hutchinson probes per step with fused layers: the weight-gradient kernels keep the running sum of
+    z_j * Hz_j of their layers and the last probe's applies the update.  The unfused path with the same n (checked
+    against the oracle by test_several_hutchinson_probes_per_step) adds the same terms in the same order."""
+    dims, batch, k = (512, 2048, 1024, 10), 128, 8
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=5150 + n, bf16=True, avg_block=avg_block)
+    theta0 = W.init_theta(w.dims, w.seed)
+    hA = B.Handle(B.config_from_workload(w, n_samples=n), theta0)
+    hB = B.Handle(B.config_from_workload(w, n_samples=n, fuse_update=1), theta0)
+    assert B.lib().dw_workspace_bytes(C.byref(hB.cfg)) > B.lib().dw_workspace_bytes(C.byref(hA.cfg))   # a layer is fused
+    x, y = W.minibatch_pool(w, 3, bf16_round=W.to_bf16_f32)
+    for step, active in ((0, [1] * k), (1, [1, 1, 0, 1, 1, 1, 1, 1]), (2, [1] * k)):
+        prev = hA.all_state(B.DW_S_THETA)
+        xb, yb = _to_bf16_bits(x[step]), torch.from_numpy(y[step]).cuda()
+        lossA, lossB = torch.zeros(k, device="cuda"), torch.zeros(k, device="cuda")
+        hA.worker_step(xb, yb, loss=lossA, active=active)
+        hB.worker_step(xb, yb, loss=lossB, active=active)
+        np.testing.assert_array_equal(lossA.cpu().numpy(), lossB.cpu().numpy())
+        for i in range(k):
+            thA, mA, vA = (hA.get_state(s, i) for s in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V))
+            thB, mB, vB = (hB.get_state(s, i) for s in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V))
+            assert int(hB.get_state(B.DW_S_STEPS, i)[0]) == int(hA.get_state(B.DW_S_STEPS, i)[0])
+            if not active[i]:
+                np.testing.assert_array_equal(thB, prev[i])
+                np.testing.assert_array_equal(thB, thA)
+                continue
+            assert np.any(thA != prev[i])
+            close(thB - prev[i], thA - prev[i], 1e-6, "probes fused vs unfused update[%d] step %d" % (i, step),
+                  extra=2.0 ** -23 * np.abs(thA))
+            close(mB, mA, 1e-6, "probes fused vs unfused m[%d]" % i)
+            close(vB, vA, 1e-6, "probes fused vs unfused v[%d]" % i)
+        if step == 1:
+            assert hA.elastic_sync(B.DW_DYNAMIC, tau=1) == 1 and hB.elastic_sync(B.DW_DYNAMIC, tau=1) == 1
+            for i in range(k):
+                sa, sb = hA.get_state(B.DW_S_SCORE, i), hB.get_state(B.DW_S_SCORE, i)
+                assert abs(sa[0] - sb[0]) < 1e-6 and abs(sa[2] - sb[2]) < 1e-5 and abs(sa[3] - sb[3]) < 1e-5, (i, sa, sb)
+            close(hB.get_state(B.DW_S_CENTRE), hA.get_state(B.DW_S_CENTRE), 1e-6, "probes fused vs unfused centre")
     hA.close(); hB.close()
 
 

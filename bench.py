@@ -305,7 +305,7 @@ def main():
     value = w.k * args.steps / elapsed
 
     fl = class_flops(w)
-    fused = fused_layers(w, not args.no_fuse and (args.samples <= 1 or w.bf16))     # fp32 fuses one-probe steps only
+    fused = fused_layers(w, not args.no_fuse)
     if args.samples > 1:
         fl = {c: v * args.samples for c, v in fl.items()}
     by = class_bytes(w, w.P, w.k, fused, part, args.samples)

@@ -108,9 +108,9 @@ typedef struct {
                                        estimate; the experiments use 1).  0 or 1: one probe.  Up to DW_MAX_SAMPLES:
                                        D is the mean of z_j*(Hz_j); probe j of a worker's step t comes from
                                        position t*n + j of its stream; the network runs once per probe and
-                                       dw_worker_step takes no caller-supplied z.  With fuse_update = 1 only
-                                       DW_BF16 handles fuse (the weight-gradient kernels then keep the running
-                                       sum of z_j*(Hz_j) of their layers); DW_F32 handles run unfused.          */
+                                       dw_worker_step takes no caller-supplied z.  With fuse_update = 1 the
+                                       weight-gradient kernels keep the running sum of z_j*(Hz_j) of their
+                                       layers and the last probe's applies the update.                         */
   int32_t fuse_update;              /* 0: g and Hz of the last dw_worker_step stay readable (DW_S_G, DW_S_HZ).
                                        1: the library may apply the update of a weight matrix inside the kernel
                                           that produces its gradient; the W-parts of g and Hz of such layers are

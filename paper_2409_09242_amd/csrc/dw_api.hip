@@ -195,8 +195,7 @@ int validate(const dw_config* c, Layout* lay) {
   for (int l = 1; l <= L; ++l) {
     lay->fuse_base[l - 1] = -1;
     const bool b16 = c->dtype == DW_BF16;
-    // several probes: the bf16 kernel keeps the running sum of z*Hz itself; the fp32 kernel does not
-    if (!c->fuse_update || (c->n_samples > 1 && !b16)) continue;
+    if (!c->fuse_update) continue;
     if (b16 ? gemm_bf16_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])
             : gemm_f32_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])) {
       lay->fuse_base[l - 1] = lay->n_fuse_slots;

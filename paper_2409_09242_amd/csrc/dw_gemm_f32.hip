@@ -104,7 +104,7 @@ struct TileLoader {
   }
 };
 
-template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI>
+template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0>
 __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
   static_assert(WM * WN == 4, "four waves per block");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -216,9 +216,16 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
     const karg_floats bc = (karg_floats)(ka + offsetof(GemmArgs, fu) + offsetof(FuseArgs, sc));
     const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];    // scalar loads from the kernel-argument block
     static_assert(offsetof(UpdateScalars, inv_bc2) == DW_MAX_K * sizeof(float), "inv_bc2 follows inv_bc1");
-    const float nsum = fused_update_wave_tile<TM, false>(acc, racc, fused_lds + wave * fused_update_lds_floats(), f,
-                                                         (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
-                                                         zb + (a.z_off >> 5), ib1, ib2, lane);
+    // FM: 0 one Hutchinson probe; 1 a probe before the last (only the running sum of z*Hz is written); 2 the last
+    // of several probes
+    float nsum = 0.f;
+    if constexpr (FM == 1)
+      fused_probe_sum_wave_tile<TM>(racc, fused_lds + wave * fused_update_lds_floats(), f, (int64_t)worker * a.c_wstride,
+                                    a.ldc, row0 + wm0, col0 + wn0, zb + (a.z_off >> 5), lane);
+    else
+      nsum = fused_update_wave_tile<TM, false, FM == 2>(acc, racc, fused_lds + wave * fused_update_lds_floats(), f,
+                                                        (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
+                                                        zb + (a.z_off >> 5), ib1, ib2, lane);
     double ws = (double)nsum;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) ws += __shfl_xor(ws, off);
@@ -355,15 +362,16 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
 }
 
 // weight gradient that applies the update itself: 128 x 128 tiles, dynamic LDS for the epilogue's per-wave regions
-static hipError_t launch_fused_wgrad(const GemmArgs& a, hipStream_t s) {
+template <int FM>
+static hipError_t launch_fused_wgrad_mode(const GemmArgs& a, hipStream_t s) {
   const int tiles = (a.M / 128) * (a.N / 128);
   const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k)), block(NT);
   constexpr int smem = (NT / 64) * fused_update_lds_floats() * (int)sizeof(float);
   static bool configured_on[64] = {false};
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  auto with_ry = dual_gemm_f32<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD_FUSED>;
-  auto without_ry = dual_gemm_f32<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD_FUSED>;
+  auto with_ry = dual_gemm_f32<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD_FUSED, FM>;
+  auto without_ry = dual_gemm_f32<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD_FUSED, FM>;
   if (!configured_on[dev]) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(with_ry), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e == hipSuccess)
@@ -374,6 +382,13 @@ static hipError_t launch_fused_wgrad(const GemmArgs& a, hipStream_t s) {
   if (a.RY) hipLaunchKernelGGL(with_ry, grid, block, smem, s, a);
   else hipLaunchKernelGGL(without_ry, grid, block, smem, s, a);
   return hipGetLastError();
+}
+
+// several Hutchinson probes: own instances for the probes before the last and for the last one
+static hipError_t launch_fused_wgrad(const GemmArgs& a, hipStream_t s) {
+  if (a.fu.probe_mode == 1) return launch_fused_wgrad_mode<1>(a, s);
+  if (a.fu.probe_mode == 2) return launch_fused_wgrad_mode<2>(a, s);
+  return launch_fused_wgrad_mode<0>(a, s);
 }
 
 // The fp32 weight-gradient product of W[n_out][n_in] can apply the update in its epilogue when W is made of whole

@@ -126,7 +126,7 @@ struct FuseArgs {
   int avg_block;                      // power of two, 1..32
   float lr, beta1, beta2, eps, hpow;
   UpdateScalars sc;
-  // several Hutchinson probes (bf16 product only).  0: one probe.  1: a probe that is not the last, only
+  // several Hutchinson probes.  0: one probe.  1: a probe that is not the last, only
   // dacc (+)= z*Hz is written (first: stored, not added).  2: the last probe, D = (dacc + z*Hz) * d_scale
   int probe_mode, first;
   float* dacc;                        // the layer's W block of worker 0 in the running sum, worker stride c_wstride

@@ -269,7 +269,8 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.yb[j], acc[i][j], 0, 0, 0);
+        if (FM != 1)                                         // (a probe before the last only needs the R-products)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.yb[j], acc[i][j], 0, 0, 0);
     if (HAS_RX) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -334,7 +335,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   }
 
   // epilogue: lane holds column n = l32 of each 32x32 tile, rows (r/4)*8 + lhalf*4 + r%4
-  if (EPI == EPI_WGRAD && a.fu.on) {
+  if (EPI == EPI_WGRAD && (FM != 0 || a.fu.on)) {           // (the instances for several probes are always fused)
     // The update of Section IV-B applied to the tile while g and Hz are still in registers (same arithmetic as
     // update_kernel, Hessian power 1).  Element (m, n) is parameter m*ldc + n of the layer's W block; the 32
     // lanes of a half-wave hold 32 consecutive n of one row, so the sign bits of a row segment are one word and

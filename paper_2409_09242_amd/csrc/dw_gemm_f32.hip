@@ -195,7 +195,8 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[i], yb[j], acc[i][j], 0, 0, 0);
+          // (a Hutchinson probe before the last, FM == 1, only needs the R-products)
+          if (FM != 1) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[i], yb[j], acc[i][j], 0, 0, 0);
           if (HAS_RX) racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(rxa[i], yb[j], racc[i][j], 0, 0, 0);
           if (RYM != RY_NONE) racc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(xa[i], ryb[j], racc[i][j], 0, 0, 0);
         }

@@ -29,6 +29,7 @@ SHAPES = [
     ((64, 260, 132, 12), 70, 3),
     ((256, 1024, 1024, 10), 160, 8),       # large tiles
     ((48, 40, 36, 28, 24, 4), 33, 2),      # deep and narrow
+    ((16, 24, 4), 5, 64),                  # the maximum number of workers
 ]
 
 
@@ -206,6 +207,7 @@ BF16_SHAPES = [
     ((512, 2048, 1024, 10), 512, 8),       # large tiles (128 x 256); layer 1 forward and layer 2 data gradient on the global->LDS path
     ((256, 1024, 1024, 10), 512, 16),      # layer 2 forward (with R-operand) and data gradient on the global->LDS path
     ((256, 1024, 1024, 10), 200, 32),      # the same path with a ragged last row tile (200 = 128 + 72 rows)
+    ((16, 24, 8), 6, 64),                  # the maximum number of workers
 ]
 
 

@@ -78,6 +78,49 @@ def test_update_and_dynamic_sync_follow_the_oracle(P, k, avg_block, hpow):
     np.testing.assert_allclose(hist[1:6], tr.u_hist[0], atol=1e-5)
 
 
+def test_maximum_worker_count_and_degenerate_masks():
+    """k = 64 workers (the maximum); a step that nobody takes; a round that nobody joins (every worker still
+    records its distance, Section V-B: the estimate of the master comes from the peers); a single survivor."""
+    P, k = 4096 + 64, 64
+    w, theta0, rng = _flat_case(P, k, 640, avg_block=4)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    tr = O.OracleTrainer(oracle_config(w, dims=None), theta0.astype(np.float64))
+    none, last = [0] * k, [0] * (k - 1) + [1]
+    for step, (active, part) in enumerate(((None, None), (none, None), (None, none), (last, last), (None, None))):
+        g = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+        hz = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+        before = h.all_state(B.DW_S_THETA), h.get_state(B.DW_S_CENTRE)
+        steps_before = [int(h.get_state(B.DW_S_STEPS, i)[0]) for i in range(k)]
+        h.update_only(torch.from_numpy(g).cuda(), torch.from_numpy(hz).cuda(), active=active)
+        tr.update_only(g, hz, active=active)
+        steps_now = [int(h.get_state(B.DW_S_STEPS, i)[0]) for i in range(k)]
+        assert steps_now == [int(t) for t in tr.t]
+        if active is none:
+            np.testing.assert_array_equal(h.all_state(B.DW_S_THETA), before[0])
+            assert steps_now == steps_before
+        _compare_state(h, tr, ("theta", "m", "v"), tag="step %d" % step)
+        mid = h.all_state(B.DW_S_THETA)
+        assert h.elastic_sync(B.DW_DYNAMIC, tau=1, participate=part) == 1
+        assert tr.elastic_sync(O.MODE_DYNAMIC, tau=1, participate=part)
+        for i in range(k):
+            sc = h.get_state(B.DW_S_SCORE, i)
+            # u = ln(distance): a relative error r of the distance moves u by r, and the updates that make up the
+            # distance are held to RTOL_UPDATE = 1e-4 (with 64 workers the worst of them lands above the 1e-5 that
+            # the smaller cases meet); a is a weighted difference of two u, h has slope (1 - alpha)/|kappa| = 9 in a
+            assert abs(sc[0] - tr.last_u[i]) < 5e-5 and abs(sc[1] - tr.last_a[i]) < 1e-4, (step, i, sc)
+            assert abs(sc[2] - tr.last_h1[i]) < 1e-3 and abs(sc[3] - tr.last_h2[i]) < 1e-3
+        if part is none:                                   # nobody exchanged anything
+            np.testing.assert_array_equal(h.all_state(B.DW_S_THETA), mid)
+            np.testing.assert_array_equal(h.get_state(B.DW_S_CENTRE), before[1])
+        if part is last:                                   # the absent workers keep their parameters bit for bit
+            np.testing.assert_array_equal(h.all_state(B.DW_S_THETA)[:k - 1], mid[:k - 1])
+            assert np.any(h.get_state(B.DW_S_CENTRE) != before[1])
+        _compare_state(h, tr, ("theta", "centre"), tag="sync %d" % step)
+    hist = h.get_state(B.DW_S_U_HIST, k - 1)
+    assert int(hist[0]) == 5                               # five rounds recorded, joined or not
+    np.testing.assert_allclose(hist[1:6], tr.u_hist[k - 1], atol=5e-5)
+
+
 def test_fixed_manual_modes_tau_gating_and_exact_reset():
     P, k = 4096 + 128, 4
     w, theta0, rng = _flat_case(P, k, 5)

@@ -3,6 +3,8 @@ configurations on the host (no kernel is launched here)."""
 import ctypes as C
 import os
 import re
+import shutil
+import subprocess
 
 import numpy as np
 import pytest
@@ -140,3 +142,28 @@ def test_convolutional_configuration_is_validated_on_the_host():
     assert B.lib().dw_workspace_bytes(C.byref(cfg)) > 0
     for kw in (dict(ok, dims=(64, 16, 10)), dict(ok, conv=(4, 6)), dict(ok, img=(9, 10, 1)), dict(ok, bf16=True)):
         assert B.lib().dw_param_count(C.byref(B.make_config(**kw)), C.byref(n)) == -2
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="no C compiler")
+def test_header_is_plain_c_and_a_c_program_can_call_the_library(tmp_path):
+    """include/dw.h compiles as C99, and a C program linked against the library reaches the host-side calls."""
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                    os.path.join(inc, "dw.h")], check=True)
+    libdir = os.path.dirname(B.LIB_PATH)
+    src = tmp_path / "use_dw.c"
+    src.write_text(
+        '#include <stdio.h>\n#include <string.h>\n#include "dw.h"\n'
+        'int main(void) {\n'
+        '  dw_config c; memset(&c, 0, sizeof c);\n'
+        '  c.n_layers = 2; c.dims[0] = 32; c.dims[1] = 64; c.dims[2] = 10; c.k = 4; c.batch = 16; c.dtype = DW_F32;\n'
+        '  c.lr = 0.01f; c.beta1 = 0.9f; c.beta2 = 0.999f; c.eps = 1e-4f; c.hpow = 1.0f; c.avg_block = 1;\n'
+        '  c.alpha = 0.1f; c.kappa = -0.1f; c.p = 1; c.c[0] = 1.0f; c.seed = 1;\n'
+        '  int64_t n = 0; int st = dw_param_count(&c, &n);\n'
+        '  printf("%d %lld %s %zu\\n", st, (long long)n, dw_strerror(DW_ERR_WORKSPACE), dw_workspace_bytes(&c));\n'
+        '  c.k = 0; return dw_param_count(&c, &n) == DW_ERR_CONFIG ? 0 : 1;\n}\n')
+    exe = tmp_path / "use_dw"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-l:" +
+                    os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert out[0] == "0" and int(out[1]) == 32 * 64 + 64 + 64 * 10 + 10 and int(out[-1]) > 0

@@ -52,6 +52,25 @@ def fused_layers(w, fuse):
     return out
 
 
+def r_only_products(w):
+    """(forward layers, data-gradient layers) whose bf16 products run on the global->LDS kernel (the library's rule:
+    whole 256-column tiles that fill the chip, contraction a multiple of 128, a hidden layer with an R-operand); with
+    several Hutchinson probes the probes after the first leave out the plain product there."""
+    if not w.bf16 or w.dims is None or w.conv:
+        return [], []
+    d, L = w.dims, len(w.dims) - 1
+    rows = (w.batch + 127) // 128
+    off, woff = 0, {}
+    for l in range(1, L + 1):
+        woff[l] = off
+        off += d[l] * d[l - 1] + d[l]
+    fwd = [l for l in range(2, L) if w.batch >= 128 and d[l] % 256 == 0 and d[l - 1] % 128 == 0
+           and rows * (d[l] // 256) * w.k >= 256 and woff[l] % 128 == 0]
+    dgrad = [l for l in range(2, L) if w.batch >= 128 and d[l - 1] % 256 == 0 and d[l] % 128 == 0
+             and rows * (d[l - 1] // 256) * w.k >= 256 and woff[l] % 128 == 0]
+    return fwd, dgrad
+
+
 def class_bytes(w, P, k, fused=(), part=1.0, samples=1):
     """Algorithmic HBM bytes per step for the HBM-bound classes.  The update reads g, Hz, theta, m, v and writes
     theta, m, v (32 B per parameter and worker, +2 B for the bf16 weight copy); the pull reads and writes theta
@@ -313,6 +332,13 @@ def main():
         skipped = sum(2.0 * w.batch * w.dims[l] * w.dims[l - 1] for l in fused) * w.k * (args.samples - 1)
         if "gemm_wgrad" in fl:
             fl["gemm_wgrad"] -= skipped
+        # and so do the large forward and data-gradient products of the probes after the first
+        fwd_r, dgrad_r = r_only_products(w)
+        for cls, layers in (("gemm_fwd", fwd_r), ("gemm_dgrad", dgrad_r)):
+            less = sum(2.0 * w.batch * w.dims[l] * w.dims[l - 1] for l in layers) * w.k * (args.samples - 1)
+            if cls in fl:
+                fl[cls] -= less
+                skipped += less
     by = class_bytes(w, w.P, w.k, fused, part, args.samples)
     per_step = {"update": 1, "pull": 1.0 / w.tau, "gemm_wgrad": 1, "gather": 1}
     by["gather"] = 2.0 * w.k * w.batch * w.dims[0] * (2 if w.bf16 else 4)        # every drawn row read and written once

@@ -351,7 +351,9 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
       if (last || j == 0) fill_update_args(h, a, h->at<float>(h->lay.g), dacc, h->lay.Pp, zb, zs, active, fused);
       a.d_scale = 1.0f / (float)n;
       a.probe_mode = last ? 2 : 1; a.probe_first = j == 0 ? 1 : 0; a.dacc = dacc;
-      st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fused ? &a : nullptr, true, s);
+      // probes after the first find the activations and the plain data gradients of this minibatch in the workspace
+      st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fused ? &a : nullptr, true, s, nullptr,
+                       nullptr, nullptr, j > 0);
       if (st != DW_OK) return st;
       DW_HIP(launch_probe_sum(dacc, h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->cfg.k, active, j == 0 ? 1 : 0,
                               a.fused, s));

@@ -112,29 +112,34 @@ struct DmaTileK {
   // wait for every outstanding global -> LDS load (it cannot tell that they read other stages), which serialises the
   // pipeline.  The price: the compiler does not know when their results arrive.  The kernel waits for its LDS reads
   // explicitly (the waits it needs anyway before a barrier or a multiply) and then passes the registers through
-  // `settle`, which pins every use behind that wait.
-  __device__ static __forceinline__ bf16x8 frag(const char* lds, int row0, int ks, int lane) {
+  // `settle`, which pins every use behind that wait.  Between the read and `settle` the two halves stay the
+  // read's own output registers (Raw): nothing is computed from them, not even the 16-byte operand they form, so
+  // the compiler has no reason to copy a register whose value has not arrived yet.
+  struct Raw { uint2 lo, hi; };
+  __device__ static __forceinline__ Raw frag_raw(const char* lds, int row0, int ks, int lane) {
     const int s = lane & 15, kq = s >> 2;
     const int k = ks * 16 + (lane >> 5) * 8 + kq;           // k%4 == kq; the second read is 4 k-rows further on
     const int lp = (row0 >> 4) + ((lane >> 4) & 1);
     const uint32_t addr = (uint32_t)(uintptr_t)(lds_char)(lds + k * (R * 2) + ((lp ^ (kq << 1)) << 5) + (s & 3) * 8);
-    uint2 lo, hi;
-    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(addr));
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"(4 * R * 2));
-    return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+    Raw r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(r.lo) : "v"(addr));
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r.hi) : "v"(addr), "n"(4 * R * 2));
+    return r;
   }
-  __device__ static __forceinline__ void settle(bf16x8& f) {
-    uint4 u = __builtin_bit_cast(uint4, f);
-    asm volatile("" : "+v"(u.x), "+v"(u.y), "+v"(u.z), "+v"(u.w));
-    f = __builtin_bit_cast(bf16x8, u);
+  __device__ static __forceinline__ bf16x8 settle(Raw& r) {  // after the wait for this wave's LDS reads
+    asm volatile("" : "+v"(r.lo), "+v"(r.hi));
+    return __builtin_bit_cast(bf16x8, make_uint4(r.lo.x, r.lo.y, r.hi.x, r.hi.y));
   }
 };
 
 // DGRAD = false: forward product, Y = W stored [n][k], epilogue bias + ReLU.
 // DGRAD = true: data gradient, Y = W stored [k][n] (k = the layer's outputs), sign bits from the transposed copy of
 // z's W-part (bit (n, k) at z_off + n*K + k), epilogue = the ReLU mask of the layer below.
-template <bool HAS_RX, bool DGRAD>
+// RONLY: only the R-companion RC is computed and stored (a later Hutchinson probe of the same minibatch: the plain
+// product C is in memory already, and its stored sign is the forward product's ReLU mask).
+template <bool HAS_RX, bool DGRAD, bool RONLY = false>
 __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
+  static_assert(HAS_RX || !RONLY, "the R-only form is for layers with an R-operand");
   using TX = DmaTile<BM>;
   using TY = typename std::conditional<DGRAD, DmaTileK<BN>, DmaTile<BN>>::type;
   constexpr int X_B = TX::BYTES, Y_B = TY::BYTES;
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; racc[i][j][r] = 0.f; }
 
-  struct Frags { bf16x8 xa[TM], rxa[TM], yb[TN], ryb[TN]; };
+  struct Frags { bf16x8 xa[TM], rxa[TM], yb[TN], ryb[TN]; typename DmaTileK<BN>::Raw yraw[TN]; };
   uint32_t zw[TN], zn[TN];                                  // this lane's 32 sign bits of the current and of the next k-tile, per column tile
   auto read_frags = [&](Frags& f, int st, int ks) {
     const char* base = smem + st * STAGE_B;
@@ -217,12 +222,15 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
       if (HAS_RX) f.rxa[i] = TX::frag(base + OFF_RX, wm0 + i * 32, ks, lane);
     }
 #pragma unroll
-    for (int j = 0; j < TN; ++j) f.yb[j] = TY::frag(base + OFF_Y, wn0 + j * 32, ks, lane);
+    for (int j = 0; j < TN; ++j) {
+      if constexpr (DGRAD) f.yraw[j] = TY::frag_raw(base + OFF_Y, wn0 + j * 32, ks, lane);
+      else f.yb[j] = TY::frag(base + OFF_Y, wn0 + j * 32, ks, lane);
+    }
   };
   auto settle = [&](Frags& f) {                             // after a wait for this wave's LDS reads
     if constexpr (DGRAD) {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) TY::settle(f.yb[j]);
+      for (int j = 0; j < TN; ++j) f.yb[j] = TY::settle(f.yraw[j]);
     }
   };
   auto read_bits = [&](int kt) {
@@ -243,7 +251,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.yb[j], acc[i][j], 0, 0, 0);
+        if (!RONLY) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.xa[i], f.yb[j], acc[i][j], 0, 0, 0);
     if (HAS_RX) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
@@ -276,7 +284,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
 
   // Scheduling groups: after every multiply, one LDS read or one global load (while there are any) and two vector
   // instructions (address arithmetic, sign expansion) of the code that prepares the next k-step.
-  constexpr int N_MFMA = TM * TN * (HAS_RX ? 3 : 2);        // multiplies per k-step
+  constexpr int N_MFMA = TM * TN * ((HAS_RX ? 3 : 2) - (RONLY ? 1 : 0));   // multiplies per k-step
   constexpr int N_DS = TM * (HAS_RX ? 2 : 1) + TN;          // operand reads from LDS per k-step
   auto interleave = [&](auto n_vmem_, auto n_ds_) {
     constexpr int n_vmem = decltype(n_vmem_)::value, n_ds = decltype(n_ds_)::value;
@@ -336,7 +344,9 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
   // applied while the rows leave.  The two bf16 outputs go through LDS (free after the barrier above) so that they
   // leave as 16-byte stores of whole row pieces (see dw_gemm_epi.h)
   char* wl = smem + wave * epi_bf16_lds_bytes(TN);
-  const uint16_t* msk = DGRAD ? reinterpret_cast<const uint16_t*>(a.mask_src) + (int64_t)worker * a.mask_wstride : nullptr;
+  const uint16_t* msk = DGRAD ? reinterpret_cast<const uint16_t*>(a.mask_src) + (int64_t)worker * a.mask_wstride
+                        : RONLY ? reinterpret_cast<const uint16_t*>(a.C) + (int64_t)worker * a.c_wstride : nullptr;
+  const int ld_msk = DGRAD ? a.ld_mask : a.ldc;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     floatx16 cv[TN], rcv[TN];
@@ -352,25 +362,26 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float c = acc[i][j][r] + bias, rc = racc[i][j][r] + cz;
-          const bool on = c > 0.f;
+          const bool on = RONLY || c > 0.f;                 // (R-only: masked by the stored activation as the row leaves)
           cv[j][r] = on ? c : 0.f; rcv[j][r] = on ? rc : 0.f;
         }
       }
     }
     const int rbase = row0 + wm0 + i * 32, cbase = col0 + wn0;
-    epi_bf16_rows_out<TN, DGRAD>(wl, cv, rcv, lane, reinterpret_cast<uint16_t*>(a.C), reinterpret_cast<uint16_t*>(a.RC),
-                                 (int64_t)worker * a.c_wstride + (int64_t)rbase * a.ldc + cbase, a.ldc, a.M - rbase,
-                                 a.N - cbase, msk, (int64_t)rbase * a.ld_mask + cbase, a.ld_mask);
+    epi_bf16_rows_out<TN, DGRAD || RONLY, !RONLY>(wl, cv, rcv, lane, reinterpret_cast<uint16_t*>(a.C),
+                                                  reinterpret_cast<uint16_t*>(a.RC),
+                                                  (int64_t)worker * a.c_wstride + (int64_t)rbase * a.ldc + cbase, a.ldc,
+                                                  a.M - rbase, a.N - cbase, msk, (int64_t)rbase * ld_msk + cbase, ld_msk);
   }
 }
 
-template <bool RX, bool DGRAD>
+template <bool RX, bool DGRAD, bool RONLY = false>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * (a.N / BN);
   const dim3 grid((unsigned)((tiles * active_count(a.active_mask, a.k) + 7) / 8 * 8)), block(NT);
   constexpr int smem = (BM * BK * 2 * (RX ? 2 : 1) + BN * BK * 2) * STAGES + 2 * BN * 16;
   static_assert(smem <= 160 * 1024, "LDS budget");
-  auto kern = dual_gemm_bf16_dma<RX, DGRAD>;
+  auto kern = dual_gemm_bf16_dma<RX, DGRAD, RONLY>;
   // raise the dynamic LDS limit once per instantiation and device (the attribute belongs to the device's code object)
   static bool configured_on[64] = {false};
   int dev = 0;
@@ -408,8 +419,9 @@ bool gemm_bf16_dma_ok(const GemmArgs& a) {
 }
 
 hipError_t launch_gemm_bf16_dma(const GemmArgs& a, hipStream_t s) {
-  if (a.epi == EPI_MASK) return b16d::launch_one<true, true>(a, s);
-  return a.RX ? b16d::launch_one<true, false>(a, s) : b16d::launch_one<false, false>(a, s);
+  if (a.epi == EPI_MASK) return a.r_only ? b16d::launch_one<true, true, true>(a, s) : b16d::launch_one<true, true>(a, s);
+  if (a.RX) return a.r_only ? b16d::launch_one<true, false, true>(a, s) : b16d::launch_one<true, false>(a, s);
+  return b16d::launch_one<false, false>(a, s);
 }
 
 }  // namespace dw

@@ -31,7 +31,8 @@ constexpr int epi_bf16_lds_bytes(int tn) { return 2 * 32 * (tn * 64 + 16); }    
 // cv, rcv: the TN accumulator tiles of the row, already with bias / activation applied (fp32)
 // out0: element offset of the tile row's first element in C and RC; rows_left, cols_left: valid extent from there
 // MASK: keep an element only where mask[msk0 + row*ld_mask + col] > 0 (same shape as the outputs)
-template <int TN, bool MASK>
+// STORE_C = false: only RC is written (cv is not read)
+template <int TN, bool MASK, bool STORE_C = true>
 __device__ __forceinline__ void epi_bf16_rows_out(char* wl, const epi_floatx16* cv, const epi_floatx16* rcv, int lane,
                                                   uint16_t* C, uint16_t* RC, int64_t out0, int ldc, int rows_left,
                                                   int cols_left, const uint16_t* msk, int64_t msk0, int ld_mask) {
@@ -43,7 +44,7 @@ __device__ __forceinline__ void epi_bf16_rows_out(char* wl, const epi_floatx16* 
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int off = ((r >> 2) * 8 + lhalf * 4 + (r & 3)) * RS + (j * 32 + l32) * 2;
-      *reinterpret_cast<uint16_t*>(wl + off) = epi_f2bf(cv[j][r]);
+      if (STORE_C) *reinterpret_cast<uint16_t*>(wl + off) = epi_f2bf(cv[j][r]);
       *reinterpret_cast<uint16_t*>(wr + off) = epi_f2bf(rcv[j][r]);
     }
   constexpr int LPR = TN * 4, RPP = 64 / LPR;                 // lanes per row, rows per pass
@@ -51,7 +52,7 @@ __device__ __forceinline__ void epi_bf16_rows_out(char* wl, const epi_floatx16* 
 #pragma unroll
   for (int p = 0; p < 32 / RPP; ++p) {
     const int row = p * RPP + prow;
-    uint4 v = *reinterpret_cast<const uint4*>(wl + row * RS + ch * 16);
+    uint4 v = STORE_C ? *reinterpret_cast<const uint4*>(wl + row * RS + ch * 16) : make_uint4(0u, 0u, 0u, 0u);
     uint4 rv = *reinterpret_cast<const uint4*>(wr + row * RS + ch * 16);
     if (row < rows_left && ch * 8 < cols_left) {
       if (MASK) {
@@ -60,7 +61,7 @@ __device__ __forceinline__ void epi_bf16_rows_out(char* wl, const epi_floatx16* 
         v.x &= k0; v.y &= k1; v.z &= k2; v.w &= k3;
         rv.x &= k0; rv.y &= k1; rv.z &= k2; rv.w &= k3;
       }
-      *reinterpret_cast<uint4*>(C + out0 + (int64_t)row * ldc + ch * 8) = v;
+      if (STORE_C) *reinterpret_cast<uint4*>(C + out0 + (int64_t)row * ldc + ch * 8) = v;
       *reinterpret_cast<uint4*>(RC + out0 + (int64_t)row * ldc + ch * 8) = rv;
     }
   }

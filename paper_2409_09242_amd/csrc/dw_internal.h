@@ -161,6 +161,7 @@ struct GemmArgs {
   // partial bias sums (weight gradient) to part_b + ((s*k + i)*2 + {0,1})*M; a second kernel adds the slices in order and
   // applies the epilogue (bias, ReLU) into C, RC, gb, hzb
   int ksplit; float* part; int64_t part_stride; float* part_b;
+  int r_only;                         // 1: C is in memory already (an earlier probe of this minibatch); kernels may compute RC alone
   int epi;
   int k;
   uint64_t active_mask;
@@ -240,7 +241,9 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
                 bool fuse_dist, hipStream_t s, const void* in_ract = nullptr, void* d_in = nullptr,
-                void* rd_in = nullptr);
+                void* rd_in = nullptr, bool r_only = false);
+// `r_only`: the same minibatch went through the network before (an earlier Hutchinson probe of this step), so the
+// activations and the plain data gradients are in the workspace; kernels that can then compute the R-parts alone.
 // `in_ract` above: directional derivative of the input (nullptr: the input does not depend on the parameters).
 // `d_in`, `rd_in`: when given, the gradient with respect to the input and its R-companion ([k][B][d_0], zero where
 // the input is not positive: the input is then the ReLU output of a layer in front).

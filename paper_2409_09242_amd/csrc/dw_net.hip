@@ -98,7 +98,7 @@ hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
-                bool fuse_dist, hipStream_t s, const void* in_ract, void* d_in, void* rd_in) {
+                bool fuse_dist, hipStream_t s, const void* in_ract, void* d_in, void* rd_in, bool r_only) {
   const bool b16 = cfg.dtype == DW_BF16;
   const int L = cfg.n_layers, k = cfg.k, B = cfg.batch;
   const int HL = DW_MAX_CLASSES;                     // row stride of the output-layer buffers
@@ -139,7 +139,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.bias = theta + lay.boff[l - 1]; a.bias_wstride = lay.Pp;
     if (l < L) {
       a.C = ws + lay.act[l]; a.RC = ws + lay.ract[l]; a.ldc = cfg.dims[l]; a.c_wstride = act_stride(l);
-      a.epi = EPI_RELU;
+      a.epi = EPI_RELU; a.r_only = r_only ? 1 : 0;
     } else {
       a.C = ws + lay.sL; a.RC = ws + lay.rsL; a.ldc = HL; a.c_wstride = (int64_t)B * HL;
       a.epi = EPI_LINEAR;
@@ -218,7 +218,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.ldc = cfg.dims[l - 1];
     a.c_wstride = act_stride(l - 1);
     a.mask_src = act(l - 1); a.ld_mask = cfg.dims[l - 1]; a.mask_wstride = act_stride(l - 1);
-    a.epi = EPI_MASK; a.k = k; a.active_mask = active;
+    a.epi = EPI_MASK; a.k = k; a.active_mask = active; a.r_only = (r_only && l > 1) ? 1 : 0;
     if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
   }
   // weight gradients

@@ -425,10 +425,13 @@ def test_bf16_fused_update_measures_distances_only_when_a_round_is_due():
 # ---------------------------------------------------------------------------------------------------------
 # Several Rademacher probes per step (Section IV-B's n): D is the mean of z_j * (H z_j).
 # ---------------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("bf16,n", [(False, 3), (False, 2), (True, 4)])
-def test_several_hutchinson_probes_per_step(bf16, n):
-    dims, batch, k = (72, 96, 40, 10), 37 if not bf16 else 40, 3
-    dims = dims if not bf16 else (72, 96, 40, 8)
+@pytest.mark.parametrize("bf16,n,shape", [
+    (False, 3, ((72, 96, 40, 10), 37, 3)), (False, 2, ((72, 96, 40, 10), 37, 3)), (True, 4, ((72, 96, 40, 8), 40, 3)),
+    # layer 2 on the global->LDS kernels: the probes after the first run their R-only form there
+    (True, 2, ((256, 1024, 1024, 10), 512, 16)),
+])
+def test_several_hutchinson_probes_per_step(bf16, n, shape):
+    dims, batch, k = shape
     w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=600 + n, bf16=bf16, avg_block=2)
     theta0 = W.init_theta(w.dims, w.seed)
     h = B.Handle(B.config_from_workload(w, n_samples=n), theta0)
@@ -444,7 +447,7 @@ def test_several_hutchinson_probes_per_step(bf16, n):
         prev = tr.theta.copy()
         xb = _to_bf16_bits(x[step]) if bf16 else torch.from_numpy(x[step]).cuda()
         loss = torch.zeros(k, device="cuda")
-        active = None if step == 0 else [1, 0, 1]
+        active = None if step == 0 else [int(i % 3 != 1) for i in range(k)]
         h.worker_step(xb, torch.from_numpy(y[step]).cuda(), loss=loss, active=active)
         ref_loss = tr.worker_step(x[step], y[step], active=active, tie_band=band, tie_choice=slopes(h, w))
         now_gpu = h.all_state(B.DW_S_THETA)

@@ -167,3 +167,21 @@ def test_header_is_plain_c_and_a_c_program_can_call_the_library(tmp_path):
                     os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
     assert out[0] == "0" and int(out[1]) == 32 * 64 + 64 + 64 * 10 + 10 and int(out[-1]) > 0
+
+
+def test_transposed_lds_reads_are_not_touched_before_their_wait():
+    """The data-gradient kernel reads LDS with transpose reads issued from inline assembly; the build checks in the
+    kernels' own assembly that nothing touches their destination registers before the wait for LDS.  Here: the
+    checker finds a planted copy, and the assembly of the current sources is clean."""
+    from paper_2409_09242_amd import build as BLD
+    planted = ("\n_ZN2dw4b16d18dual_gemm_bf16_dmaILb1ELb1ELb0EEEvNS_8GemmArgsE: ; @kernel\n"
+               "\tds_read_b64_tr_b16 v[60:61], v7\n\tv_mfma_f32_32x32x16_bf16 a[0:15], v[2:5], v[8:11], a[0:15]\n"
+               "\tv_mov_b32_e32 v14, v60\n\ts_waitcnt lgkmcnt(0)\n\tv_mov_b32_e32 v15, v61\n\ts_endpgm\n")
+    found, n = BLD.premature_uses_of_transposed_reads(planted)
+    assert n == 1 and [f[2] for f in found] == ["v_mov_b32_e32 v14, v60"]
+    asm = os.path.join(BLD.OBJ, BLD.ASM_CHECKED + ".s")
+    src = os.path.join(BLD.CSRC, BLD.ASM_CHECKED)
+    if not (os.path.exists(asm) and os.path.getmtime(asm) >= os.path.getmtime(src)):
+        asm = BLD.check_transposed_reads()              # compiles (about a minute)
+    found, n = BLD.premature_uses_of_transposed_reads(open(asm).read())
+    assert n >= 8 and found == []

@@ -28,7 +28,7 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA
 # HBM-side bytes per launch of the fused weight-gradient kernel at configuration 4 (mean of the three launches of
 # a step), from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel (factors 2.00 and 1.00);
 # see profiles/dual_gemm_bf16_c4_mfma_utilisation_hbm_traffic.txt.  Valid only for the kernel as profiled there.
-TRAFFIC_C4_FUSED_WGRAD = 8.30e9
+TRAFFIC_C4_FUSED_WGRAD = 8.31e9
 
 
 def class_flops(w):

@@ -316,19 +316,22 @@ def _fused_against_unfused_and_oracle(dims, batch, k, bf16, avg_block, fused_lay
     hA.close(); hB.close()
 
 
-@pytest.mark.parametrize("n,avg_block,bf16", [(2, 8, True), (3, 1, True), (2, 1, False), (3, 16, False)])
-def test_fused_update_with_several_probes_matches_the_unfused_path(n, avg_block, bf16):
+@pytest.mark.parametrize("n,avg_block,bf16,large", [(2, 8, True, False), (3, 1, True, False), (2, 1, False, False),
+                                                     (3, 16, False, False), (2, 4, True, True)])
+def test_fused_update_with_several_probes_matches_the_unfused_path(n, avg_block, bf16, large):
     """Several Hutchinson probes per step with fused layers: the weight-gradient kernels keep the running sum of
     z_j * Hz_j of their layers and the last probe's applies the update.  The unfused path with the same n (checked
     against the oracle by test_several_hutchinson_probes_per_step) adds the same terms in the same order."""
     dims, batch, k = ((512, 2048, 1024, 10), 128, 8) if bf16 else ((256, 1024, 1024, 10), 64, 8)
+    if large:           # layer 2 on the large-tile kernels (R-only form in the second probe) and fused
+        dims, batch, k = (256, 1024, 1024, 10), 512, 16
     w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=5150 + n, bf16=bf16, avg_block=avg_block)
     theta0 = W.init_theta(w.dims, w.seed)
     hA = B.Handle(B.config_from_workload(w, n_samples=n), theta0)
     hB = B.Handle(B.config_from_workload(w, n_samples=n, fuse_update=1), theta0)
     assert B.lib().dw_workspace_bytes(C.byref(hB.cfg)) > B.lib().dw_workspace_bytes(C.byref(hA.cfg))   # a layer is fused
     x, y = W.minibatch_pool(w, 3, bf16_round=W.to_bf16_f32 if bf16 else None)
-    for step, active in ((0, [1] * k), (1, [1, 1, 0, 1, 1, 1, 1, 1]), (2, [1] * k)):
+    for step, active in ((0, [1] * k), (1, [1, 1, 0] + [1] * (k - 3)), (2, [1] * k)):
         prev = hA.all_state(B.DW_S_THETA)
         xb = _to_bf16_bits(x[step]) if bf16 else torch.from_numpy(x[step]).cuda()
         yb = torch.from_numpy(y[step]).cuda()

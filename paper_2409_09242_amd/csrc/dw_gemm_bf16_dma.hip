@@ -139,7 +139,8 @@ struct DmaTileK {
 // product C is in memory already, and its stored sign is the forward product's ReLU mask).
 template <bool HAS_RX, bool DGRAD, bool RONLY = false>
 __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
-  static_assert(HAS_RX || !RONLY, "the R-only form is for layers with an R-operand");
+  // the R-only form of a layer without an R-operand (the first layer) is X V^T alone: W is not even loaded
+  constexpr bool NO_Y = RONLY && !HAS_RX;
   using TX = DmaTile<BM>;
   using TY = typename std::conditional<DGRAD, DmaTileK<BN>, DmaTile<BN>>::type;
   constexpr int X_B = TX::BYTES, Y_B = TY::BYTES;
@@ -151,7 +152,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
   // vector-memory operations every wave issues per k-tile; the sign-bit fetches (one more operation per wave every
   // fourth k-tile) are left out: counts are only used as "at most n outstanding", operations complete in order, so
   // an uncounted operation makes a wait slightly longer, never too short
-  constexpr int LPT = TX::CPW * (HAS_RX ? 2 : 1) + TY::CPW;
+  constexpr int LPT = TX::CPW * (HAS_RX ? 2 : 1) + (NO_Y ? 0 : TY::CPW);
 
   const int tiles_m = (a.M + BM - 1) / BM;
   const int tiles = tiles_m * (a.N / BN);
@@ -199,9 +200,11 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
       if (HAS_RX)
         __builtin_amdgcn_global_load_lds((glb_void)(grx[c] + (int64_t)kt * BK), (lds_void)(base + OFF_RX + (wave_u * TX::CPW + c) * 1024), 16, 0, 0);
     }
+    if constexpr (!NO_Y) {
 #pragma unroll
-    for (int c = 0; c < TY::CPW; ++c)
-      __builtin_amdgcn_global_load_lds((glb_void)(gy[c] + kt * y_step), (lds_void)(base + OFF_Y + (wave_u * TY::CPW + c) * 1024), 16, 0, kStreamed);
+      for (int c = 0; c < TY::CPW; ++c)
+        __builtin_amdgcn_global_load_lds((glb_void)(gy[c] + kt * y_step), (lds_void)(base + OFF_Y + (wave_u * TY::CPW + c) * 1024), 16, 0, kStreamed);
+    }
   };
 
   floatx16 acc[TM][TN], racc[TM][TN];
@@ -224,7 +227,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       if constexpr (DGRAD) f.yraw[j] = TY::frag_raw(base + OFF_Y, wn0 + j * 32, ks, lane);
-      else f.yb[j] = TY::frag(base + OFF_Y, wn0 + j * 32, ks, lane);
+      else if constexpr (!NO_Y) f.yb[j] = TY::frag(base + OFF_Y, wn0 + j * 32, ks, lane);
     }
   };
   auto settle = [&](Frags& f) {                             // after a wait for this wave's LDS reads
@@ -285,7 +288,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
   // Scheduling groups: after every multiply, one LDS read or one global load (while there are any) and two vector
   // instructions (address arithmetic, sign expansion) of the code that prepares the next k-step.
   constexpr int N_MFMA = TM * TN * ((HAS_RX ? 3 : 2) - (RONLY ? 1 : 0));   // multiplies per k-step
-  constexpr int N_DS = TM * (HAS_RX ? 2 : 1) + TN;          // operand reads from LDS per k-step
+  constexpr int N_DS = TM * (HAS_RX ? 2 : 1) + (NO_Y ? 0 : TN);   // operand reads from LDS per k-step
   auto interleave = [&](auto n_vmem_, auto n_ds_) {
     constexpr int n_vmem = decltype(n_vmem_)::value, n_ds = decltype(n_ds_)::value;
 #pragma unroll
@@ -421,7 +424,7 @@ bool gemm_bf16_dma_ok(const GemmArgs& a) {
 hipError_t launch_gemm_bf16_dma(const GemmArgs& a, hipStream_t s) {
   if (a.epi == EPI_MASK) return a.r_only ? b16d::launch_one<true, true, true>(a, s) : b16d::launch_one<true, true>(a, s);
   if (a.RX) return a.r_only ? b16d::launch_one<true, false, true>(a, s) : b16d::launch_one<true, false>(a, s);
-  return b16d::launch_one<false, false>(a, s);
+  return a.r_only ? b16d::launch_one<false, false, true>(a, s) : b16d::launch_one<false, false>(a, s);
 }
 
 }  // namespace dw

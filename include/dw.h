@@ -119,7 +119,7 @@ typedef struct {
   /* Convolutional front end (Section VI trains a small CNN): n_conv 3x3 convolutions, stride 1, no padding, each
    * followed by ReLU, one 2x2 max-pool after the last, then the flattened map (row, column, channel) feeds the
    * linear layers, so dims[0] must equal (H_out/2)*(W_out/2)*conv_c[n_conv-1].  Needs DW_F32, avg_block = 1,
-   * n_samples <= 1, fuse_update = 0.  The minibatch x is then [k][B][img_h][img_w][img_c] floats (channels last).
+   * fuse_update = 0.  The minibatch x is then [k][B][img_h][img_w][img_c] floats (channels last).
    * Parameters of convolution j come first in the canonical layout: W_j [C_j][K_j] with K_j = 9*C_{j-1} rounded up
    * to a multiple of 4, entry (dy*3 + dx)*C_{j-1} + ci of a row being tap (dy, dx) on input channel ci, the last
    * K_j - 9*C_{j-1} entries of a row padding (they must be 0 in theta_0 and then stay 0); then b_j [C_j]. */

@@ -54,8 +54,8 @@ int validate(const dw_config* c, Layout* lay) {
     if (nc < 0 || nc > DW_MAX_CONV) return DW_ERR_CONFIG;
     lay->n_conv = nc;
     if (nc > 0) {
-      // convolutional front end: fp32, one probe, no fusion; maps shrink by 2 per convolution, the last is pooled 2x2
-      if (c->dtype != DW_F32 || c->fuse_update != 0 || c->n_samples > 1) return DW_ERR_CONFIG;
+      // convolutional front end: fp32, no fusion; maps shrink by 2 per convolution, the last is pooled 2x2
+      if (c->dtype != DW_F32 || c->fuse_update != 0) return DW_ERR_CONFIG;
       if (c->conv_avg != 0 && c->conv_avg != 1) return DW_ERR_CONFIG;
       if (c->img_h < 3 || c->img_w < 3 || c->img_c < 1 || c->img_h > 4096 || c->img_w > 4096 || c->img_c > 1024)
         return DW_ERR_CONFIG;
@@ -352,8 +352,15 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
       a.d_scale = 1.0f / (float)n;
       a.probe_mode = last ? 2 : 1; a.probe_first = j == 0 ? 1 : 0; a.dacc = dacc;
       // probes after the first find the activations and the plain data gradients of this minibatch in the workspace
-      st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fused ? &a : nullptr, true, s, nullptr,
-                       nullptr, nullptr, j > 0);
+      if (h->lay.n_conv > 0) {
+        // the window mean is linear: taken per probe on z_j*Hz_j, it gives the window mean of their mean
+        st = run_network_cnn(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, s);
+        if (st == DW_OK && h->cfg.conv_avg)
+          DW_HIP(launch_conv_window_mean(h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->lay, h->cfg.k, active, s));
+      } else {
+        st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fused ? &a : nullptr, true, s, nullptr,
+                         nullptr, nullptr, j > 0);
+      }
       if (st != DW_OK) return st;
       DW_HIP(launch_probe_sum(dacc, h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->cfg.k, active, j == 0 ? 1 : 0,
                               a.fused, s));

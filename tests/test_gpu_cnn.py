@@ -124,7 +124,7 @@ def test_cnn_configuration_errors():
     bad = [dict(ok, dims=(64, 16, 10)),                 # flatten size does not match
            dict(ok, conv=(4, 6)),                       # channels not a multiple of 4
            dict(ok, img=(9, 10, 1)),                    # odd map before the pooling
-           dict(ok, bf16=True), dict(ok, n_samples=2), dict(ok, fuse_update=1), dict(ok, conv_avg=2)]
+           dict(ok, bf16=True), dict(ok, fuse_update=1), dict(ok, conv_avg=2)]
     for kw in bad:
         assert B.lib().dw_param_count(C.byref(B.make_config(**kw)), C.byref(n)) == -2, kw
     assert B.lib().dw_param_count(C.byref(B.make_config(**dict(ok, avg_block=2))), C.byref(n)) == -3
@@ -168,4 +168,43 @@ def test_cnn_steps_and_rounds_follow_the_oracle():
         np.testing.assert_allclose(sc[2:], want[2:], rtol=5e-3)
     c = h.get_state(B.DW_S_CENTRE)[idx]
     assert np.linalg.norm(c - tr.centre) <= 2e-3 * np.linalg.norm(tr.centre - theta0)
+    h.close()
+
+
+def test_cnn_step_with_two_hutchinson_probes_follows_the_oracle():
+    """n = 2 probes of the same minibatch through the convolutional model: D is the mean over the probes of the
+    window-averaged z_j * Hz_j (the averaging is linear, so it can be taken per probe), then one update and a round."""
+    spec, batch, k = SPECS["two_conv"]
+    theta0, _, _ = _inputs(spec, batch, k, 100)
+    offs, P = spec.offsets()
+    idx, P_lib = B.conv_param_index(spec.img, spec.conv, spec.fc)
+    n, seed = 2, 11
+    cfg = B.make_config(dims=(spec.flat,) + spec.fc, k=k, batch=batch, img=spec.img, conv=spec.conv, conv_avg=1,
+                        seed=seed, lr=0.01, eps=1e-4, n_samples=n)
+    th_lib = np.zeros(P_lib, dtype=np.float32); th_lib[idx] = theta0
+    h = B.Handle(cfg, th_lib, DEV)
+    tr = O.OracleTrainer(O.OracleConfig(dims=None, k=k, n_params=P, lr=0.01, eps=1e-4, seed=seed), theta0.copy())
+    rng = W.rng_for(26, 1)
+    for step in range(2):
+        x = rng.uniform(0, 1, size=(k, batch) + spec.img).astype(np.float32)
+        y = rng.integers(0, spec.fc[-1], size=(k, batch)).astype(np.int32)
+        h.worker_step(torch.from_numpy(x).to(DEV), torch.from_numpy(y).to(DEV))
+        g_all, d_all = [], []
+        for i in range(k):
+            D = np.zeros(P)
+            for j in range(n):
+                # probe j of the worker's step t sits at position t*n + j of its stream (library index space)
+                z = O.words_to_signs(O.rademacher_words(seed, i, step * n + j, P_lib), P_lib)[idx]
+                _, g, hz, margin = OC.grad_and_hvp(tr.theta[i], x[i], y[i], spec, z)
+                assert margin > 1e-6
+                D += OC.spatial_average(z * hz, spec) / n
+            np.testing.assert_array_equal(_signs(h.get_state(B.DW_S_ZBITS, i), P_lib)[idx], z)   # the last probe's bits
+            g_all.append(g); d_all.append(D)
+        tr.update_only(np.stack(g_all), np.stack(d_all), z_signs=np.ones((k, P)))
+        assert h.elastic_sync(B.DW_DYNAMIC, tau=1) and tr.elastic_sync(O.MODE_DYNAMIC, tau=1)
+    for i in range(k):
+        th = h.get_state(B.DW_S_THETA, i)[idx]
+        assert np.linalg.norm(th - tr.theta[i]) <= 2e-3 * np.linalg.norm(tr.theta[i] - theta0), i
+        sc = h.get_state(B.DW_S_SCORE, i)
+        assert abs(sc[0] - tr.last_u[i]) <= 5e-4 and abs(sc[1] - tr.last_a[i]) <= 1e-3, (sc, tr.last_u[i], tr.last_a[i])
     h.close()

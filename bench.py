@@ -306,10 +306,12 @@ def main():
         return 2
 
     import torch
+    from paper_2409_09242_amd import build as BLD
     from paper_2409_09242_amd import workloads as W
     if not torch.cuda.is_available():
         print("no GPU visible", file=sys.stderr)
         return 3
+    BLD.ensure_built()                      # loads what is built; builds only when nothing is
     if args.stress_only:
         print(json.dumps({"update_stress": run_update_stress()}))
         return 0

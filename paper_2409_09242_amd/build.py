@@ -119,5 +119,11 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build the library when none is there (tests, the smoke check and the benchmark call this; they never rebuild
+    an existing one).  The binding itself does not: without a library it raises."""
+    return LIB if os.path.exists(LIB) else build(verbose=True)
+
+
 if __name__ == "__main__":
     build()

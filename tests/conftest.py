@@ -10,3 +10,10 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _library_is_built():
+    """The tests load the library that is built; only when there is none do they build it first."""
+    from paper_2409_09242_amd import build
+    build.ensure_built()

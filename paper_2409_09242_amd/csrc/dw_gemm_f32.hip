@@ -145,7 +145,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
   float gb_acc = 0.f, hzb_acc = 0.f;     // EPI_WGRAD: column sums of X and RX (bias gradients)
 
   // the slice of the contraction this block covers (all of it unless the weight gradient is cut along k)
-  const bool sliced = (EPI == EPI_WGRAD || EPI == EPI_RELU || EPI == EPI_LINEAR) && a.ksplit > 1;
+  const bool sliced = (EPI == EPI_WGRAD || EPI == EPI_RELU || EPI == EPI_LINEAR || EPI == EPI_MASK) && a.ksplit > 1;
   const int kchunk = sliced ? ((a.K + a.ksplit - 1) / a.ksplit + BK - 1) / BK * BK : a.K;
   const int kbeg = sliced ? (int)blockIdx.z * kchunk : 0;
   const int kend = sliced ? (kbeg + kchunk < a.K ? kbeg + kchunk : a.K) : a.K;
@@ -320,6 +320,9 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(GemmArgs a) {
       c += a.bias[(int64_t)worker * a.bias_wstride + n];
       rc += ((zb[bi >> 5] >> (bi & 31)) & 1u) ? 1.f : -1.f;
       if (a.epi == EPI_RELU && !(c > 0.f)) { c = 0.f; rc = 0.f; }
+    } else if (a.epi == EPI_MASK) {
+      const float* msk = reinterpret_cast<const float*>(a.mask_src) + (int64_t)worker * a.mask_wstride;
+      if (!(msk[(e / a.ldc) * a.ld_mask + n] > 0.f)) { c = 0.f; rc = 0.f; }
     }
     reinterpret_cast<float*>(a.C)[(int64_t)worker * a.c_wstride + e] = c;
     reinterpret_cast<float*>(a.RC)[(int64_t)worker * a.c_wstride + e] = rc;
@@ -338,7 +341,7 @@ __global__ __launch_bounds__(256) void sum_slices_kernel(GemmArgs a) {
 template <int BM, int BN, int WM, int WN>
 static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
-  const bool sliced = (a.epi == EPI_WGRAD || a.epi == EPI_RELU || a.epi == EPI_LINEAR) && a.ksplit > 1;
+  const bool sliced = (a.epi == EPI_WGRAD || a.epi == EPI_RELU || a.epi == EPI_LINEAR || a.epi == EPI_MASK) && a.ksplit > 1;
   const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k), (unsigned)(sliced ? a.ksplit : 1)), block(NT);
 #define DW_LAUNCH(XKC, YKC, RX, RYM, EPI) \
   hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>), grid, block, 0, s, a)

@@ -215,6 +215,7 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   bool zt_layer[DW_MAX_LAYERS] = {false};   // index l-1: the data gradient through W_l reads the transposed bits
   size_t dacc = 0;                    // [k][Pp] floats, n_samples > 1 only: sum over the probes of z_j*Hz_j
   int fwdSplit[DW_MAX_LAYERS] = {0};   // fp32: slices of layer l+1's forward contraction (0 or 1: not cut)
+  int dgSplit[DW_MAX_LAYERS] = {0};    // fp32: slices of the data gradient through W_{l+1} (0 or 1: not cut)
   int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
   int n_fuse_slots = 0;
   size_t partials_f = 0;              // [k][n_fuse_slots] doubles

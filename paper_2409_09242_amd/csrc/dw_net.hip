@@ -219,6 +219,10 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.c_wstride = act_stride(l - 1);
     a.mask_src = act(l - 1); a.ld_mask = cfg.dims[l - 1]; a.mask_wstride = act_stride(l - 1);
     a.epi = EPI_MASK; a.k = k; a.active_mask = active; a.r_only = (r_only && l > 1) ? 1 : 0;
+    if (!b16 && l > 1 && lay.dgSplit[l - 1] > 1) {      // long contraction, few output tiles
+      a.ksplit = lay.dgSplit[l - 1]; a.part = reinterpret_cast<float*>(ws + lay.cPart);
+      a.part_stride = (int64_t)B * a.ldc; a.part_b = nullptr;
+    }
     if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
   }
   // weight gradients

@@ -115,9 +115,9 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
   const float inv_b = 1.0f / (float)a.avg_block;
   const int group_lanes = a.avg_block >> 2;           // lanes that share one averaging block (when b > 4)
 
-  // a listed launch spreads the workers over the grid's second dimension: few chunks, so the chain of k dependent
-  // memory round trips per block would otherwise set the kernel's duration
-  const int i0 = a.n_list > 0 ? (int)blockIdx.y : 0, i1 = a.n_list > 0 ? i0 + 1 : a.k;
+  // a launch of few chunks spreads the workers over the grid's second dimension: the chain of k dependent memory
+  // round trips per block would otherwise set the kernel's duration
+  const int i0 = gridDim.y > 1 ? (int)blockIdx.y : 0, i1 = gridDim.y > 1 ? i0 + 1 : a.k;
   for (int i = i0; i < i1; ++i) {
     const bool active = (a.active_mask >> i) & 1ull;
     float nsum = 0.f;
@@ -245,6 +245,9 @@ hipError_t launch_update(const UpdateArgs& args, int n_blocks, hipStream_t s) {
       a.n_list = n; grid = n; grid_y = a.k;
     }
   }
+  // few chunks (small models): one worker per block row as well; with many chunks a block walks through the workers
+  // and reads its piece of the centre once
+  if (a.n_list == 0 && n_blocks < 1024 && a.k > 1) grid_y = a.k;
   if (a.wb16)
     hipLaunchKernelGGL(update_kernel<true>, dim3(grid, grid_y), dim3(kUpdThreads), 0, s, a);
   else

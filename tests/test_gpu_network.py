@@ -542,3 +542,28 @@ def test_training_reduces_the_loss_with_suppressed_communication(bf16):
     assert bool(np.all(np.isfinite(losses)))
     assert bool(np.all(last < 0.7 * first)), (first, last)
     h.close()
+
+
+@pytest.mark.parametrize("bf16", [True, False])
+def test_two_runs_of_the_same_steps_give_the_same_bits(bf16):
+    """No kernel on the path adds floating-point terms in an order that depends on timing (slices, partial tiles and
+    distance partial sums are added in index order, the centre reduction is one thread per element): two handles fed
+    the same inputs end with bit-identical parameters, moments, centre and scores."""
+    dims, batch, k = ((256, 1024, 1024, 10), 512, 16) if bf16 else ((784, 512, 512, 10), 128, 4)
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=31337, bf16=bf16, avg_block=4, tau=2, stale="third")
+    theta0 = W.init_theta(w.dims, w.seed)
+    x, y = W.minibatch_pool(w, 2, bf16_round=W.to_bf16_f32 if bf16 else None)
+    xs = [(_to_bf16_bits(x[j]) if bf16 else torch.from_numpy(x[j]).cuda()) for j in range(2)]
+    ys = [torch.from_numpy(y[j]).cuda() for j in range(2)]
+    part = W.participation_schedule(w, 4)
+    runs = []
+    for _ in range(2):
+        h = B.Handle(B.config_from_workload(w, fuse_update=1), theta0)
+        for t in range(4):
+            h.worker_step(xs[t % 2], ys[t % 2], active=None if t != 2 else [int(i != 1) for i in range(k)])
+            h.elastic_sync(B.DW_DYNAMIC, tau=w.tau, participate=part[t // w.tau])
+        runs.append((h.all_state(B.DW_S_THETA), h.all_state(B.DW_S_M), h.all_state(B.DW_S_V), h.get_state(B.DW_S_CENTRE),
+                     np.array([h.get_state(B.DW_S_SCORE, i) for i in range(k)])))
+        h.close()
+    for a, b in zip(*runs):
+        np.testing.assert_array_equal(a, b)

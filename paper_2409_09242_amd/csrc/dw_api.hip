@@ -547,8 +547,7 @@ int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint
     const int st = draw_z(h, active, s);
     if (st != DW_OK) return st;
   }
-  float* loss = d_loss ? d_loss : h->at<float>(h->lay.loss);
-  return run_step(h, d_x, d_y, d_zbits, active, loss, s);
+  return run_step(h, d_x, d_y, d_zbits, active, d_loss, s);    // (no loss wanted: nothing adds it up)
 }
 
 int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint32_t* d_zbits,

@@ -203,6 +203,10 @@ struct HeadArgs {                     // softmax cross-entropy on the output lay
   uint64_t active_mask;
 };
 hipError_t launch_head(const HeadArgs& a, hipStream_t s);
+// fp32 output layer and head in one kernel (dw_out_head_f32.hip): `a` as for the output layer's forward product
+// (its C and RC are not written), loss_part: k * ceil(M / 16) floats of scratch
+bool out_head_f32_ok(const GemmArgs& a);
+hipError_t launch_out_head_f32(const GemmArgs& a, const HeadArgs& h, float* loss_part, hipStream_t s);
 
 struct Layout {            // byte offsets into the workspace, all multiples of 256
   int64_t P = 0, Pp = 0, z_stride = 0, n_upd_blocks = 0;

@@ -10,6 +10,7 @@
 // Every matrix product above runs in the dual GEMM kernels; this file holds the softmax head and the
 // order of the launches.
 #include "dw_internal.h"
+#include "dw_head_math.h"
 
 namespace dw {
 
@@ -31,51 +32,21 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a) {
   const float invB = 1.0f / (float)a.B;
   float loss = 0.f;
   for (int n = threadIdx.x; n < a.B; n += blockDim.x) {
-    float s[DW_MAX_CLASSES], rs[DW_MAX_CLASSES];
-    float mx = -INFINITY;
-    int amax = 0;
+    float s[DW_MAX_CLASSES], rs[DW_MAX_CLASSES], d[DW_MAX_CLASSES], rd[DW_MAX_CLASSES];
 #pragma unroll
     for (int c = 0; c < DW_MAX_CLASSES; ++c) {
-      s[c] = c < a.C ? S[(int64_t)n * a.ld + c] : -INFINITY;
+      s[c] = c < a.C ? S[(int64_t)n * a.ld + c] : 0.f;
       rs[c] = c < a.C ? RS[(int64_t)n * a.ld + c] : 0.f;
-      if (s[c] > mx) { mx = s[c]; amax = c; }
     }
-    const int y = Y[n];
-    // e_c = exp(s_c - max); the largest term is exactly 1, so sums that leave it (or the label's term)
-    // out keep full relative precision when the prediction is confident
-    float rest_max = 0.f, rest_y = 0.f, sy = 0.f;
+    loss += head_row(s, rs, Y[n], a.C, invB, d, rd);
 #pragma unroll
     for (int c = 0; c < DW_MAX_CLASSES; ++c) {
-      const float e = c < a.C ? expf(s[c] - mx) : 0.f;
-      if (c == y) sy = s[c] - mx;
-      if (c != amax) rest_max += e;
-      if (c != y) rest_y += e;
-      s[c] = e;
-    }
-    const float sum = 1.0f + rest_max;
-    const float inv = 1.0f / sum;
-#pragma unroll
-    for (int c = 0; c < DW_MAX_CLASSES; ++c) s[c] *= inv;   // p_c
-    loss += log1pf(rest_max) - sy;                   // -log p_y = log(sum_c e_c) - (s_y - max)
-    const float one_minus_py = rest_y * inv;         // 1 - p_y without cancellation
-#pragma unroll
-    for (int c = 0; c < DW_MAX_CLASSES; ++c) {
-      float d = 0.f, rd = 0.f;
-      if (c < a.C) {
-        d = (c == y ? -one_minus_py : s[c]) * invB;  // d(mean loss)/d s_L = (p - onehot)/B
-        // its derivative along Rs_L: p_c (Rs_c - <p, Rs>) / B, with Rs_c - <p, Rs> written as
-        // sum_c' p_c' (Rs_c - Rs_c') so that a confident prediction does not cancel
-        float ctr = 0.f;
-#pragma unroll
-        for (int c2 = 0; c2 < DW_MAX_CLASSES; ++c2) ctr += s[c2] * (rs[c] - rs[c2]);
-        rd = s[c] * ctr * invB;
-      }
       if (c < a.ld) {
-        D[(int64_t)n * a.ld + c] = d;
-        RD[(int64_t)n * a.ld + c] = rd;
+        D[(int64_t)n * a.ld + c] = d[c];
+        RD[(int64_t)n * a.ld + c] = rd[c];
         if (a.delta_b16) {
-          a.delta_b16[((int64_t)i * a.B + n) * a.ld + c] = bf16_rne(d);
-          a.Rdelta_b16[((int64_t)i * a.B + n) * a.ld + c] = bf16_rne(rd);
+          a.delta_b16[((int64_t)i * a.B + n) * a.ld + c] = bf16_rne(d[c]);
+          a.Rdelta_b16[((int64_t)i * a.B + n) * a.ld + c] = bf16_rne(rd[c]);
         }
       }
     }
@@ -128,6 +99,14 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       return DW_ERR_HIP;
   }
 
+  HeadArgs hd{};
+  hd.s = reinterpret_cast<const float*>(ws + lay.sL); hd.Rs = reinterpret_cast<const float*>(ws + lay.rsL);
+  hd.delta = reinterpret_cast<float*>(ws + lay.dL); hd.Rdelta = reinterpret_cast<float*>(ws + lay.rdL);
+  hd.delta_b16 = b16 ? reinterpret_cast<uint16_t*>(ws + lay.dL16) : nullptr;
+  hd.Rdelta_b16 = b16 ? reinterpret_cast<uint16_t*>(ws + lay.rdL16) : nullptr;
+  hd.y = d_y; hd.loss = d_loss; hd.B = B; hd.C = cfg.dims[L]; hd.ld = HL; hd.k = k; hd.active_mask = active;
+  bool head_done = false;
+
   // forward with R-forward
   for (int l = 1; l <= L; ++l) {
     GemmArgs a{};
@@ -145,6 +124,13 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.epi = EPI_LINEAR;
     }
     a.k = k; a.active_mask = active;
+    if (!b16 && l == L && out_head_f32_ok(a)) {
+      // fp32: the output layer's product and the softmax head in one kernel (the logits buffer serves as its
+      // scratch for the per-block losses)
+      if ((e = launch_out_head_f32(a, hd, reinterpret_cast<float*>(ws + lay.sL), s)) != hipSuccess) return DW_ERR_HIP;
+      head_done = true;
+      break;
+    }
     if (!b16 && lay.fwdSplit[l - 1] > 1) {             // long contraction, few output tiles
       a.ksplit = lay.fwdSplit[l - 1]; a.part = reinterpret_cast<float*>(ws + lay.cPart);
       a.part_stride = (int64_t)B * a.ldc; a.part_b = nullptr;
@@ -153,13 +139,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
   }
 
   // softmax cross-entropy head
-  {
-    HeadArgs hd{};
-    hd.s = reinterpret_cast<const float*>(ws + lay.sL); hd.Rs = reinterpret_cast<const float*>(ws + lay.rsL);
-    hd.delta = reinterpret_cast<float*>(ws + lay.dL); hd.Rdelta = reinterpret_cast<float*>(ws + lay.rdL);
-    hd.delta_b16 = b16 ? reinterpret_cast<uint16_t*>(ws + lay.dL16) : nullptr;
-    hd.Rdelta_b16 = b16 ? reinterpret_cast<uint16_t*>(ws + lay.rdL16) : nullptr;
-    hd.y = d_y; hd.loss = d_loss; hd.B = B; hd.C = cfg.dims[L]; hd.ld = HL; hd.k = k; hd.active_mask = active;
+  if (!head_done) {
     if ((e = launch_head(hd, s)) != hipSuccess) return DW_ERR_HIP;
   }
 

@@ -30,6 +30,8 @@ SHAPES = [
     ((256, 1024, 1024, 10), 160, 8),       # large tiles
     ((48, 40, 36, 28, 24, 4), 33, 2),      # deep and narrow
     ((16, 24, 4), 5, 64),                  # the maximum number of workers
+    ((40, 128, 10), 37, 3),                # output layer + head in one kernel, ragged last block of samples
+    ((40, 64, 16), 21, 2),                 # the same with the maximum number of classes
 ]
 
 

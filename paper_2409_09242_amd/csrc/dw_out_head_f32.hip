@@ -18,6 +18,7 @@ typedef float f32o_x4 __attribute__((ext_vector_type(4)));
 namespace f32o {
 
 constexpr int ROWS = 16, NT = 256, NW = NT / 64, KSTEP = 16;
+static_assert(DW_MAX_CLASSES == ROWS, "a 16-lane group holds one sample's logits, one class per lane");
 
 // grid: (ceil(M / 16), active workers); requirements in out_head_f32_ok
 __global__ __launch_bounds__(NT) void out_head_f32_kernel(GemmArgs a, HeadArgs h, float* loss_part) {

@@ -114,7 +114,7 @@ def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, residen
 
     if resident is not None:
         # the step's input comes from a data set resident in HBM: n points shaped like the workload's inputs, split
-        # among the workers with overlap ratio `resident` (Section IV-A), every step's minibatch drawn on the device
+        # among the workers with overlap ratio `resident` (Section V-A), every step's minibatch drawn on the device
         n_points = 60000
         gen = torch.Generator(device="cuda"); gen.manual_seed(w.seed)
         data = torch.randn((n_points, w.dims[0]), device="cuda", generator=gen)

@@ -60,7 +60,7 @@ typedef enum {
 
 /* how dw_elastic_sync chooses the per-worker weights (h1_i, h2_i) */
 #define DW_FIXED 0           /* h1 = h2 = alpha: plain elastic averaging (Section IV-A)                 */
-#define DW_MANUAL 1          /* caller-supplied, "as if we know when a node will fail" (Section VI)     */
+#define DW_MANUAL 1          /* caller-supplied: weights set with foreknowledge of the failures (Section VI) */
 #define DW_DYNAMIC 2         /* h1(a), h2(a) from the raw score (Section V-B)                           */
 /* may be OR-ed into the mode: the participating workers exchange with the master one after the other, in index
  * order, each exchange being eq.(12)-(13) with the centre as the previous one left it (asynchronous procedure,
@@ -83,6 +83,8 @@ typedef enum {
                                 whose data gradient runs on the large-tile bf16 kernel, bit (r, c) of V_l [d_l][d_{l-1}]
                                 sits at woff_l + c*d_l + r; other positions are unspecified; get only; DW_ERR_MODE when
                                 the handle keeps no such copy                                                */
+#define DW_S_COUNTERS 11     /* int64[3]   {calls of dw_worker_step/dw_update_only so far, communication rounds so far,
+                                period tau of the latest dw_elastic_sync call}; belongs to the handle, worker ignored */
 #define DW_S_ACT 16          /* DW_S_ACT + l, l = 1..L-1: hidden activations a_l of the last step, [B][d_l]
                                 floats (DW_F32) or bfloat16 bit patterns as uint16 (DW_BF16); get only      */
 
@@ -174,9 +176,10 @@ int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint
                    const uint8_t* h_active, float* d_loss, void* stream);
 
 /*
- * The optimizer part of dw_worker_step alone, on caller-supplied gradients and Hessian-vector products
- * d_g, d_hz ([k][P] floats each, 16-byte aligned; worker i at offset i*P).  Other arguments as above.
- * Valid for flat problems and for MLP problems.
+ * The optimizer part of dw_worker_step alone (Section IV-B: Hutchinson diagonal D = z*(Hz), its spatial average,
+ * Adam-like moments with D in the second moment, bias correction; the preconditioned step of eq.(4)), on
+ * caller-supplied gradients and Hessian-vector products d_g, d_hz ([k][P] floats each, 16-byte aligned; worker i
+ * at offset i*P).  Other arguments as above.  Valid for flat problems and for MLP problems.
  */
 int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint32_t* d_zbits,
                    const uint8_t* h_active, void* stream);
@@ -199,14 +202,23 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
 
 /*
  * Copy `count` elements starting at element `offset` of a state array to / from host memory.  Both calls
- * synchronise the stream before returning.  dw_set_state accepts DW_S_THETA, DW_S_M, DW_S_V, DW_S_CENTRE and
- * DW_S_STEPS (for DW_BF16 the bf16 weight copy is refreshed after THETA is set).
+ * synchronise the stream before returning.  dw_set_state accepts DW_S_THETA, DW_S_M, DW_S_V, DW_S_CENTRE,
+ * DW_S_STEPS, DW_S_COUNTERS and DW_S_U_HIST (for DW_BF16 the bf16 weight copy is refreshed after THETA is set).
+ *
+ * Checkpoint of a run: theta, m, v and the step count of every worker, the centre, the counters and every worker's
+ * history of u (the state the raw score of eq.(10)-(11) is computed from).  Restore them into a handle created with
+ * the same configuration, DW_S_COUNTERS before DW_S_U_HIST: the history of a worker must then hold
+ * n = min(rounds, p + 1) values, as it does after `rounds` communication rounds (else DW_ERR_ARG).  A restored handle
+ * continues bit for bit like the original when the checkpoint was taken right after a communication round; taken
+ * between a step and its round it continues with distances summed in another order (same values to rounding).
+ * Setting a history by hand is also the way to put a chosen raw score, and so a chosen branch of h1 and h2
+ * (Section V-B), in front of the next round.
  */
 int dw_get_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, void* h_buf, void* stream);
 int dw_set_state(dw_handle* h, int what, int worker, int64_t offset, int64_t count, const void* h_buf, void* stream);
 
 /*
- * Data overlap (Section IV-A).  The n data points are shuffled by one seeded permutation (the order of the keys
+ * Data overlap (Section V-A).  The n data points are shuffled by one seeded permutation (the order of the keys
  * mix(mix(seed) + GAMMA*(i+1)), SplitMix64's output function and increment, equal keys by index); its first o
  * entries are the subset O shared by all workers, the next k blocks of s = floor((n-o)/k) entries the private
  * subsets S_1..S_k; the last (n-o) mod k entries belong to no worker.

@@ -3,7 +3,7 @@
 TEST INFRASTRUCTURE ONLY, like the rest of this package: only the tests, the smoke check and the
 benchmark's CPU-baseline leg may import it, and it shares no code with the HIP kernels.
 
-  * shared subset O and private subsets S_j, D_j = O u S_j     -- Section IV-A ("Data Overlap")
+  * shared subset O and private subsets S_j, D_j = O u S_j     -- Section V-A ("Data Overlap")
   * a worker's minibatch drawn from its own D_j                -- Section II eq.(3): the gradient of
                                                                   a sampled minibatch, per worker
 
@@ -39,7 +39,7 @@ def partition_keys(n: int, seed: int) -> List[int]:
 
 
 def overlap_partition(n: int, o: int, k: int, seed: int) -> Tuple[np.ndarray, np.ndarray]:
-    """Section IV-A: returns (O [o], S [k][floor((n-o)/k)]) as point indices in permutation order."""
+    """Section V-A: returns (O [o], S [k][floor((n-o)/k)]) as point indices in permutation order."""
     assert n >= 1 and 0 <= o <= n and k >= 1
     keys = partition_keys(n, seed)
     pi = sorted(range(n), key=lambda i: (keys[i], i))

@@ -20,7 +20,7 @@ DW_F32, DW_BF16 = 0, 1
 DW_FIXED, DW_MANUAL, DW_DYNAMIC = 0, 1, 2
 DW_SEQUENTIAL = 16      # OR-ed into the mode of elastic_sync: exchanges one after the other, in index order
 (DW_S_THETA, DW_S_M, DW_S_V, DW_S_G, DW_S_HZ, DW_S_CENTRE, DW_S_ZBITS, DW_S_SCORE, DW_S_U_HIST,
- DW_S_STEPS, DW_S_ZBITS_T) = range(11)
+ DW_S_STEPS, DW_S_ZBITS_T, DW_S_COUNTERS) = range(12)
 DW_S_ACT = 16
 
 EXPORTS = ("dw_strerror", "dw_last_hip_error", "dw_param_count", "dw_workspace_bytes", "dw_init", "dw_destroy",
@@ -171,7 +171,7 @@ def _ptr(a):
 
 
 def overlap_partition(n: int, o: int, k: int, seed: int, device="cuda:0"):
-    """Section IV-A on the device: an int32 tensor [k][o + floor((n-o)/k)], row j = D_j (O first)."""
+    """Section V-A on the device: an int32 tensor [k][o + floor((n-o)/k)], row j = D_j (O first)."""
     import torch
     dev = torch.device(device)
     nbytes = lib().dw_partition_scratch_bytes(n)
@@ -263,7 +263,8 @@ class Handle:
             raise DwError(st, "dw_draw_batch")
 
     # ---- state access --------------------------------------------------------------------------------
-    _DT = {DW_S_ZBITS: np.uint32, DW_S_ZBITS_T: np.uint32, DW_S_SCORE: np.float64, DW_S_U_HIST: np.float64, DW_S_STEPS: np.int64}
+    _DT = {DW_S_ZBITS: np.uint32, DW_S_ZBITS_T: np.uint32, DW_S_SCORE: np.float64, DW_S_U_HIST: np.float64, DW_S_STEPS: np.int64,
+           DW_S_COUNTERS: np.int64}
 
     def get_state(self, what: int, worker: int = 0, offset: int = 0, count: Optional[int] = None) -> np.ndarray:
         if what > DW_S_ACT:
@@ -275,7 +276,8 @@ class Handle:
                 raise DwError(st, "dw_get_state")
             return out.reshape(self.cfg.batch, self.cfg.dims[l])
         if count is None:
-            count = {DW_S_ZBITS: self.zwords, DW_S_ZBITS_T: self.zwords, DW_S_SCORE: 4, DW_S_U_HIST: 2 + DW_MAX_P, DW_S_STEPS: 1}.get(
+            count = {DW_S_ZBITS: self.zwords, DW_S_ZBITS_T: self.zwords, DW_S_SCORE: 4, DW_S_U_HIST: 2 + DW_MAX_P, DW_S_STEPS: 1,
+                     DW_S_COUNTERS: 3}.get(
                 what, self.P) - offset
         out = np.empty(count, dtype=self._DT.get(what, np.float32))
         st = lib().dw_get_state(self._h, what, worker, offset, count, _ptr(out), self._stream())
@@ -309,3 +311,23 @@ class Handle:
 
     def all_state(self, what: int) -> np.ndarray:
         return np.stack([self.get_state(what, i) for i in range(self.k)])
+
+    # ---- checkpoint: plain copies through dw_get_state / dw_set_state ------------------------------------
+    def checkpoint(self) -> dict:
+        """Everything a run needs to go on elsewhere: parameters, moments and step counts of every worker, the
+        centre, the handle's counters and every worker's history of u."""
+        return {"theta": self.all_state(DW_S_THETA), "m": self.all_state(DW_S_M), "v": self.all_state(DW_S_V),
+                "centre": self.get_state(DW_S_CENTRE), "steps": self.all_state(DW_S_STEPS),
+                "counters": self.get_state(DW_S_COUNTERS), "u_hist": self.all_state(DW_S_U_HIST)}
+
+    def restore(self, ck: dict):
+        """Put a checkpoint into this handle (created with the same configuration); the counters go in before the
+        histories, as dw_set_state asks."""
+        self.set_state(DW_S_COUNTERS, 0, ck["counters"])
+        for i in range(self.k):
+            self.set_state(DW_S_THETA, i, ck["theta"][i])
+            self.set_state(DW_S_M, i, ck["m"][i])
+            self.set_state(DW_S_V, i, ck["v"][i])
+            self.set_state(DW_S_STEPS, i, ck["steps"][i])
+            self.set_state(DW_S_U_HIST, i, ck["u_hist"][i])
+        self.set_state(DW_S_CENTRE, 0, ck["centre"])

@@ -15,6 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libdw.so")
+STAMP = os.path.join(HERE, "libdw.sources.sha256")      # digest of the sources the library was built from
 
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -103,8 +104,21 @@ def check_transposed_reads() -> str:
     return out
 
 
+def _source_digest() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h")))
+    files.append(os.path.join(ROOT, "include", "dw.h"))
+    for f in files:
+        h.update(os.path.basename(f).encode() + b"\0")
+        h.update(open(f, "rb").read())
+    h.update(" ".join(FLAGS).encode())
+    return h.hexdigest()
+
+
 def build(verbose: bool = True) -> str:
     os.makedirs(OBJ, exist_ok=True)
+    digest = _source_digest()
     srcs = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
     with ThreadPoolExecutor(max_workers=min(8, len(srcs) + 1)) as ex:
         check = ex.submit(check_transposed_reads)
@@ -114,15 +128,23 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n%s\n%s" % (r.stdout, r.stderr))
+    with open(STAMP, "w") as f:
+        f.write(digest + "\n")
     if verbose:
         print("built", LIB)
     return LIB
 
 
 def ensure_built() -> str:
-    """Build the library when none is there (tests, the smoke check and the benchmark call this; they never rebuild
-    an existing one).  The binding itself does not: without a library it raises."""
-    return LIB if os.path.exists(LIB) else build(verbose=True)
+    """Build the library when none is there, or when the sources have changed since the one that is there was built
+    (its digest file says so; a library without a digest file is taken as it is).  Tests, the smoke check and the
+    benchmark call this.  The binding itself does not: without a library it raises."""
+    if not os.path.exists(LIB):
+        return build(verbose=True)
+    if os.path.exists(STAMP) and open(STAMP).read().strip() != _source_digest():
+        sys.stderr.write("libdw.so is older than its sources: building again\n")
+        return build(verbose=True)
+    return LIB
 
 
 if __name__ == "__main__":

@@ -2,6 +2,7 @@
 // which the kernels of one worker step / one communication round are enqueued.  Nothing here computes
 // any part of the method on the host except the scalars 1 - beta^t (Section IV-B bias correction) and
 // the keys of the Rademacher stream.
+#include <climits>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -704,6 +705,12 @@ int dw_get_state(dw_handle* h, int what, int worker, int64_t offset, int64_t cou
     *reinterpret_cast<int64_t*>(h_buf) = h->t[worker];
     return DW_OK;
   }
+  if (what == DW_S_COUNTERS) {
+    if (offset != 0 || count != 3) return DW_ERR_ARG;
+    int64_t* out = reinterpret_cast<int64_t*>(h_buf);
+    out[0] = h->calls; out[1] = h->rounds; out[2] = h->last_tau;
+    return DW_OK;
+  }
   if (what == DW_S_U_HIST) {
     if (worker < 0 || worker >= h->cfg.k || offset != 0 || count != 2 + DW_MAX_P) return DW_ERR_ARG;
     double ring[DW_MAX_P + 1];
@@ -738,6 +745,33 @@ int dw_set_state(dw_handle* h, int what, int worker, int64_t offset, int64_t cou
     const int64_t t = *reinterpret_cast<const int64_t*>(h_buf);
     if (t < 0) return DW_ERR_ARG;
     h->t[worker] = t;
+    return DW_OK;
+  }
+  if (what == DW_S_COUNTERS) {
+    if (offset != 0 || count != 3) return DW_ERR_ARG;
+    const int64_t* in = reinterpret_cast<const int64_t*>(h_buf);
+    if (in[0] < 0 || in[1] < 0 || in[2] < 1 || in[2] > INT32_MAX) return DW_ERR_ARG;
+    h->calls = in[0]; h->rounds = in[1]; h->last_tau = (int)in[2];
+    h->norms_valid = false;                               // whatever was measured belongs to another point of the run
+    return DW_OK;
+  }
+  if (what == DW_S_U_HIST) {
+    // the n most recent u of one worker, oldest first: value j is that of round rounds - n + j and goes to the ring
+    // slot the weight kernel reads it from
+    if (worker < 0 || worker >= h->cfg.k || offset != 0 || count != 2 + DW_MAX_P) return DW_ERR_ARG;
+    const double* in = reinterpret_cast<const double*>(h_buf);
+    const int R = h->cfg.p + 1;
+    const int64_t want = h->rounds < R ? h->rounds : R;
+    if (!(in[0] == (double)want)) return DW_ERR_ARG;
+    double ring[DW_MAX_P + 1];
+    for (int j = 0; j < DW_MAX_P + 1; ++j) ring[j] = 0.0;
+    for (int j = 0; j < (int)want; ++j) {
+      if (!std::isfinite(in[1 + j])) return DW_ERR_ARG;
+      ring[(h->rounds - want + j) % R] = in[1 + j];
+    }
+    DW_HIP(hipMemcpyAsync(h->at<double>(h->lay.u_ring) + (size_t)worker * (DW_MAX_P + 1), ring, sizeof(ring),
+                          hipMemcpyHostToDevice, s));
+    DW_HIP(hipStreamSynchronize(s));                      // `ring` lives on this frame
     return DW_OK;
   }
   if (what != DW_S_THETA && what != DW_S_M && what != DW_S_V && what != DW_S_CENTRE) return DW_ERR_ARG;

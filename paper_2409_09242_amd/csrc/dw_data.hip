@@ -1,6 +1,6 @@
 // Data side of the method on the device (gfx950, wave64).
 //
-//   partition kernels   Section IV-A: one seeded permutation of the n data points, by ranking 64-bit keys; its first
+//   partition kernels   Section V-A: one seeded permutation of the n data points, by ranking 64-bit keys; its first
 //                       o entries are the shared subset O, the next k blocks of floor((n-o)/k) the private subsets
 //                       S_j, and row j of the index array holds D_j = O u S_j (O first, permutation order).
 //   gather_kernel       each worker's minibatch: B uniform draws (with replacement) from its own D_j at its local

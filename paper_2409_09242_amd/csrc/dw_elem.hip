@@ -14,26 +14,9 @@
 #include <cstddef>
 
 #include "dw_internal.h"
+#include "dw_device_util.h"
 
 namespace dw {
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
-// The optimizer state streams through once per launch: 16-byte accesses marked non-temporal so that they do not
-// displace lines that are reused (the centre, the sign bits, other kernels' operand tiles).
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 nt_load4(const float4* p) {
-  const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void nt_store4(float4* p, float4 x) {
-  const f32x4 v = {x.x, x.y, x.z, x.w};
-  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
-}
 
 __device__ __forceinline__ float sign_from_bit(uint32_t bits, int b) {
   // bit set -> +1, clear -> -1

@@ -18,25 +18,11 @@
 #include <stdint.h>
 
 #include "dw_internal.h"
+#include "dw_device_util.h"
 
 namespace dw {
 
 typedef float fu_floatx16 __attribute__((ext_vector_type(16)));
-typedef float fu_f32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float4 fu_nt_load4(const float* p) {       // 16-byte load that does not displace L2 lines
-  const fu_f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const fu_f32x4*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void fu_nt_store4(float* p, float4 x) {
-  const fu_f32x4 v = {x.x, x.y, x.z, x.w};
-  __builtin_nontemporal_store(v, reinterpret_cast<fu_f32x4*>(p));
-}
-__device__ __forceinline__ uint16_t fu_f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 
 // floats of LDS one wave needs: g and Hz of one row of MFMA tiles, [32][72] each
 __host__ __device__ constexpr int fused_update_lds_floats() { return 2 * 32 * 72; }
@@ -67,11 +53,11 @@ __device__ __forceinline__ float fused_update_wave_tile(const fu_floatx16 (&acc)
     const int i = bb / 8, b = bb % 8;
     const uint32_t m = (uint32_t)(row_base + i * 32 + b * 4 + brow), n = (uint32_t)(col_base + bcol);
     bt.e = m * (uint32_t)ldc + n;                         // offset inside the W block, a multiple of 4
-    bt.th = fu_nt_load4(th_w + bt.e); bt.mm = fu_nt_load4(m_w + bt.e);   // the state streams through once: no reuse in L2
-    bt.vv = fu_nt_load4(v_w + bt.e);
+    bt.th = nt_load4(th_w + bt.e); bt.mm = nt_load4(m_w + bt.e);   // the state streams through once: no reuse in L2
+    bt.vv = nt_load4(v_w + bt.e);
     bt.cc = f.dist ? *reinterpret_cast<const float4*>(f.centre + bt.e) : make_float4(0.f, 0.f, 0.f, 0.f);
     bt.zw = zrow[bt.e >> 5];
-    if constexpr (PROBES) bt.dd = fu_nt_load4(dacc_w + bt.e);
+    if constexpr (PROBES) bt.dd = nt_load4(dacc_w + bt.e);
   };
   float nsum = 0.f;
   const int group_lanes = f.avg_block >> 2;                 // lanes that share one averaging block (when b > 4)
@@ -113,11 +99,11 @@ __device__ __forceinline__ float fused_update_wave_tile(const fu_floatx16 (&acc)
       const float d = t1[q] - cc[q];
       nsum += d * d;
     }
-    fu_nt_store4(th_w + bt.e, make_float4(t1[0], t1[1], t1[2], t1[3]));
-    fu_nt_store4(m_w + bt.e, make_float4(m1[0], m1[1], m1[2], m1[3]));
-    fu_nt_store4(v_w + bt.e, make_float4(v1[0], v1[1], v1[2], v1[3]));
+    nt_store4(th_w + bt.e, make_float4(t1[0], t1[1], t1[2], t1[3]));
+    nt_store4(m_w + bt.e, make_float4(m1[0], m1[1], m1[2], m1[3]));
+    nt_store4(v_w + bt.e, make_float4(v1[0], v1[1], v1[2], v1[3]));
     if (B16) {
-      ushort4 w16; w16.x = fu_f2bf(t1[0]); w16.y = fu_f2bf(t1[1]); w16.z = fu_f2bf(t1[2]); w16.w = fu_f2bf(t1[3]);
+      ushort4 w16; w16.x = f32_to_bf16_rne(t1[0]); w16.y = f32_to_bf16_rne(t1[1]); w16.z = f32_to_bf16_rne(t1[2]); w16.w = f32_to_bf16_rne(t1[3]);
       __builtin_nontemporal_store(__builtin_bit_cast(unsigned long long, w16), reinterpret_cast<unsigned long long*>(b16_w + bt.e));
     }
   };
@@ -170,7 +156,7 @@ __device__ __forceinline__ void fused_probe_sum_wave_tile(const fu_floatx16 (&ra
     for (int b = 0; b < 8; ++b) {
       e[b] = (uint32_t)(row_base + i * 32 + b * 4 + brow) * (uint32_t)ldc + (uint32_t)(col_base + bcol);
       zw[b] = zrow[e[b] >> 5];
-      dd[b] = f.first ? make_float4(0.f, 0.f, 0.f, 0.f) : fu_nt_load4(dacc_w + e[b]);
+      dd[b] = f.first ? make_float4(0.f, 0.f, 0.f, 0.f) : nt_load4(dacc_w + e[b]);
     }
 #pragma unroll
     for (int b = 0; b < 8; ++b) {
@@ -179,7 +165,7 @@ __device__ __forceinline__ void fused_probe_sum_wave_tile(const fu_floatx16 (&ra
       float4 o;
       o.x = dd[b].x + ((zb4 & 1u) ? h4.x : -h4.x); o.y = dd[b].y + ((zb4 & 2u) ? h4.y : -h4.y);
       o.z = dd[b].z + ((zb4 & 4u) ? h4.z : -h4.z); o.w = dd[b].w + ((zb4 & 8u) ? h4.w : -h4.w);
-      fu_nt_store4(dacc_w + e[b], o);
+      nt_store4(dacc_w + e[b], o);
     }
   }
 }

@@ -18,6 +18,7 @@
 #include <cstddef>
 
 #include "dw_internal.h"
+#include "dw_device_util.h"
 #include "dw_gemm_epi.h"
 #include "dw_fused_update.h"
 
@@ -36,20 +37,6 @@ constexpr int NT = 512;
 
 enum RyMode { RY_NONE = 0, RY_MEM = 1, RY_BITS = 2 };
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 nt_load4(const float* p) {          // 16-byte load that does not displace L2 lines
-  const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void nt_store4(float* p, float4 x) {
-  const f32x4 v = {x.x, x.y, x.z, x.w};
-  __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
-}
-__device__ __forceinline__ uint16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 __device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // two bf16 values +-1 from two sign bits (bit set -> +1 = 0x3F80, clear -> -1 = 0xBF80)
@@ -458,8 +445,8 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
         if (EPI == EPI_RELU) {
           c += bias; rc += cz;
           const bool on = c > 0.f;
-          reinterpret_cast<uint16_t*>(a.C)[o] = f2bf(on ? c : 0.f);
-          reinterpret_cast<uint16_t*>(a.RC)[o] = f2bf(on ? rc : 0.f);
+          reinterpret_cast<uint16_t*>(a.C)[o] = f32_to_bf16_rne(on ? c : 0.f);
+          reinterpret_cast<uint16_t*>(a.RC)[o] = f32_to_bf16_rne(on ? rc : 0.f);
         } else if (EPI == EPI_LINEAR) {
           reinterpret_cast<float*>(a.C)[o] = c + bias;
           reinterpret_cast<float*>(a.RC)[o] = rc + cz;
@@ -467,8 +454,8 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
           const uint16_t* msk = reinterpret_cast<const uint16_t*>(a.mask_src) + (int64_t)worker * a.mask_wstride;
           const uint16_t mv = msk[(int64_t)m * a.ld_mask + n];
           const bool on = mv != 0 && !(mv & 0x8000u);     // stored activation > 0
-          reinterpret_cast<uint16_t*>(a.C)[o] = f2bf(on ? c : 0.f);
-          reinterpret_cast<uint16_t*>(a.RC)[o] = f2bf(on ? rc : 0.f);
+          reinterpret_cast<uint16_t*>(a.C)[o] = f32_to_bf16_rne(on ? c : 0.f);
+          reinterpret_cast<uint16_t*>(a.RC)[o] = f32_to_bf16_rne(on ? rc : 0.f);
         } else {
           reinterpret_cast<float*>(a.C)[o] = c;
           reinterpret_cast<float*>(a.RC)[o] = rc;
@@ -499,16 +486,8 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   constexpr int smem = tiles_b > epi_b ? (tiles_b > out_b ? tiles_b : out_b) : (epi_b > out_b ? epi_b : out_b);
   static_assert(smem <= 160 * 1024, "LDS budget");
   auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, FM>;
-  // raise the dynamic LDS limit once per instantiation and device (the attribute belongs to the device's code object)
-  static bool configured_on[64] = {false};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  bool& configured = configured_on[dev];
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static LdsLimitOnce lds_limit;
+  { const hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), smem); if (e != hipSuccess) return e; }
   hipLaunchKernelGGL(kern, grid, block, smem, s, a);
   return hipGetLastError();
 }

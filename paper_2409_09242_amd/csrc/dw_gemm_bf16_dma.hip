@@ -385,16 +385,8 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   constexpr int smem = (BM * BK * 2 * (RX ? 2 : 1) + BN * BK * 2) * STAGES + 2 * BN * 16;
   static_assert(smem <= 160 * 1024, "LDS budget");
   auto kern = dual_gemm_bf16_dma<RX, DGRAD, RONLY>;
-  // raise the dynamic LDS limit once per instantiation and device (the attribute belongs to the device's code object)
-  static bool configured_on[64] = {false};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
-  bool& configured = configured_on[dev];
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static LdsLimitOnce lds_limit;
+  { const hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), smem); if (e != hipSuccess) return e; }
   hipLaunchKernelGGL(kern, grid, block, smem, s, a);
   return hipGetLastError();
 }

@@ -10,15 +10,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "dw_device_util.h"
+
 namespace dw {
 
 typedef float epi_floatx16 __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ uint16_t epi_f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 
 // 0xFFFF for each 16-bit half of m2 that holds a bf16 value > 0 (stored activation of a unit that is on)
 __device__ __forceinline__ uint32_t epi_keep(uint32_t m2) {
@@ -44,8 +40,8 @@ __device__ __forceinline__ void epi_bf16_rows_out(char* wl, const epi_floatx16* 
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int off = ((r >> 2) * 8 + lhalf * 4 + (r & 3)) * RS + (j * 32 + l32) * 2;
-      if (STORE_C) *reinterpret_cast<uint16_t*>(wl + off) = epi_f2bf(cv[j][r]);
-      *reinterpret_cast<uint16_t*>(wr + off) = epi_f2bf(rcv[j][r]);
+      if (STORE_C) *reinterpret_cast<uint16_t*>(wl + off) = f32_to_bf16_rne(cv[j][r]);
+      *reinterpret_cast<uint16_t*>(wr + off) = f32_to_bf16_rne(rcv[j][r]);
     }
   constexpr int LPR = TN * 4, RPP = 64 / LPR;                 // lanes per row, rows per pass
   const int prow = lane / LPR, ch = lane % LPR;

@@ -371,18 +371,12 @@ static hipError_t launch_fused_wgrad_mode(const GemmArgs& a, hipStream_t s) {
   const int tiles = (a.M / 128) * (a.N / 128);
   const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k)), block(NT);
   constexpr int smem = (NT / 64) * fused_update_lds_floats() * (int)sizeof(float);
-  static bool configured_on[64] = {false};
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
   auto with_ry = dual_gemm_f32<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD_FUSED, FM>;
   auto without_ry = dual_gemm_f32<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD_FUSED, FM>;
-  if (!configured_on[dev]) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(with_ry), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(without_ry), hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured_on[dev] = true;
-  }
+  static LdsLimitOnce lim_with, lim_without;
+  hipError_t e = lim_with.raise(reinterpret_cast<const void*>(with_ry), smem);
+  if (e == hipSuccess) e = lim_without.raise(reinterpret_cast<const void*>(without_ry), smem);
+  if (e != hipSuccess) return e;
   if (a.RY) hipLaunchKernelGGL(with_ry, grid, block, smem, s, a);
   else hipLaunchKernelGGL(without_ry, grid, block, smem, s, a);
   return hipGetLastError();

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "dw.h"
 
 namespace dw {
@@ -176,6 +178,21 @@ __device__ __forceinline__ int nth_active_worker(uint64_t mask, int j) {
   while (j-- > 0) mask &= mask - 1;                   // drop the j lowest set bits (uniform scalar work)
   return __builtin_ctzll(mask);
 }
+
+// Raises the dynamic-LDS limit of a kernel the first time it is launched on a device (the attribute belongs to the
+// device's code object).  One instance per kernel instantiation, as a function-local static of its launcher.  Host
+// threads may race to the first launch: the flag is atomic and setting the attribute twice is harmless.
+struct LdsLimitOnce {
+  std::atomic<bool> done[64] = {};
+  hipError_t raise(const void* kern, int bytes) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done[dev].store(true, std::memory_order_release);
+    return e;
+  }
+};
 
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);

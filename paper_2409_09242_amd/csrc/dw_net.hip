@@ -10,15 +10,10 @@
 // Every matrix product above runs in the dual GEMM kernels; this file holds the softmax head and the
 // order of the launches.
 #include "dw_internal.h"
+#include "dw_device_util.h"
 #include "dw_head_math.h"
 
 namespace dw {
-
-__device__ __forceinline__ uint16_t bf16_rne(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
 
 // one block per worker; thread n handles sample n (looping when B > blockDim)
 __global__ __launch_bounds__(256) void head_kernel(HeadArgs a) {
@@ -45,8 +40,8 @@ __global__ __launch_bounds__(256) void head_kernel(HeadArgs a) {
         D[(int64_t)n * a.ld + c] = d[c];
         RD[(int64_t)n * a.ld + c] = rd[c];
         if (a.delta_b16) {
-          a.delta_b16[((int64_t)i * a.B + n) * a.ld + c] = bf16_rne(d[c]);
-          a.Rdelta_b16[((int64_t)i * a.B + n) * a.ld + c] = bf16_rne(rd[c]);
+          a.delta_b16[((int64_t)i * a.B + n) * a.ld + c] = f32_to_bf16_rne(d[c]);
+          a.Rdelta_b16[((int64_t)i * a.B + n) * a.ld + c] = f32_to_bf16_rne(rd[c]);
         }
       }
     }

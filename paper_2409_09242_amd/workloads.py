@@ -183,7 +183,7 @@ def participation_schedule(w: Workload, n_rounds: int) -> np.ndarray:
       "geometric0.3":  after each participation a worker draws s ~ Geometric(0.3) on {0,1,2,...}
                        and is absent for the next s rounds.
       "third":         every worker's communication is suppressed in a round with probability 1/3,
-                       independently (Section VI: "one-third of time").
+                       independently (the suppression rate of Section VI).
     Suppressed workers keep taking local steps.
     """
     part = np.ones((n_rounds, w.k), dtype=np.uint8)

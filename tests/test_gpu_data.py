@@ -1,4 +1,4 @@
-"""GPU parity of the data side: the overlap partition (Section IV-A) and the minibatch draws, against the
+"""GPU parity of the data side: the overlap partition (Section V-A) and the minibatch draws, against the
 oracle, bit for bit (index work); the library is called through its C ABI."""
 import ctypes as C
 

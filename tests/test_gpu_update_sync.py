@@ -228,3 +228,97 @@ def test_sequential_flag_is_validated():
     with pytest.raises(B.DwError):
         h.elastic_sync(7 | B.DW_SEQUENTIAL)
     assert h.elastic_sync(B.DW_FIXED | B.DW_SEQUENTIAL)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Checkpoint of the whole state, communication state included: a restored handle continues bit for bit.
+# ---------------------------------------------------------------------------------------------------------
+def _bits(h):
+    return (h.all_state(B.DW_S_THETA), h.all_state(B.DW_S_M), h.all_state(B.DW_S_V), h.get_state(B.DW_S_CENTRE),
+            h.all_state(B.DW_S_STEPS), h.all_state(B.DW_S_U_HIST), h.get_state(B.DW_S_COUNTERS),
+            np.stack([h.get_state(B.DW_S_SCORE, i) for i in range(h.k)]))
+
+
+def test_checkpoint_restore_continues_bit_for_bit():
+    """Six steps with rounds every second step (one third of the communications suppressed, one worker frozen
+    once), everything dumped through dw_get_state, restored into a fresh handle through dw_set_state, six more steps
+    on both: parameters, moments, centre, histories, counters and the scores of the last round agree in every bit."""
+    P, k, tau = 3 * 4096 + 256, 5, 2
+    w, theta0, rng = _flat_case(P, k, 4711, stale="third", avg_block=4)
+    sched = W.participation_schedule(w, 6)
+    g = [torch.from_numpy((rng.standard_normal((k, P)) * 0.1).astype(np.float32)).cuda() for _ in range(12)]
+    hz = [torch.from_numpy((rng.standard_normal((k, P)) * 0.1).astype(np.float32)).cuda() for _ in range(12)]
+
+    def run(h, first, last):
+        for t in range(first, last):
+            h.update_only(g[t], hz[t], active=[1, 1, t != 3, 1, 1])
+            assert h.elastic_sync(B.DW_DYNAMIC, tau=tau, participate=sched[t // tau]) == ((t + 1) % tau == 0)
+
+    hA = B.Handle(B.config_from_workload(w), theta0)
+    run(hA, 0, 6)
+    ck = hA.checkpoint()
+    assert list(ck["counters"]) == [6, 3, tau] and int(ck["u_hist"][0][0]) == 3
+    hB = B.Handle(B.config_from_workload(w), theta0)
+    hB.restore(ck)
+    for a, b in zip(_bits(hA)[:7], _bits(hB)[:7]):
+        np.testing.assert_array_equal(a, b)
+    run(hA, 6, 12); run(hB, 6, 12)
+    for a, b in zip(_bits(hA), _bits(hB)):
+        np.testing.assert_array_equal(a, b)
+    assert int(hB.get_state(B.DW_S_U_HIST, 0)[0]) == 5                    # the ring (p + 1 = 5) is full by now
+    # a handle that was not given the history scores the next round differently
+    hC = B.Handle(B.config_from_workload(w), theta0)
+    ck2 = dict(ck); ck2["counters"] = np.array([6, 0, tau]); ck2["u_hist"] = np.zeros_like(ck["u_hist"])
+    hC.restore(ck2)
+    run(hC, 6, 8)
+    hD = B.Handle(B.config_from_workload(w), theta0)
+    hD.restore(ck)
+    run(hD, 6, 8)
+    assert any(hC.get_state(B.DW_S_SCORE, i)[1] != hD.get_state(B.DW_S_SCORE, i)[1] for i in range(k))
+    # the history must fit the round counter
+    bad = ck["u_hist"][0].copy(); bad[0] = 2
+    with pytest.raises(B.DwError):
+        hD.set_state(B.DW_S_U_HIST, 0, bad)
+    with pytest.raises(B.DwError):
+        hD.set_state(B.DW_S_COUNTERS, 0, np.array([1, 1, 0]))             # period below 1
+
+
+@pytest.mark.parametrize("du,branch", [(-0.3, "reset"), (-0.05, "ramp"), (0.2, "plain"), (-0.1 / 0.4, "kink")])
+def test_history_set_by_hand_puts_each_branch_of_the_weights_before_the_next_round(du, branch):
+    """Section V-B: a < kappa gives (h1, h2) = (1, 0), kappa <= a <= 0 the two ramps, a > 0 gives (alpha, alpha).
+    The previous u of every worker is written through dw_set_state so that the round that follows sees the raw score
+    a = c_0 (u_now - u_prev) = c_0 * du; the oracle is handed the same history."""
+    P, k = 2 * 4096, 3
+    w, theta0, rng = _flat_case(P, k, 31 + int(abs(du) * 100))
+    h = B.Handle(B.config_from_workload(w), theta0)
+    tr = O.OracleTrainer(oracle_config(w, dims=None), theta0.astype(np.float64))
+    g = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+    hz = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+    h.update_only(torch.from_numpy(g).cuda(), torch.from_numpy(hz).cuda()); tr.update_only(g, hz)
+    h.set_state(B.DW_S_COUNTERS, 0, np.array([1, 1, 1]))                   # one round behind us
+    for i in range(k):
+        u_now = O.log_distance(tr.theta[i], tr.centre)
+        hist = np.zeros(2 + B.DW_MAX_P); hist[0] = 1; hist[1] = u_now - du
+        h.set_state(B.DW_S_U_HIST, i, hist)
+        tr.u_hist[i] = [u_now - du]
+    pre_t, pre_c = h.all_state(B.DW_S_THETA).astype(np.float64), h.get_state(B.DW_S_CENTRE).astype(np.float64)
+    tr.theta, tr.centre = pre_t.copy(), pre_c.copy()
+    assert h.elastic_sync(B.DW_DYNAMIC, tau=1) and tr.elastic_sync(O.MODE_DYNAMIC, tau=1)
+    for i in range(k):
+        sc = h.get_state(B.DW_S_SCORE, i)
+        assert abs(sc[1] - w.c[0] * du) < 2e-5 and abs(sc[1] - tr.last_a[i]) < 2e-5, (i, sc, tr.last_a[i])
+        assert abs(sc[2] - tr.last_h1[i]) < 5e-4 and abs(sc[3] - tr.last_h2[i]) < 5e-4
+        if branch == "reset":
+            assert sc[2] == 1.0 and sc[3] == 0.0
+            np.testing.assert_array_equal(h.get_state(B.DW_S_THETA, i), pre_c.astype(np.float32))
+        elif branch == "plain":
+            assert sc[2] == pytest.approx(w.alpha, abs=1e-7) and sc[3] == pytest.approx(w.alpha, abs=1e-7)
+        elif branch == "ramp":
+            assert w.alpha < sc[2] < 1.0 and 0.0 < sc[3] < w.alpha
+        else:                                                              # a = kappa: the ramps meet (1, 0) there
+            assert abs(sc[2] - 1.0) < 5e-4 and abs(sc[3]) < 5e-4
+        slack = 5e-4 * np.abs(pre_t[i] - pre_c)
+        close(h.get_state(B.DW_S_THETA, i) - pre_t[i], tr.theta[i] - pre_t[i], RTOL_UPDATE, "branch pull[%d]" % i,
+              extra=slack + 2.0 ** -23 * np.abs(tr.theta[i]))
+    if branch == "reset":
+        np.testing.assert_array_equal(h.get_state(B.DW_S_CENTRE), pre_c.astype(np.float32))

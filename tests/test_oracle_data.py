@@ -1,6 +1,6 @@
 """Pins for the oracle's overlap partition and minibatch draws (CPU only).
 
-The partition is checked against the set identities Section IV-A states (D_j = O u S_j, the S_j disjoint,
+The partition is checked against the set identities Section V-A states (D_j = O u S_j, the S_j disjoint,
 |S_j| = floor((n-o)/k), their union D - O), at the paper's own sizes (n = 60000, k in {4, 8}, the overlap
 ratios of its figure), and for being a uniform shuffle; the draws against exact rational arithmetic, closed
 forms for special |D_j|, the already pinned Rademacher stream, and uniformity.

@@ -51,7 +51,8 @@ typedef enum {
   DW_ERR_WORKSPACE = -4,     /* workspace too small or not 256-byte aligned                  */
   DW_ERR_ARG = -5,           /* bad call argument (mode, worker index, range, alignment)     */
   DW_ERR_HIP = -6,           /* a HIP runtime call failed (see dw_last_hip_error)            */
-  DW_ERR_MODE = -7           /* call not valid for this handle (MLP call on a flat problem ...) */
+  DW_ERR_MODE = -7,          /* call not valid for this handle (MLP call on a flat problem ...) */
+  DW_ERR_TOO_LARGE = -8      /* size beyond the fixed capacity of a call that allocates nothing */
 } dw_status;
 
 /* arithmetic type of the network part (optimizer state is always fp32) */
@@ -233,6 +234,18 @@ int dw_set_state(dw_handle* h, int what, int worker, int64_t offset, int64_t cou
 size_t dw_partition_scratch_bytes(int64_t n);
 int64_t dw_overlap_partition(int64_t n, int64_t o, int k, uint64_t seed, int32_t* d_index, void* d_scratch,
                              size_t scratch_bytes, void* stream);
+
+/*
+ * dw_overlap_partition for callers that cannot allocate device memory or hand in a scratch buffer: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same result,
+ * but the scratch is a fixed array inside the library's device image (12 bytes per point, DW_STATIC_MAX_POINTS points:
+ * 1.5 MiB held by every GPU the library runs on until the process ends).  The call allocates and frees nothing.
+ *   n           1 <= n <= DW_STATIC_MAX_POINTS; a larger n returns DW_ERR_TOO_LARGE and nothing is enqueued
+ * Every call on one GPU uses that GPU's one array (the kernels reset the part they use): calls that overlap in time
+ * on the same GPU, on any streams, race with each other; calls on one stream are ordered and safe.
+ */
+#define DW_STATIC_MAX_POINTS (1 << 17)
+int64_t dw_overlap_partition_static(int64_t n, int64_t o, int k, uint64_t seed, int32_t* d_index, void* stream);
 
 /*
  * The minibatch of every active worker (Section II eq.(3): each worker's gradient is that of a minibatch sampled

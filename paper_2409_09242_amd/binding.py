@@ -16,6 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libdw.so")
 
 DW_MAX_LAYERS, DW_MAX_K, DW_MAX_P, DW_MAX_CLASSES, DW_MAX_CONV = 8, 64, 8, 16, 2
+DW_STATIC_MAX_POINTS = 1 << 17
 DW_F32, DW_BF16 = 0, 1
 DW_FIXED, DW_MANUAL, DW_DYNAMIC = 0, 1, 2
 DW_SEQUENTIAL = 16      # OR-ed into the mode of elastic_sync: exchanges one after the other, in index order
@@ -25,7 +26,8 @@ DW_S_ACT = 16
 
 EXPORTS = ("dw_strerror", "dw_last_hip_error", "dw_param_count", "dw_workspace_bytes", "dw_init", "dw_destroy",
            "dw_worker_step", "dw_update_only", "dw_elastic_sync", "dw_get_state", "dw_set_state",
-           "dw_profile", "dw_profile_read", "dw_partition_scratch_bytes", "dw_overlap_partition", "dw_draw_batch")
+           "dw_profile", "dw_profile_read", "dw_partition_scratch_bytes", "dw_overlap_partition", "dw_draw_batch",
+           "dw_overlap_partition_static")
 KERNEL_CLASSES = ("rademacher", "gemm_fwd", "head", "gemm_wgrad", "gemm_dgrad", "update", "weights", "pull", "gather")
 
 
@@ -79,6 +81,8 @@ def lib() -> C.CDLL:
     L.dw_partition_scratch_bytes.restype = C.c_size_t; L.dw_partition_scratch_bytes.argtypes = [i64]
     L.dw_overlap_partition.restype = i64
     L.dw_overlap_partition.argtypes = [i64, i64, i32, C.c_uint64, vp, vp, C.c_size_t, vp]
+    L.dw_overlap_partition_static.restype = i64
+    L.dw_overlap_partition_static.argtypes = [i64, i64, i32, C.c_uint64, vp, vp]
     L.dw_draw_batch.restype = i32
     L.dw_draw_batch.argtypes = [vp, vp, vp, i64, vp, i64, C.c_uint64, vp, vp, vp, vp]
     _LIB = L
@@ -188,6 +192,17 @@ def overlap_partition(n: int, o: int, k: int, seed: int, device="cuda:0"):
         raise DwError(int(s), "dw_overlap_partition")
     torch.cuda.current_stream(dev).synchronize()          # the scratch tensor goes away with this frame
     return index
+
+
+def overlap_partition_static(n: int, o: int, k: int, seed: int, index) -> int:
+    """dw_overlap_partition_static into a caller-allocated int32 tensor [k][o + floor((n-o)/k)]; returns floor((n-o)/k).
+    Nothing is allocated here or in the library; the work is enqueued on the current stream of the tensor's device."""
+    import torch
+    stream = C.c_void_p(torch.cuda.current_stream(index.device).cuda_stream)
+    s = lib().dw_overlap_partition_static(n, o, k, seed, C.c_void_p(index.data_ptr()) if index.numel() else None, stream)
+    if s < 0:
+        raise DwError(int(s), "dw_overlap_partition_static")
+    return int(s)
 
 
 class Handle:

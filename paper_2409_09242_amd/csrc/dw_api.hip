@@ -26,6 +26,12 @@ inline int hip_fail(hipError_t e) {
     if (e__ != hipSuccess) return hip_fail(e__);       \
   } while (0)
 
+}  // namespace
+
+int dw::note_hip_error(hipError_t e) { return hip_fail(e); }
+
+namespace {
+
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline bool is_pow2(int x) { return x > 0 && (x & (x - 1)) == 0; }
 
@@ -427,6 +433,7 @@ const char* dw_strerror(int status) {
     case DW_ERR_ARG: return "invalid call argument";
     case DW_ERR_HIP: return "HIP runtime error";
     case DW_ERR_MODE: return "call not valid for this handle";
+    case DW_ERR_TOO_LARGE: return "size beyond the fixed capacity of a call that allocates nothing";
     default: return status > 0 ? "ok (positive result)" : "unknown status";
   }
 }

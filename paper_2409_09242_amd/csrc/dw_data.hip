@@ -9,7 +9,14 @@
 // The permutation is found by counting, for every point, the points whose (key, index) pair is smaller: n^2
 // comparisons, but exact, free of any ordering of equal work between threads, and done once per run
 // (n = 60000 takes well under a millisecond of compares).  The gather is a plain row copy bound by HBM bandwidth.
+#include <mutex>
+
 #include "dw_internal.h"
+
+// Scratch of dw_overlap_partition_static: keys and ranks of up to DW_STATIC_MAX_POINTS points, in the layout
+// partition_scratch_bytes describes.  Every device the library runs on holds its own copy at its own address until the
+// process ends; host code reaches it only through the address hipGetSymbolAddress returns for the current device.
+static __device__ __align__(256) unsigned char scratch[(size_t)DW_STATIC_MAX_POINTS * 12];
 
 namespace dw {
 
@@ -129,4 +136,40 @@ hipError_t launch_gather(const void* data, const int32_t* labels, const int32_t*
   return hipGetLastError();
 }
 
+// device address of `scratch` on the current device, looked up once per device
+hipError_t static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {nullptr};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
+}
+
 }  // namespace dw
+
+extern "C" int64_t dw_overlap_partition_static(int64_t n, int64_t o, int k, uint64_t seed, int32_t* d_index,
+                                               void* stream) {
+  if (n < 1 || o < 0 || o > n || k < 1 || k > DW_MAX_K) return DW_ERR_ARG;
+  if (n > DW_STATIC_MAX_POINTS) return DW_ERR_TOO_LARGE;
+  static_assert(sizeof(scratch) % 256 == 0, "the rank array starts at a multiple of 256 bytes");
+  if (dw::partition_scratch_bytes(n) > sizeof(scratch)) return DW_ERR_TOO_LARGE;
+  const int64_t sz = (n - o) / k;
+  if (!d_index && o + sz > 0) return DW_ERR_NULL;
+  void* d_scratch = nullptr;
+  hipError_t e = dw::static_scratch(&d_scratch);
+  if (e == hipSuccess) e = dw::launch_partition(n, o, k, seed, d_index, d_scratch, (hipStream_t)stream);
+  if (e != hipSuccess) return dw::note_hip_error(e);
+  return sz;
+}

@@ -104,6 +104,9 @@ hipError_t launch_broadcast(float* theta, const float* centre, uint16_t* wb16, i
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hipStream_t s);
 
+// records a failed HIP call for dw_last_hip_error (this thread) and returns DW_ERR_HIP
+int note_hip_error(hipError_t e);
+
 // ---- data side ---------------------------------------------------------------------------------------
 size_t partition_scratch_bytes(int64_t n);
 // index [k][o + s], s = floor((n-o)/k): row j = the shared points then worker j's own, in permutation order

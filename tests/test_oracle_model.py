@@ -242,3 +242,173 @@ def test_trainer_draws_distinct_probes_per_step_and_keeps_the_single_probe_strea
     assert hz.shape == (3, P)
     D = (np.stack(zs) * hz).mean(axis=0)
     np.testing.assert_allclose(three.v[0], 0.001 * D ** 2, rtol=1e-12, atol=1e-30)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# ReLU ties: the only place where a caller may dictate anything to the oracle.  The pins below fix what that
+# is: nothing outside the band, and inside it one of the two one-sided derivatives.
+# ---------------------------------------------------------------------------------------------------------
+def test_tie_choice_cannot_touch_a_unit_outside_the_band():
+    dims = DIMS_DEEP
+    theta, x, y, P = _problem(dims, 40, 11)
+    z = np.random.default_rng(3).choice([-1.0, 1.0], size=P)
+    plain = O.grad_and_hvp(theta, x, y, dims, z)
+    band = 0.05
+    tr = O.StepTrace()
+    O.grad_and_hvp(theta, x, y, dims, z, trace=tr, tie_band=band)
+    # the reported ties are exactly the units with |s| < band * rms(s_l), counted here from the pre-activations
+    n_ties = 0
+    for l, s_l in enumerate(tr.pre_acts[:-1]):
+        want = np.abs(s_l) < band * np.sqrt(np.mean(s_l ** 2))
+        np.testing.assert_array_equal(tr.ties[l], want)
+        n_ties += int(want.sum())
+    assert 0 < n_ties < 0.1 * sum(s.size for s in tr.pre_acts[:-1])
+    rng = np.random.default_rng(4)
+    natural = [s_l > 0 for s_l in tr.pre_acts[:-1]]
+    # any choice that agrees with the natural slopes inside the band gives the plain result, whatever it says outside
+    noise = [np.where(t, n, rng.random(n.shape) < 0.5) for t, n in zip(tr.ties, natural)]
+    got = O.grad_and_hvp(theta, x, y, dims, z, tie_band=band, tie_choice=noise)
+    for a, b in zip(got, plain):
+        np.testing.assert_array_equal(a, b)
+    # without a band a choice is ignored altogether
+    got = O.grad_and_hvp(theta, x, y, dims, z, tie_band=0.0, tie_choice=[~n for n in natural])
+    for a, b in zip(got, plain):
+        np.testing.assert_array_equal(a, b)
+    # flipping the units inside the band does change the result (the band is not a dead letter)
+    flipped = [np.where(t, ~n, n) for t, n in zip(tr.ties, natural)]
+    got = O.grad_and_hvp(theta, x, y, dims, z, tie_band=band, tie_choice=flipped)
+    assert np.abs(got[1] - plain[1]).max() > 1e-6 and np.abs(got[2] - plain[2]).max() > 1e-6
+    assert got[0] == plain[0]                                   # the loss never depends on the slope chosen
+
+
+@pytest.mark.parametrize("side", ["on", "off"])
+def test_a_dictated_tie_is_the_one_sided_derivative(side):
+    """A hidden unit a hair's breadth from its kink, its slope dictated through tie_choice: g and Hz must be those of
+    the network with that unit moved just across the kink (bias shifted by twice the distance), where no tie exists."""
+    dims = DIMS_DEEP
+    theta, x, y, P = _problem(dims, 6, 21)
+    z = np.random.default_rng(5).choice([-1.0, 1.0], size=P)
+    offs, _ = O.layer_offsets(dims)
+    n, j, gap = 2, 3, 1e-10
+    tr = O.StepTrace()
+    O.grad_and_hvp(theta, x, y, dims, z, trace=tr)
+    theta = theta.copy()
+    # put s_1[n, j] at -gap (natural slope off) or +gap (natural slope on) by moving the unit's bias
+    theta[offs[0][1] + j] += (gap if side == "off" else -gap) - tr.pre_acts[0][n, j]
+    tr = O.StepTrace()
+    O.grad_and_hvp(theta, x, y, dims, z, trace=tr)
+    assert abs(abs(tr.pre_acts[0][n, j]) - gap) < 1e-14 and (tr.pre_acts[0][n, j] > 0) == (side == "off")
+    others = min(np.abs(np.delete(tr.pre_acts[0].reshape(-1), n * dims[1] + j)).min(), np.abs(tr.pre_acts[1]).min())
+    band = 1e-8 / np.sqrt(np.mean(tr.pre_acts[0] ** 2))
+    assert others > 1e-6                                         # the band below holds this one unit only
+    choice = [s_l > 0 for s_l in tr.pre_acts[:-1]]
+    choice[0][n, j] = side == "on"
+    tr2 = O.StepTrace()
+    forced = O.grad_and_hvp(theta, x, y, dims, z, trace=tr2, tie_band=band, tie_choice=choice)
+    assert int(tr2.ties[0].sum()) == 1 and tr2.ties[0][n, j] and int(tr2.ties[1].sum()) == 0
+    across = theta.copy()
+    across[offs[0][1] + j] += 2 * gap if side == "on" else -2 * gap
+    want = O.grad_and_hvp(across, x, y, dims, z)
+    natural = O.grad_and_hvp(theta, x, y, dims, z)
+    for a, b, c in zip(forced[1:], want[1:], natural[1:]):
+        assert np.abs(a - b).max() < 1e-8 and np.abs(a - c).max() > 1e-5
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Mixed precision: where the oracle rounds to bfloat16.  The pipeline stores x, the weights, a_l, Ra_l and the
+# back-propagated d_l, Rd_l in bf16 and keeps every sum, g and Hz wider.
+# ---------------------------------------------------------------------------------------------------------
+class _Rounder:
+    """round_bf16 that can leave one of its call sites out; records what went through it."""
+
+    def __init__(self, skip=None):
+        self.skip, self.calls = skip, []
+
+    def __call__(self, a):
+        idx = len(self.calls)
+        self.calls.append(np.shape(a))
+        return np.asarray(a, dtype=np.float64) if idx == self.skip else O.round_bf16(a)
+
+
+def test_bf16_mode_rounds_at_the_stored_tensors_and_every_rounding_point_matters():
+    dims, B = (8, 12, 6, 4), 10                 # L = 3: two hidden layers
+    theta, x, y, P = _problem(dims, B, 33)
+    z = np.random.default_rng(6).choice([-1.0, 1.0], size=P)
+    L = len(dims) - 1
+    q = _Rounder()
+    loss, g, hz = O.grad_and_hvp(theta, x, y, dims, z, q)
+    # what is rounded, by shape: x once; every W_l (read by the forward pass and again by the R- and backward passes);
+    # a_l and Ra_l of the hidden layers; d_l and Rd_l of every layer
+    shapes = q.calls
+    assert shapes.count((B, dims[0])) == 1
+    for l in range(1, L + 1):
+        assert shapes.count((dims[l], dims[l - 1])) == 2
+    hidden = sum(shapes.count((B, dims[l])) for l in range(1, L))
+    assert hidden == 4 * (L - 1)                                 # a_l, Ra_l, d_l, Rd_l per hidden layer
+    assert shapes.count((B, dims[L])) == 2                       # d_L, Rd_L
+    assert len(shapes) == 1 + 2 * L + 4 * (L - 1) + 2
+    # every result is computed from rounded operands only: the same call on inputs that are already bf16 values
+    # and with the weights pre-rounded gives the same bits
+    offs, _ = O.layer_offsets(dims)
+    th_r = theta.copy()
+    for l, (w_off, b_off) in enumerate(offs):
+        th_r[w_off:b_off] = O.round_bf16(theta[w_off:b_off])
+    same = O.grad_and_hvp(th_r, O.round_bf16(x), y, dims, z, O.round_bf16)
+    assert same[0] == loss
+    np.testing.assert_array_equal(same[1], g); np.testing.assert_array_equal(same[2], hz)
+    # the biases are not rounded (fp32 state added in the epilogue): rounding them as well changes the result
+    th_b = th_r.copy()
+    for l, (w_off, b_off) in enumerate(offs):
+        th_b[b_off:b_off + dims[l + 1]] = O.round_bf16(th_b[b_off:b_off + dims[l + 1]])
+    assert np.abs(O.grad_and_hvp(th_b, x, y, dims, z, O.round_bf16)[1] - g).max() > 0
+    # leaving out any single rounding point changes g or Hz.  The one exception: the copy of W_1 read after the
+    # forward pass multiplies Ra_0 = 0 only (the input does not depend on the parameters) and no error is propagated
+    # below the first layer, so its rounding cannot show
+    w1_again = [i for i, sh in enumerate(shapes) if sh == (dims[1], dims[0])][1]
+    for skip, shape in enumerate(shapes):
+        q2 = _Rounder(skip)
+        l2, g2, hz2 = O.grad_and_hvp(theta, x, y, dims, z, q2)
+        assert q2.calls == shapes
+        dg, dh = np.abs(g2 - g).max(), np.abs(hz2 - hz).max()
+        assert (dg > 0 or dh > 0) == (skip != w1_again), (skip, shape)
+    # identity rounding is the full-precision oracle
+    full = O.grad_and_hvp(theta, x, y, dims, z)
+    ident = O.grad_and_hvp(theta, x, y, dims, z, lambda a: a)
+    for a, b in zip(full, ident):
+        np.testing.assert_array_equal(a, b)
+    # and bf16 results sit within bf16 rounding of it: a few 2^-9 per rounding point, far from equal
+    rel = np.linalg.norm(g - full[1]) / np.linalg.norm(full[1])
+    assert 1e-4 < rel < 3e-2, rel
+
+
+def test_r_pass_rounding_points_leave_the_gradient_alone():
+    """Ra_l and Rd_l feed only the Hessian-vector product: leaving their rounding out must not move g or the loss."""
+    dims, B = (8, 12, 6, 4), 10
+    theta, x, y, P = _problem(dims, B, 34)
+    z = np.random.default_rng(7).choice([-1.0, 1.0], size=P)
+    q = _Rounder()
+    loss, g, hz = O.grad_and_hvp(theta, x, y, dims, z, q)
+    q_none = _Rounder()
+    loss_n, g_n, _ = O.grad_and_hvp(theta, x, y, dims, None, q_none)          # no z: no R-pass, fewer roundings
+    assert loss_n == loss
+    np.testing.assert_array_equal(g_n, g)
+    L = len(dims) - 1
+    assert len(q.calls) - len(q_none.calls) == (L - 1) + L                    # Ra_l of the hidden layers, Rd_l of all
+
+
+def test_trainer_bf16_flag_selects_the_rounding():
+    dims, B = (8, 12, 4), 6
+    theta, x, y, P = _problem(dims, B, 35)
+    theta32 = theta.astype(np.float32).astype(np.float64)
+    a = O.OracleTrainer(O.OracleConfig(dims=dims, k=1, seed=2, bf16=True), theta32)
+    b = O.OracleTrainer(O.OracleConfig(dims=dims, k=1, seed=2, bf16=False), theta32)
+    a.worker_step(x[None], y[None]); b.worker_step(x[None], y[None])
+    zz = a.traces[0].z
+    want = O.grad_and_hvp(theta32, x, y, dims, zz, O.round_bf16)
+    np.testing.assert_array_equal(a.traces[0].g, want[1]); np.testing.assert_array_equal(a.traces[0].hz, want[2])
+    a.q = lambda v: v                                                          # identity rounding = the fp32 trainer
+    a.theta[0] = theta32; a.m[:] = 0; a.v[:] = 0; a.t[:] = 0
+    a.worker_step(x[None], y[None])
+    np.testing.assert_array_equal(a.traces[0].g, b.traces[0].g)
+    np.testing.assert_array_equal(a.traces[0].hz, b.traces[0].hz)
+    np.testing.assert_array_equal(a.theta[0], b.theta[0])

@@ -11,6 +11,7 @@ Distributed Deep Learning"):
   * minibatch mean loss and gradient                     -- Section II eq.(2), Section III-B eq.(6)
   * Hutchinson estimate z * (Hz), z Rademacher           -- Section IV-B, un-numbered display
   * spatial averaging, Adam-like moments, update         -- Section IV-B last paragraph, eq.(4)
+  * SGD and momentum steps of the baselines              -- Section II eq.(3), Section VI, Section VII
   * log-distance u, weighted raw score a                 -- Section V-B, eq.(10)-(11)
   * piecewise-linear weights h1, h2                      -- Section V-B, un-numbered displays
   * elastic pull of worker and master                    -- Section V-B eq.(12)-(13)
@@ -339,6 +340,30 @@ def adahessian_update(theta, m, v, g, hz, z, t, *, lr, beta1, beta2, eps, hpow, 
 
 
 # ---------------------------------------------------------------------------------------------
+# First-order worker steps of the baselines the paper compares with (Section VI: EASGD, and EASGD
+# with momentum; Section VII: eta = 0.01, momentum delta = 0.5).  They share the elastic pull.
+#
+# Reading: the paper does not write the momentum step out; it is taken as the classical heavy-ball
+# form of the framework it used (velocity b <- delta*b + g, theta <- theta - eta*b, no dampening,
+# no Nesterov look-ahead).
+# ---------------------------------------------------------------------------------------------
+
+
+def sgd_update(theta, g, *, lr):
+    """Plain stochastic gradient step (Section II eq.(3)): theta <- theta - eta * g."""
+    return theta - lr * g
+
+
+def momentum_update(theta, buf, g, *, lr, momentum):
+    """SGD with momentum: b <- delta*b + g, theta <- theta - eta*b.  Returns (theta, b)."""
+    buf_new = momentum * buf + g
+    return theta - lr * buf_new, buf_new
+
+
+OPT_ADAHESSIAN, OPT_SGD, OPT_MOMENTUM = 0, 1, 2
+
+
+# ---------------------------------------------------------------------------------------------
 # Dynamic weighting (Section V-B).
 # ---------------------------------------------------------------------------------------------
 
@@ -453,6 +478,8 @@ class OracleConfig:
     bf16: bool = False
     n_params: int = 0
     n_samples: int = 1                # Rademacher probes per step (Section IV-B's n)
+    optimizer: int = OPT_ADAHESSIAN   # worker step: AdaHessian, or a baseline's SGD / SGD with momentum (Section VI)
+    momentum: float = 0.5             # delta of Section VII (OPT_MOMENTUM only; the velocity lives in self.m)
 
 
 class OracleTrainer:
@@ -496,6 +523,15 @@ class OracleTrainer:
         for i in range(cfg.k):
             if active is not None and not active[i]:
                 continue
+            if cfg.optimizer != OPT_ADAHESSIAN:
+                # baseline worker step: the minibatch gradient alone, no Hessian-vector product
+                tr = StepTrace()
+                loss, g, _ = grad_and_hvp(self.theta[i], x[i], y[i], cfg.dims, None, self.q, tr)
+                self.traces[i] = tr
+                self.t[i] += 1
+                self._first_order(i, g)
+                losses[i] = loss
+                continue
             if cfg.n_samples == 1:
                 z = self.draw_z(i) if z_signs is None else np.asarray(z_signs[i], dtype=F64)
                 tr = StepTrace()
@@ -523,11 +559,22 @@ class OracleTrainer:
         self.global_step += 1
         return losses
 
+    def _first_order(self, i, g):
+        cfg = self.cfg
+        if cfg.optimizer == OPT_SGD:
+            self.theta[i] = sgd_update(self.theta[i], g, lr=cfg.lr)
+        else:
+            self.theta[i], self.m[i] = momentum_update(self.theta[i], self.m[i], g, lr=cfg.lr, momentum=cfg.momentum)
+
     def update_only(self, g, hz, z_signs=None, active=None):
-        """The optimizer part alone on caller-supplied g and Hz ([k,P] each)."""
+        """The optimizer part alone on caller-supplied g and Hz ([k,P] each; Hz is not used by the baselines)."""
         cfg = self.cfg
         for i in range(cfg.k):
             if active is not None and not active[i]:
+                continue
+            if cfg.optimizer != OPT_ADAHESSIAN:
+                self.t[i] += 1
+                self._first_order(i, np.asarray(g[i], dtype=F64))
                 continue
             z = self.draw_z(i) if z_signs is None else np.asarray(z_signs[i], dtype=F64)
             self.t[i] += 1

@@ -294,3 +294,89 @@ def test_trainer_sequential_round_uses_the_scores_of_the_round_start():
     np.testing.assert_array_equal(ta.last_u, tb.last_u)          # same u, a, h1, h2 ...
     np.testing.assert_array_equal(ta.last_h1, tb.last_h1)
     assert np.max(np.abs(ta.centre - tb.centre)) > 0             # ... different pull
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Baseline worker steps (Section II eq.(3); EASGD and EASGD with momentum of Section VI, delta = 0.5 in Section VII)
+# ---------------------------------------------------------------------------------------------------------
+def test_sgd_step_closed_forms():
+    # eq.(3) on f = a/2 theta^2 (g = a theta): theta_t = (1 - eta a)^t theta_0
+    a, eta = np.array([0.5, 2.0, 30.0]), 0.01
+    th = np.array([1.0, -2.0, 0.25])
+    th0 = th.copy()
+    for _ in range(7):
+        th = O.sgd_update(th, a * th, lr=eta)
+    np.testing.assert_allclose(th, (1.0 - eta * a) ** 7 * th0, rtol=1e-14)
+    # a constant gradient moves the parameters along a straight line
+    g = np.array([3.0, -1.0, 0.0])
+    np.testing.assert_array_equal(O.sgd_update(th0, g, lr=0.5), th0 - 0.5 * g)
+
+
+def test_momentum_step_against_torch_sgd_and_its_closed_form():
+    import torch
+    rng = np.random.default_rng(12)
+    P, steps, eta, delta = 50, 9, 0.01, 0.5
+    th0 = rng.standard_normal(P)
+    gs = rng.standard_normal((steps, P))
+    th, buf = th0.copy(), np.zeros(P)
+    t = torch.tensor(th0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([t], lr=eta, momentum=delta)
+    for s in range(steps):
+        th, buf = O.momentum_update(th, buf, gs[s], lr=eta, momentum=delta)
+        t.grad = torch.tensor(gs[s])
+        opt.step()
+        np.testing.assert_allclose(th, t.detach().numpy(), rtol=1e-13, atol=1e-15)
+    # constant gradient: velocity g (1 - delta^t)/(1 - delta), position theta_0 - eta g sum_s (1 - delta^s)/(1 - delta)
+    g = rng.standard_normal(P)
+    th, buf = th0.copy(), np.zeros(P)
+    for s in range(1, 6):
+        th, buf = O.momentum_update(th, buf, g, lr=eta, momentum=delta)
+    np.testing.assert_allclose(buf, g * (1 - delta ** 5) / (1 - delta), rtol=1e-14)
+    np.testing.assert_allclose(th, th0 - eta * g * sum((1 - delta ** s) / (1 - delta) for s in range(1, 6)), rtol=1e-13)
+    # delta = 0 is plain SGD
+    np.testing.assert_array_equal(O.momentum_update(th0, buf, g, lr=eta, momentum=0.0)[0], O.sgd_update(th0, g, lr=eta))
+
+
+@pytest.mark.parametrize("opt", [O.OPT_SGD, O.OPT_MOMENTUM])
+def test_easgd_trainer_is_first_order_steps_plus_the_fixed_rate_pull(opt):
+    """EASGD / EAMSGD as the trainer runs them against a loop written out here with torch's autograd for the gradients:
+    k = 2 workers of a tiny ReLU classifier, a fixed-rate round (eq.(8)-(9) with the signs of eq.(12)-(13)) every
+    second step, worker 1 suppressed in the first round."""
+    import torch
+    dims, B, k, eta, delta, alpha = (5, 6, 3), 7, 2, 0.01, 0.5, 0.1
+    rng = np.random.default_rng(77)
+    _, P = O.layer_offsets(dims)
+    theta0 = rng.standard_normal(P) * 0.3
+    xs = rng.standard_normal((4, k, B, dims[0])); ys = rng.integers(0, dims[-1], size=(4, k, B))
+    tr = O.OracleTrainer(O.OracleConfig(dims=dims, k=k, lr=eta, alpha=alpha, optimizer=opt, momentum=delta), theta0)
+
+    def torch_grad(theta, x, y):
+        t = torch.tensor(theta, dtype=torch.float64, requires_grad=True)
+        W1 = t[:30].reshape(6, 5); b1 = t[30:36]; W2 = t[36:54].reshape(3, 6); b2 = t[54:57]
+        out = torch.relu(torch.tensor(x) @ W1.T + b1) @ W2.T + b2
+        torch.nn.functional.cross_entropy(out, torch.tensor(y)).backward()
+        return t.grad.numpy()
+
+    th = np.tile(theta0, (k, 1)); buf = np.zeros((k, P)); centre = theta0.copy()
+    for step in range(4):
+        tr.worker_step(xs[step], ys[step])
+        for i in range(k):
+            g = torch_grad(th[i], xs[step][i], ys[step][i])
+            if opt == O.OPT_SGD:
+                th[i] = th[i] - eta * g
+            else:
+                buf[i] = delta * buf[i] + g
+                th[i] = th[i] - eta * buf[i]
+        part = [1, 0] if step == 1 else [1, 1]
+        did = tr.elastic_sync(O.MODE_FIXED, tau=2, participate=part)
+        assert did == (step % 2 == 1)
+        if did:
+            d = [th[i] - centre for i in range(k)]
+            for i in range(k):
+                if part[i]:
+                    th[i] = th[i] - alpha * d[i]
+                    centre = centre + alpha * d[i]
+        np.testing.assert_allclose(tr.theta, th, rtol=1e-11, atol=1e-14)
+        np.testing.assert_allclose(tr.centre, centre, rtol=1e-11, atol=1e-14)
+    assert np.all(tr.v == 0.0) and (np.all(tr.m == 0.0) == (opt == O.OPT_SGD))       # no second moment; velocity in m
+    assert list(tr.t) == [4, 4]

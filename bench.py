@@ -25,10 +25,34 @@ sys.path.insert(0, ROOT)
 
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA
-# HBM-side bytes per launch of the fused weight-gradient kernel at configuration 4 (mean of the three launches of
-# a step), from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE scaled by a plain copy kernel (factors 2.00 and 1.00);
-# see profiles/dual_gemm_bf16_c4_mfma_utilisation_hbm_traffic.txt.  Valid only for the kernel as profiled there.
-TRAFFIC_C4_FUSED_WGRAD = 8.31e9
+# HBM-side bytes per launch of the fused weight-gradient kernel at configuration 4 come from a counter run
+# (rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, scaled by a plain copy kernel of known size); its summary under
+# profiles/ carries the figure and the digest of the kernel's sources at the time.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "dual_gemm_bf16_c4_mfma_utilisation_hbm_traffic.txt")
+TRAFFIC_SOURCES = ("dw_gemm_bf16.hip", "dw_fused_update.h", "dw_gemm_epi.h", "dw_device_util.h")
+
+
+def kernel_sources_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for f in TRAFFIC_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2409_09242_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic():
+    """Bytes per launch read from the counter summary, or None when there is none or the kernel's sources have
+    changed since the counters were taken (lines `traffic_bytes_per_launch: X` and `kernel_sources_digest: D`)."""
+    import re
+    try:
+        text = open(TRAFFIC_SUMMARY).read()
+    except OSError:
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, flags=re.M)
+    d = re.search(r"^kernel_sources_digest:\s*([0-9a-f]+)", text, flags=re.M)
+    if not m or not d or d.group(1) != kernel_sources_digest():
+        return None
+    return float(m.group(1))
 
 
 def class_flops(w):
@@ -96,7 +120,7 @@ def class_bytes(w, P, k, fused=(), part=1.0, samples=1):
     return out
 
 
-def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, resident=None):
+def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, resident=None, repeats=5):
     import torch
     from paper_2409_09242_amd import binding as B
     from paper_2409_09242_amd import workloads as W
@@ -108,7 +132,7 @@ def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, residen
         xd = xd.to(torch.bfloat16)
     yd = torch.from_numpy(y).cuda()
     h = B.Handle(B.config_from_workload(w, fuse_update=1 if (fuse and not w.conv) else 0, n_samples=samples), theta0)
-    sched = W.participation_schedule(w, (2 * steps + warmup) // w.tau + 2)
+    sched = W.participation_schedule(w, ((repeats + 1) * steps + warmup) // w.tau + 2)
     state = {"round": 0, "step": 0}
     mode = B.DW_DYNAMIC | (B.DW_SEQUENTIAL if sequential else 0)
 
@@ -139,12 +163,16 @@ def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, residen
 
     for _ in range(warmup):
         one_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        one_step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    # the timed region (exactly `steps` steps between two synchronisations), `repeats` times back to back
+    regions = []
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one_step()
+        torch.cuda.synchronize()
+        regions.append(time.perf_counter() - t0)
+    elapsed = float(np.median(regions))
 
     # second pass over the same number of steps with every launch bracketed by HIP events
     h.profile(True)
@@ -156,7 +184,7 @@ def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, residen
     elapsed_prof = time.perf_counter() - t1
     h.profile(False)
     part = float(np.mean([np.mean(r) for r in sched[:max(state["round"], 1)]]))
-    return h, elapsed, prof, elapsed_prof, part
+    return h, elapsed, prof, elapsed_prof, part, regions
 
 
 def calibration_copy(n=1 << 28, reps=5):
@@ -173,19 +201,20 @@ def calibration_copy(n=1 << 28, reps=5):
     torch.cuda.empty_cache()
 
 
-def run_update_stress(iters=20, warmup=3):
+def run_update_stress(iters=20, warmup=3, optimizer=0):
     """Configuration 5: flat P = 1e8 per replica, k = 16; one fused AdaHessian update + one dynamic-weighted
-    elastic round per iteration.  Returns GB/s figures against the HBM peak."""
+    elastic round per iteration.  Returns GB/s figures against the HBM peak.  optimizer 1 / 2: the same with the
+    first-order step of the baselines (SGD: 12 B per parameter and worker, momentum: 20 B, where AdaHessian moves 32)."""
     import torch
     from paper_2409_09242_amd import binding as B
     from paper_2409_09242_amd import workloads as W
 
-    w = W.C5
+    w = W.scaled(W.C5, optimizer=optimizer)
     P, k = w.n_params, w.k
     gen = torch.Generator(device="cuda").manual_seed(w.seed)
     theta0 = (torch.rand(P, device="cuda", generator=gen) - 0.5) * 0.02
     g = torch.randn(k, P, device="cuda", generator=gen) * 0.1
-    hz = torch.randn(k, P, device="cuda", generator=gen) * 0.1
+    hz = torch.randn(k, P, device="cuda", generator=gen) * 0.1 if optimizer == 0 else None
     h = B.Handle(B.config_from_workload(w), theta0)
     for _ in range(warmup):
         h.update_only(g, hz)
@@ -204,11 +233,13 @@ def run_update_stress(iters=20, warmup=3):
     prof = h.profile_read()
     h.profile(False)
     by = class_bytes(w, P, k)
+    if optimizer:
+        by["update"] = (12.0 if optimizer == 1 else 20.0) * P * k
     total_bytes = by["update"] + by["pull"] + 4.0 * P          # + the centre read by the update
     upd_ms = prof["update"][1] / max(prof["update"][0], 1)
     pull_ms = prof["pull"][1] / max(prof["pull"][0], 1)
     out = {
-        "workload": w.name, "P": P, "k": k, "iters": iters,
+        "workload": w.name, "P": P, "k": k, "iters": iters, "worker_step": ("adahessian", "sgd", "momentum")[optimizer],
         "ms_per_iter": 1e3 * el / iters,
         "bytes_per_iter": total_bytes,
         "GB/s": total_bytes / (el / iters) / 1e9,
@@ -295,6 +326,8 @@ def main():
     ap.add_argument("--resident-data", type=float, default=None, metavar="RATIO",
                     help="draw every step's minibatches on the device from a resident synthetic data set of 60000 "
                          "points, partitioned among the workers with this overlap ratio (e.g. 0.125)")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="how many times the timed region of --steps steps is run; the line reports the median region")
     ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stress-only", action="store_true",
@@ -319,8 +352,8 @@ def main():
     n_pool = 4 if w.bf16 else 8
     if args.calibrate:
         calibration_copy()
-    h, elapsed, prof, elapsed_prof, part = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse, args.sequential, args.samples,
-                                                  args.resident_data)
+    h, elapsed, prof, elapsed_prof, part, regions = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse,
+                                                           args.sequential, args.samples, args.resident_data, args.repeats)
     dtype = "bf16" if w.bf16 else "f32"
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.k * args.steps / elapsed
@@ -380,7 +413,7 @@ def main():
             roof["bytes_per_launch"] = by[dominant] / n_big
             roof["avg_ms"] = kernels[dominant]["ms_per_step"] / n_big
             if w.name.startswith("c4") and args.samples <= 1:
-                roof["traffic"] = TRAFFIC_C4_FUSED_WGRAD
+                roof["traffic"] = measured_traffic()
     gemm_roof = None
     if gemm_ms > 0:
         ach_g = gemm_fl / (gemm_ms * 1e-3) / 1e12
@@ -393,6 +426,8 @@ def main():
     out = {
         "metric": "AdaHessian worker-steps/s (incl. Hv)", "value": value, "unit": "worker-steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "timed_regions": len(regions), "ms_per_step_min": 1e3 * min(regions) / args.steps,
+        "ms_per_step_max": 1e3 * max(regions) / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w.name, "k": w.k, "dims": list(w.dims), "batch": w.batch, "tau": w.tau,
                    **({"img": list(w.img), "conv": list(w.conv), "conv_avg": w.conv_avg} if w.conv else {}),
@@ -409,6 +444,8 @@ def main():
     }
     if not args.no_stress:
         out["update_stress"] = run_update_stress()
+        # the first-order worker steps of the baselines (elastic averaging SGD, with and without momentum) on the same vectors
+        out["update_stress_baselines"] = [run_update_stress(10, 2, opt) for opt in (1, 2)]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(out))

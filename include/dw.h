@@ -59,6 +59,12 @@ typedef enum {
 #define DW_F32 0             /* fp32 weights, activations, MFMA accumulation                            */
 #define DW_BF16 1            /* bf16 weights/activations (round-to-nearest-even), fp32 accumulation     */
 
+/* the local step a worker takes (dw_config.optimizer) */
+#define DW_OPT_ADAHESSIAN 0  /* Section IV-B, the method's own step                                             */
+#define DW_OPT_SGD 1         /* theta -= lr * g  (Section II eq.(3)): worker step of the EASGD baseline, Section VI */
+#define DW_OPT_MOMENTUM 2    /* b = momentum * b + g; theta -= lr * b: EASGD with momentum (Section VI; Section VII
+                                uses momentum 0.5, lr 0.01).  The velocity b is the state read through DW_S_M.   */
+
 /* how dw_elastic_sync chooses the per-worker weights (h1_i, h2_i) */
 #define DW_FIXED 0           /* h1 = h2 = alpha: plain elastic averaging (Section IV-A)                 */
 #define DW_MANUAL 1          /* caller-supplied: weights set with foreknowledge of the failures (Section VI) */
@@ -132,6 +138,12 @@ typedef struct {
   int32_t conv_avg;                 /* 1: D = z*Hz of a convolution kernel is replaced by its mean over the
                                        3x3 window of each (output, input) channel pair (Section IV-B); biases
                                        and linear layers are not averaged                                    */
+  /* Baseline worker steps (Section VI compares against elastic averaging SGD with and without momentum).  With
+   * DW_OPT_SGD or DW_OPT_MOMENTUM the step uses the minibatch gradient alone: no z is drawn, avg_block, hpow, the
+   * betas and eps are not used, n_samples must be 0 or 1 and fuse_update 0, and dw_update_only ignores d_hz (it
+   * may be NULL).  The communication round is the same call (DW_FIXED gives elastic averaging SGD). */
+  int32_t optimizer;                /* DW_OPT_ADAHESSIAN (0, default) | DW_OPT_SGD | DW_OPT_MOMENTUM          */
+  float momentum;                   /* delta of DW_OPT_MOMENTUM, 0 <= momentum < 1                           */
 } dw_config;
 
 /* Human-readable text for a status code (never NULL). */

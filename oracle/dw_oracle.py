@@ -526,7 +526,8 @@ class OracleTrainer:
             if cfg.optimizer != OPT_ADAHESSIAN:
                 # baseline worker step: the minibatch gradient alone, no Hessian-vector product
                 tr = StepTrace()
-                loss, g, _ = grad_and_hvp(self.theta[i], x[i], y[i], cfg.dims, None, self.q, tr)
+                loss, g, _ = grad_and_hvp(self.theta[i], x[i], y[i], cfg.dims, None, self.q, tr, tie_band,
+                                          None if tie_choice is None else tie_choice[i])
                 self.traces[i] = tr
                 self.t[i] += 1
                 self._first_order(i, g)

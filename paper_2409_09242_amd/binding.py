@@ -19,6 +19,7 @@ DW_MAX_LAYERS, DW_MAX_K, DW_MAX_P, DW_MAX_CLASSES, DW_MAX_CONV = 8, 64, 8, 16, 2
 DW_STATIC_MAX_POINTS = 1 << 17
 DW_F32, DW_BF16 = 0, 1
 DW_FIXED, DW_MANUAL, DW_DYNAMIC = 0, 1, 2
+DW_OPT_ADAHESSIAN, DW_OPT_SGD, DW_OPT_MOMENTUM = 0, 1, 2
 DW_SEQUENTIAL = 16      # OR-ed into the mode of elastic_sync: exchanges one after the other, in index order
 (DW_S_THETA, DW_S_M, DW_S_V, DW_S_G, DW_S_HZ, DW_S_CENTRE, DW_S_ZBITS, DW_S_SCORE, DW_S_U_HIST,
  DW_S_STEPS, DW_S_ZBITS_T, DW_S_COUNTERS) = range(12)
@@ -41,6 +42,7 @@ class dw_config(C.Structure):
         ("seed", C.c_uint64), ("n_samples", C.c_int32), ("fuse_update", C.c_int32),
         ("n_conv", C.c_int32), ("img_h", C.c_int32), ("img_w", C.c_int32), ("img_c", C.c_int32),
         ("conv_c", C.c_int32 * DW_MAX_CONV), ("conv_avg", C.c_int32),
+        ("optimizer", C.c_int32), ("momentum", C.c_float),
     ]
 
 
@@ -93,7 +95,7 @@ def make_config(*, dims: Optional[Sequence[int]], k: int, batch: int = 0, bf16: 
                 lr=0.01, beta1=0.9, beta2=0.999, eps=1e-4, hpow=1.0, avg_block=1, alpha=0.1, kappa=-0.1,
                 c: Sequence[float] = (0.4, 0.3, 0.2, 0.1), seed: int = 0, fuse_update: int = 0,
                 n_samples: int = 1, img: Optional[Sequence[int]] = None, conv: Sequence[int] = (),
-                conv_avg: int = 0) -> dw_config:
+                conv_avg: int = 0, optimizer: int = DW_OPT_ADAHESSIAN, momentum: float = 0.5) -> dw_config:
     cfg = dw_config()
     if dims is None:
         cfg.n_layers = 0
@@ -117,13 +119,15 @@ def make_config(*, dims: Optional[Sequence[int]], k: int, batch: int = 0, bf16: 
         for j, cj in enumerate(conv):
             cfg.conv_c[j] = cj
     cfg.conv_avg = conv_avg
+    cfg.optimizer, cfg.momentum = optimizer, momentum
     return cfg
 
 
 def config_from_workload(w, **overrides) -> dw_config:
     kw = dict(dims=w.dims, k=w.k, batch=w.batch, bf16=w.bf16, n_params=w.n_params if w.dims is None else 0,
               lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, hpow=w.hpow, avg_block=w.avg_block,
-              alpha=w.alpha, kappa=w.kappa, c=w.c, seed=w.seed)
+              alpha=w.alpha, kappa=w.kappa, c=w.c, seed=w.seed, optimizer=getattr(w, "optimizer", 0),
+              momentum=getattr(w, "momentum", 0.5))
     if getattr(w, "conv", ()):
         kw.update(img=w.img, conv=w.conv, conv_avg=w.conv_avg)
     kw.update(overrides)

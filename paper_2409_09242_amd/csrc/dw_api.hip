@@ -42,6 +42,10 @@ int validate(const dw_config* c, Layout* lay) {
   if (c->dtype != DW_F32 && c->dtype != DW_BF16) return DW_ERR_CONFIG;
   if (c->fuse_update != 0 && c->fuse_update != 1) return DW_ERR_CONFIG;
   if (c->n_samples < 0 || c->n_samples > DW_MAX_SAMPLES) return DW_ERR_CONFIG;
+  if (c->optimizer != DW_OPT_ADAHESSIAN && c->optimizer != DW_OPT_SGD && c->optimizer != DW_OPT_MOMENTUM)
+    return DW_ERR_CONFIG;
+  if (c->optimizer != DW_OPT_ADAHESSIAN && (c->n_samples > 1 || c->fuse_update != 0)) return DW_ERR_CONFIG;
+  if (c->optimizer == DW_OPT_MOMENTUM && !(c->momentum >= 0.f && c->momentum < 1.f)) return DW_ERR_HYPER;
   if (c->n_layers < 0 || c->n_layers > DW_MAX_LAYERS) return DW_ERR_CONFIG;
   const int L = c->n_layers;
   const int align = c->dtype == DW_BF16 ? 8 : 4;
@@ -279,6 +283,7 @@ void fill_update_args(dw_handle* h, UpdateArgs& a, const float* g, const float* 
   a.P = L.P; a.Pp = L.Pp; a.g_stride = g_stride; a.z_stride = z_stride;
   a.k = c.k; a.avg_block = c.avg_block;
   a.lr = c.lr; a.beta1 = c.beta1; a.beta2 = c.beta2; a.eps = c.eps; a.hpow = c.hpow;
+  a.optimizer = c.optimizer; a.momentum = c.momentum;
   a.d_scale = 0.f;
   a.probe_mode = 0; a.probe_first = 0; a.dacc = nullptr;
   a.active_mask = active;
@@ -551,7 +556,9 @@ int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint
   const uint64_t active = mask_from(h_active, h->cfg.k);
   if (active == 0) { h->calls += 1; return DW_OK; }
   if (probes(h) > 1 && d_zbits) return DW_ERR_ARG;       // several probes per step come from the library's stream
-  if (!d_zbits && probes(h) == 1) {
+  // (a baseline's first-order step draws no z: the direction the network's R-parts then run along is whatever the
+  // sign-bit buffer holds, and their result is not used)
+  if (!d_zbits && probes(h) == 1 && h->cfg.optimizer == DW_OPT_ADAHESSIAN) {
     const int st = draw_z(h, active, s);
     if (st != DW_OK) return st;
   }
@@ -560,7 +567,10 @@ int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint
 
 int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint32_t* d_zbits,
                    const uint8_t* h_active, void* stream) {
-  if (!h || !d_g || !d_hz) return DW_ERR_NULL;
+  if (!h || !d_g) return DW_ERR_NULL;
+  const bool first_order = h->cfg.optimizer != DW_OPT_ADAHESSIAN;
+  if (!d_hz && !first_order) return DW_ERR_NULL;
+  if (!d_hz) d_hz = d_g;                              // never read by a first-order step
   if (h->lay.P % 4 != 0) return DW_ERR_MODE;          // worker i sits at offset i*P: needs 16-byte rows
   if (h->lay.n_conv > 0 && h->cfg.conv_avg) return DW_ERR_MODE;   // the window mean needs a writable Hz
   ProfilerGuard pg(h);
@@ -570,7 +580,7 @@ int dw_update_only(dw_handle* h, const float* d_g, const float* d_hz, const uint
   hipStream_t s = (hipStream_t)stream;
   const uint64_t active = mask_from(h_active, h->cfg.k);
   if (active == 0) { h->calls += 1; return DW_OK; }
-  if (!d_zbits) {
+  if (!d_zbits && !first_order) {
     const int st = draw_z(h, active, s);
     if (st != DW_OK) return st;
   }

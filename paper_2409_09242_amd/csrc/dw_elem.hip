@@ -53,7 +53,10 @@ __device__ __forceinline__ float denom_pow(float vhat, float hpow) {
   return powf(vhat, 0.5f * hpow);
 }
 
-template <bool HAS_B16>
+// OPT: the local step (DW_OPT_*).  The baselines' first-order steps (Section II eq.(3); Section VI) move 12 bytes
+// (SGD: g and theta read, theta written) or 20 bytes (momentum: also the velocity read and written) per parameter
+// and worker where the AdaHessian step moves 32.
+template <bool HAS_B16, int OPT>
 __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -117,17 +120,47 @@ __global__ __launch_bounds__(kUpdThreads) void update_kernel(UpdateArgs a) {
 #pragma unroll
       for (int u = 0; u < kUpdQuads; ++u) {
         const int64_t q = qbase + (int64_t)u * kUpdThreads;
+        G[u] = H[u] = T[u] = M[u] = V[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        Z[u] = 0;
         if (valid[u] && !fz[u]) {
-          G[u] = nt_load4(g4 + q); H[u] = nt_load4(h4 + q); T[u] = nt_load4(th4 + q);
-          M[u] = nt_load4(m4 + q); V[u] = nt_load4(v4 + q);
-          Z[u] = zb[q >> 3] >> zshift[u];
-        } else {
-          G[u] = H[u] = T[u] = M[u] = V[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-          Z[u] = 0;
+          G[u] = nt_load4(g4 + q); T[u] = nt_load4(th4 + q);
+          if (OPT != DW_OPT_SGD) M[u] = nt_load4(m4 + q);
+          if (OPT == DW_OPT_ADAHESSIAN) {
+            H[u] = nt_load4(h4 + q); V[u] = nt_load4(v4 + q);
+            Z[u] = zb[q >> 3] >> zshift[u];
+          }
+        }
+      }
+      if (OPT != DW_OPT_ADAHESSIAN) {
+        // first-order step of a baseline: theta -= lr * g, or the same through the velocity b = momentum * b + g
+#pragma unroll
+        for (int u = 0; u < kUpdQuads; ++u) {
+          const int64_t q = qbase + (int64_t)u * kUpdThreads;
+          float g[4] = {G[u].x, G[u].y, G[u].z, G[u].w};
+          float th[4] = {T[u].x, T[u].y, T[u].z, T[u].w};
+          float bb[4] = {M[u].x, M[u].y, M[u].z, M[u].w};
+          const float cc[4] = {cen[u].x, cen[u].y, cen[u].z, cen[u].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            if (OPT == DW_OPT_MOMENTUM) { bb[e] = a.momentum * bb[e] + g[e]; th[e] = th[e] - a.lr * bb[e]; }
+            else th[e] = th[e] - a.lr * g[e];
+            const float d = th[e] - cc[e];
+            nsum += d * d;
+          }
+          if (valid[u]) {
+            nt_store4(th4 + q, make_float4(th[0], th[1], th[2], th[3]));
+            if (OPT == DW_OPT_MOMENTUM) nt_store4(m4 + q, make_float4(bb[0], bb[1], bb[2], bb[3]));
+            if (HAS_B16) {
+              ushort4 w;
+              w.x = f32_to_bf16_rne(th[0]); w.y = f32_to_bf16_rne(th[1]);
+              w.z = f32_to_bf16_rne(th[2]); w.w = f32_to_bf16_rne(th[3]);
+              reinterpret_cast<ushort4*>(a.wb16 + (int64_t)i * a.Pp)[q] = w;
+            }
+          }
         }
       }
 #pragma unroll
-      for (int u = 0; u < kUpdQuads; ++u) {
+      for (int u = 0; OPT == DW_OPT_ADAHESSIAN && u < kUpdQuads; ++u) {
         const int64_t q = qbase + (int64_t)u * kUpdThreads;
         float g[4] = {G[u].x, G[u].y, G[u].z, G[u].w};
         float hz[4] = {H[u].x, H[u].y, H[u].z, H[u].w};
@@ -231,10 +264,17 @@ hipError_t launch_update(const UpdateArgs& args, int n_blocks, hipStream_t s) {
   // few chunks (small models): one worker per block row as well; with many chunks a block walks through the workers
   // and reads its piece of the centre once
   if (a.n_list == 0 && n_blocks < 1024 && a.k > 1) grid_y = a.k;
-  if (a.wb16)
-    hipLaunchKernelGGL(update_kernel<true>, dim3(grid, grid_y), dim3(kUpdThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL(update_kernel<false>, dim3(grid, grid_y), dim3(kUpdThreads), 0, s, a);
+  const dim3 g3(grid, grid_y), b3(kUpdThreads);
+  if (a.optimizer == DW_OPT_SGD) {
+    if (a.wb16) hipLaunchKernelGGL((update_kernel<true, DW_OPT_SGD>), g3, b3, 0, s, a);
+    else hipLaunchKernelGGL((update_kernel<false, DW_OPT_SGD>), g3, b3, 0, s, a);
+  } else if (a.optimizer == DW_OPT_MOMENTUM) {
+    if (a.wb16) hipLaunchKernelGGL((update_kernel<true, DW_OPT_MOMENTUM>), g3, b3, 0, s, a);
+    else hipLaunchKernelGGL((update_kernel<false, DW_OPT_MOMENTUM>), g3, b3, 0, s, a);
+  } else {
+    if (a.wb16) hipLaunchKernelGGL((update_kernel<true, DW_OPT_ADAHESSIAN>), g3, b3, 0, s, a);
+    else hipLaunchKernelGGL((update_kernel<false, DW_OPT_ADAHESSIAN>), g3, b3, 0, s, a);
+  }
   return hipGetLastError();
 }
 

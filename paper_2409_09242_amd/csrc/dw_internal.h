@@ -48,6 +48,8 @@ struct UpdateArgs {
   int k;
   int avg_block;                      // power of two, 1..256
   float lr, beta1, beta2, eps, hpow;
+  int optimizer;                      // DW_OPT_*: AdaHessian, or a baseline's first-order step on g alone
+  float momentum;                     // DW_OPT_MOMENTUM: the velocity lives in m
   float d_scale;                      // 0: D = z*hz (one probe); > 0: hz holds the sum of z_j*Hz_j, D = hz * d_scale
   uint64_t active_mask;               // bit i: worker i takes the step (others only report their distance)
   BiasRanges bias;

@@ -43,6 +43,8 @@ class Workload:
     img: Optional[Tuple[int, int, int]] = None   # convolutional front end: input image (H, W, C), channels last
     conv: Tuple[int, ...] = ()               # output channels of its 3x3 convolutions (dims[0] = the pooled, flattened map)
     conv_avg: int = 0                        # 3x3 window averaging of the Hutchinson estimate
+    optimizer: int = 0                       # 0 AdaHessian; 1 SGD, 2 SGD with momentum (the baselines of Section VI)
+    momentum: float = 0.5                    # Section VII
 
     @property
     def P(self) -> int:

@@ -120,7 +120,7 @@ def close_update(gpu_upd, ref_upd, tr, i, dims, rtol, what):
 def oracle_config(w, **kw):
     d = dict(dims=w.dims, k=w.k, lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, hpow=w.hpow,
              avg_block=w.avg_block, alpha=w.alpha, kappa=w.kappa, c=w.c, seed=w.seed, bf16=w.bf16,
-             n_params=w.n_params)
+             n_params=w.n_params, optimizer=getattr(w, "optimizer", 0), momentum=getattr(w, "momentum", 0.5))
     d.update(kw)
     return O.OracleConfig(**d)
 

@@ -207,6 +207,60 @@ def test_trajectory_c2_free_running():
     assert _run_trajectory(W.C2, W.C2.steps, forced=False) < 0.05
 
 
+@pytest.mark.parametrize("opt,bf16", [(B.DW_OPT_SGD, False), (B.DW_OPT_MOMENTUM, False), (B.DW_OPT_MOMENTUM, True)])
+def test_baseline_worker_steps_on_the_network(opt, bf16):
+    """EASGD / EAMSGD (Section VI) on an MLP: five forced steps, a fixed-rate round after every step with one third of
+    the communications suppressed.  The gradient is the network's; the step is first order (Section II eq.(3))."""
+    w = W.scaled(W.C1, dims=(72, 96, 40, 10), batch=37 if not bf16 else 40, k=3, seed=8100 + opt, bf16=bf16, optimizer=opt,
+                 momentum=0.5, stale="third")
+    h, tr, theta0 = _setup(w)
+    x, y = W.minibatch_pool(w, 2, bf16_round=W.to_bf16_f32 if bf16 else None)
+    sched = W.participation_schedule(w, 5)
+    parity.reset()
+    for step in range(5):
+        if step:
+            for i in range(w.k):
+                h.set_state(B.DW_S_THETA, i, tr.theta[i]); h.set_state(B.DW_S_M, i, tr.m[i])
+            h.set_state(B.DW_S_CENTRE, 0, tr.centre)
+        prev_gpu, prev = h.all_state(B.DW_S_THETA), tr.theta.copy()
+        xb = _to_bf16_bits(x[step % 2]) if bf16 else torch.from_numpy(x[step % 2]).cuda()
+        loss = torch.zeros(w.k, device="cuda")
+        h.worker_step(xb, torch.from_numpy(y[step % 2]).cuda(), loss=loss)
+        ref_loss = _oracle_step_with_ties(h, w, tr, x[step % 2], y[step % 2], bf16, "baseline step %d" % step)
+        close(loss.cpu().numpy(), ref_loss, 1e-4 if bf16 else 1e-5, "loss")
+        now_gpu = h.all_state(B.DW_S_THETA)
+        for i in range(w.k):
+            g = h.get_state(B.DW_S_G, i)
+            if bf16:
+                for name, sl in parity.per_layer(w.dims):
+                    close_norm(g[sl], tr.traces[i].g[sl], RTOL_BF16_G, "baseline g[%d]/%s" % (i, name))
+                    close_norm(now_gpu[i][sl] - prev_gpu[i][sl], tr.theta[i][sl] - prev[i][sl], 2 * RTOL_BF16_G,
+                               "baseline update[%d]/%s" % (i, name))
+            else:
+                close_layers(g, tr.traces[i].g, w.dims, RTOL_GRAD, "baseline g[%d]" % i)
+                # theta - eta*g (or its velocity form) is linear in g: the update inherits g's tolerance and floor
+                # (read back as a difference of two stored fp32 values: one ulp of theta on top)
+                for name, sl in parity.per_layer(w.dims):
+                    close(now_gpu[i][sl] - prev_gpu[i][sl], tr.theta[i][sl] - prev[i][sl], RTOL_UPDATE,
+                          "baseline update[%d]/%s" % (i, name), extra=2.0 ** -23 * np.abs(tr.theta[i][sl]))
+                close_layers(h.get_state(B.DW_S_M, i), tr.m[i], w.dims, RTOL_UPDATE, "baseline velocity[%d]" % i)
+        if not bf16:                                                   # the round from identical states
+            for i in range(w.k):
+                h.set_state(B.DW_S_THETA, i, tr.theta[i])
+        pre_t, pre_c = h.all_state(B.DW_S_THETA).astype(np.float64), h.get_state(B.DW_S_CENTRE).astype(np.float64)
+        assert h.elastic_sync(B.DW_FIXED, tau=1, participate=sched[step])
+        if bf16:
+            continue
+        tr.theta, tr.centre = pre_t.copy(), pre_c.copy()
+        assert tr.elastic_sync(O.MODE_FIXED, tau=1, participate=sched[step])
+        for i in range(w.k):
+            close(h.get_state(B.DW_S_THETA, i) - pre_t[i], tr.theta[i] - pre_t[i], RTOL_UPDATE, "easgd pull[%d]" % i,
+                  extra=2.0 ** -23 * np.abs(tr.theta[i]))
+        close(h.get_state(B.DW_S_CENTRE) - pre_c, tr.centre - pre_c, RTOL_UPDATE, "easgd centre", extra=2.0 ** -23 * np.abs(tr.centre))
+    parity.bound_ties(bf16)
+    assert not np.any(h.all_state(B.DW_S_V))
+
+
 # ---------------------------------------------------------------------------------------------------------
 # bf16 network (bf16 weights / activations, fp32 accumulation and state).  A value that lands next to a bf16
 # rounding boundary may round differently on the two sides (2^-8 relative on that one entry), so tensors are

@@ -322,3 +322,38 @@ def test_history_set_by_hand_puts_each_branch_of_the_weights_before_the_next_rou
               extra=slack + 2.0 ** -23 * np.abs(tr.theta[i]))
     if branch == "reset":
         np.testing.assert_array_equal(h.get_state(B.DW_S_CENTRE), pre_c.astype(np.float32))
+
+
+# ---------------------------------------------------------------------------------------------------------
+# Baseline worker steps: elastic averaging SGD with and without momentum (Section II eq.(3); Section VI-VII)
+# ---------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("opt", [B.DW_OPT_SGD, B.DW_OPT_MOMENTUM])
+@pytest.mark.parametrize("P,k", [(4096 * 3 + 64, 4), (8, 1), (4096 + 260, 5)])
+def test_first_order_steps_and_fixed_rate_rounds_follow_the_oracle(opt, P, k):
+    """EASGD / EAMSGD on a flat parameter vector: six steps on fresh gradients (one with frozen workers), a fixed-rate
+    round after every second step with one third of the communications suppressed; then a dynamic-weighted round."""
+    w, theta0, rng = _flat_case(P, k, 300 + opt, optimizer=opt, momentum=0.5, stale="third", tau=2)
+    h = B.Handle(B.config_from_workload(w), theta0)
+    tr = O.OracleTrainer(oracle_config(w, dims=None), theta0.astype(np.float64))
+    sched = W.participation_schedule(w, 4)
+    for step in range(6):
+        g = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+        active = None if step != 2 else [i % 2 == 0 for i in range(k)]
+        h.update_only(torch.from_numpy(g).cuda(), None, active=active)
+        tr.update_only(g, None, active=active)
+        _compare_state(h, tr, ("theta", "m", "v"), tag="first-order step %d" % step)
+        did = h.elastic_sync(B.DW_FIXED, tau=2, participate=sched[step // 2])
+        assert did == tr.elastic_sync(O.MODE_FIXED, tau=2, participate=sched[step // 2]) == (step % 2 == 1)
+        _compare_state(h, tr, ("theta", "centre"), tag="easgd round after step %d" % step)
+    assert [int(h.get_state(B.DW_S_STEPS, i)[0]) for i in range(k)] == [int(t) for t in tr.t]
+    assert not np.any(h.all_state(B.DW_S_V))                         # no second moment in a first-order step
+    assert np.any(h.all_state(B.DW_S_M)) == (opt == B.DW_OPT_MOMENTUM)
+    # the dynamic weights work on the baselines' replicas as on any others
+    g = (rng.standard_normal((k, P)) * 0.1).astype(np.float32)
+    for _ in range(2):
+        h.update_only(torch.from_numpy(g).cuda(), None); tr.update_only(g, None)
+    assert h.elastic_sync(B.DW_DYNAMIC, tau=2) and tr.elastic_sync(O.MODE_DYNAMIC, tau=2)
+    for i in range(k):
+        sc = h.get_state(B.DW_S_SCORE, i)
+        assert abs(sc[0] - tr.last_u[i]) < 1e-5 and abs(sc[1] - tr.last_a[i]) < 2e-5 and abs(sc[2] - tr.last_h1[i]) < 5e-4
+    _compare_state(h, tr, ("theta", "centre"), tag="dynamic round")

@@ -169,6 +169,31 @@ def test_header_is_plain_c_and_a_c_program_can_call_the_library(tmp_path):
     assert out[0] == "0" and int(out[1]) == 32 * 64 + 64 + 64 * 10 + 10 and int(out[-1]) > 0
 
 
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="no C compiler")
+def test_binding_lays_the_configuration_out_as_the_header_does(tmp_path):
+    """The ctypes mirror of dw_config against the C compiler's own layout of the header's struct: size and the offset
+    of every field."""
+    names = [f[0] for f in B.dw_config._fields_]
+    src = tmp_path / "layout.c"
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "dw.h"\nint main(void) {\n'
+                   '  printf("%zu\\n", sizeof(dw_config));\n' +
+                   "".join('  printf("%%zu\\n", offsetof(dw_config, %s));\n' % n for n in names) + "  return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert out[0] == C.sizeof(B.dw_config)
+    assert out[1:] == [getattr(B.dw_config, n).offset for n in names]
+
+
+def test_baseline_optimizers_are_validated_on_the_host():
+    n = C.c_int64()
+    for kw, status in ((dict(optimizer=B.DW_OPT_SGD), 0), (dict(optimizer=B.DW_OPT_MOMENTUM, momentum=0.5), 0),
+                       (dict(optimizer=3), -2), (dict(optimizer=B.DW_OPT_MOMENTUM, momentum=1.0), -3),
+                       (dict(optimizer=B.DW_OPT_SGD, fuse_update=1), -2), (dict(optimizer=B.DW_OPT_SGD, n_samples=2), -2)):
+        cfg = B.make_config(dims=(32, 64, 10), k=2, batch=4, **kw)
+        assert B.lib().dw_param_count(C.byref(cfg), C.byref(n)) == status, kw
+
+
 def test_transposed_lds_reads_are_not_touched_before_their_wait():
     """The data-gradient kernel reads LDS with transpose reads issued from inline assembly; the build checks in the
     kernels' own assembly that nothing touches their destination registers before the wait for LDS.  Here: the

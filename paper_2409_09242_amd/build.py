@@ -112,7 +112,7 @@ def _source_digest() -> str:
     for f in files:
         h.update(os.path.basename(f).encode() + b"\0")
         h.update(open(f, "rb").read())
-    h.update(" ".join(FLAGS).encode())
+    h.update(" ".join(f for f in FLAGS if not os.path.isabs(f)).encode())      # (the tree may sit anywhere)
     return h.hexdigest()
 
 

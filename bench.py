@@ -65,7 +65,7 @@ def fused_layers(w, fuse):
     W made of whole tiles that fill the chip, averaging block <= 32, Hessian power 1, no convolutional front end)."""
     if not fuse or w.dims is None or w.conv or w.avg_block > 32 or w.hpow != 1.0:
         return []
-    tile_n, min_tiles = (256, 256) if w.bf16 else (128, 512)        # bf16: 128 x 256 tiles; fp32: 128 x 128
+    tile_n, min_tiles = 128, 512                                   # 128 x 128 tiles in both types
     out, off = [], 0
     for l in range(1, len(w.dims)):
         n_out, n_in = w.dims[l], w.dims[l - 1]

@@ -33,7 +33,7 @@ namespace b16 {
 constexpr int BK = 32;          // k per tile (two MFMA k-steps of 16)
 constexpr int LDK = 40;         // row stride (elements) of a [row][k] tile
 constexpr int KPAD = 32;        // row padding (elements) of a [k][row] tile
-constexpr int NT = 512;
+[[maybe_unused]] constexpr int NT = 512;   // block size of every shape but the fused weight gradient's
 
 enum RyMode { RY_NONE = 0, RY_MEM = 1, RY_BITS = 2 };
 
@@ -148,9 +148,10 @@ __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int row0, int ks, in
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0>
-__global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
-  static_assert(WM * WN == NT / 64, "eight waves per block");
+template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0, int NTH = 512>
+__global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmArgs a) {   // (two waves per SIMD either way)
+  constexpr int NT = NTH;                                   // threads per block: 512, or 256 (see launch_fused_wgrad)
+  static_assert(WM * WN == NT / 64, "one wave tile per wave");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
   // Workgroups are handed to the 8 XCDs round-robin by their index.  The index is remapped so that each XCD
@@ -175,8 +176,9 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   int tm = tile % tiles_m, tn = tile / tiles_m;
   if (EPI == EPI_WGRAD && tiles_m % 8 == 0) {
     // Weight gradient: both operands are panels of the minibatch (512 k x 128 or 256 columns, with their
-    // R-companions 256 KB and 512 KB).  The 32 blocks an XCD runs at a time are 8 row tiles x 4 column tiles
-    // (2 + 2 MB of panels, which its 4 MB L2 can hold) instead of a column of 32 row tiles (8 MB).
+    // R-companions 256 KB and 512 KB).  The blocks an XCD runs at a time (32 of 128 x 256, or 64 of 128 x 128) are
+    // 8 row tiles x 4 or 8 column tiles (2 + 2 MB of panels, which its 4 MB L2 can hold) instead of a column of
+    // row tiles (8 MB and more).
     const int tiles_n = tiles / tiles_m;
     const int g = tile / (8 * tiles_n), r = tile - g * (8 * tiles_n);
     tn = r / 8; tm = g * 8 + r % 8;
@@ -337,7 +339,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
     const karg_floats bc = (karg_floats)(ka + offsetof(GemmArgs, fu) + offsetof(FuseArgs, sc));
     const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];
     static_assert(offsetof(UpdateScalars, inv_bc2) == DW_MAX_K * sizeof(float), "inv_bc2 follows inv_bc1");
-    static_assert(TN == 2 || !(BM == 128 && BN == 256), "the wave's tile row is 64 columns wide");
+    static_assert(TN == 2 || !(BM == 128 && (BN == 256 || BN == 128)), "the wave's tile row is 64 columns wide");
     float* gl = reinterpret_cast<float*>(smem) + wave * fused_update_lds_floats();     // free after the main loop
     float nsum = 0.f;
     if constexpr (TN == 2) {                                  // (the tile shapes that can be asked to fuse)
@@ -473,19 +475,20 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16(GemmArgs a) {
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI, int FM = 0>
+template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI, int FM = 0, int NTH = 512>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
+  constexpr int NT = NTH;
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
   const dim3 grid((unsigned)((tiles * active_count(a.active_mask, a.k) + 7) / 8 * 8)), block(NT);
   constexpr int XTH = RX ? NT / 2 : NT;
   constexpr int tiles_b = 2 * 2 * (Tile<BM, XTH, XKC>::LDS_ELEMS * (RX ? 2 : 1) +
                                    Tile<BN, NT, YKC>::LDS_ELEMS * (RYM != RY_NONE ? 2 : 1));
   // the fused weight-gradient epilogue passes g and Hz through LDS: per wave two arrays of 32 rows x 72 floats
-  constexpr int epi_b = (EPI == EPI_WGRAD && BM == 128 && BN == 256) ? (NT / 64) * 2 * 32 * 72 * 4 : 0;
+  constexpr int epi_b = (EPI == EPI_WGRAD && BM == 128 && (BN == 256 || BN == 128)) ? (NT / 64) * 2 * 32 * 72 * 4 : 0;
   constexpr int out_b = (EPI == EPI_RELU || EPI == EPI_MASK) ? (NT / 64) * epi_bf16_lds_bytes(BN / WN / 32) : 0;
   constexpr int smem = tiles_b > epi_b ? (tiles_b > out_b ? tiles_b : out_b) : (epi_b > out_b ? epi_b : out_b);
   static_assert(smem <= 160 * 1024, "LDS budget");
-  auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, FM>;
+  auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, FM, NTH>;
   static LdsLimitOnce lds_limit;
   { const hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), smem); if (e != hipSuccess) return e; }
   hipLaunchKernelGGL(kern, grid, block, smem, s, a);
@@ -504,35 +507,43 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
   } else if (a.epi == EPI_MASK) {
     return launch_one<BM, BN, WM, WN, true, false, true, RY_BITS, EPI_MASK>(a, s);
   }
-  if constexpr (BM == 128 && BN == 256) {
-    // the fused update with several Hutchinson probes: own instances, so that the one-probe kernel keeps its registers
-    if (a.fu.on && a.fu.probe_mode == 1)
-      return a.RY ? launch_one<BM, BN, WM, WN, false, false, true, RY_MEM, EPI_WGRAD, 1>(a, s)
-                  : launch_one<BM, BN, WM, WN, false, false, true, RY_NONE, EPI_WGRAD, 1>(a, s);
-    if (a.fu.on && a.fu.probe_mode == 2)
-      return a.RY ? launch_one<BM, BN, WM, WN, false, false, true, RY_MEM, EPI_WGRAD, 2>(a, s)
-                  : launch_one<BM, BN, WM, WN, false, false, true, RY_NONE, EPI_WGRAD, 2>(a, s);
-  }
   return a.RY ? launch_one<BM, BN, WM, WN, false, false, true, RY_MEM, EPI_WGRAD>(a, s)
               : launch_one<BM, BN, WM, WN, false, false, true, RY_NONE, EPI_WGRAD>(a, s);
 }
 
+// Weight gradient that applies the update itself: 128 x 128 tiles and 256 threads (four waves of 64 x 64), two blocks
+// per compute unit (2 x 80 KB of LDS, one wave of each per SIMD), so that one block's state traffic runs under the
+// other's multiplications and neither's start-up and drain leaves the unit idle.  Own instances for the steps of
+// several Hutchinson probes (FM 1: a probe before the last, 2: the last), so that the one-probe kernel keeps its
+// registers.
+static hipError_t launch_fused_wgrad(const GemmArgs& a, hipStream_t s) {
+  if (a.fu.probe_mode == 1)
+    return a.RY ? launch_one<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD, 1, 256>(a, s)
+                : launch_one<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD, 1, 256>(a, s);
+  if (a.fu.probe_mode == 2)
+    return a.RY ? launch_one<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD, 2, 256>(a, s)
+                : launch_one<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD, 2, 256>(a, s);
+  return a.RY ? launch_one<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD, 0, 256>(a, s)
+              : launch_one<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD, 0, 256>(a, s);
+}
+
 }  // namespace b16
 
-// The weight-gradient product of W[n_out][n_in] takes the 128 x 256 shape (see launch_gemm_bf16) and can apply the
-// update in its epilogue when W is made of whole tiles (rows are then whole 32-lane segments and sign-bit words),
+// The weight-gradient product of W[n_out][n_in] can apply the update in its epilogue (128 x 128 tiles, see
+// launch_fused_wgrad) when W is made of whole tiles (rows are then whole 32-lane segments and sign-bit words),
 // an averaging block is at most one segment and the Hessian power is 1.
 bool gemm_bf16_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff) {
-  if (n_out % 128 != 0 || n_in % 256 != 0 || woff % 32 != 0 || avg_block > 32 || hpow != 1.0f) return false;
+  if (n_out % 128 != 0 || n_in % 128 != 0 || woff % 32 != 0 || avg_block > 32 || hpow != 1.0f) return false;
   if ((int64_t)n_out * n_in >= (1ll << 31)) return false;
-  return (int64_t)(n_out / 128) * (n_in / 256) * k >= 256;
+  return (int64_t)(n_out / 128) * (n_in / 128) * k >= 512;
 }
-int gemm_bf16_wgrad_tiles(int n_out, int n_in) { return ((n_out + 127) / 128) * ((n_in + 255) / 256); }
+int gemm_bf16_wgrad_tiles(int n_out, int n_in) { return ((n_out + 127) / 128) * ((n_in + 127) / 128); }
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : a.epi == EPI_MASK ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);
   if (gemm_bf16_dma_ok(a)) return launch_gemm_bf16_dma(a, s);
   if (gemm_bf16_out_ok(a)) return launch_gemm_bf16_out(a, s);
+  if (a.epi == EPI_WGRAD && a.fu.on) return b16::launch_fused_wgrad(a, s);
   if (a.N <= 32) return b16::launch_shape<256, 32, 8, 1>(a, s);
   if (a.M <= 32) return b16::launch_shape<32, 256, 1, 8>(a, s);
   const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 255) / 256) * a.k;

@@ -378,7 +378,7 @@ def main():
     per_step = {"update": 1, "pull": 1.0 / w.tau, "gemm_wgrad": 1, "gather": 1}
     by["gather"] = 2.0 * w.k * w.batch * w.dims[0] * (2 if w.bf16 else 4)        # every drawn row read and written once
     kernels = {}
-    for name in ("gemm_fwd", "gemm_wgrad", "gemm_dgrad", "head", "update", "weights", "pull", "rademacher", "gather"):
+    for name in ("step", "gemm_fwd", "gemm_wgrad", "gemm_dgrad", "head", "update", "weights", "pull", "rademacher", "gather"):
         n, ms = prof[name]
         if n == 0:
             continue
@@ -389,12 +389,21 @@ def main():
             # bytes of the class per step over its time per step (the pull runs every tau-th step)
             entry["GB/s"] = by[name] * per_step[name] / (ms / args.steps * 1e-3) / 1e9
         kernels[name] = entry
+    if "step" in kernels:
+        # a small model's whole step in one kernel: plain fp32 FMA loops out of LDS (no matrix cores)
+        kernels["step"]["TFLOP/s"] = sum(fl.values()) / (kernels["step"]["ms_per_step"] * 1e-3) / 1e12
     # classes bound by the matrix cores: all GEMMs, except weight gradients that carry the update (HBM-bound then)
     mfma = [c for c in fl if c in kernels and not (c == "gemm_wgrad" and fused)]
     gemm_ms = sum(kernels[c]["ms_per_step"] for c in mfma)
     gemm_fl = sum(fl[c] for c in mfma)
     dominant = max(kernels, key=lambda c: kernels[c]["ms_per_step"])
-    if dominant in mfma:
+    if dominant == "step":
+        ach = kernels["step"]["TFLOP/s"]
+        roof = {"kernel": "tiny_step_kernel (one block per worker, the whole step)", "bound": "alu", "achieved": ach,
+                "peak": PEAK_TFLOPS["f32"], "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS["f32"], "traffic": None,
+                "avg_ms": kernels["step"]["avg_ms"],
+                "note": "latency-bound: one compute unit per worker, a chain of dependent phases"}
+    elif dominant in mfma:
         # one roofline entry for the GEMM family (one kernel template): all its launches of a step together
         ach = gemm_fl / (gemm_ms * 1e-3) / 1e12
         roof = {"kernel": "dual_gemm (%s)" % dtype, "bound": "mfma", "achieved": ach, "peak": PEAK_TFLOPS[dtype],

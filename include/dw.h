@@ -285,7 +285,7 @@ int dw_draw_batch(dw_handle* h, const void* d_data, const int32_t* d_labels, int
  * (arrays of DW_N_KERNEL_CLASSES entries), then clears the record.  At most 8192 launches are kept between
  * reads; *n_dropped receives how many were not recorded (may be NULL).
  */
-#define DW_N_KERNEL_CLASSES 9
+#define DW_N_KERNEL_CLASSES 10
 #define DW_K_RADEMACHER 0    /* Rademacher bit generator                         */
 #define DW_K_GEMM_FWD 1      /* forward + R-forward GEMMs                        */
 #define DW_K_HEAD 2          /* softmax cross-entropy head                       */
@@ -295,6 +295,7 @@ int dw_draw_batch(dw_handle* h, const void* d_data, const int32_t* d_labels, int
 #define DW_K_WEIGHTS 6       /* dynamic-weight scalars                           */
 #define DW_K_PULL 7          /* elastic pull + centre reduction                  */
 #define DW_K_GATHER 8        /* minibatch rows drawn from a resident data set    */
+#define DW_K_STEP 9          /* whole worker step of a small model in one kernel */
 int dw_profile(dw_handle* h, int enable);
 int dw_profile_read(dw_handle* h, int64_t* n_launches, double* total_ms, int64_t* n_dropped, void* stream);
 

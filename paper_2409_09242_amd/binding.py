@@ -29,7 +29,7 @@ EXPORTS = ("dw_strerror", "dw_last_hip_error", "dw_param_count", "dw_workspace_b
            "dw_worker_step", "dw_update_only", "dw_elastic_sync", "dw_get_state", "dw_set_state",
            "dw_profile", "dw_profile_read", "dw_partition_scratch_bytes", "dw_overlap_partition", "dw_draw_batch",
            "dw_overlap_partition_static")
-KERNEL_CLASSES = ("rademacher", "gemm_fwd", "head", "gemm_wgrad", "gemm_dgrad", "update", "weights", "pull", "gather")
+KERNEL_CLASSES = ("rademacher", "gemm_fwd", "head", "gemm_wgrad", "gemm_dgrad", "update", "weights", "pull", "gather", "step")
 
 
 class dw_config(C.Structure):

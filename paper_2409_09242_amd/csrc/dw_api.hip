@@ -396,6 +396,23 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
     h->calls += 1;
     return DW_OK;
   }
+  if (tiny_step_ok(h->cfg, h->lay)) {
+    // a model that fits in one compute unit's LDS: z, network, update and distances in one kernel, a block per worker
+    uint64_t keys[DW_MAX_K];
+    const uint64_t G = 0x9E3779B97F4A7C15ull;
+    for (int i = 0; i < h->cfg.k; ++i) {
+      const uint64_t k1 = mix64_host(h->cfg.seed + G * (uint64_t)(i + 1));
+      keys[i] = mix64_host(k1 + G * (uint64_t)(h->t[i] + 1));          // stream position t_i: before the increment
+    }
+    for (int i = 0; i < h->cfg.k; ++i)
+      if ((active >> i) & 1ull) h->t[i] += 1;
+    UpdateArgs a;
+    fill_update_args(h, a, h->at<float>(h->lay.g), h->at<float>(h->lay.hz), h->lay.Pp, zb, zs, active, false);
+    DW_HIP(launch_tiny_step(h->cfg, h->ws, h->lay, d_x, d_y, d_zbits, a, keys, loss, s));
+    h->norms_valid = true;
+    h->calls += 1;
+    return DW_OK;
+  }
   for (int i = 0; i < h->cfg.k; ++i)
     if ((active >> i) & 1ull) h->t[i] += 1;
   const bool fused = h->lay.n_fuse_slots > 0;
@@ -558,7 +575,7 @@ int dw_worker_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint
   if (probes(h) > 1 && d_zbits) return DW_ERR_ARG;       // several probes per step come from the library's stream
   // (a baseline's first-order step draws no z: the direction the network's R-parts then run along is whatever the
   // sign-bit buffer holds, and their result is not used)
-  if (!d_zbits && probes(h) == 1 && h->cfg.optimizer == DW_OPT_ADAHESSIAN) {
+  if (!d_zbits && probes(h) == 1 && h->cfg.optimizer == DW_OPT_ADAHESSIAN && !tiny_step_ok(h->cfg, h->lay)) {
     const int st = draw_z(h, active, s);
     if (st != DW_OK) return st;
   }
@@ -627,7 +644,6 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
     w.man_h1[i] = (mode == DW_MANUAL && i < c.k) ? h_h1[i] : 0.f;
     w.man_h2[i] = (mode == DW_MANUAL && i < c.k) ? h_h2[i] : 0.f;
   }
-  DW_HIP(launch_weights(w, s));
   PullArgs p;
   p.theta = h->at<float>(L.theta); p.centre = h->at<float>(L.centre);
   p.wb16 = c.dtype == DW_BF16 ? h->at<uint16_t>(L.wb16) : nullptr;
@@ -635,7 +651,12 @@ int dw_elastic_sync(dw_handle* h, int mode, const float* h_h1, const float* h_h2
   p.Pp = L.Pp; p.k = c.k;
   p.part_mask = mask_from(h_participate, c.k);
   p.sequential = sequential;
-  DW_HIP(launch_pull(p, s));
+  if (sync_fusable(w, p)) {
+    DW_HIP(launch_weights_and_pull(w, p, s));
+  } else {
+    DW_HIP(launch_weights(w, s));
+    DW_HIP(launch_pull(p, s));
+  }
   h->rounds += 1;
   h->norms_valid = false;
   return 1;

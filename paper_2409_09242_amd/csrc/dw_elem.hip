@@ -12,6 +12,7 @@
 // worker: the centre values stay in registers while the block walks over the k replicas, so the centre is
 // read once per launch, and the reduction over workers into the centre needs no atomics.
 #include <cstddef>
+#include <type_traits>
 
 #include "dw_internal.h"
 #include "dw_device_util.h"
@@ -265,22 +266,66 @@ hipError_t launch_update(const UpdateArgs& args, int n_blocks, hipStream_t s) {
   // and reads its piece of the centre once
   if (a.n_list == 0 && n_blocks < 1024 && a.k > 1) grid_y = a.k;
   const dim3 g3(grid, grid_y), b3(kUpdThreads);
-  if (a.optimizer == DW_OPT_SGD) {
-    if (a.wb16) hipLaunchKernelGGL((update_kernel<true, DW_OPT_SGD>), g3, b3, 0, s, a);
-    else hipLaunchKernelGGL((update_kernel<false, DW_OPT_SGD>), g3, b3, 0, s, a);
-  } else if (a.optimizer == DW_OPT_MOMENTUM) {
-    if (a.wb16) hipLaunchKernelGGL((update_kernel<true, DW_OPT_MOMENTUM>), g3, b3, 0, s, a);
-    else hipLaunchKernelGGL((update_kernel<false, DW_OPT_MOMENTUM>), g3, b3, 0, s, a);
-  } else {
-    if (a.wb16) hipLaunchKernelGGL((update_kernel<true, DW_OPT_ADAHESSIAN>), g3, b3, 0, s, a);
-    else hipLaunchKernelGGL((update_kernel<false, DW_OPT_ADAHESSIAN>), g3, b3, 0, s, a);
-  }
+  auto launch = [&](auto b16, auto opt) {
+    hipLaunchKernelGGL((update_kernel<decltype(b16)::value, decltype(opt)::value>), g3, b3, 0, s, a);
+  };
+  auto by_opt = [&](auto b16) {
+    if (a.optimizer == DW_OPT_SGD) launch(b16, std::integral_constant<int, DW_OPT_SGD>{});
+    else if (a.optimizer == DW_OPT_MOMENTUM) launch(b16, std::integral_constant<int, DW_OPT_MOMENTUM>{});
+    else launch(b16, std::integral_constant<int, DW_OPT_ADAHESSIAN>{});
+  };
+  if (a.wb16) by_opt(std::true_type{}); else by_opt(std::false_type{});
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------------
 // Dynamic-weight scalars: one block per worker.
 // ---------------------------------------------------------------------------------------------------
+// Dynamic-weight scalars of worker i from its squared distance S (Section V-B): u = log||theta_i - centre||, the raw
+// score a over the history ring (eq.(10)-(11)), the piecewise-linear weights h1(a), h2(a).  `write`: record u in the
+// ring and the scores in memory (one caller per worker and round); the ring slot of this round is not read here, so
+// other blocks may evaluate the same worker without writing while one block records.
+// man1, man2: the caller's weights of this worker (DW_MANUAL).
+__device__ __forceinline__ void weight_scalars(const WeightArgs& a, int i, double S, float man1, float man2, bool write,
+                                               float* omh1, float* h2o) {
+  // u = log ||theta_i - centre||_2 (natural log; squared norm floored so identical vectors stay finite)
+  const double u = 0.5 * log(S > 1e-30 ? S : 1e-30);
+  const int ring = a.p + 1;
+  double* R = a.u_ring + (int64_t)i * (DW_MAX_P + 1);
+  // raw score: c_0 weighs the newest difference u_t - u_{t-1}, c_1 the one before, ...; differences the
+  // history cannot supply yet contribute nothing
+  double sc = 0.0;
+  for (int j = 0; j < a.p; ++j) {
+    if (j + 1 >= a.n_valid) break;
+    const int hi = (a.slot - j + 2 * ring) % ring;
+    const int lo = (a.slot - j - 1 + 2 * ring) % ring;
+    sc += (double)a.c[j] * ((j == 0 ? u : R[hi]) - R[lo]);
+  }
+  double h1, h2;
+  const double alpha = a.alpha, kappa = a.kappa;
+  if (a.mode == DW_FIXED) {
+    h1 = alpha; h2 = alpha;
+  } else if (a.mode == DW_MANUAL) {
+    h1 = man1; h2 = man2;
+  } else if (sc < kappa) {
+    h1 = 1.0; h2 = 0.0;
+  } else if (sc <= 0.0) {
+    h1 = 1.0 + (1.0 - alpha) / kappa * (sc - kappa);
+    h2 = -alpha / kappa * sc + alpha;
+  } else {
+    h1 = alpha; h2 = alpha;
+  }
+  *omh1 = (float)(1.0 - h1);
+  *h2o = (float)h2;
+  if (write) {
+    R[a.slot] = u;
+    double* out = a.score + (int64_t)i * 4;
+    out[0] = u; out[1] = sc; out[2] = h1; out[3] = h2;
+    a.omh1[i] = (float)(1.0 - h1);
+    a.h2[i] = (float)h2;
+  }
+}
+
 __global__ __launch_bounds__(256) void weight_kernel(WeightArgs a) {
   const int i = blockIdx.x;
   const int tid = threadIdx.x;
@@ -294,38 +339,8 @@ __global__ __launch_bounds__(256) void weight_kernel(WeightArgs a) {
   if (tid != 0) return;
   double S = 0.0;
   for (int w = 0; w < 256 / 64; ++w) S += red[w];
-  // u = log ||theta_i - centre||_2 (natural log; squared norm floored so identical vectors stay finite)
-  const double u = 0.5 * log(S > 1e-30 ? S : 1e-30);
-  const int ring = a.p + 1;
-  double* R = a.u_ring + (int64_t)i * (DW_MAX_P + 1);
-  R[a.slot] = u;
-  // raw score: c_0 weighs the newest difference u_t - u_{t-1}, c_1 the one before, ...; differences the
-  // history cannot supply yet contribute nothing
-  double sc = 0.0;
-  for (int j = 0; j < a.p; ++j) {
-    if (j + 1 >= a.n_valid) break;
-    const int hi = (a.slot - j + 2 * ring) % ring;
-    const int lo = (a.slot - j - 1 + 2 * ring) % ring;
-    sc += (double)a.c[j] * (R[hi] - R[lo]);
-  }
-  double h1, h2;
-  const double alpha = a.alpha, kappa = a.kappa;
-  if (a.mode == DW_FIXED) {
-    h1 = alpha; h2 = alpha;
-  } else if (a.mode == DW_MANUAL) {
-    h1 = a.man_h1[i]; h2 = a.man_h2[i];
-  } else if (sc < kappa) {
-    h1 = 1.0; h2 = 0.0;
-  } else if (sc <= 0.0) {
-    h1 = 1.0 + (1.0 - alpha) / kappa * (sc - kappa);
-    h2 = -alpha / kappa * sc + alpha;
-  } else {
-    h1 = alpha; h2 = alpha;
-  }
-  double* out = a.score + (int64_t)i * 4;
-  out[0] = u; out[1] = sc; out[2] = h1; out[3] = h2;
-  a.omh1[i] = (float)(1.0 - h1);
-  a.h2[i] = (float)h2;
+  float o, w;
+  weight_scalars(a, i, S, a.man_h1[i], a.man_h2[i], true, &o, &w);      // (i is uniform: scalar loads)
 }
 
 hipError_t launch_weights(const WeightArgs& a, hipStream_t s) {
@@ -340,8 +355,29 @@ hipError_t launch_weights(const WeightArgs& a, hipStream_t s) {
 // Sequential rounds apply eq.(13) after every worker instead: the thread that owns a parameter keeps the
 // centre in a register and walks the workers in index order, so the bytes moved are the same.
 // ---------------------------------------------------------------------------------------------------
-template <bool HAS_B16>
-__global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a) {
+// FUSED_W: a model with few partial sums computes the weights inside the pull (every block for itself, in the same
+// order, so all blocks pull with the same values; block 0 records them): one launch per round instead of two.
+template <bool HAS_B16, bool FUSED_W>
+__global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a, WeightArgs wa) {
+  __shared__ float s_omh1[DW_MAX_K], s_h2[DW_MAX_K];
+  if (FUSED_W) {
+    const int i = threadIdx.x;
+    if (i < wa.k) {
+      double S = 0.0;
+      for (int b = 0; b < wa.n_blocks; ++b) S += wa.partials[(int64_t)i * wa.n_blocks + b];
+      for (int b = 0; b < wa.n_blocks_f; ++b) S += wa.partials_f[(int64_t)i * wa.n_blocks_f + b];
+      // the caller's weights sit in the kernel-argument block behind the first argument; they are read from there by
+      // address (indexing the by-value argument with the thread index would copy it to scratch memory)
+      typedef const char __attribute__((address_space(4)))* karg_bytes;
+      typedef const float __attribute__((address_space(4)))* karg_floats;
+      constexpr size_t wa_at = (sizeof(PullArgs) + alignof(WeightArgs) - 1) / alignof(WeightArgs) * alignof(WeightArgs);
+      const karg_bytes ka = (karg_bytes)__builtin_amdgcn_kernarg_segment_ptr();
+      const float man1 = ((karg_floats)(ka + wa_at + offsetof(WeightArgs, man_h1)))[i];
+      const float man2 = ((karg_floats)(ka + wa_at + offsetof(WeightArgs, man_h2)))[i];
+      weight_scalars(wa, i, S, man1, man2, blockIdx.x == 0, &s_omh1[i], &s_h2[i]);
+    }
+    __syncthreads();
+  }
   const int64_t nq = a.Pp >> 2;
   const int64_t qbase = (int64_t)blockIdx.x * (kUpdThreads * kUpdQuads) + threadIdx.x;
   float4 cen[kUpdQuads], acc[kUpdQuads];
@@ -355,7 +391,7 @@ __global__ __launch_bounds__(kUpdThreads) void pull_kernel(PullArgs a) {
   }
   for (int i = 0; i < a.k; ++i) {
     if (!((a.part_mask >> i) & 1ull)) continue;
-    const float o = a.omh1[i], w = a.h2[i];
+    const float o = FUSED_W ? s_omh1[i] : a.omh1[i], w = FUSED_W ? s_h2[i] : a.h2[i];
     float4* th4 = reinterpret_cast<float4*>(a.theta + (int64_t)i * a.Pp);
     float4 T[kUpdQuads];
 #pragma unroll
@@ -403,10 +439,29 @@ hipError_t launch_pull(const PullArgs& a, hipStream_t s) {
   KernelScope ks(KC_PULL, s);
   const int64_t nq = a.Pp >> 2;
   const int n_blocks = (int)((nq + kUpdThreads * kUpdQuads - 1) / (kUpdThreads * kUpdQuads));
+  WeightArgs none{};
   if (a.wb16)
-    hipLaunchKernelGGL(pull_kernel<true>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
+    hipLaunchKernelGGL((pull_kernel<true, false>), dim3(n_blocks), dim3(kUpdThreads), 0, s, a, none);
   else
-    hipLaunchKernelGGL(pull_kernel<false>, dim3(n_blocks), dim3(kUpdThreads), 0, s, a);
+    hipLaunchKernelGGL((pull_kernel<false, false>), dim3(n_blocks), dim3(kUpdThreads), 0, s, a, none);
+  return hipGetLastError();
+}
+
+// the round of a model with few partial sums per worker in one launch: weights and pull together
+bool sync_fusable(const WeightArgs& w, const PullArgs& p) {
+  const int64_t nq = p.Pp >> 2;
+  const int64_t n_blocks = (nq + kUpdThreads * kUpdQuads - 1) / (kUpdThreads * kUpdQuads);
+  return w.n_blocks + w.n_blocks_f <= 16 && n_blocks <= 64;
+}
+
+hipError_t launch_weights_and_pull(const WeightArgs& w, const PullArgs& a, hipStream_t s) {
+  KernelScope ks(KC_PULL, s);
+  const int64_t nq = a.Pp >> 2;
+  const int n_blocks = (int)((nq + kUpdThreads * kUpdQuads - 1) / (kUpdThreads * kUpdQuads));
+  if (a.wb16)
+    hipLaunchKernelGGL((pull_kernel<true, true>), dim3(n_blocks), dim3(kUpdThreads), 0, s, a, w);
+  else
+    hipLaunchKernelGGL((pull_kernel<false, true>), dim3(n_blocks), dim3(kUpdThreads), 0, s, a, w);
   return hipGetLastError();
 }
 

@@ -93,6 +93,9 @@ struct PullArgs {
 hipError_t launch_update(const UpdateArgs& a, int n_blocks, hipStream_t s);
 hipError_t launch_weights(const WeightArgs& a, hipStream_t s);
 hipError_t launch_pull(const PullArgs& a, hipStream_t s);
+// weights and pull of one round in a single launch, for models with few distance partial sums per worker
+bool sync_fusable(const WeightArgs& w, const PullArgs& p);
+hipError_t launch_weights_and_pull(const WeightArgs& w, const PullArgs& p, hipStream_t s);
 hipError_t launch_rademacher(uint32_t* zbits, int64_t z_stride, int64_t n_words64, const uint64_t* keys_host,
                              int k, uint64_t active_mask, hipStream_t s);
 // dacc = (first ? 0 : dacc) + z*hz for the active workers: the running sum of a step's Hutchinson probes
@@ -279,6 +282,12 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
 // then back through the pooling and the convolutions (fp32 only).
 int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                     const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, hipStream_t s);
+// A small fp32 model's whole worker step in one kernel (dw_tiny.hip): can this configuration take it, and the launch.
+// `u`: the update's arguments of this step (step counts already advanced), keys_host: the workers' stream keys.
+bool tiny_step_ok(const dw_config& cfg, const Layout& lay);
+hipError_t launch_tiny_step(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
+                            const uint32_t* d_zbits, const UpdateArgs& u, const uint64_t* keys_host, float* d_loss,
+                            hipStream_t s);
 // hz <- z * (mean over each 3x3 window of z * hz) on the kernels of the convolutions (Section IV-B averaging)
 hipError_t launch_conv_window_mean(float* hz, const uint32_t* zbits, int64_t Pp, int64_t z_stride, const Layout& lay,
                                    int k, uint64_t active, hipStream_t s);
@@ -290,7 +299,7 @@ namespace dw {
 
 enum KernelClass {
   KC_RADEMACHER = 0, KC_GEMM_FWD = 1, KC_HEAD = 2, KC_GEMM_WGRAD = 3, KC_GEMM_DGRAD = 4,
-  KC_UPDATE = 5, KC_WEIGHTS = 6, KC_PULL = 7, KC_GATHER = 8, KC_COUNT = 9
+  KC_UPDATE = 5, KC_WEIGHTS = 6, KC_PULL = 7, KC_GATHER = 8, KC_STEP = 9, KC_COUNT = 10
 };
 
 struct Profiler {

@@ -59,6 +59,67 @@ def test_gradient_and_hvp_match_the_oracle(dims, batch, k):
     print("worst err/bound:", parity.OBSERVED)
 
 
+@pytest.mark.parametrize("dims,batch,k,avg_block,hpow", [
+    ((32, 64, 10), 16, 4, 4, 1.0), ((32, 64, 32, 16), 24, 3, 32, 0.5), ((48, 40, 36, 28, 24, 4), 33, 2, 2, 2.0),
+    ((64, 64, 10), 30, 5, 64, 1.0),
+])
+def test_small_models_take_the_whole_step_in_one_kernel(dims, batch, k, avg_block, hpow):
+    """A model that fits in one compute unit's LDS runs z, network, update and distances in a single kernel (one block
+    per worker).  Three forced steps with block averaging and other Hessian powers, a frozen worker in the second, a
+    dynamic-weighted round after each (weights and pull in one launch); the profiler confirms which kernels ran."""
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=5000 + avg_block, avg_block=avg_block, hpow=hpow, stale="third")
+    h, tr, theta0 = _setup(w)
+    x, y = W.minibatch_pool(w, 3)
+    sched = W.participation_schedule(w, 3)
+    h.profile(True)
+    parity.reset()
+    for step in range(3):
+        if step:
+            for i in range(k):
+                h.set_state(B.DW_S_THETA, i, tr.theta[i]); h.set_state(B.DW_S_M, i, tr.m[i]); h.set_state(B.DW_S_V, i, tr.v[i])
+            h.set_state(B.DW_S_CENTRE, 0, tr.centre)
+        active = None if step != 1 else [int(i != 1) for i in range(k)]
+        prev_gpu, prev = h.all_state(B.DW_S_THETA), tr.theta.copy()
+        loss = torch.zeros(k, device="cuda")
+        h.worker_step(torch.from_numpy(x[step]).cuda(), torch.from_numpy(y[step]).cuda(), loss=loss, active=active)
+        ref_loss = _oracle_step_with_ties(h, w, tr, x[step], y[step], False, "small step %d" % step, active=active)
+        now_gpu = h.all_state(B.DW_S_THETA)
+        for i in range(k):
+            if active is not None and not active[i]:
+                np.testing.assert_array_equal(now_gpu[i], prev_gpu[i])
+                continue
+            assert abs(loss[i].item() - ref_loss[i]) <= 1e-5 * abs(ref_loss[i])
+            np.testing.assert_array_equal(h.get_state(B.DW_S_ZBITS, i),
+                                          O.words_to_u32(O.rademacher_words(w.seed, i, int(tr.t[i]) - 1, w.P)))
+            close_layers(h.get_state(B.DW_S_G, i), tr.traces[i].g, dims, RTOL_GRAD, "small g[%d]" % i)
+            close_layers(h.get_state(B.DW_S_HZ, i), tr.traces[i].hz, dims, RTOL_HV, "small hz[%d]" % i)
+            close_update(now_gpu[i] - prev_gpu[i], tr.theta[i] - prev[i], tr, i, dims, RTOL_UPDATE, "small update[%d]" % i)
+            close(h.get_state(B.DW_S_M, i), tr.m[i], RTOL_UPDATE, "small m[%d]" % i)
+            close(h.get_state(B.DW_S_V, i), tr.v[i], RTOL_HV, "small v[%d]" % i)
+        for i in range(k):
+            h.set_state(B.DW_S_THETA, i, tr.theta[i])
+        pre_t, pre_c = h.all_state(B.DW_S_THETA).astype(np.float64), h.get_state(B.DW_S_CENTRE).astype(np.float64)
+        tr.theta = pre_t.copy()
+        assert h.elastic_sync(B.DW_DYNAMIC, tau=1, participate=sched[step])
+        assert tr.elastic_sync(O.MODE_DYNAMIC, tau=1, participate=sched[step])
+        for i in range(k):
+            sc = h.get_state(B.DW_S_SCORE, i)
+            assert abs(sc[0] - tr.last_u[i]) < 1e-5 and abs(sc[1] - tr.last_a[i]) < 2e-5, (step, i, sc)
+            assert abs(sc[2] - tr.last_h1[i]) < 5e-4 and abs(sc[3] - tr.last_h2[i]) < 5e-4
+            close(h.get_state(B.DW_S_THETA, i) - pre_t[i], tr.theta[i] - pre_t[i], RTOL_UPDATE, "small pull[%d]" % i,
+                  extra=5e-4 * np.abs(pre_t[i] - pre_c) + 2.0 ** -23 * np.abs(tr.theta[i]))
+        close(h.get_state(B.DW_S_CENTRE) - pre_c, tr.centre - pre_c, RTOL_UPDATE, "small centre",
+              extra=5e-4 * k * np.abs(pre_t - pre_c).max(axis=0) + 2.0 ** -23 * np.abs(tr.centre))
+    prof = h.profile_read()
+    # (the three launches of the update kernel are the distance-only ones that follow dw_set_state)
+    assert prof["step"][0] == 3 and prof["gemm_fwd"][0] == 0 and prof["update"][0] == 3
+    assert prof["weights"][0] == 0 and prof["pull"][0] == 3
+    parity.bound_ties(False)
+    hist = h.get_state(B.DW_S_U_HIST, 0)
+    assert int(hist[0]) == 3
+    np.testing.assert_allclose(hist[1:4], tr.u_hist[0], atol=1e-5)
+
+
 def test_caller_supplied_z_and_frozen_worker():
     w = W.scaled(W.C1, dims=(40, 48, 8), batch=21, k=3, seed=31)
     h, tr, theta0 = _setup(w)

@@ -89,8 +89,8 @@ def test_fused_update_is_an_option_of_large_layers_only():
         fused = lib.dw_workspace_bytes(C.byref(B.config_from_workload(w, fuse_update=1)))
         assert plain > 0
         if w is W.C4:
-            # three 4096 x 4096 layers, 32 x 16 tiles each, one double per tile and worker
-            assert fused - plain == 3 * 32 * 16 * 8 * w.k
+            # three 4096 x 4096 layers, 32 x 32 tiles of 128 x 128 each, one double per tile and worker
+            assert fused - plain == 3 * 32 * 32 * 8 * w.k
         elif w is W.C3:
             # fp32: 1024 x 3072 and two 1024 x 1024 layers in 128 x 128 tiles, one double per tile and worker
             assert fused - plain == (8 * 24 + 2 * 8 * 8) * 8 * w.k

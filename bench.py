@@ -254,6 +254,28 @@ def run_update_stress(iters=20, warmup=3, optimizer=0):
     return out
 
 
+def hbm_probe(n=1 << 30, reps=20):
+    """What HBM sustains for plain streaming kernels of several read : write mixes (torch's elementwise kernels on
+    4 GiB arrays; none of the library's code runs): context for the HBM-bound kernels' fractions of the 8 TB/s peak."""
+    import torch
+    x = torch.ones(n, device="cuda"); y = torch.empty_like(x); z = torch.empty_like(x)
+    cases = (("fill (0 read : 1 write)", 1, lambda: y.zero_()), ("copy (1 : 1)", 2, lambda: y.copy_(x)),
+             ("add, in place (2 : 1)", 3, lambda: torch.add(x, y, out=y)),
+             ("addcmul (3 : 1)", 4, lambda: torch.addcmul(x, y, z, out=z)))
+    out = {}
+    for name, arrays, f in cases:
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            f()
+        torch.cuda.synchronize()
+        gbs = arrays * 4.0 * n / ((time.perf_counter() - t0) / reps) / 1e9
+        out[name] = {"GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+    return out
+
+
 def cpu_baseline(w, budget_s=15.0):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     from oracle import dw_oracle as O
@@ -330,6 +352,9 @@ def main():
                     help="how many times the timed region of --steps steps is run; the line reports the median region")
     ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--hbm-probe", action="store_true",
+                    help="run only plain streaming kernels (torch fill, copy, add, addcmul on 4 GiB arrays) and print "
+                         "the rates HBM sustains for their read : write mixes")
     ap.add_argument("--stress-only", action="store_true",
                     help="run only the update-only HBM stress and print its figures (for profiling)")
     args = ap.parse_args()
@@ -345,6 +370,9 @@ def main():
         print("no GPU visible", file=sys.stderr)
         return 3
     BLD.ensure_built()                      # loads what is built; builds only when nothing is
+    if args.hbm_probe:
+        print(json.dumps({"hbm_probe": hbm_probe()}))
+        return 0
     if args.stress_only:
         print(json.dumps({"update_stress": run_update_stress()}))
         return 0

@@ -210,3 +210,24 @@ def test_transposed_lds_reads_are_not_touched_before_their_wait():
         asm = BLD.check_transposed_reads()              # compiles (about a minute)
     found, n = BLD.premature_uses_of_transposed_reads(open(asm).read())
     assert n >= 8 and found == []
+
+
+def test_bench_reads_the_traffic_figure_only_for_the_kernel_it_was_measured_on(tmp_path, monkeypatch):
+    """bench.py takes roofline.traffic from the counter summary under profiles/ and drops it (None) as soon as the
+    sources of the kernel differ from the digest recorded with the counters."""
+    import sys
+    sys.path.insert(0, ROOT)
+    import bench
+    f = tmp_path / "summary.txt"
+    f.write_text("some text\ntraffic_bytes_per_launch: 8.25e9\nkernel_sources_digest: %s\nmore text\n" % bench.kernel_sources_digest())
+    monkeypatch.setattr(bench, "TRAFFIC_SUMMARY", str(f))
+    assert bench.measured_traffic() == 8.25e9
+    f.write_text("traffic_bytes_per_launch: 8.25e9\nkernel_sources_digest: 0123456789abcdef\n")
+    assert bench.measured_traffic() is None
+    f.write_text("no figures here\n")
+    assert bench.measured_traffic() is None
+    monkeypatch.setattr(bench, "TRAFFIC_SUMMARY", str(tmp_path / "absent.txt"))
+    assert bench.measured_traffic() is None
+    # the summary that is committed belongs to the sources that are committed
+    monkeypatch.undo()
+    assert bench.measured_traffic() is not None

@@ -104,7 +104,8 @@ def class_bytes(w, P, k, fused=(), part=1.0, samples=1):
     reads the centre (4 B) on the steps before a round, and reads its four bf16 operands once (d_l, Rd_l, a_{l-1},
     Ra_{l-1}).  With n > 1 Hutchinson probes the fused launches of the first n - 1 probes only keep the running sum
     of z*Hz (first: 4 B written, later: 4 B read and 4 B written per parameter, + 1 bit of z) and the last one
-    reads the sum on top of the above (+4 B)."""
+    reads the sum on top of the above (+4 B).  Two probes in bf16 take one launch per layer for both: the state once,
+    a second bit of z, six operands instead of four."""
     d = w.dims
     p_fused = sum(d[l] * d[l - 1] for l in fused)
     upd = (32.0 + (2.0 if w.bf16 else 0.0)) * (P - p_fused) * k
@@ -115,7 +116,9 @@ def class_bytes(w, P, k, fused=(), part=1.0, samples=1):
         operands = sum(2.0 * es * w.batch * (d[l] + d[l - 1]) for l in fused)
         # the centre (4 B) is read only on the steps after which a round is due: one step in tau
         out["gemm_wgrad"] = ((24.125 + (2.0 if w.bf16 else 0.0) + 4.0 / w.tau) * p_fused + operands) * k
-        if samples > 1:
+        if samples == 2 and w.bf16:
+            out["gemm_wgrad"] += (0.125 * p_fused + 0.5 * operands) * k
+        elif samples > 1:
             out["gemm_wgrad"] += ((4.125 + 8.125 * (samples - 2) + 4.0) * p_fused + (samples - 1) * operands) * k
     return out
 
@@ -445,7 +448,7 @@ def main():
                 "bytes_per_step": by[dominant] * per_step[dominant]}
         if dominant == "gemm_wgrad":
             # per launch, like the counters: the class has one more, tiny launch per step (the output layer)
-            n_big = len(fused) * args.samples
+            n_big = len(fused) * (1 if (args.samples == 2 and w.bf16) else args.samples)
             roof["launches_per_step"] = n_big
             roof["bytes_per_launch"] = by[dominant] / n_big
             roof["avg_ms"] = kernels[dominant]["ms_per_step"] / n_big

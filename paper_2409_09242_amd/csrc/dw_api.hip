@@ -224,11 +224,19 @@ int validate(const dw_config* c, Layout* lay) {
     if (b16 ? gemm_bf16_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])
             : gemm_f32_wgrad_fusable(c->dims[l], c->dims[l - 1], k, c->avg_block, c->hpow, lay->woff[l - 1])) {
       lay->fuse_base[l - 1] = lay->n_fuse_slots;
-      lay->n_fuse_slots += b16 ? gemm_bf16_wgrad_tiles(c->dims[l], c->dims[l - 1])
+      lay->n_fuse_slots += b16 ? gemm_bf16_wgrad_tiles(c->dims[l], c->dims[l - 1], c->n_samples)
                                : gemm_f32_wgrad_tiles(c->dims[l], c->dims[l - 1]);
     }
   }
   if (lay->n_fuse_slots > 0) lay->partials_f = take((size_t)k * lay->n_fuse_slots * sizeof(double));
+  if (lay->n_fuse_slots > 0 && c->dtype == DW_BF16 && c->n_samples == 2) {
+    lay->pair = true;
+    lay->zbits_p = take((size_t)k * lay->z_stride * 4);
+    for (int l = 1; l < L; ++l) {
+      lay->ract_p[l] = take((size_t)k * c->batch * c->dims[l] * 2);
+      lay->rdelta_p[l] = take((size_t)k * c->batch * c->dims[l] * 2);
+    }
+  }
   lay->u_ring = take((size_t)k * (DW_MAX_P + 1) * sizeof(double));
   lay->score = take((size_t)k * 4 * sizeof(double));
   lay->omh1 = take((size_t)k * sizeof(float));
@@ -315,14 +323,14 @@ inline int probes(const dw_handle* h) { return h->cfg.n_samples > 1 ? h->cfg.n_s
 
 // draw probe `sample` of the active workers' next step (step counts before the increment): stream position
 // t_i * n_samples + sample, which for one probe per step is t_i
-int draw_z(dw_handle* h, uint64_t active, hipStream_t s, int sample = 0) {
+int draw_z(dw_handle* h, uint64_t active, hipStream_t s, int sample = 0, uint32_t* dst = nullptr) {
   uint64_t keys[DW_MAX_K];
   const uint64_t G = 0x9E3779B97F4A7C15ull;
   for (int i = 0; i < h->cfg.k; ++i) {
     const uint64_t k1 = mix64_host(h->cfg.seed + G * (uint64_t)(i + 1));
     keys[i] = mix64_host(k1 + G * (uint64_t)(h->t[i] * probes(h) + sample + 1));
   }
-  DW_HIP(launch_rademacher(h->at<uint32_t>(h->lay.zbits), h->lay.z_stride, (h->lay.P + 63) / 64, keys,
+  DW_HIP(launch_rademacher(dst ? dst : h->at<uint32_t>(h->lay.zbits), h->lay.z_stride, (h->lay.P + 63) / 64, keys,
                            h->cfg.k, active, s));
   return DW_OK;
 }
@@ -361,22 +369,27 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
     // n probes of the same minibatch: the network runs once per probe (loss and g come out the same each time),
     // z_j*Hz_j is summed, and the update takes D = sum / n.  Fused layers keep their part of the sum in the
     // weight-gradient kernel and apply the update in the last probe's; the rest goes through the sum kernel.
+    // Two probes with fused bf16 layers (lay.pair): the earlier probe's pass leaves the fused weight gradients out
+    // and keeps its z, Ra_l, Rd_l; the later probe's kernels multiply for both and need no sum in memory.
     const int n = probes(h);
     const bool fused = h->lay.n_fuse_slots > 0;
+    const bool pair = h->lay.pair && !d_zbits;
+    uint32_t* zb_p = pair ? h->at<uint32_t>(h->lay.zbits_p) : nullptr;
     float* dacc = h->at<float>(h->lay.dacc);
     int st = clear_fused_partials(h, s);
     if (st != DW_OK) return st;
     UpdateArgs a;
     for (int j = 0; j < n; ++j) {
       const bool last = j == n - 1;
-      st = draw_z(h, active, s, j);
+      const uint32_t* zj = pair && !last ? zb_p : zb;      // this probe's sign bits
+      st = draw_z(h, active, s, j, pair && !last ? zb_p : nullptr);
       if (st != DW_OK) return st;
       if (last)
         for (int i = 0; i < h->cfg.k; ++i)
           if ((active >> i) & 1ull) h->t[i] += 1;
       if (last || j == 0) fill_update_args(h, a, h->at<float>(h->lay.g), dacc, h->lay.Pp, zb, zs, active, fused);
       a.d_scale = 1.0f / (float)n;
-      a.probe_mode = last ? 2 : 1; a.probe_first = j == 0 ? 1 : 0; a.dacc = dacc;
+      a.probe_mode = pair ? 3 : last ? 2 : 1; a.probe_first = j == 0 ? 1 : 0; a.dacc = dacc;
       // probes after the first find the activations and the plain data gradients of this minibatch in the workspace
       if (h->lay.n_conv > 0) {
         // the window mean is linear: taken per probe on z_j*Hz_j, it gives the window mean of their mean
@@ -384,11 +397,11 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
         if (st == DW_OK && h->cfg.conv_avg)
           DW_HIP(launch_conv_window_mean(h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->lay, h->cfg.k, active, s));
       } else {
-        st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fused ? &a : nullptr, true, s, nullptr,
-                         nullptr, nullptr, j > 0);
+        st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zj, zs, active, loss, fused ? &a : nullptr, true, s, nullptr,
+                         nullptr, nullptr, j > 0, pair ? j + 1 : 0);
       }
       if (st != DW_OK) return st;
-      DW_HIP(launch_probe_sum(dacc, h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->cfg.k, active, j == 0 ? 1 : 0,
+      DW_HIP(launch_probe_sum(dacc, h->at<float>(h->lay.hz), zj, h->lay.Pp, zs, h->cfg.k, active, j == 0 ? 1 : 0,
                               a.fused, s));
     }
     DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));

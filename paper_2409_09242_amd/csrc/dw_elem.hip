@@ -679,4 +679,46 @@ hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hi
   return hipGetLastError();
 }
 
+// Column sums of a bf16 matrix [B][n] per worker.  Block: 32 units of 8 columns x 8 row groups; a thread adds the rows
+// r = group, group + 8, ... of its 8 columns, the groups are then added in order through LDS.
+__global__ __launch_bounds__(256) void col_sums_bf16_kernel(const uint16_t* src, int B, int n, float* out, int64_t out_wstride,
+                                                            uint64_t active_mask) {
+  const int worker = blockIdx.y;
+  if (!((active_mask >> worker) & 1ull)) return;
+  const int unit = threadIdx.x & 31, group = threadIdx.x >> 5;
+  const int col = (blockIdx.x * 32 + unit) * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (col < n) {
+    const uint16_t* p = src + (int64_t)worker * B * n + col;
+#pragma unroll 4
+    for (int r = group; r < B; r += 8) {
+      const uint4 u = *reinterpret_cast<const uint4*>(p + (int64_t)r * n);
+      const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        acc[2 * q] += __uint_as_float(w[q] << 16);
+        acc[2 * q + 1] += __uint_as_float(w[q] & 0xFFFF0000u);
+      }
+    }
+  }
+  __shared__ float part[8][32][9];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) part[group][unit][q] = acc[q];
+  __syncthreads();
+  const int c = threadIdx.x;                                  // one thread per column of the block's 256
+  if (blockIdx.x * 256 + c < n) {
+    float t = 0.f;
+#pragma unroll
+    for (int gq = 0; gq < 8; ++gq) t += part[gq][c >> 3][c & 7];
+    out[(int64_t)worker * out_wstride + blockIdx.x * 256 + c] = t;
+  }
+}
+
+hipError_t launch_col_sums_bf16(const uint16_t* src, int B, int n, float* out, int64_t out_wstride, int k,
+                                uint64_t active_mask, hipStream_t s) {
+  hipLaunchKernelGGL(col_sums_bf16_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)k), dim3(256), 0, s, src, B, n, out,
+                     out_wstride, active_mask);
+  return hipGetLastError();
+}
+
 }  // namespace dw

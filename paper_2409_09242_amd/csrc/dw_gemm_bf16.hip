@@ -16,6 +16,7 @@
 //     12+i/4), which hands each lane its 4 consecutive k for one row.
 // The +-1 operand V (z reshaped like W) is expanded from the sign bits of z in the loader.
 #include <cstddef>
+#include <type_traits>
 
 #include "dw_internal.h"
 #include "dw_device_util.h"
@@ -53,17 +54,19 @@ __device__ __forceinline__ uint4 pm1_x8(uint32_t b) {
 // One operand tile: R rows (the non-contraction index) x BK, moved by NTH threads in 16-byte units.
 //   KC = true : memory is [row][k]; unit u = 8 k of row u/4; LDS [R][LDK]
 //   KC = false: memory is [k][row]; unit u = 8 rows at k = u/(R/8); LDS [BK][R+KPAD]
-template <int R, int NTH, bool KC>
+//   BKT: k per tile (BK, or 16 for [k][row] tiles of the two-probe weight gradient)
+template <int R, int NTH, bool KC, int BKT = BK>
 struct Tile {
-  static constexpr int UNITS = R * BK / 8;
+  static_assert(BKT == BK || (!KC && BKT == 16), "[row][k] tiles have the row stride of BK = 32");
+  static constexpr int UNITS = R * BKT / 8;
   static constexpr int UPT = (UNITS + NTH - 1) / NTH;
-  static constexpr int LDS_ELEMS = KC ? R * LDK : BK * (R + KPAD);
+  static constexpr int LDS_ELEMS = KC ? R * LDK : BKT * (R + KPAD);
   static constexpr int LDR = R + KPAD;
 
   // Unit u of this thread is unit number u*NTH + tl of the tile; a thread's units differ by constants, so
   // only the first one's offsets are kept.
   static constexpr bool FULL = UNITS % NTH == 0;                          // every thread owns UPT units
-  static constexpr int ROWS_PER_PASS = KC ? NTH / (BK / 8) : 0;           // KC: rows between a thread's units
+  static constexpr int ROWS_PER_PASS = KC ? NTH / (BKT / 8) : 0;          // KC: rows between a thread's units
   static constexpr int K_PER_PASS = KC ? 0 : (NTH >= R / 8 ? NTH / (R / 8) : 0);   // !KC: k rows between them
   int goff0;              // element offset of unit 0 in the source at k0 = 0 (an operand has < 2^31 elements)
   int loff0;              // element offset of unit 0 in the LDS tile
@@ -73,7 +76,7 @@ struct Tile {
   __device__ __forceinline__ void init(int tl, int ld, int r0, int Rmax) {
     okmask = 0;
     if (KC) {
-      const int row = tl / (BK / 8), kc = (tl % (BK / 8)) * 8;
+      const int row = tl / (BKT / 8), kc = (tl % (BKT / 8)) * 8;
       goff0 = (r0 + row) * ld + kc; loff0 = row * LDK + kc; kk0 = kc;
 #pragma unroll
       for (int u = 0; u < UPT; ++u)
@@ -148,6 +151,12 @@ __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int row0, int ks, in
   }
 }
 
+struct NoUpdateTile {                                       // stands in for FusedUpdateTile in kernels that do not update
+  template <class... A> __device__ __forceinline__ NoUpdateTile(A&&...) {}
+  template <int EARLY> __device__ __forceinline__ void prefetch() {}
+  template <int EARLY, class... A> __device__ __forceinline__ float run(A&&...) { return 0.f; }
+};
+
 template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0, int NTH = 512>
 __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmArgs a) {   // (two waves per SIMD either way)
   constexpr int NT = NTH;                                   // threads per block: 512, or 256 (see launch_fused_wgrad)
@@ -165,7 +174,7 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
   if (slot >= active_count(a.active_mask, a.k)) return;
   const int worker = nth_active_worker(a.active_mask, slot);
   const int tile = logical - slot * tiles;
-  if (EPI == EPI_WGRAD && FM != 1 && a.fu.on && blockIdx.x < 256 * 8) {
+  if (EPI == EPI_WGRAD && NTH == 256 && FM != 1 && blockIdx.x < 256 * 8) {
     // Fused update: a block alternates between a compute-bound main loop and an HBM-bound epilogue of about twice
     // its length.  Blocks that start together stay in step, leaving HBM idle while everybody multiplies, so the
     // first block of every compute unit starts with one of 16 delays spread over about one block period.
@@ -222,6 +231,13 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
 #pragma unroll
       for (int r = 0; r < 16; ++r) { acc[i][j][r] = 0.f; racc[i][j][r] = 0.f; }
   float gb_acc = 0.f, hzb_acc = 0.f;
+
+  // launch_fused_wgrad's instances apply the update of Section IV-B to the tile (FM: 0 one Hutchinson probe; 1 a probe
+  // before the last, only the running sum of z*Hz is written; 2 the last of several probes)
+  constexpr bool FUSED = EPI == EPI_WGRAD && NTH == 256 && TN == 2;
+  using UpdateTile = std::conditional_t<FUSED && FM != 1, FusedUpdateTile<TM, true, FM == 2 ? 1 : 0>, NoUpdateTile>;
+  UpdateTile upd(a.fu, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0, zb + (a.z_off >> 5), nullptr, lane);
+  constexpr int EARLY = 0;      // batches of the update loaded before the main loop ends: no registers to spare here
 
   const int nkt = (a.K + BK - 1) / BK;
   auto fetch = [&](int kt) {
@@ -313,6 +329,7 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
   const bool compute_first = wave < (NT / 64) / 2;
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
+    if (kt == nkt - 1) upd.template prefetch<EARLY>();       // the update's first state loads run under the last k-tile
     if (compute_first) {
       compute_tile(cur);
       move_tiles(kt, cur);
@@ -324,12 +341,10 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
   }
 
   // epilogue: lane holds column n = l32 of each 32x32 tile, rows (r/4)*8 + lhalf*4 + r%4
-  if (EPI == EPI_WGRAD && (FM != 0 || a.fu.on)) {           // (the instances for several probes are always fused)
-    // The update of Section IV-B applied to the tile while g and Hz are still in registers (same arithmetic as
-    // update_kernel, Hessian power 1).  Element (m, n) is parameter m*ldc + n of the layer's W block; the 32
-    // lanes of a half-wave hold 32 consecutive n of one row, so the sign bits of a row segment are one word and
-    // the block mean of D = z*Hz along fan-in is a butterfly over avg_block lanes.  M % 128 == 0 and N % 256 == 0:
-    // no element of the tile is out of range.  Offsets inside the block fit 32 bits.
+  if constexpr (FUSED) {
+    // The update applied to the tile while g and Hz are still in registers (same arithmetic as update_kernel, Hessian
+    // power 1).  Element (m, n) is parameter m*ldc + n of the layer's W block; W is made of whole tiles, so no
+    // element is out of range, and offsets inside the block fit 32 bits.
     const FuseArgs& f = a.fu;
     // bias corrections of this worker, read from the kernel-argument block by a scalar load (indexing the by-value
     // argument with a variable would copy it to scratch memory)
@@ -339,19 +354,13 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
     const karg_floats bc = (karg_floats)(ka + offsetof(GemmArgs, fu) + offsetof(FuseArgs, sc));
     const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];
     static_assert(offsetof(UpdateScalars, inv_bc2) == DW_MAX_K * sizeof(float), "inv_bc2 follows inv_bc1");
-    static_assert(TN == 2 || !(BM == 128 && (BN == 256 || BN == 128)), "the wave's tile row is 64 columns wide");
     float* gl = reinterpret_cast<float*>(smem) + wave * fused_update_lds_floats();     // free after the main loop
     float nsum = 0.f;
-    if constexpr (TN == 2) {                                  // (the tile shapes that can be asked to fuse)
-      // FM: 0 one Hutchinson probe; 1 a probe before the last (only the running sum of z*Hz is written);
-      // 2 the last of several probes
-      if constexpr (FM == 1)
-        fused_probe_sum_wave_tile<TM>(racc, gl, f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
-                                      zb + (a.z_off >> 5), lane);
-      else
-        nsum = fused_update_wave_tile<TM, true, FM == 2>(acc, racc, gl, f, (int64_t)worker * a.c_wstride, a.ldc,
-                                                         row0 + wm0, col0 + wn0, zb + (a.z_off >> 5), ib1, ib2, lane);
-    }
+    if constexpr (FM == 1)
+      fused_probe_sum_wave_tile<TM>(racc, gl, f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
+                                    zb + (a.z_off >> 5), lane);
+    else
+      nsum = upd.template run<EARLY>(acc, racc, racc, gl, ib1, ib2);
     // squared distance of the tile's new parameters to the centre: one slot per (worker, tile)
     double ws = (double)nsum;
 #pragma unroll
@@ -475,6 +484,197 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
   }
 }
 
+// Weight gradient of a layer for two Hutchinson probes of one minibatch at once, with the update in its epilogue:
+// g = X^T Y as above, Hz_p = RXp^T Y + X^T RYp along the earlier probe's z and Hz = RX^T Y + X^T RY along the later
+// one's, D = (z_p*Hz_p + z*Hz) / 2 (Section IV-B with two samples of the estimate).  X = d_l and Y = a_{l-1} are
+// staged once for both probes and the parameters, moments and bf16 copy are moved once, where one launch per probe
+// reads the operands twice and carries the first probe's z*Hz through memory.  Tiles of BM x 128 with BM/32 x 2 waves
+// of 32 x 64 (three accumulator sets of 32 registers), six operand tiles of PK k per stage.  Launched with BM = 128,
+// PK = 32: 8 waves, 120 KB of LDS, one block per compute unit.  Measured on a 4096 x 4096 layer of 16 workers:
+// 2.38 ms, the multiplications alone 1.36 ms (80 % of the matrix cores' peak) and the update alone 1.39 ms, so the
+// two phases of a block mostly follow each other; BM = 64, PK = 16 puts two blocks of 4 waves on a unit, which do
+// overlap, but its main loop is bound by LDS traffic and the launch takes 2.64 ms.
+template <bool HAS_RY, int BM, int PK>
+__global__ __launch_bounds__(BM * 4, BM == 128 ? 1 : 2) void fused_wgrad_pair_bf16(GemmArgs a) {
+  constexpr int NT = BM * 4, BN = 128, WM = BM / 32, KS = PK / 16;
+  const int tiles_m = a.M / BM, tiles_n = a.N / BN;
+  const int tiles = tiles_m * tiles_n;
+  const int per_xcd = gridDim.x >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);     // an XCD walks a contiguous range
+  const int slot = logical / tiles;
+  if (slot >= active_count(a.active_mask, a.k)) return;
+  const int worker = nth_active_worker(a.active_mask, slot);
+  const int tile = logical - slot * tiles;
+  if (blockIdx.x < 256) {                                    // first block of every compute unit: staggered start
+    const int ph = (blockIdx.x >> 3) & 15;
+    for (int i = 0; i < ph; ++i) __builtin_amdgcn_s_sleep(127);
+  }
+  int tm = tile % tiles_m, tn = tile / tiles_m;
+  constexpr int GR = 1024 / BM;                              // groups of 1024 x 1024 share their operand panels in L2
+  if (tiles_m % GR == 0) {
+    const int g = tile / (GR * tiles_n), r = tile - g * (GR * tiles_n);
+    tn = r / GR; tm = g * GR + r % GR;
+  }
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave % WM) * 32, wn0 = (wave / WM) * 64;
+
+  using TX = Tile<BM, NT, false, PK>;                        // every operand is [k][row]; a thread moves at most one
+  using TY = Tile<BN, NT, false, PK>;                        // 16-byte unit of each tile
+  static_assert(TX::UPT == 1 && TY::UPT == 1, "one unit per thread and tile");
+  constexpr int X_ELEMS = TX::LDS_ELEMS, Y_ELEMS = TY::LDS_ELEMS, STAGE = 3 * X_ELEMS + 3 * Y_ELEMS;
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  // tiles of a stage: X, RXp, RX, then Y, RYp, RY
+  auto xt = [&](int st, int t) { return smem + st * STAGE + t * X_ELEMS; };
+  auto yt = [&](int st, int t) { return smem + st * STAGE + 3 * X_ELEMS + t * Y_ELEMS; };
+
+  const int64_t xo = (int64_t)worker * a.x_wstride, yo = (int64_t)worker * a.y_wstride;
+  const uint16_t* xsrc[3] = {reinterpret_cast<const uint16_t*>(a.X) + xo, reinterpret_cast<const uint16_t*>(a.RXp) + xo,
+                             reinterpret_cast<const uint16_t*>(a.RX) + xo};
+  const uint16_t* ysrc[3] = {reinterpret_cast<const uint16_t*>(a.Y) + yo,
+                             HAS_RY ? reinterpret_cast<const uint16_t*>(a.RYp) + yo : nullptr,
+                             HAS_RY ? reinterpret_cast<const uint16_t*>(a.RY) + yo : nullptr};
+  TX tx; TY ty;
+  tx.init(tid, a.ldx, row0, a.M);
+  ty.init(tid, a.ldy, col0, a.N);
+  constexpr int NY = HAS_RY ? 3 : 1;
+  uint4 xr[3][1], yr[NY][1];
+
+  floatx16 acc[1][2], raccp[1][2], racc[1][2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { acc[0][j][r] = 0.f; raccp[0][j][r] = 0.f; racc[0][j][r] = 0.f; }
+  float gb_acc = 0.f, hzb_acc = 0.f;
+  const int64_t zw0 = (int64_t)worker * a.z_stride + (a.z_off >> 5);
+  FusedUpdateTile<1, true, 2> upd(a.fu, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0, a.zbits + zw0,
+                                  a.zbits_p + zw0, lane);
+
+  const int nkt = (a.K + PK - 1) / PK;
+  auto fetch = [&](int kt) {
+#pragma unroll
+    for (int t = 0; t < 3; ++t) tx.load(xsrc[t], a.ldx, kt * PK, a.K, xr[t]);
+#pragma unroll
+    for (int t = 0; t < NY; ++t) ty.load(ysrc[t], a.ldy, kt * PK, a.K, yr[t]);
+  };
+  auto stash = [&](int st, int kt) {
+#pragma unroll
+    for (int t = 0; t < 3; ++t) tx.store(xt(st, t), xr[t], tid, kt * PK, a.K);
+#pragma unroll
+    for (int t = 0; t < NY; ++t) ty.store(yt(st, t), yr[t], tid, kt * PK, a.K);
+  };
+  struct Frags { bf16x8 x, rxp, rx, y[2], ryp[2], ry[2]; };
+  auto compute_tile = [&](int cur) {
+    if (tn == 0 && tid < BM) {                               // bias gradients of the later probe (X is [k][m])
+      const uint16_t* xs = xt(cur, 0);
+      const uint16_t* rxs = xt(cur, 2);
+#pragma unroll
+      for (int kq = 0; kq < PK; ++kq) {
+        gb_acc += bf2f(xs[kq * TX::LDR + tid]);
+        hzb_acc += bf2f(rxs[kq * TX::LDR + tid]);
+      }
+    }
+    Frags f[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      f[ks].x = frag<BM, false>(xt(cur, 0), wm0, ks, lane);
+      f[ks].rxp = frag<BM, false>(xt(cur, 1), wm0, ks, lane);
+      f[ks].rx = frag<BM, false>(xt(cur, 2), wm0, ks, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        f[ks].y[j] = frag<BN, false>(yt(cur, 0), wn0 + j * 32, ks, lane);
+        if (HAS_RY) {
+          f[ks].ryp[j] = frag<BN, false>(yt(cur, 1), wn0 + j * 32, ks, lane);
+          f[ks].ry[j] = frag<BN, false>(yt(cur, 2), wn0 + j * 32, ks, lane);
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[ks].x, f[ks].y[j], acc[0][j], 0, 0, 0);
+        raccp[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[ks].rxp, f[ks].y[j], raccp[0][j], 0, 0, 0);
+        racc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[ks].rx, f[ks].y[j], racc[0][j], 0, 0, 0);
+      }
+      if (HAS_RY) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          raccp[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[ks].x, f[ks].ryp[j], raccp[0][j], 0, 0, 0);
+          racc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[ks].x, f[ks].ry[j], racc[0][j], 0, 0, 0);
+        }
+      }
+    }
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  auto move_tiles = [&](int kt, int cur) {
+    if (kt + 1 < nkt) stash(cur ^ 1, kt + 1);
+    if (kt + 2 < nkt) fetch(kt + 2);
+  };
+
+  fetch(0);
+  stash(0, 0);
+  if (nkt > 1) fetch(1);
+  __syncthreads();
+  const bool compute_first = wave < NT / 128;                // half of the waves multiply first, half move first
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int cur = kt & 1;
+    if (compute_first) {
+      compute_tile(cur);
+      move_tiles(kt, cur);
+    } else {
+      move_tiles(kt, cur);
+      compute_tile(cur);
+    }
+    __syncthreads();
+  }
+
+  const FuseArgs& f = a.fu;
+  typedef const char __attribute__((address_space(4)))* karg_bytes;
+  typedef const float __attribute__((address_space(4)))* karg_floats;
+  const karg_bytes ka = (karg_bytes)__builtin_amdgcn_kernarg_segment_ptr();
+  const karg_floats bc = (karg_floats)(ka + offsetof(GemmArgs, fu) + offsetof(FuseArgs, sc));
+  const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];   // scalar loads from the kernel-argument block
+  float* gl = reinterpret_cast<float*>(smem) + wave * fused_update_lds_floats(true);   // free after the main loop
+  const float nsum = upd.template run<0>(acc, racc, raccp, gl, ib1, ib2);
+  double ws = (double)nsum;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) ws += __shfl_xor(ws, off);
+  __syncthreads();                                           // everybody is done with the staging regions
+  double* red = reinterpret_cast<double*>(smem);
+  if (lane == 0) red[wave] = ws;
+  __syncthreads();
+  if (tid == 0 && f.dist) {
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < NT / 64; ++w) t += red[w];
+    f.partials[(int64_t)worker * f.part_stride + f.part_base + tile] = t;
+  }
+  if (tn == 0 && tid < BM) {
+    a.gb[(int64_t)worker * a.c_wstride + row0 + tid] = gb_acc;
+    a.hzb[(int64_t)worker * a.c_wstride + row0 + tid] = hzb_acc;
+  }
+}
+
+template <bool HAS_RY>
+static hipError_t launch_pair(const GemmArgs& a, hipStream_t s) {
+  constexpr int BM = 128, PK = 32, NT = BM * 4;
+  const int tiles = (a.M / BM) * (a.N / 128);
+  const dim3 grid((unsigned)((tiles * active_count(a.active_mask, a.k) + 7) / 8 * 8)), block(NT);
+  constexpr int tiles_b = 2 * 2 * 3 * (Tile<BM, NT, false, PK>::LDS_ELEMS + Tile<128, NT, false, PK>::LDS_ELEMS);
+  constexpr int epi_b = (NT / 64) * fused_update_lds_floats(true) * 4;
+  constexpr int smem = tiles_b > epi_b ? tiles_b : epi_b;
+  static_assert(smem <= 160 * 1024, "LDS budget");
+  auto kern = fused_wgrad_pair_bf16<HAS_RY, BM, PK>;
+  static LdsLimitOnce lds_limit;
+  { const hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), smem); if (e != hipSuccess) return e; }
+  hipLaunchKernelGGL(kern, grid, block, smem, s, a);
+  return hipGetLastError();
+}
+
 template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI, int FM = 0, int NTH = 512>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   constexpr int NT = NTH;
@@ -517,6 +717,7 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
 // several Hutchinson probes (FM 1: a probe before the last, 2: the last), so that the one-probe kernel keeps its
 // registers.
 static hipError_t launch_fused_wgrad(const GemmArgs& a, hipStream_t s) {
+  if (a.fu.probe_mode == 3) return a.RY ? launch_pair<true>(a, s) : launch_pair<false>(a, s);
   if (a.fu.probe_mode == 1)
     return a.RY ? launch_one<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD, 1, 256>(a, s)
                 : launch_one<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD, 1, 256>(a, s);
@@ -537,7 +738,7 @@ bool gemm_bf16_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hp
   if ((int64_t)n_out * n_in >= (1ll << 31)) return false;
   return (int64_t)(n_out / 128) * (n_in / 128) * k >= 512;
 }
-int gemm_bf16_wgrad_tiles(int n_out, int n_in) { return ((n_out + 127) / 128) * ((n_in + 127) / 128); }
+int gemm_bf16_wgrad_tiles(int n_out, int n_in, int /*n_samples*/) { return ((n_out + 127) / 128) * ((n_in + 127) / 128); }
 
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s) {
   KernelScope ks(a.epi == EPI_WGRAD ? KC_GEMM_WGRAD : a.epi == EPI_MASK ? KC_GEMM_DGRAD : KC_GEMM_FWD, s);

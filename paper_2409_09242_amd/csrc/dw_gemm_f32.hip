@@ -223,10 +223,11 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
     if constexpr (FM == 1)
       fused_probe_sum_wave_tile<TM>(racc, fused_lds + wave * fused_update_lds_floats(), f, (int64_t)worker * a.c_wstride,
                                     a.ldc, row0 + wm0, col0 + wn0, zb + (a.z_off >> 5), lane);
-    else
-      nsum = fused_update_wave_tile<TM, false, FM == 2>(acc, racc, fused_lds + wave * fused_update_lds_floats(), f,
-                                                        (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
-                                                        zb + (a.z_off >> 5), ib1, ib2, lane);
+    else {
+      FusedUpdateTile<TM, false, FM == 2 ? 1 : 0> upd(f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
+                                                     zb + (a.z_off >> 5), nullptr, lane);
+      nsum = upd.template run<0>(acc, racc, racc, fused_lds + wave * fused_update_lds_floats(), ib1, ib2);
+    }
     double ws = (double)nsum;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) ws += __shfl_xor(ws, off);

@@ -108,6 +108,10 @@ hipError_t launch_transpose_bits(const uint32_t* z, int64_t z_stride, uint32_t* 
 hipError_t launch_broadcast(float* theta, const float* centre, uint16_t* wb16, int64_t Pp, int k, hipStream_t s);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_refresh_bf16(const float* theta, uint16_t* wb16, int64_t n, hipStream_t s);
+// out[i][c] = sum over the B rows of src[i][.][c] (bf16 [k][B][n], n a multiple of 8, 16-byte aligned) for the
+// active workers: the bias part of a weight gradient when the product itself is left to another launch
+hipError_t launch_col_sums_bf16(const uint16_t* src, int B, int n, float* out, int64_t out_wstride, int k,
+                                uint64_t active_mask, hipStream_t s);
 
 // records a failed HIP call for dw_last_hip_error (this thread) and returns DW_ERR_HIP
 int note_hip_error(hipError_t e);
@@ -137,7 +141,8 @@ struct FuseArgs {
   float lr, beta1, beta2, eps, hpow;
   UpdateScalars sc;
   // several Hutchinson probes.  0: one probe.  1: a probe that is not the last, only
-  // dacc (+)= z*Hz is written (first: stored, not added).  2: the last probe, D = (dacc + z*Hz) * d_scale
+  // dacc (+)= z*Hz is written (first: stored, not added).  2: the last probe, D = (dacc + z*Hz) * d_scale.
+  // 3: both of two probes in this kernel (GemmArgs::RXp, RYp, zbits_p), D = (z_p*Hz_p + z*Hz) / 2
   int probe_mode, first;
   float* dacc;                        // the layer's W block of worker 0 in the running sum, worker stride c_wstride
   float d_scale;
@@ -172,6 +177,9 @@ struct GemmArgs {
   // applies the epilogue (bias, ReLU) into C, RC, gb, hzb
   int ksplit; float* part; int64_t part_stride; float* part_b;
   int r_only;                         // 1: C is in memory already (an earlier probe of this minibatch); kernels may compute RC alone
+  // EPI_WGRAD with fu.probe_mode == 3 (two Hutchinson probes in one kernel): the earlier probe's R-companions of X
+  // and Y (laid out like RX and RY; RYp == nullptr with RY) and its sign bits (strides and offsets as zbits)
+  const void* RXp; const void* RYp; const uint32_t* zbits_p;
   int epi;
   int k;
   uint64_t active_mask;
@@ -205,9 +213,9 @@ struct LdsLimitOnce {
 hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& a, hipStream_t s);
 // can the bf16 weight-gradient kernel of a layer W[n_out][n_in] (bit/parameter offset woff) apply the update itself,
-// and how many partial-sum slots (tiles) does it then write per worker?
+// and how many partial-sum slots (tiles) does it then write per worker when a step has n_samples Hutchinson probes?
 bool gemm_bf16_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff);
-int gemm_bf16_wgrad_tiles(int n_out, int n_in);
+int gemm_bf16_wgrad_tiles(int n_out, int n_in, int n_samples);
 bool gemm_f32_wgrad_fusable(int n_out, int n_in, int k, int avg_block, float hpow, int64_t woff);   // same for fp32 (128 x 128 tiles)
 int gemm_f32_wgrad_tiles(int n_out, int n_in);
 // would the data gradient through W[n_out][n_in] of a minibatch of `batch` samples take the large-tile kernel
@@ -243,6 +251,10 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t zbits_t = 0;                 // [k][z_stride] words: z with the W-parts of the layers in zt_layer transposed
   bool zt_layer[DW_MAX_LAYERS] = {false};   // index l-1: the data gradient through W_l reads the transposed bits
   size_t dacc = 0;                    // [k][Pp] floats, n_samples > 1 only: sum over the probes of z_j*Hz_j
+  // two probes per step with fused bf16 weight gradients: those kernels take both probes at once, so the earlier
+  // probe's z, Ra_l and Rd_l (hidden layers, index l) are kept in buffers of their own until the later probe's are there
+  bool pair = false;
+  size_t zbits_p = 0, ract_p[DW_MAX_LAYERS] = {0}, rdelta_p[DW_MAX_LAYERS] = {0};
   int fwdSplit[DW_MAX_LAYERS] = {0};   // fp32: slices of layer l+1's forward contraction (0 or 1: not cut)
   int dgSplit[DW_MAX_LAYERS] = {0};    // fp32: slices of the data gradient through W_{l+1} (0 or 1: not cut)
   int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
@@ -271,9 +283,12 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
                 bool fuse_dist, hipStream_t s, const void* in_ract = nullptr, void* d_in = nullptr,
-                void* rd_in = nullptr, bool r_only = false);
+                void* rd_in = nullptr, bool r_only = false, int pair_phase = 0);
 // `r_only`: the same minibatch went through the network before (an earlier Hutchinson probe of this step), so the
 // activations and the plain data gradients are in the workspace; kernels that can then compute the R-parts alone.
+// `pair_phase` (lay.pair): 1 = the earlier of two probes: its R-quantities go to the buffers kept for it, the fused
+// layers' weight gradients are left to the later probe's launch and only their bias parts of hz are written;
+// 2 = the later probe: the fused weight-gradient kernels take both probes (zbits of the earlier one: lay.zbits_p).
 // `in_ract` above: directional derivative of the input (nullptr: the input does not depend on the parameters).
 // `d_in`, `rd_in`: when given, the gradient with respect to the input and its R-companion ([k][B][d_0], zero where
 // the input is not positive: the input is then the ReLU output of a layer in front).

@@ -64,7 +64,8 @@ hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
-                bool fuse_dist, hipStream_t s, const void* in_ract, void* d_in, void* rd_in, bool r_only) {
+                bool fuse_dist, hipStream_t s, const void* in_ract, void* d_in, void* rd_in, bool r_only,
+                int pair_phase) {
   const bool b16 = cfg.dtype == DW_BF16;
   const int L = cfg.n_layers, k = cfg.k, B = cfg.batch;
   const int HL = DW_MAX_CLASSES;                     // row stride of the output-layer buffers
@@ -72,7 +73,11 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
   float* g = reinterpret_cast<float*>(ws + lay.g);
   float* hz = reinterpret_cast<float*>(ws + lay.hz);
   auto act = [&](int l) -> const void* { return l == 0 ? d_x : (const void*)(ws + lay.act[l]); };
-  auto ract = [&](int l) -> const void* { return l == 0 ? in_ract : (const void*)(ws + lay.ract[l]); };
+  // R-quantities of the hidden layers: the earlier of two probes taken together keeps its own (see Layout::pair)
+  const bool keep = pair_phase == 1;
+  auto ract_buf = [&](int l) -> void* { return ws + (keep ? lay.ract_p[l] : lay.ract[l]); };
+  auto rdelta_buf = [&](int l) -> void* { return ws + (keep ? lay.rdelta_p[l] : lay.rdelta[l]); };
+  auto ract = [&](int l) -> const void* { return l == 0 ? in_ract : (const void*)ract_buf(l); };
   auto act_stride = [&](int l) -> int64_t { return (int64_t)B * cfg.dims[l]; };
   // weights as the GEMMs read them: fp32 master copy, or its bf16 rounding kept by the update and the pull
   auto weights = [&](int l) -> const void* {
@@ -112,7 +117,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.M = B; a.N = cfg.dims[l]; a.K = cfg.dims[l - 1];
     a.bias = theta + lay.boff[l - 1]; a.bias_wstride = lay.Pp;
     if (l < L) {
-      a.C = ws + lay.act[l]; a.RC = ws + lay.ract[l]; a.ldc = cfg.dims[l]; a.c_wstride = act_stride(l);
+      a.C = ws + lay.act[l]; a.RC = ract_buf(l); a.ldc = cfg.dims[l]; a.c_wstride = act_stride(l);
       a.epi = EPI_RELU; a.r_only = r_only ? 1 : 0;
     } else {
       a.C = ws + lay.sL; a.RC = ws + lay.rsL; a.ldc = HL; a.c_wstride = (int64_t)B * HL;
@@ -143,7 +148,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     if (l == L) {
       dl = ws + (b16 ? lay.dL16 : lay.dL); rdl = ws + (b16 ? lay.rdL16 : lay.rdL); ldd = HL; dstride = (int64_t)B * HL;
     } else {
-      dl = ws + lay.delta[l]; rdl = ws + lay.rdelta[l]; ldd = cfg.dims[l]; dstride = act_stride(l);
+      dl = ws + lay.delta[l]; rdl = rdelta_buf(l); ldd = cfg.dims[l]; dstride = act_stride(l);
     }
   };
   auto weight_gradient = [&](int l) -> hipError_t {   // and its R-companion: contraction over the minibatch
@@ -158,6 +163,12 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.C = g + lay.woff[l - 1]; a.RC = hz + lay.woff[l - 1]; a.ldc = cfg.dims[l - 1]; a.c_wstride = lay.Pp;
     a.gb = g + lay.boff[l - 1]; a.hzb = hz + lay.boff[l - 1];
     a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
+    if (fuse != nullptr && lay.fuse_base[l - 1] >= 0 && keep) {
+      // left to the later probe's launch; the bias part of this probe's Hz is the column sum of Rd_l
+      KernelScope ks(KC_GEMM_WGRAD, s);
+      return launch_col_sums_bf16(reinterpret_cast<const uint16_t*>(rdl), B, cfg.dims[l], hz + lay.boff[l - 1], lay.Pp, k,
+                                  active, s);
+    }
     if (fuse != nullptr && lay.fuse_base[l - 1] >= 0) {
       // the kernel applies this step's update to W_l instead of storing gW_l and HzW_l
       const int64_t wo = lay.woff[l - 1];
@@ -173,6 +184,10 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.fu.sc = fuse->sc;
       a.fu.probe_mode = fuse->probe_mode; a.fu.first = fuse->probe_first;
       a.fu.dacc = fuse->dacc ? fuse->dacc + wo : nullptr; a.fu.d_scale = fuse->d_scale;
+      if (pair_phase == 2) {                          // (a fused layer is a hidden layer: its Rd_l has a kept copy)
+        a.RXp = ws + lay.rdelta_p[l]; a.RYp = l == 1 ? nullptr : (const void*)(ws + lay.ract_p[l - 1]);
+        a.zbits_p = reinterpret_cast<const uint32_t*>(ws + lay.zbits_p);
+      }
     }
     return gemm(a);
   };
@@ -189,7 +204,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.woff[l - 1];
     a.zbits_t = lay.zt_layer[l - 1] ? zt : nullptr; a.zt_stride = lay.z_stride;
     a.M = B; a.N = cfg.dims[l - 1]; a.K = cfg.dims[l];
-    a.C = l == 1 ? d_in : (void*)(ws + lay.delta[l - 1]); a.RC = l == 1 ? rd_in : (void*)(ws + lay.rdelta[l - 1]);
+    a.C = l == 1 ? d_in : (void*)(ws + lay.delta[l - 1]); a.RC = l == 1 ? rd_in : rdelta_buf(l - 1);
     a.ldc = cfg.dims[l - 1];
     a.c_wstride = act_stride(l - 1);
     a.mask_src = act(l - 1); a.ld_mask = cfg.dims[l - 1]; a.mask_wstride = act_stride(l - 1);

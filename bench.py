@@ -33,10 +33,15 @@ TRAFFIC_SOURCES = ("dw_gemm_bf16.hip", "dw_fused_update.h", "dw_gemm_epi.h", "dw
 
 
 def kernel_sources_digest():
+    """Digest of the code of the fused weight gradient's sources: comments (the kernels use // only) and white space
+    do not count, so rewording a comment does not part the counters from the kernel they were taken on."""
     import hashlib
+    import re
     h = hashlib.sha256()
     for f in TRAFFIC_SOURCES:
-        h.update(open(os.path.join(ROOT, "paper_2409_09242_amd", "csrc", f), "rb").read())
+        text = open(os.path.join(ROOT, "paper_2409_09242_amd", "csrc", f)).read()
+        code = [re.sub(r"\s+", " ", re.sub(r"//.*", "", line)).strip() for line in text.splitlines()]
+        h.update("\n".join(c for c in code if c).encode())
     return h.hexdigest()[:16]
 
 

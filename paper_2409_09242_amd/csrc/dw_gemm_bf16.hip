@@ -491,9 +491,10 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
 // reads the operands twice and carries the first probe's z*Hz through memory.  Tiles of BM x 128 with BM/32 x 2 waves
 // of 32 x 64 (three accumulator sets of 32 registers), six operand tiles of PK k per stage.  Launched with BM = 128,
 // PK = 32: 8 waves, 120 KB of LDS, one block per compute unit.  Measured on a 4096 x 4096 layer of 16 workers:
-// 2.38 ms, the multiplications alone 1.36 ms (80 % of the matrix cores' peak) and the update alone 1.39 ms, so the
-// two phases of a block mostly follow each other; BM = 64, PK = 16 puts two blocks of 4 waves on a unit, which do
-// overlap, but its main loop is bound by LDS traffic and the launch takes 2.64 ms.
+// 2.38 ms, the multiplications alone 1.36 ms (1.37 Tflop: 40 % of the matrix cores' peak; operand reads from LDS take
+// as many cycles as the MFMAs) and the update alone 1.39 ms, so the two phases of a block mostly follow each other;
+// BM = 64, PK = 16 puts two blocks of 4 waves on a unit, which do overlap, but with more LDS traffic per product the
+// launch takes 2.64 ms.
 template <bool HAS_RY, int BM, int PK>
 __global__ __launch_bounds__(BM * 4, BM == 128 ? 1 : 2) void fused_wgrad_pair_bf16(GemmArgs a) {
   constexpr int NT = BM * 4, BN = 128, WM = BM / 32, KS = PK / 16;

@@ -246,6 +246,73 @@ def test_c4_full_size_configured_schedule():
     parity.bound_fractions({"update": (0.05, 0.01), "m": (0.05, 0.0), "v": (0.05, 0.0)})
 
 
+def test_c4_two_probes_per_step_at_full_size():
+    """C4 with two Hutchinson probes per step (Section IV-B with n = 2), first step of all 16 workers at full size.
+    With `fuse_update` the 4096 x 4096 layers take both probes in one weight-gradient launch (three accumulator sets,
+    the earlier probe's Ra_l, Rd_l and z kept in buffers of their own); beside it the handle that runs the update as a
+    kernel of its own on the running sum of z_j * Hz_j.  The oracle follows workers 1 and 14: g and the last probe's Hz
+    of the unfused handle layer by layer in norm, the moments of both handles in norm (they are linear in g and
+    quadratic in the mean of the probes), and the two handles against each other entry by entry on every parameter
+    (the same terms added in the same order)."""
+    w, n = W.C4, 2
+    follow = [1, 14]
+    theta0 = W.init_theta(w.dims, w.seed)
+    x, y = W.minibatch_pool(w, 1, bf16_round=W.to_bf16_f32)
+    xb, yb = torch.from_numpy(x[0]).to(torch.bfloat16).cuda(), torch.from_numpy(y[0]).cuda()
+    hA = B.Handle(B.config_from_workload(w, n_samples=n), theta0)
+    hB = B.Handle(B.config_from_workload(w, n_samples=n, fuse_update=1), theta0)
+    hp = dict(lr=w.lr, beta1=w.beta1, beta2=w.beta2, eps=w.eps, hpow=w.hpow, dims=w.dims, avg_block=w.avg_block)
+    P = w.P
+    parity.reset()
+    lossA, lossB = torch.zeros(w.k, device="cuda"), torch.zeros(w.k, device="cuda")
+    hA.worker_step(xb, yb, loss=lossA)
+    hB.worker_step(xb, yb, loss=lossB)
+    np.testing.assert_array_equal(lossA.cpu().numpy(), lossB.cpu().numpy())
+    hidden = parity.gpu_hidden(hA, w, follow)
+    choice = parity.slopes_of(hidden)
+    traces = {}
+    th0 = theta0.astype(np.float64)
+    for i in follow:
+        print("worker", i, flush=True)
+        words = [O.rademacher_words(w.seed, i, j, P) for j in range(n)]        # stream positions t*n + j, t = 0
+        np.testing.assert_array_equal(hA.get_state(B.DW_S_ZBITS, i), O.words_to_u32(words[-1]))
+        np.testing.assert_array_equal(hB.get_state(B.DW_S_ZBITS, i), O.words_to_u32(words[-1]))
+        zs = [O.words_to_signs(wd, P) for wd in words]
+        hzs = []
+        for j in range(n):
+            trc = O.StepTrace()
+            ref_loss, g, hz = O.grad_and_hvp(th0, x[0][i], y[0][i], w.dims, zs[j], O.round_bf16, trc, parity.TIE_BAND_BF16,
+                                             choice[i])
+            hzs.append(hz)
+        traces[i] = trc
+        assert abs(float(lossA[i]) - ref_loss) <= 1e-4 * abs(ref_loss), i
+        gg, hh_ = hA.get_state(B.DW_S_G, i), hA.get_state(B.DW_S_HZ, i)
+        for name, sl in parity.per_layer(w.dims):
+            T.close_norm(gg[sl], g[sl], T.RTOL_BF16_G, "c4 probes g[%d]/%s" % (i, name), cap=100.0)
+            T.close_norm(hh_[sl], hzs[-1][sl], T.RTOL_BF16_HZ, "c4 probes hz[%d]/%s" % (i, name), cap=100.0)
+        th_new, m_new, v_new = O.adahessian_update(th0, np.zeros(P), np.zeros(P), g, np.stack(hzs), np.stack(zs), 1, **hp)
+        tA, mA, vA = (hA.get_state(s, i) for s in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V))
+        tB, mB, vB = (hB.get_state(s, i) for s in (B.DW_S_THETA, B.DW_S_M, B.DW_S_V))
+        for name, (t_, m_, v_) in (("unfused", (tA, mA, vA)), ("fused", (tB, mB, vB))):
+            T.close_norm(m_, m_new, T.RTOL_BF16_G, "c4 probes %s m[%d]" % (name, i), cap=100.0)
+            T.close_norm(v_, v_new, 4 * T.RTOL_BF16_HZ, "c4 probes %s v[%d]" % (name, i), cap=100.0)
+            rel = np.linalg.norm(t_.astype(np.float64) - th_new) / np.linalg.norm(th_new - th0)
+            parity.OBSERVED["c4 probes step displacement " + name] = max(parity.OBSERVED.get("c4 probes step displacement " + name, 0.0), rel)
+            assert rel < 0.1, (name, i, rel)
+        assert np.any(tA != theta0)
+        close(tB - theta0, tA - theta0, 1e-6, "c4 probes fused vs unfused update[%d]" % i, extra=2.0 ** -23 * np.abs(tA))
+        close(mB, mA, 1e-6, "c4 probes fused vs unfused m[%d]" % i)
+        close(vB, vA, 1e-6, "c4 probes fused vs unfused v[%d]" % i)
+    parity.check_hidden(hidden, traces, True, "c4 probes")
+    # a worker the oracle does not follow: the two handles still agree (sampled ranges)
+    for (o0, n0) in _sample_slices(w, W.rng_for(w.seed, 41), per_layer=8):
+        tA, tB = hA.get_state(B.DW_S_THETA, 7, o0, n0), hB.get_state(B.DW_S_THETA, 7, o0, n0)
+        close(tB - theta0[o0:o0 + n0], tA - theta0[o0:o0 + n0], 1e-6, "c4 probes fused vs unfused update[7]", extra=2.0 ** -23 * np.abs(tA))
+    parity.bound_ties(True)
+    print("worst err/bound:", {k_: v_ for k_, v_ in parity.OBSERVED.items() if "probes" in k_})
+    hA.close(); hB.close()
+
+
 def test_c5_full_size_update_and_rounds():
     """k=16, flat P=1e8: two update + round iterations; the oracle follows workers 0 and 15 and the centre in
     full, and checks sampled slices of every other worker."""

@@ -237,6 +237,12 @@ int validate(const dw_config* c, Layout* lay) {
       lay->rdelta_p[l] = take((size_t)k * c->batch * c->dims[l] * 2);
     }
   }
+  // small models without a convolutional front end or fused layers: weight gradients beside the data gradients
+  if (L >= 2 && lay->n_conv == 0 && lay->n_fuse_slots == 0) {
+    int64_t blocks = 0;                                   // 64 x 64 output tiles of all weight gradients
+    for (int l = 1; l <= L; ++l) blocks += (int64_t)((c->dims[l] + 63) / 64) * ((c->dims[l - 1] + 63) / 64) * k;
+    lay->overlap_wgrad = blocks < 4096 && !tiny_step_ok(*c, *lay);
+  }
   lay->u_ring = take((size_t)k * (DW_MAX_P + 1) * sizeof(double));
   lay->score = take((size_t)k * 4 * sizeof(double));
   lay->omh1 = take((size_t)k * sizeof(float));
@@ -272,6 +278,7 @@ struct dw_handle {
   bool norms_valid;         // the squared distances in `partials` match the current theta and centre
   int last_tau;             // communication period of the latest dw_elastic_sync call (1 before the first)
   Profiler* prof;           // non-null while per-kernel timing is enabled
+  SideStream* side;         // non-null when lay.overlap_wgrad
 
   template <class T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
 };
@@ -398,7 +405,7 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
           DW_HIP(launch_conv_window_mean(h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->lay, h->cfg.k, active, s));
       } else {
         st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zj, zs, active, loss, fused ? &a : nullptr, true, s, nullptr,
-                         nullptr, nullptr, j > 0, pair ? j + 1 : 0);
+                         nullptr, nullptr, j > 0, pair ? j + 1 : 0, h->side);
       }
       if (st != DW_OK) return st;
       DW_HIP(launch_probe_sum(dacc, h->at<float>(h->lay.hz), zj, h->lay.Pp, zs, h->cfg.k, active, j == 0 ? 1 : 0,
@@ -444,7 +451,8 @@ int run_step(dw_handle* h, const void* d_x, const int32_t* d_y, const uint32_t* 
     if (h->cfg.conv_avg)
       DW_HIP(launch_conv_window_mean(h->at<float>(h->lay.hz), zb, h->lay.Pp, zs, h->lay, h->cfg.k, active, s));
   } else {
-    st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fu, dist, s);
+    st = run_network(h->cfg, h->ws, h->lay, d_x, d_y, zb, zs, active, loss, fu, dist, s, nullptr, nullptr, nullptr, false, 0,
+                     h->side);
     if (st != DW_OK) return st;
   }
   DW_HIP(launch_update(a, (int)h->lay.n_upd_blocks, s));
@@ -484,6 +492,28 @@ int dw_param_count(const dw_config* cfg, int64_t* n_params) {
   return DW_OK;
 }
 
+// stream (default priority, not synchronising with the legacy default stream) and events of a SideStream
+static hipError_t make_side_stream(SideStream** out, int n_layers) {
+  SideStream* sd = new (std::nothrow) SideStream();
+  if (!sd) return hipErrorOutOfMemory;
+  sd->s = nullptr; sd->join = nullptr;
+  for (int l = 0; l <= DW_MAX_LAYERS; ++l) sd->fork[l] = nullptr;
+  hipError_t e = hipStreamCreateWithFlags(&sd->s, hipStreamNonBlocking);
+  for (int l = 2; l <= n_layers && e == hipSuccess; ++l) e = hipEventCreateWithFlags(&sd->fork[l], hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&sd->join, hipEventDisableTiming);
+  *out = sd;                                             // (freed by the caller, also after a failure)
+  return e;
+}
+
+static void free_side_stream(SideStream* sd) {
+  if (!sd) return;
+  for (int l = 0; l <= DW_MAX_LAYERS; ++l)
+    if (sd->fork[l]) (void)hipEventDestroy(sd->fork[l]);
+  if (sd->join) (void)hipEventDestroy(sd->join);
+  if (sd->s) { (void)hipStreamSynchronize(sd->s); (void)hipStreamDestroy(sd->s); }
+  delete sd;
+}
+
 size_t dw_workspace_bytes(const dw_config* cfg) {
   Layout lay;
   if (validate(cfg, &lay) != DW_OK) return 0;
@@ -504,9 +534,13 @@ int dw_init(dw_handle** out, const dw_config* cfg, void* d_workspace, size_t wor
   h->lay = lay;
   h->ws = reinterpret_cast<char*>(d_workspace);
   std::memset(h->t, 0, sizeof(h->t));
-  h->calls = 0; h->rounds = 0; h->norms_valid = false; h->prof = nullptr; h->last_tau = 1;
+  h->calls = 0; h->rounds = 0; h->norms_valid = false; h->prof = nullptr; h->last_tau = 1; h->side = nullptr;
   int rc = DW_OK;
   do {
+    if (lay.overlap_wgrad) {
+      const hipError_t es = make_side_stream(&h->side, cfg->n_layers);
+      if (es != hipSuccess) { rc = hip_fail(es); break; }
+    }
     hipError_t e = launch_fill_zero(h->ws, lay.total, s);            // moments, padding, history: all zero
     if (e != hipSuccess) { rc = hip_fail(e); break; }
     e = hipMemcpyAsync(h->at<float>(lay.centre), theta0, (size_t)lay.P * sizeof(float),
@@ -520,7 +554,7 @@ int dw_init(dw_handle** out, const dw_config* cfg, void* d_workspace, size_t wor
       if (e != hipSuccess) { rc = hip_fail(e); break; }
     }
   } while (0);
-  if (rc != DW_OK) { delete h; return rc; }
+  if (rc != DW_OK) { free_side_stream(h->side); delete h; return rc; }
   *out = h;
   return DW_OK;
 }
@@ -572,6 +606,7 @@ int dw_profile_read(dw_handle* h, int64_t* n_launches, double* total_ms, int64_t
 int dw_destroy(dw_handle* h) {
   if (!h) return DW_ERR_NULL;
   free_profiler(h);
+  free_side_stream(h->side);
   delete h;
   return DW_OK;
 }

@@ -257,6 +257,7 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t zbits_p = 0, ract_p[DW_MAX_LAYERS] = {0}, rdelta_p[DW_MAX_LAYERS] = {0};
   int fwdSplit[DW_MAX_LAYERS] = {0};   // fp32: slices of layer l+1's forward contraction (0 or 1: not cut)
   int dgSplit[DW_MAX_LAYERS] = {0};    // fp32: slices of the data gradient through W_{l+1} (0 or 1: not cut)
+  bool overlap_wgrad = false;          // small model without fused layers: weight gradients on the handle's side stream
   int fuse_base[DW_MAX_LAYERS] = {0};  // first partial-sum slot of layer l+1's fused weight gradient, -1: not fused
   int n_fuse_slots = 0;
   size_t partials_f = 0;              // [k][n_fuse_slots] doubles
@@ -275,6 +276,15 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   size_t total = 0;
 };
 
+// A second stream of a handle for launches that do not depend on each other: the weight gradients of a small model
+// run beside its chain of data gradients (each launch fills a fraction of the chip and lasts about as long as the
+// gap to the next one).  Forked from and joined to the caller's stream by events; the host never waits.
+struct SideStream {
+  hipStream_t s;
+  hipEvent_t fork[DW_MAX_LAYERS + 1];   // index l: d_l and Rd_l are there
+  hipEvent_t join;
+};
+
 // Enqueue forward, R-forward, backward and R-backward of all layers for the active workers; leaves the mean
 // gradient in the g buffer and the Hessian-vector product in the hz buffer (returns a dw_status).  With `fuse`
 // (the arguments of this step's update) the layers marked in lay.fuse_base are updated by their weight-gradient
@@ -283,12 +293,14 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
                 bool fuse_dist, hipStream_t s, const void* in_ract = nullptr, void* d_in = nullptr,
-                void* rd_in = nullptr, bool r_only = false, int pair_phase = 0);
+                void* rd_in = nullptr, bool r_only = false, int pair_phase = 0, const SideStream* side = nullptr);
 // `r_only`: the same minibatch went through the network before (an earlier Hutchinson probe of this step), so the
 // activations and the plain data gradients are in the workspace; kernels that can then compute the R-parts alone.
 // `pair_phase` (lay.pair): 1 = the earlier of two probes: its R-quantities go to the buffers kept for it, the fused
 // layers' weight gradients are left to the later probe's launch and only their bias parts of hz are written;
 // 2 = the later probe: the fused weight-gradient kernels take both probes (zbits of the earlier one: lay.zbits_p).
+// `side` (lay.overlap_wgrad): the weight gradients of the layers above the first are launched on that stream as soon
+// as their d_l is there; the call returns with the caller's stream waiting for them.
 // `in_ract` above: directional derivative of the input (nullptr: the input does not depend on the parameters).
 // `d_in`, `rd_in`: when given, the gradient with respect to the input and its R-companion ([k][B][d_0], zero where
 // the input is not positive: the input is then the ReLU output of a layer in front).

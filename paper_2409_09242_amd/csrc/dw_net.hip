@@ -65,7 +65,7 @@ hipError_t launch_head(const HeadArgs& a, hipStream_t s) {
 int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d_x, const int32_t* d_y,
                 const uint32_t* zbits, int64_t z_stride, uint64_t active, float* d_loss, const UpdateArgs* fuse,
                 bool fuse_dist, hipStream_t s, const void* in_ract, void* d_in, void* rd_in, bool r_only,
-                int pair_phase) {
+                int pair_phase, const SideStream* side) {
   const bool b16 = cfg.dtype == DW_BF16;
   const int L = cfg.n_layers, k = cfg.k, B = cfg.batch;
   const int HL = DW_MAX_CLASSES;                     // row stride of the output-layer buffers
@@ -84,7 +84,8 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     return b16 ? (const void*)(reinterpret_cast<uint16_t*>(ws + lay.wb16) + lay.woff[l - 1])
                : (const void*)(theta + lay.woff[l - 1]);
   };
-  auto gemm = [&](const GemmArgs& a) { return b16 ? launch_gemm_bf16(a, s) : launch_gemm_f32(a, s); };
+  auto gemm_on = [&](const GemmArgs& a, hipStream_t st) { return b16 ? launch_gemm_bf16(a, st) : launch_gemm_f32(a, st); };
+  auto gemm = [&](const GemmArgs& a) { return gemm_on(a, s); };
   hipError_t e;
 
   // layers whose data gradient reads the sign bits of V_l column by column get a transposed copy of those bits
@@ -151,7 +152,7 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       dl = ws + lay.delta[l]; rdl = rdelta_buf(l); ldd = cfg.dims[l]; dstride = act_stride(l);
     }
   };
-  auto weight_gradient = [&](int l) -> hipError_t {   // and its R-companion: contraction over the minibatch
+  auto weight_gradient = [&](int l, hipStream_t st) -> hipError_t {   // and its R-companion: contraction over the minibatch
     const void* dl; const void* rdl; int ldd; int64_t dstride;
     delta_of(l, dl, rdl, ldd, dstride);
     GemmArgs a{};
@@ -165,9 +166,9 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
     a.epi = EPI_WGRAD; a.k = k; a.active_mask = active;
     if (fuse != nullptr && lay.fuse_base[l - 1] >= 0 && keep) {
       // left to the later probe's launch; the bias part of this probe's Hz is the column sum of Rd_l
-      KernelScope ks(KC_GEMM_WGRAD, s);
+      KernelScope ks(KC_GEMM_WGRAD, st);
       return launch_col_sums_bf16(reinterpret_cast<const uint16_t*>(rdl), B, cfg.dims[l], hz + lay.boff[l - 1], lay.Pp, k,
-                                  active, s);
+                                  active, st);
     }
     if (fuse != nullptr && lay.fuse_base[l - 1] >= 0) {
       // the kernel applies this step's update to W_l instead of storing gW_l and HzW_l
@@ -189,8 +190,17 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
         a.zbits_p = reinterpret_cast<const uint32_t*>(ws + lay.zbits_p);
       }
     }
-    return gemm(a);
+    return gemm_on(a, st);
   };
+  // A small model without fused layers: the weight gradient of layer l only needs d_l, so those of the layers above
+  // the first go to the side stream as soon as d_l is there and run beside the data gradients further down.
+  const bool overlap = side != nullptr && lay.overlap_wgrad && fuse == nullptr && d_in == nullptr && L >= 2;
+  auto fork_wgrad = [&](int l) -> hipError_t {        // d_l, Rd_l were just enqueued on s
+    if ((e = hipEventRecord(side->fork[l], s)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(side->s, side->fork[l], 0)) != hipSuccess) return e;
+    return weight_gradient(l, side->s);
+  };
+  if (overlap && fork_wgrad(L) != hipSuccess) return DW_ERR_HIP;
   // The data gradients, output layer first.  A fused weight gradient overwrites W_l, which the data gradient
   // through W_l reads, so all data gradients are launched before the weight gradients.
   // (down to the first layer only when the caller wants the gradient with respect to the input)
@@ -214,10 +224,15 @@ int run_network(const dw_config& cfg, char* ws, const Layout& lay, const void* d
       a.part_stride = (int64_t)B * a.ldc; a.part_b = nullptr;
     }
     if ((e = gemm(a)) != hipSuccess) return DW_ERR_HIP;
+    if (overlap && l - 1 >= 2 && fork_wgrad(l - 1) != hipSuccess) return DW_ERR_HIP;
   }
-  // weight gradients
-  for (int l = L; l >= 1; --l)
-    if ((e = weight_gradient(l)) != hipSuccess) return DW_ERR_HIP;
+  // weight gradients (with the side stream: only the first layer's is left; then the caller's stream waits for the others)
+  for (int l = overlap ? 1 : L; l >= 1; --l)
+    if ((e = weight_gradient(l, s)) != hipSuccess) return DW_ERR_HIP;
+  if (overlap) {
+    if ((e = hipEventRecord(side->join, side->s)) != hipSuccess) return DW_ERR_HIP;
+    if ((e = hipStreamWaitEvent(s, side->join, 0)) != hipSuccess) return DW_ERR_HIP;
+  }
   return DW_OK;
 }
 

@@ -119,7 +119,8 @@ typedef struct {
                                        position t*n + j of its stream; the network runs once per probe and
                                        dw_worker_step takes no caller-supplied z.  With fuse_update = 1 the
                                        weight-gradient kernels keep the running sum of z_j*(Hz_j) of their
-                                       layers and the last probe's applies the update.                         */
+                                       layers and the last probe's applies the update; with two probes in
+                                       DW_BF16 one launch per layer multiplies for both probes instead.         */
   int32_t fuse_update;              /* 0: g and Hz of the last dw_worker_step stay readable (DW_S_G, DW_S_HZ).
                                        1: the library may apply the update of a weight matrix inside the kernel
                                           that produces its gradient; the W-parts of g and Hz of such layers are

@@ -158,8 +158,7 @@ int validate(const dw_config* c, Layout* lay) {
     const int64_t B = c->batch;
     for (int j = 0; j < lay->n_conv; ++j) {
       const size_t M = (size_t)B * lay->cH[j + 1] * lay->cW[j + 1];
-      lay->cP[j] = take((size_t)k * M * lay->cK[j] * 4);
-      if (j > 0) lay->cRP[j] = take((size_t)k * M * lay->cK[j] * 4);
+      if (j == 0) lay->cP[j] = take((size_t)k * M * lay->cK[j] * 4);   // (the later convolutions read the map itself)
       const size_t out = (size_t)k * M * lay->cC[j + 1] * 4;
       lay->cA[j] = take(out); lay->cRA[j] = take(out); lay->cD[j] = take(out); lay->cRD[j] = take(out);
     }

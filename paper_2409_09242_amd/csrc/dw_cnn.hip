@@ -10,8 +10,13 @@
 //   data grad    dP = D W,                RdP = RD W + D V,   then summed back onto the map ("col2im")
 // are the three products of Section IV-B's Hessian-vector product with B*(H-2)*(W-2) rows instead of B.  ReLU and
 // max-pool pass the directional derivative through their selections (their curvature is zero almost everywhere).
-// This file holds the data movement around those products (patch extraction, its adjoint, pooling and its
-// adjoint, the 3x3 window mean of the Hutchinson estimate) and the order of the launches.
+// Only the first convolution (one input channel in the paper's model: 9 columns) has its patch matrix in memory.
+// The others read the map itself: the GEMM's loader takes the patch matrix as a view of the map (OperandView), and
+// the data gradient is the same product written from the input positions' side, dA = sum over taps of the shifted
+// gradient map times W's tap, so that the nine contributions of a map entry are added inside the contraction and
+// no patch-shaped gradient is ever stored.
+// This file holds the data movement around those products (patch extraction for the first convolution, pooling and
+// its adjoint, the 3x3 window mean of the Hutchinson estimate) and the order of the launches.
 #include "dw_internal.h"
 
 namespace dw {
@@ -56,40 +61,6 @@ __global__ __launch_bounds__(256) void im2col3x3_kernel(const float* in, const f
       P[dst] = v[0];
       if (RP) RP[dst] = rv[0];
     }
-  }
-}
-
-// adjoint of the patch extraction, followed by the ReLU mask of the map the patches were cut from: one thread per
-// four consecutive channels of a map entry (the convolutions below the first have C % 4 == 0), summing the (up to
-// nine) patch entries that were copied from them
-__global__ __launch_bounds__(256) void col2im3x3_kernel(const float* dP, const float* RdP, const float* act, float* D,
-                                                        float* RD, int B, int H, int W, int C, int K, uint64_t active_mask) {
-  const int worker = blockIdx.y;
-  if (!((active_mask >> worker) & 1ull)) return;
-  const int Ho = H - 2, Wo = W - 2, C4 = C / 4;
-  const int64_t total = (int64_t)B * H * W * C, groups = total / 4, p_w = (int64_t)B * Ho * Wo * K;
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < groups; e += (int64_t)gridDim.x * 256) {
-    const int ci = (int)(e % C4) * 4;
-    const int x = (int)((e / C4) % W), y = (int)((e / ((int64_t)C4 * W)) % H);
-    const int64_t b = e / ((int64_t)C4 * W * H);
-    float4 s = make_float4(0.f, 0.f, 0.f, 0.f), rs = s;
-    for (int dy = 0; dy < 3; ++dy) {
-      const int oy = y - dy;
-      if (oy < 0 || oy >= Ho) continue;
-      for (int dx = 0; dx < 3; ++dx) {
-        const int ox = x - dx;
-        if (ox < 0 || ox >= Wo) continue;
-        const int64_t src = worker * p_w + ((b * Ho + oy) * Wo + ox) * K + (dy * 3 + dx) * C + ci;
-        const float4 t = *reinterpret_cast<const float4*>(dP + src), r = *reinterpret_cast<const float4*>(RdP + src);
-        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
-        rs.x += r.x; rs.y += r.y; rs.z += r.z; rs.w += r.w;
-      }
-    }
-    const float4 a = *reinterpret_cast<const float4*>(act + worker * total + e * 4);
-    *reinterpret_cast<float4*>(D + worker * total + e * 4) =
-        make_float4(a.x > 0.f ? s.x : 0.f, a.y > 0.f ? s.y : 0.f, a.z > 0.f ? s.z : 0.f, a.w > 0.f ? s.w : 0.f);
-    *reinterpret_cast<float4*>(RD + worker * total + e * 4) =
-        make_float4(a.x > 0.f ? rs.x : 0.f, a.y > 0.f ? rs.y : 0.f, a.z > 0.f ? rs.z : 0.f, a.w > 0.f ? rs.w : 0.f);
   }
 }
 
@@ -193,21 +164,25 @@ int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const voi
     const float* in = j == 0 ? reinterpret_cast<const float*>(d_x) : f(lay.cA[j - 1]);
     const float* rin = j == 0 ? nullptr : f(lay.cRA[j - 1]);
     const int64_t M = rows(j);
-    {
+    const int64_t in_stride = (int64_t)B * lay.cH[j] * lay.cW[j] * lay.cC[j];
+    if (j == 0) {
       KernelScope ks(KC_GEMM_FWD, s);
       if (lay.cC[j] % 4 == 0)
         hipLaunchKernelGGL(im2col3x3_kernel<4>, dim3(blocks_for(M * lay.cK[j] / 4), (unsigned)k), dim3(256), 0, s, in, rin,
-                           f(lay.cP[j]), j == 0 ? nullptr : f(lay.cRP[j]), B, lay.cH[j], lay.cW[j], lay.cC[j], lay.cK[j],
-                           active);
+                           f(lay.cP[j]), nullptr, B, lay.cH[j], lay.cW[j], lay.cC[j], lay.cK[j], active);
       else
         hipLaunchKernelGGL(im2col3x3_kernel<1>, dim3(blocks_for(M * lay.cK[j]), (unsigned)k), dim3(256), 0, s, in, rin,
-                           f(lay.cP[j]), j == 0 ? nullptr : f(lay.cRP[j]), B, lay.cH[j], lay.cW[j], lay.cC[j], lay.cK[j],
-                           active);
+                           f(lay.cP[j]), nullptr, B, lay.cH[j], lay.cW[j], lay.cC[j], lay.cK[j], active);
       if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
     }
     GemmArgs a{};
-    a.X = f(lay.cP[j]); a.RX = j == 0 ? nullptr : f(lay.cRP[j]); a.x_wstride = M * lay.cK[j]; a.x_kcontig = 1;
-    a.ldx = lay.cK[j];
+    if (j == 0) {
+      a.X = f(lay.cP[j]); a.RX = nullptr; a.x_wstride = M * lay.cK[j];
+    } else {                                             // the patches of the map below, read in place
+      a.X = in; a.RX = rin; a.x_wstride = in_stride; a.x_view = VIEW_PATCH;
+      a.cv.H = lay.cH[j]; a.cv.W = lay.cW[j]; a.cv.C = lay.cC[j];
+    }
+    a.x_kcontig = 1; a.ldx = lay.cK[j];
     a.Y = theta + lay.cwoff[j]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 1; a.ldy = lay.cK[j];
     a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.cwoff[j]; a.zb_off = lay.cboff[j];
     a.M = (int)M; a.N = lay.cC[j + 1]; a.K = lay.cK[j];
@@ -239,15 +214,21 @@ int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const voi
                        lay.cH[nc], lay.cW[nc], lay.cC[nc], active);
     if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
   }
-  // back through the convolutions: weight gradient first (it reads the patches), then the data gradient into the
-  // patch buffers and from there onto the map below
+  // back through the convolutions: weight gradient (contraction over all output positions of the minibatch), then
+  // the data gradient onto the map below with that map's ReLU mask
   for (int j = nc - 1; j >= 0; --j) {
     const int64_t M = rows(j);
+    const int64_t in_stride = (int64_t)B * lay.cH[j] * lay.cW[j] * lay.cC[j];
     {
       GemmArgs a{};
       a.X = f(lay.cD[j]); a.RX = f(lay.cRD[j]); a.x_wstride = M * lay.cC[j + 1]; a.x_kcontig = 0; a.ldx = lay.cC[j + 1];
-      a.Y = f(lay.cP[j]); a.RY = j == 0 ? nullptr : f(lay.cRP[j]); a.ry_bits = 0; a.y_wstride = M * lay.cK[j];
-      a.y_kcontig = 0; a.ldy = lay.cK[j];
+      if (j == 0) {
+        a.Y = f(lay.cP[j]); a.RY = nullptr; a.y_wstride = M * lay.cK[j];
+      } else {
+        a.Y = f(lay.cA[j - 1]); a.RY = f(lay.cRA[j - 1]); a.y_wstride = in_stride; a.y_view = VIEW_PATCH;
+        a.cv.H = lay.cH[j]; a.cv.W = lay.cW[j]; a.cv.C = lay.cC[j];
+      }
+      a.ry_bits = 0; a.y_kcontig = 0; a.ldy = lay.cK[j];
       a.zbits = zbits; a.z_stride = z_stride;
       a.M = lay.cC[j + 1]; a.N = lay.cK[j]; a.K = (int)M;
       a.C = g + lay.cwoff[j]; a.RC = hz + lay.cwoff[j]; a.ldc = lay.cK[j]; a.c_wstride = lay.Pp;
@@ -261,22 +242,18 @@ int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const voi
     }
     if (j == 0) break;
     {
+      // dA[q][ci] = sum over (tap, co) of D[q - tap][co] * W[co][tap][ci] for every position q of the map below
       GemmArgs a{};
-      a.X = f(lay.cD[j]); a.RX = f(lay.cRD[j]); a.x_wstride = M * lay.cC[j + 1]; a.x_kcontig = 1; a.ldx = lay.cC[j + 1];
-      a.Y = theta + lay.cwoff[j]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0; a.ldy = lay.cK[j];
+      a.X = f(lay.cD[j]); a.RX = f(lay.cRD[j]); a.x_wstride = M * lay.cC[j + 1]; a.x_kcontig = 1; a.x_view = VIEW_SHIFTED;
+      a.Y = theta + lay.cwoff[j]; a.RY = nullptr; a.ry_bits = 1; a.y_wstride = lay.Pp; a.y_kcontig = 0; a.y_view = VIEW_TAPS;
+      a.cv.H = lay.cH[j]; a.cv.W = lay.cW[j]; a.cv.C = lay.cC[j + 1]; a.cv.Cin = lay.cC[j];
+      a.ldx = lay.cC[j + 1]; a.ldy = lay.cC[j];
       a.zbits = zbits; a.z_stride = z_stride; a.z_off = lay.cwoff[j];
-      a.M = (int)M; a.N = lay.cK[j]; a.K = lay.cC[j + 1];
-      a.C = f(lay.cP[j]); a.RC = f(lay.cRP[j]); a.ldc = lay.cK[j]; a.c_wstride = M * lay.cK[j];
-      a.epi = EPI_PLAIN; a.k = k; a.active_mask = active;
+      a.M = (int)((int64_t)B * lay.cH[j] * lay.cW[j]); a.N = lay.cC[j]; a.K = 9 * lay.cC[j + 1];
+      a.C = f(lay.cD[j - 1]); a.RC = f(lay.cRD[j - 1]); a.ldc = lay.cC[j]; a.c_wstride = in_stride;
+      a.mask_src = f(lay.cA[j - 1]); a.ld_mask = lay.cC[j]; a.mask_wstride = in_stride;
+      a.epi = EPI_MASK; a.k = k; a.active_mask = active;
       if ((e = launch_gemm_f32(a, s)) != hipSuccess) return DW_ERR_HIP;
-    }
-    {
-      KernelScope ks(KC_GEMM_DGRAD, s);
-      const int64_t total = (int64_t)B * lay.cH[j] * lay.cW[j] * lay.cC[j];
-      hipLaunchKernelGGL(col2im3x3_kernel, dim3(blocks_for(total / 4), (unsigned)k), dim3(256), 0, s, f(lay.cP[j]),
-                         f(lay.cRP[j]), f(lay.cA[j - 1]), f(lay.cD[j - 1]), f(lay.cRD[j - 1]), B, lay.cH[j], lay.cW[j],
-                         lay.cC[j], lay.cK[j], active);
-      if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
     }
   }
   return DW_OK;

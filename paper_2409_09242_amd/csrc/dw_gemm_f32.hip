@@ -40,29 +40,55 @@ struct TileLoader {
     else    { kk = idx / (ROWS / 4); r = (idx % (ROWS / 4)) * 4; }  // 4 consecutive r at one kk
   }
 
-  template <bool KC>
+  // Element offset of the float4 at row `row` (non-contraction index), contraction index `kq` of the operand, and
+  // whether it exists: a matrix in memory (ld), or a view of a map (see OperandView)
+  template <bool KC, int VIEW>
+  __device__ static __forceinline__ int64_t offset(int row, int kq, int ld, const ConvView& cv, bool& ok) {
+    if (VIEW == VIEW_NONE) return KC ? (int64_t)row * ld + kq : (int64_t)kq * ld + row;
+    // the operand's own (row, column) whichever of them the product contracts
+    const int mrow = KC ? row : kq, col = KC ? kq : row;
+    if (VIEW == VIEW_PATCH) {
+      const int Wo = cv.W - 2, Ho = cv.H - 2;
+      const int x = mrow % Wo, t = mrow / Wo, y = t % Ho, b = t / Ho;
+      const int tap = col / cv.C, ci = col - tap * cv.C, dy = tap / 3, dx = tap - dy * 3;
+      return (((int64_t)b * cv.H + (y + dy)) * cv.W + (x + dx)) * cv.C + ci;
+    }
+    if (VIEW == VIEW_SHIFTED) {
+      const int Wo = cv.W - 2, Ho = cv.H - 2;
+      const int xx = mrow % cv.W, t = mrow / cv.W, yy = t % cv.H, b = t / cv.H;
+      const int tap = col / cv.C, co = col - tap * cv.C, dy = tap / 3, dx = tap - dy * 3;
+      const int y = yy - dy, x = xx - dx;
+      ok = ok && y >= 0 && y < Ho && x >= 0 && x < Wo;
+      return (((int64_t)b * Ho + y) * Wo + x) * cv.C + co;
+    }
+    // VIEW_TAPS: operand row = tap*C + co (the contraction index of the data gradient), column = ci
+    const int tap = mrow / cv.C, co = mrow - tap * cv.C;
+    return (int64_t)co * (9 * cv.Cin) + tap * cv.Cin + col;
+  }
+
+  template <bool KC, int VIEW = VIEW_NONE>
   __device__ static __forceinline__ void load(const float* __restrict__ src, int ld, int r0, int k0, int R, int K,
-                                              float4 (&reg)[NL]) {
+                                              float4 (&reg)[NL], const ConvView& cv = ConvView{}) {
 #pragma unroll
     for (int it = 0; it < NL; ++it) {
       const int idx = it * NT + (int)threadIdx.x;
       int r, kk; pos<KC>(idx, r, kk);
-      const bool ok = idx < CNT && (r0 + r) < R && (k0 + kk) < K;
-      const int64_t off = KC ? (int64_t)(r0 + r) * ld + (k0 + kk) : (int64_t)(k0 + kk) * ld + (r0 + r);
+      bool ok = idx < CNT && (r0 + r) < R && (k0 + kk) < K;
+      const int64_t off = ok ? offset<KC, VIEW>(r0 + r, k0 + kk, ld, cv, ok) : 0;
       reg[it] = ok ? *reinterpret_cast<const float4*>(src + off) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   }
 
   // sign bits of the four elements that load<KC> would read (0 when out of range)
-  template <bool KC>
+  template <bool KC, int VIEW = VIEW_NONE>
   __device__ static __forceinline__ void load_bits(const uint32_t* __restrict__ zb, int64_t z_off, int ld, int r0,
-                                                   int k0, int R, int K, uint32_t (&reg)[NL]) {
+                                                   int k0, int R, int K, uint32_t (&reg)[NL], const ConvView& cv = ConvView{}) {
 #pragma unroll
     for (int it = 0; it < NL; ++it) {
       const int idx = it * NT + (int)threadIdx.x;
       int r, kk; pos<KC>(idx, r, kk);
-      const bool ok = idx < CNT && (r0 + r) < R && (k0 + kk) < K;
-      const int64_t off = z_off + (KC ? (int64_t)(r0 + r) * ld + (k0 + kk) : (int64_t)(k0 + kk) * ld + (r0 + r));
+      bool ok = idx < CNT && (r0 + r) < R && (k0 + kk) < K;
+      const int64_t off = z_off + (ok ? offset<KC, VIEW>(r0 + r, k0 + kk, ld, cv, ok) : 0);
       reg[it] = ok ? (zb[off >> 5] >> (off & 31)) & 0xFu : 0u;
     }
   }
@@ -104,7 +130,9 @@ struct TileLoader {
   }
 };
 
-template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0>
+// XV, YV: OperandView of X/RX and of Y/RY (convolutions without a patch matrix in memory)
+template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0, int XV = VIEW_NONE,
+          int YV = VIEW_NONE>
 __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
   static_assert(WM * WN == 4, "four waves per block");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -152,11 +180,11 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
   const int nkt = kend > kbeg ? (kend - kbeg + BK - 1) / BK : 0;
   auto fetch = [&](int kt) {
     const int k0 = kbeg + kt * BK;
-    LX::template load<X_KC>(X, a.ldx, row0, k0, a.M, kend, xr);
-    if (HAS_RX) LX::template load<X_KC>(RX, a.ldx, row0, k0, a.M, kend, rxr);
-    LY::template load<Y_KC>(Y, a.ldy, col0, k0, a.N, kend, yr);
-    if (RYM == RY_MEM) LY::template load<Y_KC>(RY, a.ldy, col0, k0, a.N, kend, ryr);
-    if (RYM == RY_BITS) LY::template load_bits<Y_KC>(zb, a.z_off, a.ldy, col0, k0, a.N, kend, zr);
+    LX::template load<X_KC, XV>(X, a.ldx, row0, k0, a.M, kend, xr, a.cv);
+    if (HAS_RX) LX::template load<X_KC, XV>(RX, a.ldx, row0, k0, a.M, kend, rxr, a.cv);
+    LY::template load<Y_KC, YV>(Y, a.ldy, col0, k0, a.N, kend, yr, a.cv);
+    if (RYM == RY_MEM) LY::template load<Y_KC, YV>(RY, a.ldy, col0, k0, a.N, kend, ryr, a.cv);
+    if (RYM == RY_BITS) LY::template load_bits<Y_KC, YV>(zb, a.z_off, a.ldy, col0, k0, a.N, kend, zr, a.cv);
   };
 
   if (nkt > 0) fetch(0);
@@ -346,8 +374,21 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
   const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k), (unsigned)(sliced ? a.ksplit : 1)), block(NT);
 #define DW_LAUNCH(XKC, YKC, RX, RYM, EPI) \
   hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>), grid, block, 0, s, a)
+#define DW_LAUNCH_V(XKC, YKC, RX, RYM, EPI, XV, YV) \
+  hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, 0, XV, YV>), grid, block, 0, s, a)
   const bool rx = a.RX != nullptr;
-  if (a.epi == EPI_RELU) {                     // forward, hidden layer
+  if (a.x_view != VIEW_NONE || a.y_view != VIEW_NONE) {
+    // a convolution on a map: forward (patches as X), weight gradient (patches as Y), data gradient (the gradient
+    // map seen from the input positions as X, the taps of W in the contraction index)
+    if (a.epi == EPI_RELU && rx && a.x_view == VIEW_PATCH && a.y_view == VIEW_NONE)
+      DW_LAUNCH_V(true, true, true, RY_BITS, EPI_RELU, VIEW_PATCH, VIEW_NONE);
+    else if (a.epi == EPI_WGRAD && a.RY && a.x_view == VIEW_NONE && a.y_view == VIEW_PATCH)
+      DW_LAUNCH_V(false, false, true, RY_MEM, EPI_WGRAD, VIEW_NONE, VIEW_PATCH);
+    else if (a.epi == EPI_MASK && a.x_view == VIEW_SHIFTED && a.y_view == VIEW_TAPS)
+      DW_LAUNCH_V(true, false, true, RY_BITS, EPI_MASK, VIEW_SHIFTED, VIEW_TAPS);
+    else
+      return hipErrorInvalidValue;
+  } else if (a.epi == EPI_RELU) {              // forward, hidden layer
     if (rx) DW_LAUNCH(true, true, true, RY_BITS, EPI_RELU); else DW_LAUNCH(true, true, false, RY_BITS, EPI_RELU);
   } else if (a.epi == EPI_LINEAR) {            // forward, output layer
     if (rx) DW_LAUNCH(true, true, true, RY_BITS, EPI_LINEAR); else DW_LAUNCH(true, true, false, RY_BITS, EPI_LINEAR);
@@ -359,6 +400,7 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
     if (a.RY) DW_LAUNCH(false, false, true, RY_MEM, EPI_WGRAD); else DW_LAUNCH(false, false, true, RY_NONE, EPI_WGRAD);
   }
 #undef DW_LAUNCH
+#undef DW_LAUNCH_V
   if (sliced) {
     const int64_t n_out = (int64_t)a.M * a.ldc;
     hipLaunchKernelGGL(sum_slices_kernel, dim3((unsigned)((n_out + 255) / 256), grid.y), dim3(256), 0, s, a);

@@ -149,6 +149,18 @@ struct FuseArgs {
 };
 
 enum GemmKind { GEMM_FWD = 0, GEMM_DGRAD = 1, GEMM_WGRAD = 2 };
+
+// An operand of the fp32 GEMM that is a view of a channels-last map instead of a matrix in memory (3 x 3 convolution,
+// stride 1, no padding, as a linear layer on patches; Section VI's model):
+//   VIEW_PATCH    the patch matrix of the map [B][H][W][C]: row m = output position (b, y, x) of the (H-2) x (W-2)
+//                 grid, column c = tap*C + ci, tap = dy*3 + dx  ->  map entry (b, y+dy, x+dx, ci)
+//   VIEW_SHIFTED  the gradient map [B][H-2][W-2][C] seen from the input positions: row q = (b, yy, xx) of the H x W
+//                 grid, column c = tap*C + co  ->  entry (b, yy-dy, xx-dx, co), zero outside the output grid
+//   VIEW_TAPS     the weight matrix W[C][9*Cin] with the taps moved to the contraction index: row k = tap*C + co,
+//                 column ci  ->  W[co][tap*Cin + ci] (the sign bits of V likewise)
+// C is a multiple of 4, so four consecutive columns are four consecutive floats of the map (of W).
+enum OperandView { VIEW_NONE = 0, VIEW_PATCH = 1, VIEW_SHIFTED = 2, VIEW_TAPS = 3 };
+struct ConvView { int H, W, C, Cin; };
 // PLAIN: a data gradient stored as it is.  WGRAD_FUSED: template instance of the fp32 kernel for EPI_WGRAD with fu.on
 enum Epilogue { EPI_RELU = 0, EPI_LINEAR = 1, EPI_MASK = 2, EPI_WGRAD = 3, EPI_PLAIN = 4, EPI_WGRAD_FUSED = 5 };
 
@@ -176,6 +188,8 @@ struct GemmArgs {
   // partial bias sums (weight gradient) to part_b + ((s*k + i)*2 + {0,1})*M; a second kernel adds the slices in order and
   // applies the epilogue (bias, ReLU) into C, RC, gb, hzb
   int ksplit; float* part; int64_t part_stride; float* part_b;
+  int x_view, y_view;                 // fp32 kernels: OperandView of X/RX and of Y/RY (and of the sign bits of V)
+  ConvView cv;
   int r_only;                         // 1: C is in memory already (an earlier probe of this minibatch); kernels may compute RC alone
   // EPI_WGRAD with fu.probe_mode == 3 (two Hutchinson probes in one kernel): the earlier probe's R-companions of X
   // and Y (laid out like RX and RY; RYp == nullptr with RY) and its sign bits (strides and offsets as zbits)
@@ -266,7 +280,7 @@ struct Layout {            // byte offsets into the workspace, all multiples of 
   int cH[DW_MAX_CONV + 1] = {0}, cW[DW_MAX_CONV + 1] = {0}, cC[DW_MAX_CONV + 1] = {0};   // maps: input, then each output
   int cK[DW_MAX_CONV] = {0};                                    // padded row length of W_j: 9*C_in rounded up to 4
   int64_t cwoff[DW_MAX_CONV] = {0}, cboff[DW_MAX_CONV] = {0};
-  size_t cP[DW_MAX_CONV] = {0}, cRP[DW_MAX_CONV] = {0};         // patches [k][M_j][K_j] and their R-companions
+  size_t cP[DW_MAX_CONV] = {0};                                 // patches [k][M_0][K_0] of the first convolution
   size_t cA[DW_MAX_CONV] = {0}, cRA[DW_MAX_CONV] = {0};         // outputs a_j, Ra_j [k][M_j][C_j]
   size_t cD[DW_MAX_CONV] = {0}, cRD[DW_MAX_CONV] = {0};         // their gradients
   int cSplit[DW_MAX_CONV] = {0};                                // slices of the weight gradient's contraction (1: none)

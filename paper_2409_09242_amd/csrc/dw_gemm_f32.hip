@@ -50,19 +50,19 @@ struct TileLoader {
     if (VIEW == VIEW_PATCH) {
       const int Wo = cv.W - 2, Ho = cv.H - 2;
       const int x = mrow % Wo, t = mrow / Wo, y = t % Ho, b = t / Ho;
-      const int tap = col / cv.C, ci = col - tap * cv.C, dy = tap / 3, dx = tap - dy * 3;
-      return (((int64_t)b * cv.H + (y + dy)) * cv.W + (x + dx)) * cv.C + ci;
+      const int tap = col / cv.Cin, ci = col - tap * cv.Cin, dy = tap / 3, dx = tap - dy * 3;
+      return (((int64_t)b * cv.H + (y + dy)) * cv.W + (x + dx)) * cv.Cin + ci;
     }
     if (VIEW == VIEW_SHIFTED) {
       const int Wo = cv.W - 2, Ho = cv.H - 2;
       const int xx = mrow % cv.W, t = mrow / cv.W, yy = t % cv.H, b = t / cv.H;
-      const int tap = col / cv.C, co = col - tap * cv.C, dy = tap / 3, dx = tap - dy * 3;
+      const int tap = col / cv.Cout, co = col - tap * cv.Cout, dy = tap / 3, dx = tap - dy * 3;
       const int y = yy - dy, x = xx - dx;
       ok = ok && y >= 0 && y < Ho && x >= 0 && x < Wo;
-      return (((int64_t)b * Ho + y) * Wo + x) * cv.C + co;
+      return (((int64_t)b * Ho + y) * Wo + x) * cv.Cout + co;
     }
-    // VIEW_TAPS: operand row = tap*C + co (the contraction index of the data gradient), column = ci
-    const int tap = mrow / cv.C, co = mrow - tap * cv.C;
+    // VIEW_TAPS: operand row = tap*Cout + co (the contraction index of the data gradient), column = ci
+    const int tap = mrow / cv.Cout, co = mrow - tap * cv.Cout;
     return (int64_t)co * (9 * cv.Cin) + tap * cv.Cin + col;
   }
 
@@ -386,6 +386,7 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
       DW_LAUNCH_V(false, false, true, RY_MEM, EPI_WGRAD, VIEW_NONE, VIEW_PATCH);
     else if (a.epi == EPI_MASK && a.x_view == VIEW_SHIFTED && a.y_view == VIEW_TAPS)
       DW_LAUNCH_V(true, false, true, RY_BITS, EPI_MASK, VIEW_SHIFTED, VIEW_TAPS);
+
     else
       return hipErrorInvalidValue;
   } else if (a.epi == EPI_RELU) {              // forward, hidden layer

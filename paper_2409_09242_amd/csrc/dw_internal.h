@@ -152,15 +152,15 @@ enum GemmKind { GEMM_FWD = 0, GEMM_DGRAD = 1, GEMM_WGRAD = 2 };
 
 // An operand of the fp32 GEMM that is a view of a channels-last map instead of a matrix in memory (3 x 3 convolution,
 // stride 1, no padding, as a linear layer on patches; Section VI's model):
-//   VIEW_PATCH    the patch matrix of the map [B][H][W][C]: row m = output position (b, y, x) of the (H-2) x (W-2)
-//                 grid, column c = tap*C + ci, tap = dy*3 + dx  ->  map entry (b, y+dy, x+dx, ci)
-//   VIEW_SHIFTED  the gradient map [B][H-2][W-2][C] seen from the input positions: row q = (b, yy, xx) of the H x W
-//                 grid, column c = tap*C + co  ->  entry (b, yy-dy, xx-dx, co), zero outside the output grid
-//   VIEW_TAPS     the weight matrix W[C][9*Cin] with the taps moved to the contraction index: row k = tap*C + co,
+//   VIEW_PATCH    the patch matrix of the input map [B][H][W][Cin]: row m = output position (b, y, x) of the
+//                 (H-2) x (W-2) grid, column c = tap*Cin + ci, tap = dy*3 + dx  ->  map entry (b, y+dy, x+dx, ci)
+//   VIEW_SHIFTED  the gradient map [B][H-2][W-2][Cout] seen from the input positions: row q = (b, yy, xx) of the
+//                 H x W grid, column c = tap*Cout + co  ->  entry (b, yy-dy, xx-dx, co), zero outside the output grid
+//   VIEW_TAPS     the weight matrix W[Cout][9*Cin] with the taps moved to the contraction index: row k = tap*Cout + co,
 //                 column ci  ->  W[co][tap*Cin + ci] (the sign bits of V likewise)
-// C is a multiple of 4, so four consecutive columns are four consecutive floats of the map (of W).
+// Channel counts are multiples of 4, so four consecutive columns are four consecutive floats of the map (of W).
 enum OperandView { VIEW_NONE = 0, VIEW_PATCH = 1, VIEW_SHIFTED = 2, VIEW_TAPS = 3 };
-struct ConvView { int H, W, C, Cin; };
+struct ConvView { int H, W, Cin, Cout; };   // the convolution's input map and channel counts (its output map is (H-2) x (W-2) x Cout)
 // PLAIN: a data gradient stored as it is.  WGRAD_FUSED: template instance of the fp32 kernel for EPI_WGRAD with fu.on
 enum Epilogue { EPI_RELU = 0, EPI_LINEAR = 1, EPI_MASK = 2, EPI_WGRAD = 3, EPI_PLAIN = 4, EPI_WGRAD_FUSED = 5 };
 

@@ -449,7 +449,7 @@ hipError_t launch_gemm_f32(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 32) return launch_shape<32, 128, 1, 4>(a, s);
   if (a.N <= 64 && (int64_t)((a.M + 127) / 128) * a.k >= 512) return launch_shape<128, 64, 2, 2>(a, s);   // many rows, few columns
   const int64_t big_tiles = (int64_t)((a.M + 127) / 128) * ((a.N + 127) / 128) * a.k;
-  if (big_tiles >= 512) return launch_shape<128, 128, 2, 2>(a, s);
+  if (big_tiles >= 512 && a.M > 64 && a.N > 64) return launch_shape<128, 128, 2, 2>(a, s);   // (a 128-wide tile on 64 rows is half empty)
   return launch_shape<64, 64, 2, 2>(a, s);
 }
 

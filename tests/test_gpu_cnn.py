@@ -19,6 +19,9 @@ SPECS = {
     "two_conv": (OC.CnnSpec(img=(10, 10, 1), conv=(4, 8), fc=(16, 10)), 6, 3),
     "one_conv_rgb": (OC.CnnSpec(img=(12, 8, 3), conv=(8,), fc=(12, 5)), 5, 2),
     "paper_shape": (OC.CnnSpec(img=(28, 28, 1), conv=(32, 64), fc=(128, 10)), 16, 2),
+    # maps that are not square and channel counts that are not powers of two (the second convolution reads its patches
+    # in place and takes its data gradient as a sum over taps)
+    "two_conv_odd": (OC.CnnSpec(img=(14, 12, 2), conv=(12, 20), fc=(24, 7)), 5, 2),
 }
 
 

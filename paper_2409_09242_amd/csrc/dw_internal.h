@@ -199,6 +199,9 @@ struct GemmArgs {
   uint64_t active_mask;
 };
 
+// The argument structs travel by value in the kernel-argument segment (4 KB at most)
+static_assert(sizeof(GemmArgs) <= 4096 && sizeof(UpdateArgs) <= 4096, "kernel arguments must fit the kernel-argument segment");
+
 // The GEMM grids cover the active workers only: block group j works for the j-th set bit of active_mask.
 __host__ __device__ inline int active_count(uint64_t mask, int k) {
   const uint64_t low = k >= 64 ? ~0ull : ((1ull << k) - 1ull);

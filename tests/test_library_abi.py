@@ -98,6 +98,24 @@ def test_fused_update_is_an_option_of_large_layers_only():
             assert fused == plain
 
 
+def test_two_probes_with_fused_bf16_layers_keep_the_earlier_probe():
+    """n_samples = 2 in bf16 with fused layers: the fused weight-gradient kernels take both probes in one launch, so the
+    workspace holds the earlier probe's sign bits and its Ra_l, Rd_l of the hidden layers next to the later probe's.
+    Three probes (running sum through memory) and the unfused handle have no such buffers."""
+    lib = B.lib()
+    w = W.C4
+
+    def size(**kw):
+        return lib.dw_workspace_bytes(C.byref(B.config_from_workload(w, **kw)))
+
+    def up(n, a):
+        return (n + a - 1) // a * a
+    z_bytes = w.k * up(2 * ((w.P + 63) // 64), 64) * 4
+    hidden = sum(2 * up(w.k * w.batch * d * 2, 256) for d in w.dims[1:-1])
+    assert size(n_samples=2, fuse_update=1) - size(n_samples=3, fuse_update=1) == up(z_bytes, 256) + hidden
+    assert size(n_samples=2) == size(n_samples=3)
+
+
 def test_participation_schedules():
     """Host-side recipes of the failure patterns (Section VI: communication suppressed, here per round)."""
     w = W.scaled(W.C2, k=6, stale="third", seed=4)

@@ -65,45 +65,53 @@ __global__ __launch_bounds__(256) void im2col3x3_kernel(const float* in, const f
 }
 
 // 2x2 max-pool of a map and the same selection applied to its R-companion; which[...] = 0..3 in the order
-// (0,0), (0,1), (1,0), (1,1), the first one on ties
+// (0,0), (0,1), (1,0), (1,1), the first one on ties; one thread per four consecutive channels of a pooled entry
 __global__ __launch_bounds__(256) void maxpool2_kernel(const float* A, const float* RA, float* Pm, float* RPm,
                                                        uint8_t* which, int B, int H, int W, int C, uint64_t active_mask) {
   const int worker = blockIdx.y;
   if (!((active_mask >> worker) & 1ull)) return;
-  const int Hp = H / 2, Wp = W / 2;
-  const int64_t total = (int64_t)B * Hp * Wp * C, a_w = (int64_t)B * H * W * C;
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-    const int c = (int)(e % C);
-    const int j = (int)((e / C) % Wp), i = (int)((e / ((int64_t)C * Wp)) % Hp);
-    const int64_t b = e / ((int64_t)C * Wp * Hp);
-    float best = 0.f, rbest = 0.f;
-    int sel = 0;
+  const int Hp = H / 2, Wp = W / 2, C4 = C / 4;
+  const int64_t total = (int64_t)B * Hp * Wp * C, groups = total / 4, a_w = (int64_t)B * H * W * C;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < groups; e += (int64_t)gridDim.x * 256) {
+    const int c = (int)(e % C4) * 4;
+    const int j = (int)((e / C4) % Wp), i = (int)((e / ((int64_t)C4 * Wp)) % Hp);
+    const int64_t b = e / ((int64_t)C4 * Wp * Hp);
+    float best[4] = {0.f, 0.f, 0.f, 0.f}, rbest[4] = {0.f, 0.f, 0.f, 0.f};
+    uint32_t sel[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int64_t src = ((b * H + (2 * i + (q >> 1))) * W + (2 * j + (q & 1))) * C + c;
-      const float v = A[worker * a_w + src];
-      if (q == 0 || v > best) { best = v; rbest = RA[worker * a_w + src]; sel = q; }
+      const int64_t src = worker * a_w + ((b * H + (2 * i + (q >> 1))) * W + (2 * j + (q & 1))) * C + c;
+      const float4 v4 = *reinterpret_cast<const float4*>(A + src), r4 = *reinterpret_cast<const float4*>(RA + src);
+      const float v[4] = {v4.x, v4.y, v4.z, v4.w}, r[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        if (q == 0 || v[t] > best[t]) { best[t] = v[t]; rbest[t] = r[t]; sel[t] = (uint32_t)q; }
     }
-    Pm[worker * total + e] = best;
-    RPm[worker * total + e] = rbest;
-    which[worker * total + e] = (uint8_t)sel;
+    *reinterpret_cast<float4*>(Pm + worker * total + e * 4) = make_float4(best[0], best[1], best[2], best[3]);
+    *reinterpret_cast<float4*>(RPm + worker * total + e * 4) = make_float4(rbest[0], rbest[1], rbest[2], rbest[3]);
+    *reinterpret_cast<uint32_t*>(which + worker * total + e * 4) = sel[0] | (sel[1] << 8) | (sel[2] << 16) | (sel[3] << 24);
   }
 }
 
-// adjoint of the pooling: the gradient of a pooled entry goes to the input that was selected, zero to the others
+// adjoint of the pooling: the gradient of a pooled entry goes to the input that was selected, zero to the others;
+// one thread per four consecutive channels of a map entry (channel counts are multiples of 4)
 __global__ __launch_bounds__(256) void unpool2_kernel(const float* dPm, const float* RdPm, const uint8_t* which, float* D,
                                                       float* RD, int B, int H, int W, int C, uint64_t active_mask) {
   const int worker = blockIdx.y;
   if (!((active_mask >> worker) & 1ull)) return;
-  const int Hp = H / 2, Wp = W / 2;
-  const int64_t total = (int64_t)B * H * W * C, p_w = (int64_t)B * Hp * Wp * C;
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-    const int c = (int)(e % C);
-    const int x = (int)((e / C) % W), y = (int)((e / ((int64_t)C * W)) % H);
-    const int64_t b = e / ((int64_t)C * W * H);
-    const int64_t src = ((b * Hp + (y >> 1)) * Wp + (x >> 1)) * C + c;
-    const bool mine = which[worker * p_w + src] == (uint8_t)((y & 1) * 2 + (x & 1));
-    D[worker * total + e] = mine ? dPm[worker * p_w + src] : 0.f;
-    RD[worker * total + e] = mine ? RdPm[worker * p_w + src] : 0.f;
+  const int Hp = H / 2, Wp = W / 2, C4 = C / 4;
+  const int64_t total = (int64_t)B * H * W * C, groups = total / 4, p_w = (int64_t)B * Hp * Wp * C;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < groups; e += (int64_t)gridDim.x * 256) {
+    const int c = (int)(e % C4) * 4;
+    const int x = (int)((e / C4) % W), y = (int)((e / ((int64_t)C4 * W)) % H);
+    const int64_t b = e / ((int64_t)C4 * W * H);
+    const int64_t src = worker * p_w + ((b * Hp + (y >> 1)) * Wp + (x >> 1)) * C + c;
+    const uint32_t w4 = *reinterpret_cast<const uint32_t*>(which + src);       // the selections of the four channels
+    const uint32_t mine = (uint32_t)((y & 1) * 2 + (x & 1));
+    const float4 d = *reinterpret_cast<const float4*>(dPm + src), rd = *reinterpret_cast<const float4*>(RdPm + src);
+    const bool m0 = (w4 & 0xFFu) == mine, m1 = ((w4 >> 8) & 0xFFu) == mine, m2 = ((w4 >> 16) & 0xFFu) == mine, m3 = (w4 >> 24) == mine;
+    *reinterpret_cast<float4*>(D + worker * total + e * 4) = make_float4(m0 ? d.x : 0.f, m1 ? d.y : 0.f, m2 ? d.z : 0.f, m3 ? d.w : 0.f);
+    *reinterpret_cast<float4*>(RD + worker * total + e * 4) = make_float4(m0 ? rd.x : 0.f, m1 ? rd.y : 0.f, m2 ? rd.z : 0.f, m3 ? rd.w : 0.f);
   }
 }
 
@@ -195,7 +203,7 @@ int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const voi
   {
     KernelScope ks(KC_GEMM_FWD, s);
     const int64_t total = (int64_t)B * cfg.dims[0];
-    hipLaunchKernelGGL(maxpool2_kernel, dim3(blocks_for(total), (unsigned)k), dim3(256), 0, s, f(lay.cA[nc - 1]),
+    hipLaunchKernelGGL(maxpool2_kernel, dim3(blocks_for(total / 4), (unsigned)k), dim3(256), 0, s, f(lay.cA[nc - 1]),
                        f(lay.cRA[nc - 1]), f(lay.pool), f(lay.rpool), reinterpret_cast<uint8_t*>(ws + lay.pidx), B,
                        lay.cH[nc], lay.cW[nc], lay.cC[nc], active);
     if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;
@@ -211,7 +219,7 @@ int run_network_cnn(const dw_config& cfg, char* ws, const Layout& lay, const voi
   {
     KernelScope ks(KC_GEMM_DGRAD, s);
     const int64_t total = rows(nc - 1) * lay.cC[nc];
-    hipLaunchKernelGGL(unpool2_kernel, dim3(blocks_for(total), (unsigned)k), dim3(256), 0, s, f(lay.dpool), f(lay.rdpool),
+    hipLaunchKernelGGL(unpool2_kernel, dim3(blocks_for(total / 4), (unsigned)k), dim3(256), 0, s, f(lay.dpool), f(lay.rdpool),
                        reinterpret_cast<const uint8_t*>(ws + lay.pidx), f(lay.cD[nc - 1]), f(lay.cRD[nc - 1]), B,
                        lay.cH[nc], lay.cW[nc], lay.cC[nc], active);
     if ((e = hipGetLastError()) != hipSuccess) return DW_ERR_HIP;

@@ -495,13 +495,15 @@ def _fused_against_unfused_and_oracle(dims, batch, k, bf16, avg_block, fused_lay
 
 
 @pytest.mark.parametrize("n,avg_block,bf16,large", [(2, 8, True, False), (3, 1, True, False), (2, 1, False, False),
-                                                     (3, 16, False, False), (2, 4, True, True)])
+                                                     (3, 16, False, False), (2, 4, True, True), (2, 32, True, "ragged")])
 def test_fused_update_with_several_probes_matches_the_unfused_path(n, avg_block, bf16, large):
     """Several Hutchinson probes per step with fused layers: the weight-gradient kernels keep the running sum of
     z_j * Hz_j of their layers and the last probe's applies the update.  The unfused path with the same n (checked
     against the oracle by test_several_hutchinson_probes_per_step) adds the same terms in the same order."""
     dims, batch, k = ((512, 2048, 1024, 10), 128, 8) if bf16 else ((256, 1024, 1024, 10), 64, 8)
-    if large:           # layer 2 on the large-tile kernels (R-only form in the second probe) and fused
+    if large == "ragged":   # two probes in one launch with a minibatch that ends inside a k-tile, widest averaging block
+        dims, batch, k = (512, 2048, 1024, 10), 80, 8
+    elif large:         # layer 2 on the large-tile kernels (R-only form in the second probe) and fused
         dims, batch, k = (256, 1024, 1024, 10), 512, 16
     w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=5150 + n, bf16=bf16, avg_block=avg_block)
     theta0 = W.init_theta(w.dims, w.seed)

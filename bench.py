@@ -82,18 +82,27 @@ def fused_layers(w, fuse):
 
 
 def r_only_products(w):
-    """(forward layers, data-gradient layers) whose bf16 products run on the global->LDS kernel (the library's rule:
-    whole 256-column tiles that fill the chip, contraction a multiple of 128, a hidden layer with an R-operand); with
-    several Hutchinson probes the probes after the first leave out the plain product there."""
-    if not w.bf16 or w.dims is None or w.conv:
+    """(forward layers, data-gradient layers) whose products leave out the plain part in the Hutchinson probes after the
+    first of a step (the library's rules).  bf16: the products on the global->LDS kernel (whole 256-column tiles that fill
+    the chip, contraction a multiple of 128).  fp32: the hidden layers' products whose contraction is not cut into slices
+    (at least 256 output tiles over all workers, or a contraction shorter than 128)."""
+    if w.dims is None or w.conv:
         return [], []
     d, L = w.dims, len(w.dims) - 1
+    if not w.bf16:
+        def uncut(rows, n, kk):
+            tiles = -(-rows // 128) if n <= 32 else -(-n // 128) if rows <= 32 else -(-rows // 64) * -(-n // 64)
+            split = 1024 // (tiles * w.k) if tiles * w.k < 256 else 1
+            return min(split, kk // 64, 64) <= 1
+        fwd = [l for l in range(1, L) if uncut(w.batch, d[l], d[l - 1])]
+        dgrad = [l for l in range(2, L) if uncut(w.batch, d[l - 1], d[l])]
+        return fwd, dgrad
     rows = (w.batch + 127) // 128
     off, woff = 0, {}
     for l in range(1, L + 1):
         woff[l] = off
         off += d[l] * d[l - 1] + d[l]
-    fwd = [l for l in range(2, L) if w.batch >= 128 and d[l] % 256 == 0 and d[l - 1] % 128 == 0
+    fwd = [l for l in range(1, L) if w.batch >= 128 and d[l] % 256 == 0 and d[l - 1] % 128 == 0
            and rows * (d[l] // 256) * w.k >= 256 and woff[l] % 128 == 0]
     dgrad = [l for l in range(2, L) if w.batch >= 128 and d[l - 1] % 256 == 0 and d[l] % 128 == 0
              and rows * (d[l - 1] // 256) * w.k >= 256 and woff[l] % 128 == 0]

@@ -296,6 +296,8 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
         const int64_t o = (int64_t)m * a.ldc + n;
         if (sliced) {                                 // raw partial products: the epilogue follows the sum of the slices
           C[o] = c; RC[o] = rc;
+        } else if (EPI == EPI_RELU && FM == 1) {      // a later probe: the activation is in memory, only its R-companion is new
+          RC[o] = C[o] > 0.f ? rc + cz : 0.f;
         } else if (EPI == EPI_RELU) {
           c += bias; rc += cz;
           const bool on = c > 0.f;
@@ -307,7 +309,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
         } else if (EPI == EPI_MASK) {
           const float* msk = reinterpret_cast<const float*>(a.mask_src) + (int64_t)worker * a.mask_wstride;
           const bool on = msk[(int64_t)m * a.ld_mask + n] > 0.f;
-          C[o] = on ? c : 0.f;
+          if (FM != 1) C[o] = on ? c : 0.f;           // (a later probe: the plain data gradient is in memory already)
           RC[o] = on ? rc : 0.f;
         } else {
           C[o] = c;
@@ -374,6 +376,8 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
   const dim3 grid((unsigned)tiles, (unsigned)active_count(a.active_mask, a.k), (unsigned)(sliced ? a.ksplit : 1)), block(NT);
 #define DW_LAUNCH(XKC, YKC, RX, RYM, EPI) \
   hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI>), grid, block, 0, s, a)
+#define DW_LAUNCH_R(XKC, YKC, RX, RYM, EPI) \
+  hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, 1>), grid, block, 0, s, a)
 #define DW_LAUNCH_V(XKC, YKC, RX, RYM, EPI, XV, YV) \
   hipLaunchKernelGGL((dual_gemm_f32<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, 0, XV, YV>), grid, block, 0, s, a)
   const bool rx = a.RX != nullptr;
@@ -389,6 +393,11 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
 
     else
       return hipErrorInvalidValue;
+  } else if (a.r_only && !sliced && a.epi == EPI_RELU) {
+    // a later Hutchinson probe of the same minibatch: the plain product is in memory, only the R-products are computed
+    if (rx) DW_LAUNCH_R(true, true, true, RY_BITS, EPI_RELU); else DW_LAUNCH_R(true, true, false, RY_BITS, EPI_RELU);
+  } else if (a.r_only && !sliced && a.epi == EPI_MASK) {
+    DW_LAUNCH_R(true, false, true, RY_BITS, EPI_MASK);
   } else if (a.epi == EPI_RELU) {              // forward, hidden layer
     if (rx) DW_LAUNCH(true, true, true, RY_BITS, EPI_RELU); else DW_LAUNCH(true, true, false, RY_BITS, EPI_RELU);
   } else if (a.epi == EPI_LINEAR) {            // forward, output layer
@@ -401,6 +410,7 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
     if (a.RY) DW_LAUNCH(false, false, true, RY_MEM, EPI_WGRAD); else DW_LAUNCH(false, false, true, RY_NONE, EPI_WGRAD);
   }
 #undef DW_LAUNCH
+#undef DW_LAUNCH_R
 #undef DW_LAUNCH_V
   if (sliced) {
     const int64_t n_out = (int64_t)a.M * a.ldc;

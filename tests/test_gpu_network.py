@@ -612,6 +612,8 @@ def test_bf16_fused_update_measures_distances_only_when_a_round_is_due():
     (False, 3, ((72, 96, 40, 10), 37, 3)), (False, 2, ((72, 96, 40, 10), 37, 3)), (True, 4, ((72, 96, 40, 8), 40, 3)),
     # layer 2 on the global->LDS kernels: the probes after the first run their R-only form there
     (True, 2, ((256, 1024, 1024, 10), 512, 16)),
+    # fp32 products that are not cut along the contraction: the probes after the first compute the R-parts alone
+    (False, 2, ((256, 512, 512, 10), 256, 8)),
 ])
 def test_several_hutchinson_probes_per_step(bf16, n, shape):
     dims, batch, k = shape

@@ -32,13 +32,13 @@ typedef float fu_floatx16 __attribute__((ext_vector_type(16)));
 // Hz of half a row of tiles, [16][72] each
 __host__ __device__ constexpr int fused_update_lds_floats(bool pair = false) { return pair ? 3 * 16 * 72 : 2 * 32 * 72; }
 
-// The update of one wave's tile.  init: wbase = the worker's offset in theta, m, v (and the bf16 copy); row_base,
+// The update of one wave's tile.  Constructor: wbase = the worker's offset in theta, m, v (and the bf16 copy); row_base,
 // col_base: first row and column of the wave's tile in W_l; zrow: sign bits of z from the first parameter of the W
-// block on.  prefetch: issues the loads of the first batches (state and sign bits do not depend on the product, so a
-// kernel calls it while its last multiplications run).  run: acc, racc = the wave's accumulators (plain product = g,
-// R-companion = Hz), MFMA 32x32 layout: lane holds column lane%32 of each tile, rows (r/4)*8 + (lane/32)*4 + r%4;
-// gl: the wave's LDS region; ib1, ib2: the worker's 1/(1 - beta^t).  Returns this lane's share of the squared
-// distance of the new parameters to the centre (0 unless f.dist).
+// block on.  run: acc, racc = the wave's accumulators (plain product = g, R-companion = Hz), MFMA 32x32 layout: lane
+// holds column lane%32 of each tile, rows (r/4)*8 + (lane/32)*4 + r%4; gl: the wave's LDS region; ib1, ib2: the
+// worker's 1/(1 - beta^t).  Returns this lane's share of the squared distance of the new parameters to the centre
+// (0 unless f.dist).  (Issuing the first batch's loads under the kernel's last k-tile was tried: the one-probe kernel
+// has no registers for it, the two-probe kernel gains nothing.)
 // B16: also store the bf16 copy of the new parameters.  PROBES = 1: the diagonal estimate is the mean over several
 // Hutchinson probes, D = (f.dacc + z*Hz) * f.d_scale, f.dacc holding the sum over the earlier probes.  PROBES = 2:
 // the mean over two probes, the earlier one's product in raccp and its sign bits in zrowp (both unused otherwise).
@@ -73,14 +73,6 @@ struct FusedUpdateTile {
     bt.zw = zrow[bt.e >> 5];
     if constexpr (PROBES == 1) bt.dd = nt_load4(dacc_w + bt.e);
     if constexpr (PROBES == 2) bt.zwp = zrowp[bt.e >> 5];
-  }
-
-  // loads of the first EARLY batches (EARLY < DEPTH); run<EARLY> issues the rest
-  template <int EARLY>
-  __device__ __forceinline__ void prefetch() {
-    static_assert(EARLY >= 0 && EARLY < DEPTH, "the ring holds DEPTH batches");
-#pragma unroll
-    for (int bb = 0; bb < EARLY; ++bb) load_batch(ring[bb], bb);
   }
 
   // b: the batch's place in the staged rows
@@ -141,7 +133,6 @@ struct FusedUpdateTile {
     }
   }
 
-  template <int EARLY>
   __device__ __forceinline__ float run(const fu_floatx16 (&acc)[TM][2], const fu_floatx16 (&racc)[TM][2],
                                        const fu_floatx16 (&raccp)[TM][2], float* gl, float ib1, float ib2) {
     const int l32 = lane & 31, lhalf = lane >> 5;
@@ -149,7 +140,7 @@ struct FusedUpdateTile {
     float* hlp = hl + SR * PR;                              // (two probes)
     float nsum = 0.f;
 #pragma unroll
-    for (int bb = EARLY; bb < DEPTH - 1; ++bb) load_batch(ring[bb], bb);
+    for (int bb = 0; bb < DEPTH - 1; ++bb) load_batch(ring[bb], bb);
 #pragma unroll
     for (int bb = 0; bb < NB; ++bb) {
       const int i = bb / 8, b = bb % 8;

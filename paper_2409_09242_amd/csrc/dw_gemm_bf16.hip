@@ -16,7 +16,6 @@
 //     12+i/4), which hands each lane its 4 consecutive k for one row.
 // The +-1 operand V (z reshaped like W) is expanded from the sign bits of z in the loader.
 #include <cstddef>
-#include <type_traits>
 
 #include "dw_internal.h"
 #include "dw_device_util.h"
@@ -151,12 +150,6 @@ __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int row0, int ks, in
   }
 }
 
-struct NoUpdateTile {                                       // stands in for FusedUpdateTile in kernels that do not update
-  template <class... A> __device__ __forceinline__ NoUpdateTile(A&&...) {}
-  template <int EARLY> __device__ __forceinline__ void prefetch() {}
-  template <int EARLY, class... A> __device__ __forceinline__ float run(A&&...) { return 0.f; }
-};
-
 template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0, int NTH = 512>
 __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmArgs a) {   // (two waves per SIMD either way)
   constexpr int NT = NTH;                                   // threads per block: 512, or 256 (see launch_fused_wgrad)
@@ -235,9 +228,6 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
   // launch_fused_wgrad's instances apply the update of Section IV-B to the tile (FM: 0 one Hutchinson probe; 1 a probe
   // before the last, only the running sum of z*Hz is written; 2 the last of several probes)
   constexpr bool FUSED = EPI == EPI_WGRAD && NTH == 256 && TN == 2;
-  using UpdateTile = std::conditional_t<FUSED && FM != 1, FusedUpdateTile<TM, true, FM == 2 ? 1 : 0>, NoUpdateTile>;
-  UpdateTile upd(a.fu, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0, zb + (a.z_off >> 5), nullptr, lane);
-  constexpr int EARLY = 0;      // batches of the update loaded before the main loop ends: no registers to spare here
 
   const int nkt = (a.K + BK - 1) / BK;
   auto fetch = [&](int kt) {
@@ -329,7 +319,6 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
   const bool compute_first = wave < (NT / 64) / 2;
   for (int kt = 0; kt < nkt; ++kt) {
     const int cur = kt & 1;
-    if (kt == nkt - 1) upd.template prefetch<EARLY>();       // the update's first state loads run under the last k-tile
     if (compute_first) {
       compute_tile(cur);
       move_tiles(kt, cur);
@@ -359,8 +348,11 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
     if constexpr (FM == 1)
       fused_probe_sum_wave_tile<TM>(racc, gl, f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
                                     zb + (a.z_off >> 5), lane);
-    else
-      nsum = upd.template run<EARLY>(acc, racc, racc, gl, ib1, ib2);
+    else {
+      FusedUpdateTile<TM, true, FM == 2 ? 1 : 0> upd(f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
+                                                    zb + (a.z_off >> 5), nullptr, lane);
+      nsum = upd.run(acc, racc, racc, gl, ib1, ib2);
+    }
     // squared distance of the tile's new parameters to the centre: one slot per (worker, tile)
     double ws = (double)nsum;
 #pragma unroll
@@ -547,9 +539,6 @@ __global__ __launch_bounds__(BM * 4, BM == 128 ? 1 : 2) void fused_wgrad_pair_bf
 #pragma unroll
     for (int r = 0; r < 16; ++r) { acc[0][j][r] = 0.f; raccp[0][j][r] = 0.f; racc[0][j][r] = 0.f; }
   float gb_acc = 0.f, hzb_acc = 0.f;
-  const int64_t zw0 = (int64_t)worker * a.z_stride + (a.z_off >> 5);
-  FusedUpdateTile<1, true, 2> upd(a.fu, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0, a.zbits + zw0,
-                                  a.zbits_p + zw0, lane);
 
   const int nkt = (a.K + PK - 1) / PK;
   auto fetch = [&](int kt) {
@@ -640,7 +629,10 @@ __global__ __launch_bounds__(BM * 4, BM == 128 ? 1 : 2) void fused_wgrad_pair_bf
   const karg_floats bc = (karg_floats)(ka + offsetof(GemmArgs, fu) + offsetof(FuseArgs, sc));
   const float ib1 = bc[worker], ib2 = bc[DW_MAX_K + worker];   // scalar loads from the kernel-argument block
   float* gl = reinterpret_cast<float*>(smem) + wave * fused_update_lds_floats(true);   // free after the main loop
-  const float nsum = upd.template run<0>(acc, racc, raccp, gl, ib1, ib2);
+  const int64_t zw0 = (int64_t)worker * a.z_stride + (a.z_off >> 5);
+  FusedUpdateTile<1, true, 2> upd(f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0, a.zbits + zw0,
+                                  a.zbits_p + zw0, lane);
+  const float nsum = upd.run(acc, racc, raccp, gl, ib1, ib2);
   double ws = (double)nsum;
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) ws += __shfl_xor(ws, off);

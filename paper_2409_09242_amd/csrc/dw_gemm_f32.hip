@@ -254,7 +254,7 @@ __global__ __launch_bounds__(NT) void dual_gemm_f32(GemmArgs a) {
     else {
       FusedUpdateTile<TM, false, FM == 2 ? 1 : 0> upd(f, (int64_t)worker * a.c_wstride, a.ldc, row0 + wm0, col0 + wn0,
                                                      zb + (a.z_off >> 5), nullptr, lane);
-      nsum = upd.template run<0>(acc, racc, racc, fused_lds + wave * fused_update_lds_floats(), ib1, ib2);
+      nsum = upd.run(acc, racc, racc, fused_lds + wave * fused_update_lds_floats(), ib1, ib2);
     }
     double ws = (double)nsum;
 #pragma unroll

@@ -376,7 +376,7 @@ def main():
                     help="run only the update-only HBM stress and print its figures (for profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: the simulated workers are batched on a single device and this build "
+        print("bench.py measures one GPU: the simulated workers are batched on a single device and the library "
               "has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
         return 2
 

@@ -47,13 +47,19 @@ typedef __attribute__((address_space(3))) void* lds_void;
 typedef __attribute__((address_space(3))) const char* lds_char;
 typedef __attribute__((address_space(1))) const void* glb_void;
 
-__device__ __forceinline__ uint32_t pm1_pair(uint32_t b_lo, uint32_t b_hi) {
-  return 0xBF80BF80u ^ (b_lo << 15) ^ (b_hi << 31);     // bit set -> +1 (0x3F80), clear -> -1 (0xBF80)
-}
+// eight bf16 values +-1 from the eight sign bits of b (b < 256; bit set -> +1 = 0x3F80, clear -> -1 = 0xBF80).  Two
+// values share a dword: bit 2q of b goes to bit 15 and bit 2q+1 to bit 31 by two shifts of the whole byte (no other
+// bit of b can land on 15 or 31; the compiler makes one multiply of the two), which one AND-XOR then folds into the
+// pattern of two -1.  (Measured in this loop, each against this form on one box: a form with fewer and cheaper
+// instructions, the loads' addresses as scalar base + 32-bit lane offset, and the pointer arithmetic moved into the
+// first k-step were all 2 to 5 % slower: once the vector instructions are spread over both k-steps, see `expand`,
+// their count is not what limits the loop, and the schedule is touchy.)
 __device__ __forceinline__ bf16x8 pm1_x8(uint32_t b) {
   uint4 o;
-  o.x = pm1_pair(b & 1u, (b >> 1) & 1u); o.y = pm1_pair((b >> 2) & 1u, (b >> 3) & 1u);
-  o.z = pm1_pair((b >> 4) & 1u, (b >> 5) & 1u); o.w = pm1_pair((b >> 6) & 1u, (b >> 7) & 1u);
+  o.x = 0xBF80BF80u ^ (((b << 15) | (b << 30)) & 0x80008000u);
+  o.y = 0xBF80BF80u ^ (((b << 13) | (b << 28)) & 0x80008000u);
+  o.z = 0xBF80BF80u ^ (((b << 11) | (b << 26)) & 0x80008000u);
+  o.w = 0xBF80BF80u ^ (((b << 9) | (b << 24)) & 0x80008000u);
   return __builtin_bit_cast(bf16x8, o);
 }
 
@@ -247,7 +253,14 @@ __global__ __launch_bounds__(NT) void dual_gemm_bf16_dma(GemmArgs a) {
   };
   auto expand = [&](Frags& f, int ks) {                     // V operand of k-step ks: byte ks*2 + lane/32 of the tile's word
 #pragma unroll
-    for (int j = 0; j < TN; ++j) f.ryb[j] = pm1_x8((zw[j] >> ((ks * 2 + lhalf) * 8)) & 0xFFu);
+    for (int j = 0; j < TN; ++j) {
+      f.ryb[j] = pm1_x8((zw[j] >> ((ks * 2 + lhalf) * 8)) & 0xFFu);
+      // the expansion stays where it is written: left alone, the compiler moves it down to the multiplies that use it,
+      // past the barrier, where all of a k-tile's vector arithmetic then crowds one k-step's issue slots
+      uint4 pin = __builtin_bit_cast(uint4, f.ryb[j]);
+      asm volatile("" : "+v"(pin.x), "+v"(pin.y), "+v"(pin.z), "+v"(pin.w));
+      f.ryb[j] = __builtin_bit_cast(bf16x8, pin);
+    }
   };
   auto multiply = [&](Frags& f) {
 #pragma unroll

@@ -99,10 +99,12 @@ struct Tile {
   }
   // Loads are unconditional (a unit outside the operand reads the operand's first elements instead), so the
   // prefetch is free of branches and of waits; such a unit is zeroed when it is copied into LDS.
+  // WHOLE: every unit of the tile lies inside the operand (whole tiles, a contraction of whole k-tiles): no selects
+  template <bool WHOLE = false>
   __device__ __forceinline__ void load(const uint16_t* __restrict__ src, int ld, int k0, int K, uint4 (&reg)[UPT]) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u) {
-      const int64_t o = ok(u, k0, K) ? at(u, k0, ld) : 0;
+      const int64_t o = (WHOLE || ok(u, k0, K)) ? at(u, k0, ld) : 0;
       reg[u] = *reinterpret_cast<const uint4*>(src + o);
     }
   }
@@ -115,11 +117,12 @@ struct Tile {
       reg[u] = zb[off >> 5];
     }
   }
+  template <bool WHOLE = false>
   __device__ __forceinline__ void store(uint16_t* lds, const uint4 (&reg)[UPT], int tl, int k0, int K) const {
 #pragma unroll
     for (int u = 0; u < UPT; ++u)
       if (FULL || u * NTH + tl < UNITS)
-        *reinterpret_cast<uint4*>(lds + loff(u)) = ok(u, k0, K) ? reg[u] : make_uint4(0, 0, 0, 0);
+        *reinterpret_cast<uint4*>(lds + loff(u)) = (WHOLE || ok(u, k0, K)) ? reg[u] : make_uint4(0, 0, 0, 0);
   }
   __device__ __forceinline__ void store_bits(uint16_t* lds, const uint32_t (&reg)[UPT], int tl, int64_t z_off,
                                              int k0, int ld) const {
@@ -150,7 +153,10 @@ __device__ __forceinline__ bf16x8 frag(const uint16_t* lds, int row0, int ks, in
   }
 }
 
-template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0, int NTH = 512>
+// KWHOLE (fused weight gradient): the minibatch is made of whole k-tiles, so every load and LDS store of the main loop is
+// unconditional (the tiles of a fused layer are whole anyway)
+template <int BM, int BN, int WM, int WN, bool X_KC, bool Y_KC, bool HAS_RX, int RYM, int EPI, int FM = 0, int NTH = 512,
+          bool KWHOLE = false>
 __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmArgs a) {   // (two waves per SIMD either way)
   constexpr int NT = NTH;                                   // threads per block: 512, or 256 (see launch_fused_wgrad)
   static_assert(WM * WN == NT / 64, "one wave tile per wave");
@@ -232,15 +238,15 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
   const int nkt = (a.K + BK - 1) / BK;
   auto fetch = [&](int kt) {
     const int k0 = kt * BK;
-    tx.load(xsrc, a.ldx, k0, a.K, xr);
-    ty.load(Y, a.ldy, k0, a.K, yr);
-    if (RYM == RY_MEM) ty.load(RY, a.ldy, k0, a.K, ryr);
+    tx.template load<KWHOLE>(xsrc, a.ldx, k0, a.K, xr);
+    ty.template load<KWHOLE>(Y, a.ldy, k0, a.K, yr);
+    if (RYM == RY_MEM) ty.template load<KWHOLE>(RY, a.ldy, k0, a.K, ryr);
     if (RYM == RY_BITS) ty.load_bits(zb, a.z_off, a.ldy, k0, a.K, zr);
   };
   auto stash = [&](int st, int kt) {       // kt: the k-tile held in the registers
-    tx.store(second_half ? RXs(st) : Xs(st), xr, xtl, kt * BK, a.K);
-    ty.store(Ys(st), yr, tid, kt * BK, a.K);
-    if (RYM == RY_MEM) ty.store(RYs(st), ryr, tid, kt * BK, a.K);
+    tx.template store<KWHOLE>(second_half ? RXs(st) : Xs(st), xr, xtl, kt * BK, a.K);
+    ty.template store<KWHOLE>(Ys(st), yr, tid, kt * BK, a.K);
+    if (RYM == RY_MEM) ty.template store<KWHOLE>(RYs(st), ryr, tid, kt * BK, a.K);
     if (RYM == RY_BITS) ty.store_bits(RYs(st), zr, tid, a.z_off, kt * BK, a.ldy);
   };
 
@@ -482,12 +488,12 @@ __global__ __launch_bounds__(NTH, NTH == 256 ? 2 : 1) void dual_gemm_bf16(GemmAr
 // staged once for both probes and the parameters, moments and bf16 copy are moved once, where one launch per probe
 // reads the operands twice and carries the first probe's z*Hz through memory.  Tiles of BM x 128 with BM/32 x 2 waves
 // of 32 x 64 (three accumulator sets of 32 registers), six operand tiles of PK k per stage.  Launched with BM = 128,
-// PK = 32: 8 waves, 120 KB of LDS, one block per compute unit.  Measured on a 4096 x 4096 layer of 16 workers:
-// 2.38 ms, the multiplications alone 1.36 ms (1.37 Tflop: 40 % of the matrix cores' peak; operand reads from LDS take
+// PK = 32: 8 waves, 120 KB of LDS, one block per compute unit.  KWHOLE: a minibatch of whole k-tiles, unconditional
+// loads and LDS stores in the main loop.  Measured on a 4096 x 4096 layer of 16 workers, bounds checks still in: 2.38 ms, the multiplications alone 1.36 ms (1.37 Tflop: 40 % of the matrix cores' peak; operand reads from LDS take
 // as many cycles as the MFMAs) and the update alone 1.39 ms, so the two phases of a block mostly follow each other;
 // BM = 64, PK = 16 puts two blocks of 4 waves on a unit, which do overlap, but with more LDS traffic per product the
 // launch takes 2.64 ms.
-template <bool HAS_RY, int BM, int PK>
+template <bool HAS_RY, int BM, int PK, bool KWHOLE>
 __global__ __launch_bounds__(BM * 4, BM == 128 ? 1 : 2) void fused_wgrad_pair_bf16(GemmArgs a) {
   constexpr int NT = BM * 4, BN = 128, WM = BM / 32, KS = PK / 16;
   const int tiles_m = a.M / BM, tiles_n = a.N / BN;
@@ -543,15 +549,15 @@ __global__ __launch_bounds__(BM * 4, BM == 128 ? 1 : 2) void fused_wgrad_pair_bf
   const int nkt = (a.K + PK - 1) / PK;
   auto fetch = [&](int kt) {
 #pragma unroll
-    for (int t = 0; t < 3; ++t) tx.load(xsrc[t], a.ldx, kt * PK, a.K, xr[t]);
+    for (int t = 0; t < 3; ++t) tx.template load<KWHOLE>(xsrc[t], a.ldx, kt * PK, a.K, xr[t]);
 #pragma unroll
-    for (int t = 0; t < NY; ++t) ty.load(ysrc[t], a.ldy, kt * PK, a.K, yr[t]);
+    for (int t = 0; t < NY; ++t) ty.template load<KWHOLE>(ysrc[t], a.ldy, kt * PK, a.K, yr[t]);
   };
   auto stash = [&](int st, int kt) {
 #pragma unroll
-    for (int t = 0; t < 3; ++t) tx.store(xt(st, t), xr[t], tid, kt * PK, a.K);
+    for (int t = 0; t < 3; ++t) tx.template store<KWHOLE>(xt(st, t), xr[t], tid, kt * PK, a.K);
 #pragma unroll
-    for (int t = 0; t < NY; ++t) ty.store(yt(st, t), yr[t], tid, kt * PK, a.K);
+    for (int t = 0; t < NY; ++t) ty.template store<KWHOLE>(yt(st, t), yr[t], tid, kt * PK, a.K);
   };
   struct Frags { bf16x8 x, rxp, rx, y[2], ryp[2], ry[2]; };
   auto compute_tile = [&](int cur) {
@@ -652,7 +658,7 @@ __global__ __launch_bounds__(BM * 4, BM == 128 ? 1 : 2) void fused_wgrad_pair_bf
   }
 }
 
-template <bool HAS_RY>
+template <bool HAS_RY, bool KWHOLE>
 static hipError_t launch_pair(const GemmArgs& a, hipStream_t s) {
   constexpr int BM = 128, PK = 32, NT = BM * 4;
   const int tiles = (a.M / BM) * (a.N / 128);
@@ -661,14 +667,15 @@ static hipError_t launch_pair(const GemmArgs& a, hipStream_t s) {
   constexpr int epi_b = (NT / 64) * fused_update_lds_floats(true) * 4;
   constexpr int smem = tiles_b > epi_b ? tiles_b : epi_b;
   static_assert(smem <= 160 * 1024, "LDS budget");
-  auto kern = fused_wgrad_pair_bf16<HAS_RY, BM, PK>;
+  auto kern = fused_wgrad_pair_bf16<HAS_RY, BM, PK, KWHOLE>;
   static LdsLimitOnce lds_limit;
   { const hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), smem); if (e != hipSuccess) return e; }
   hipLaunchKernelGGL(kern, grid, block, smem, s, a);
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI, int FM = 0, int NTH = 512>
+template <int BM, int BN, int WM, int WN, bool XKC, bool YKC, bool RX, int RYM, int EPI, int FM = 0, int NTH = 512,
+          bool KWHOLE = false>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   constexpr int NT = NTH;
   const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
@@ -681,7 +688,7 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
   constexpr int out_b = (EPI == EPI_RELU || EPI == EPI_MASK) ? (NT / 64) * epi_bf16_lds_bytes(BN / WN / 32) : 0;
   constexpr int smem = tiles_b > epi_b ? (tiles_b > out_b ? tiles_b : out_b) : (epi_b > out_b ? epi_b : out_b);
   static_assert(smem <= 160 * 1024, "LDS budget");
-  auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, FM, NTH>;
+  auto kern = dual_gemm_bf16<BM, BN, WM, WN, XKC, YKC, RX, RYM, EPI, FM, NTH, KWHOLE>;
   static LdsLimitOnce lds_limit;
   { const hipError_t e = lds_limit.raise(reinterpret_cast<const void*>(kern), smem); if (e != hipSuccess) return e; }
   hipLaunchKernelGGL(kern, grid, block, smem, s, a);
@@ -710,13 +717,19 @@ static hipError_t launch_shape(const GemmArgs& a, hipStream_t s) {
 // several Hutchinson probes (FM 1: a probe before the last, 2: the last), so that the one-probe kernel keeps its
 // registers.
 static hipError_t launch_fused_wgrad(const GemmArgs& a, hipStream_t s) {
-  if (a.fu.probe_mode == 3) return a.RY ? launch_pair<true>(a, s) : launch_pair<false>(a, s);
+  if (a.fu.probe_mode == 3) {
+    if (a.K % BK == 0) return a.RY ? launch_pair<true, true>(a, s) : launch_pair<false, true>(a, s);
+    return a.RY ? launch_pair<true, false>(a, s) : launch_pair<false, false>(a, s);
+  }
   if (a.fu.probe_mode == 1)
     return a.RY ? launch_one<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD, 1, 256>(a, s)
                 : launch_one<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD, 1, 256>(a, s);
   if (a.fu.probe_mode == 2)
     return a.RY ? launch_one<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD, 2, 256>(a, s)
                 : launch_one<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD, 2, 256>(a, s);
+  if (a.K % BK == 0)                  // (the usual case: the one-probe kernel without bounds checks in its main loop)
+    return a.RY ? launch_one<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD, 0, 256, true>(a, s)
+                : launch_one<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD, 0, 256, true>(a, s);
   return a.RY ? launch_one<128, 128, 2, 2, false, false, true, RY_MEM, EPI_WGRAD, 0, 256>(a, s)
               : launch_one<128, 128, 2, 2, false, false, true, RY_NONE, EPI_WGRAD, 0, 256>(a, s);
 }

@@ -137,13 +137,19 @@ def class_bytes(w, P, k, fused=(), part=1.0, samples=1):
     return out
 
 
-def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, resident=None, repeats=5):
+def run_mlp(w, steps, warmup, n_pool, fuse, sequential=False, samples=1, resident=None, repeats=5, zero_data=False):
     import torch
     from paper_2409_09242_amd import binding as B
     from paper_2409_09242_amd import workloads as W
 
     theta0 = W.init_theta_workload(w)
     x, y = W.minibatch_pool(w, n_pool, bf16_round=W.to_bf16_f32 if w.bf16 else None)
+    if zero_data:
+        # diagnostic: the same launches on all-zero parameters and inputs, i.e. with the least switching activity
+        # in the multipliers and on the data paths; against the run on the workload's own data it shows how much of
+        # a kernel's time is set by the clock the power limit leaves it rather than by its instruction schedule
+        theta0 = np.zeros_like(theta0)
+        x = np.zeros_like(x)
     xd = torch.from_numpy(x).cuda()
     if w.bf16:
         xd = xd.to(torch.bfloat16)
@@ -365,6 +371,9 @@ def main():
     ap.add_argument("--resident-data", type=float, default=None, metavar="RATIO",
                     help="draw every step's minibatches on the device from a resident synthetic data set of 60000 "
                          "points, partitioned among the workers with this overlap ratio (e.g. 0.125)")
+    ap.add_argument("--zero-data", action="store_true",
+                    help="diagnostic: all-zero parameters and inputs (the same launches with the least switching "
+                         "activity; shows what the power limit costs on the workload's own data)")
     ap.add_argument("--repeats", type=int, default=5,
                     help="how many times the timed region of --steps steps is run; the line reports the median region")
     ap.add_argument("--no-stress", action="store_true", help="skip the update-only HBM stress (configuration 5)")
@@ -379,6 +388,8 @@ def main():
         print("bench.py measures one GPU: the simulated workers are batched on a single device and the library "
               "has no multi-GPU path (--gpus %d refused)" % args.gpus, file=sys.stderr)
         return 2
+    if args.zero_data:                       # a diagnostic of the step's kernels: nothing else is run beside it
+        args.no_stress = args.no_cpu_baseline = True
 
     import torch
     from paper_2409_09242_amd import build as BLD
@@ -398,7 +409,8 @@ def main():
     if args.calibrate:
         calibration_copy()
     h, elapsed, prof, elapsed_prof, part, regions = run_mlp(w, args.steps, args.warmup, n_pool, not args.no_fuse,
-                                                           args.sequential, args.samples, args.resident_data, args.repeats)
+                                                           args.sequential, args.samples, args.resident_data, args.repeats,
+                                                           args.zero_data)
     dtype = "bf16" if w.bf16 else "f32"
     ms_per_step = 1e3 * elapsed / args.steps
     value = w.k * args.steps / elapsed
@@ -482,7 +494,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "timed_regions": len(regions), "ms_per_step_min": 1e3 * min(regions) / args.steps,
         "ms_per_step_max": 1e3 * max(regions) / args.steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype,
+        "data": "zeros (diagnostic run, not the workload)" if args.zero_data else "synthetic",
         "config": {"workload": w.name, "k": w.k, "dims": list(w.dims), "batch": w.batch, "tau": w.tau,
                    **({"img": list(w.img), "conv": list(w.conv), "conv_avg": w.conv_avg} if w.conv else {}),
                    "stale": w.stale, "sync": "dynamic, sequential" if args.sequential else "dynamic",

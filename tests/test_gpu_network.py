@@ -748,3 +748,46 @@ def test_two_runs_of_the_same_steps_give_the_same_bits(bf16):
         h.close()
     for a, b in zip(*runs):
         np.testing.assert_array_equal(a, b)
+
+
+# ---------------------------------------------------------------------------------------------------------
+# A degenerate input: all parameters and all inputs zero.  Every hidden pre-activation is exactly zero, i.e. every
+# ReLU sits on its kink (off on both sides: s > 0 is false), all weight gradients and their Hessian-vector products
+# vanish, and only the output layer's bias sees a gradient (softmax of equal logits) and a curvature (through c_L, the
+# bias part of z).  m = v = 0 everywhere else, so the update divides 0 by eps and must leave those parameters alone.
+# ---------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dims,batch,k,bf16", [
+    ((32, 64, 10), 16, 4, False),              # the whole step in one kernel
+    ((256, 512, 512, 10), 64, 4, False),       # the fp32 product kernels
+    ((256, 512, 512, 10), 64, 4, True),        # the bf16 product kernels
+])
+def test_all_zero_parameters_and_inputs(dims, batch, k, bf16):
+    w = W.scaled(W.C1, dims=dims, batch=batch, k=k, seed=4242, bf16=bf16)
+    theta0 = np.zeros(w.P, dtype=np.float32)
+    x, y = W.minibatch_pool(w, 1, bf16_round=W.to_bf16_f32 if bf16 else None)
+    x0 = np.zeros_like(x[0])
+    h = B.Handle(B.config_from_workload(w), theta0)
+    tr = O.OracleTrainer(oracle_config(w), theta0.astype(np.float64))
+    xd = _to_bf16_bits(x0) if bf16 else torch.from_numpy(x0).cuda()
+    yd = torch.from_numpy(y[0]).cuda()
+    offs, _ = O.layer_offsets(dims)
+    b_last = offs[-1][1]                                  # where the output layer's bias starts
+    for step in range(2):
+        loss = torch.zeros(k, device="cuda")
+        h.worker_step(xd, yd, loss=loss)
+        ref_loss = tr.worker_step(x0, y[0])
+        close(loss.cpu().numpy(), ref_loss, 1e-5, "loss")
+        for i in range(k):
+            g, hz = h.get_state(B.DW_S_G, i), h.get_state(B.DW_S_HZ, i)
+            assert np.all(np.isfinite(g)) and np.all(np.isfinite(hz))
+            assert not g[:b_last].any() and not hz[:b_last].any(), "step %d worker %d: a zero network has no weight gradient" % (step, i)
+            assert g[b_last:].any() and hz[b_last:].any()
+            close(g[b_last:], tr.traces[i].g[b_last:], 1e-5, "g[%d]/bL" % i)
+            close(hz[b_last:], tr.traces[i].hz[b_last:], 1e-4, "hz[%d]/bL" % i)
+            th = h.get_state(B.DW_S_THETA, i)
+            assert not th[:b_last].any(), "0 / eps must stay 0"
+            close(th[b_last:], tr.theta[i][b_last:], 1e-4, "theta[%d]/bL" % i)
+            for what, ref in ((B.DW_S_M, tr.m[i]), (B.DW_S_V, tr.v[i])):
+                st = h.get_state(what, i)
+                assert not st[:b_last].any()
+                close(st[b_last:], ref[b_last:], 1e-4, "moment[%d]/bL" % i)
